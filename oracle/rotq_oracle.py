@@ -1,0 +1,275 @@
+"""CPU oracle for the online rotate-and-quantize path (TEST INFRASTRUCTURE ONLY).
+
+A plain, slow, fp64 NumPy implementation of what the GPU library computes, written
+from the paper (arXiv 2504.13989) so the HIP kernels can be checked element by
+element.  It shares no code with the HIP path and must never be imported by it:
+only the tests, the smoke check and the benchmark's CPU-baseline leg may use it.
+
+What it follows
+  * Sylvester matrices H_{2^k}: section 2.3.2, Eq. 1 (the block recursion).
+  * Legendre symbol: section 2.3.3 (the three-case definition).
+  * Paley construction, order p+1, p prime = 3 (mod 4): Appendix B, Algorithm 2.
+  * Paley II construction, order 2(q+1), q prime = 1 (mod 4): NOT in the paper; the
+    benchmark configurations need H_28 (q=13) and H_148 (q=73).  Standard textbook
+    form: H = C (x) [[1,1],[1,-1]] + I (x) [[1,-1],[-1,-1]] with C the symmetric
+    conference matrix bordered from the Legendre symbols.
+  * Composite order n = p * 2^k ("known small matrices and power of 2", section
+    2.3.3): H_n = H_p (x) H_{2^k}, flat index j = a * 2^k + c.
+  * Dimension expansion: a row of width d < n is zero-padded to n (section 4.2, Eq. 2).
+  * Rotation is H_n / sqrt(n) (Appendix A.1.1: H H^T = n I before normalisation).
+  * Quantizer: section 2.1, X^ = round(X / Delta) * Delta, Delta = max|X| / (2^b - 1),
+    per token (one Delta per row), with the clip ratio of section 3.1 scaling the
+    maximum: Delta = clip * max|y| / (2^b - 1).
+
+Readings taken where the paper is silent (each also listed in the design notes)
+  * codes are clamped to the signed b-bit range [-2^(b-1), 2^(b-1)-1] while Delta
+    keeps the paper's 2^b - 1 denominator;
+  * "round" is round-half-to-even;
+  * an all-zero row gets Delta = 0 and all-zero codes;
+  * the mean in the quantization error runs over all rows * n rotated elements.
+  PARITY UNPINNED for the first two readings: the paper prints no worked numeric
+  quantization example, so only internal consistency pins them.
+
+Everything is float64 unless stated.  Rotation is always a dense product of the
+constructed +-1 matrices - never a butterfly.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+MAX_PALEY_ORDER = 256
+
+
+# --------------------------------------------------------------------------- matrices
+
+def sylvester(k: int) -> np.ndarray:
+    """H_{2^k} by the block recursion of Eq. 1: H_{2m} = [[H_m, H_m], [H_m, -H_m]], H_1 = [1]."""
+    h = np.ones((1, 1), dtype=np.int64)
+    for _ in range(k):
+        h = np.block([[h, h], [h, -h]])
+    return h
+
+
+def is_prime(p: int) -> bool:
+    if p < 2:
+        return False
+    for f in range(2, int(math.isqrt(p)) + 1):
+        if p % f == 0:
+            return False
+    return True
+
+
+def legendre_symbol(a: int, p: int) -> int:
+    """(a/p) for a prime p, by the definition of section 2.3.3: 0 if a = 0 (mod p), +1 if some
+    x has x^2 = a (mod p), else -1."""
+    a %= p
+    if a == 0:
+        return 0
+    squares = {(x * x) % p for x in range(1, p)}
+    return 1 if a in squares else -1
+
+
+def paley1(p: int) -> np.ndarray:
+    """Order p+1 Hadamard matrix, p prime with p = 3 (mod 4); Algorithm 2 (Appendix B).
+
+    All ones; first row and first column (except the corner) are -1; the diagonal below the
+    corner is -1; every other entry [i, j] is the Legendre symbol of (i-1) - (j-1)."""
+    if not is_prime(p) or p % 4 != 3:
+        raise ValueError("Paley construction needs a prime p = 3 (mod 4)")
+    n = p + 1
+    h = np.ones((n, n), dtype=np.int64)
+    for i in range(1, n):
+        h[i, 0] = -1
+        h[0, i] = -1
+        for j in range(1, n):
+            h[i, j] = -1 if i == j else legendre_symbol((i - 1) - (j - 1), p)
+    return h
+
+
+def paley2(q: int) -> np.ndarray:
+    """Order 2(q+1) Hadamard matrix, q prime with q = 1 (mod 4) (textbook Paley II).
+
+    C is (q+1) x (q+1): C[0,0] = 0, C[0,j] = C[j,0] = 1, C[i,j] = legendre(i-j, q) otherwise.
+    H[2i+u, 2j+v] = C[i,j] * A[u,v] + (i == j) * B[u,v], A = [[1,1],[1,-1]], B = [[1,-1],[-1,-1]]."""
+    if not is_prime(q) or q % 4 != 1:
+        raise ValueError("Paley II construction needs a prime q = 1 (mod 4)")
+    m = q + 1
+    c = np.zeros((m, m), dtype=np.int64)
+    c[0, 1:] = 1
+    c[1:, 0] = 1
+    for i in range(1, m):
+        for j in range(1, m):
+            c[i, j] = legendre_symbol(i - j, q)
+    a = np.array([[1, 1], [1, -1]], dtype=np.int64)
+    b = np.array([[1, -1], [-1, -1]], dtype=np.int64)
+    return np.kron(c, a) + np.kron(np.eye(m, dtype=np.int64), b)
+
+
+def paley_kind(p: int):
+    """(kind, q) for a block order p: (1, p-1) if Paley I applies, else (2, p/2-1) if Paley II
+    applies, else None.  Order rules: q+1 for q = 3 (mod 4), 2(q+1) for q = 1 (mod 4)."""
+    if p >= 4 and is_prime(p - 1) and (p - 1) % 4 == 3:
+        return 1, p - 1
+    if p >= 4 and p % 2 == 0 and is_prime(p // 2 - 1) and (p // 2 - 1) % 4 == 1:
+        return 2, p // 2 - 1
+    return None
+
+
+def factor_order(n: int):
+    """n = p * 2^k with the largest 2^k such that p is 1 or a constructible Paley order
+    (p <= MAX_PALEY_ORDER).  Returns (p, kind, q, k); kind 0 = pure Sylvester.  None if no
+    such factorisation exists."""
+    if n < 1:
+        return None
+    k = 0
+    while n % (1 << (k + 1)) == 0:
+        k += 1
+    while k >= 0:
+        p = n >> k
+        if p == 1:
+            return 1, 0, 0, k
+        if p <= MAX_PALEY_ORDER:
+            kq = paley_kind(p)
+            if kq is not None:
+                return p, kq[0], kq[1], k
+        k -= 1
+    return None
+
+
+def next_order(d: int, min_pow2: int = 32) -> int:
+    """Dimension expansion target (section 4.2): the smallest n >= d with a factorisation
+    p * 2^k as above and 2^k >= min_pow2."""
+    n = d
+    while True:
+        f = factor_order(n)
+        if f is not None and (1 << f[3]) >= min_pow2:
+            return n
+        n += 1
+
+
+def hadamard_factors(n: int):
+    """(H_p, H_{2^k}) with H_n = H_p (x) H_{2^k}."""
+    f = factor_order(n)
+    if f is None:
+        raise ValueError(f"no Hadamard order {n}")
+    p, kind, q, k = f
+    hp = np.ones((1, 1), dtype=np.int64) if kind == 0 else (paley1(q) if kind == 1 else paley2(q))
+    return hp, sylvester(k)
+
+
+def hadamard_dense(n: int) -> np.ndarray:
+    hp, hs = hadamard_factors(n)
+    return np.kron(hp, hs)
+
+
+# --------------------------------------------------------------------------- rotation
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Widen bfloat16 bit patterns (uint16) exactly to float64."""
+    u = np.asarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return u.view(np.float32).astype(np.float64)
+
+
+def as_f64(x: np.ndarray) -> np.ndarray:
+    x = np.asarray(x)
+    return bf16_bits_to_f64(x) if x.dtype == np.uint16 else x.astype(np.float64)
+
+
+def rotate(x: np.ndarray, n: int) -> np.ndarray:
+    """y = H_n pad(x) / sqrt(n) for every row of x [rows, d], d <= n.
+
+    The dense product with H_p (x) H_{2^k} is taken as the two dense Kronecker factors on the
+    row viewed as [p, 2^k]: y[a', c'] = sum_a sum_c H_p[a', a] H_{2^k}[c', c] x[a, c]."""
+    x = as_f64(x)
+    rows, d = x.shape
+    if d > n:
+        raise ValueError("d > n")
+    hp, hs = hadamard_factors(n)
+    p, m = hp.shape[0], hs.shape[0]
+    xp = np.zeros((rows, n), dtype=np.float64)
+    xp[:, :d] = x
+    xm = xp.reshape(rows, p, m)
+    y = np.matmul(xm, hs.astype(np.float64).T)               # along c
+    y = np.einsum("ab,rbc->rac", hp.astype(np.float64), y)   # along a
+    return y.reshape(rows, n) / math.sqrt(n)
+
+
+# --------------------------------------------------------------------------- quantizer
+
+def quant_params(b: int):
+    """(L, qmin, qmax): L = 2^b - 1 is the paper's denominator; codes live in the signed b-bit
+    range."""
+    return (1 << b) - 1, -(1 << (b - 1)), (1 << (b - 1)) - 1
+
+
+def quantize(y: np.ndarray, b: int, clip) -> tuple:
+    """Per-row symmetric quantization of rotated rows y [rows, n].
+
+    Returns (codes int8 [rows, n], delta f64 [rows], t f64 [rows, n]) with
+    delta = clip * max|y| / (2^b - 1), t = y / delta, codes = clamp(round_half_even(t)).
+    ``clip`` is a float32 value widened to float64 (the library takes it as a C float)."""
+    lvl, qmin, qmax = quant_params(b)
+    clip64 = float(np.float32(clip))
+    amax = np.max(np.abs(y), axis=1)
+    delta = clip64 * amax / lvl
+    safe = np.where(delta > 0, delta, 1.0)
+    t = y / safe[:, None]
+    t[delta == 0] = 0.0
+    codes = np.clip(np.rint(t), qmin, qmax).astype(np.int8)
+    return codes, delta, t
+
+
+def dequantize(codes: np.ndarray, delta: np.ndarray) -> np.ndarray:
+    return codes.astype(np.float64) * np.asarray(delta, dtype=np.float64)[:, None]
+
+
+def rotate_quantize(x: np.ndarray, n: int, b: int, clip) -> tuple:
+    """The whole path for rows of x: returns (codes, delta, t, y)."""
+    y = rotate(x, n)
+    codes, delta, t = quantize(y, b, clip)
+    return codes, delta, t, y
+
+
+def quant_error(x: np.ndarray, n: int, b: int, clips) -> np.ndarray:
+    """mse[k] = mean over all rows * n rotated elements of (dequant(quant(y; clips[k])) - y)^2."""
+    y = rotate(x, n)
+    out = np.empty(len(clips), dtype=np.float64)
+    for k, c in enumerate(clips):
+        codes, delta, _ = quantize(y, b, c)
+        out[k] = np.mean((dequantize(codes, delta) - y) ** 2)
+    return out
+
+
+# --------------------------------------------------------------------------- packing
+
+def pack_codes(codes: np.ndarray, b: int) -> np.ndarray:
+    """Dense little-endian bitstream per row: element j occupies stream bits [j*b, (j+1)*b),
+    stream bit i is bit i % 8 of byte i // 8; the field is the code's low b bits (two's
+    complement).  Returns uint8 [rows, n*b/8]."""
+    rows, n = codes.shape
+    if (n * b) % 8:
+        raise ValueError("row bit length must be a whole number of bytes")
+    field = codes.astype(np.int64) & ((1 << b) - 1)
+    bits = ((field[:, :, None] >> np.arange(b)) & 1).astype(np.uint8).reshape(rows, n * b)
+    return np.packbits(bits, axis=1, bitorder="little")
+
+
+def unpack_codes(packed: np.ndarray, b: int, n: int) -> np.ndarray:
+    """Inverse of pack_codes: int8 codes [rows, n] (sign-extended)."""
+    rows = packed.shape[0]
+    bits = np.unpackbits(np.asarray(packed, dtype=np.uint8), axis=1, bitorder="little")[:, : n * b]
+    field = (bits.reshape(rows, n, b).astype(np.int64) << np.arange(b)).sum(axis=2)
+    field = np.where(field >= (1 << (b - 1)), field - (1 << b), field)
+    return field.astype(np.int8)
+
+
+# --------------------------------------------------------------------------- checker helpers
+
+def boundary_exempt(t: np.ndarray, b: int, tol: float = 1e-6) -> np.ndarray:
+    """Mask of elements whose pre-round value t lies within ``tol`` of a rounding boundary
+    k + 1/2, k in [qmin, qmax - 1] (beyond those the clamp makes the code insensitive)."""
+    _, qmin, qmax = quant_params(b)
+    frac = np.abs(t - np.floor(t) - 0.5)
+    return (frac < tol) & (t >= qmin + 0.5 - tol) & (t <= qmax - 0.5 + tol)

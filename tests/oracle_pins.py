@@ -1,0 +1,429 @@
+"""Pins for the CPU oracle: checks against what the paper and the mathematics fix.
+
+Every check takes the oracle module as its argument, so the same checks can be run on a
+deliberately broken copy (tests/test_oracle_pins.py plants mistakes and expects a pin to
+fail).  Nothing here calls the HIP path.
+"""
+from __future__ import annotations
+
+import math
+import os
+
+import numpy as np
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+# ----------------------------------------------------------------------------- fixtures
+
+def _read_matrices(name):
+    mats, cur, key = {}, None, None
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            if line[0].isalpha():
+                key = line
+                mats[key] = []
+            else:
+                mats[key].append([int(v) for v in line.split()])
+    return {k: np.array(v, dtype=np.int64) for k, v in mats.items()}
+
+
+def _read_residues():
+    out = {}
+    with open(os.path.join(GOLDEN, "quadratic_residues.txt")) as f:
+        for line in f:
+            if line.startswith("#") or ":" not in line:
+                continue
+            p, r = line.split(":")
+            out[int(p)] = {int(v) for v in r.split()}
+    return out
+
+
+def _read_pack_examples():
+    out = []
+    with open(os.path.join(GOLDEN, "pack_examples.txt")) as f:
+        for line in f:
+            if line.startswith("#") or "|" not in line:
+                continue
+            b, codes, by = line.split("|")
+            out.append((int(b), [int(v) for v in codes.split()], [int(v, 16) for v in by.split()]))
+    return out
+
+
+def fwht_reference(v):
+    """Textbook in-place fast Walsh-Hadamard transform (natural order), test helper only."""
+    v = np.array(v, dtype=np.float64)
+    n = v.shape[-1]
+    h = 1
+    while h < n:
+        for i in range(0, n, 2 * h):
+            a = v[..., i:i + h].copy()
+            b = v[..., i + h:i + 2 * h].copy()
+            v[..., i:i + h] = a + b
+            v[..., i + h:i + 2 * h] = a - b
+        h *= 2
+    return v
+
+
+# ----------------------------------------------------------------------------- P1 Sylvester
+
+def check_sylvester_literal(o):
+    g = _read_matrices("eq1_sylvester.txt")
+    assert np.array_equal(o.sylvester(1), g["H2"])
+    assert np.array_equal(o.sylvester(2), g["H4"])
+
+
+def check_sylvester_popcount(o):
+    for k in range(0, 8):
+        h = o.sylvester(k)
+        n = 1 << k
+        i, j = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+        pc = np.array([[bin(a & b).count("1") for b in range(n)] for a in range(n)])
+        assert np.array_equal(h, 1 - 2 * (pc % 2))
+        assert np.array_equal(h @ h.T, n * np.eye(n, dtype=np.int64))
+
+
+# ----------------------------------------------------------------------------- P2 Legendre
+
+def check_legendre_tables(o):
+    for p, res in _read_residues().items():
+        for a in range(-p, 2 * p):
+            want = 0 if a % p == 0 else (1 if (a % p) in res else -1)
+            assert o.legendre_symbol(a, p) == want, (a, p)
+
+
+def check_legendre_euler(o):
+    for p in (3, 7, 11, 13, 29, 73, 103):
+        tot = 0
+        for a in range(p):
+            e = pow(a, (p - 1) // 2, p)
+            e = -1 if e == p - 1 else e
+            assert o.legendre_symbol(a, p) == e
+            tot += e
+        assert tot == 0
+        for a in range(1, p):
+            for b in (2, 3, p - 1):
+                assert o.legendre_symbol(a * b, p) == o.legendre_symbol(a, p) * o.legendre_symbol(b, p)
+
+
+# ----------------------------------------------------------------------------- P3 Paley
+
+def check_paley1_literal(o):
+    g = _read_matrices("alg2_paley_p3.txt")
+    assert np.array_equal(o.paley1(3), g["H4"])
+
+
+def check_paley1_structure(o):
+    # Algorithm 2's fixed entries, and its orientation: entry [i,j] is the symbol of i-j, so for
+    # p = 11 (residues 1,3,4,5,9) H[2,1] = (1/11) = +1 and H[1,2] = (-1/11) = (10/11) = -1.
+    h = o.paley1(11)
+    assert h[0, 0] == 1 and np.all(h[0, 1:] == -1) and np.all(h[1:, 0] == -1)
+    assert np.all(np.diag(h)[1:] == -1)
+    assert h[2, 1] == 1 and h[1, 2] == -1
+    assert h[4, 1] == 1 and h[1, 4] == -1     # 3 is a residue, -3 = 8 is not
+
+
+def check_paley2_structure(o):
+    # layout of the stated Paley II definition: 2x2 blocks indexed [2i+u, 2j+v]; diagonal blocks
+    # are B = [[1,-1],[-1,-1]] (C has a zero diagonal), block (0, j>0) is +A = [[1,1],[1,-1]],
+    # block (i, j) off the border is legendre(i-j, q) * A.  q = 5: residues 1, 4.
+    h = o.paley2(5)
+    for i in range(6):
+        assert h[2 * i:2 * i + 2, 2 * i:2 * i + 2].tolist() == [[1, -1], [-1, -1]]
+    for j in range(1, 6):
+        assert h[0:2, 2 * j:2 * j + 2].tolist() == [[1, 1], [1, -1]]
+        assert h[2 * j:2 * j + 2, 0:2].tolist() == [[1, 1], [1, -1]]
+    assert h[2:4, 4:6].tolist() == [[1, 1], [1, -1]]          # i=1, j=2: (-1/5) = (4/5) = +1
+    assert h[2:4, 6:8].tolist() == [[-1, -1], [-1, 1]]        # i=1, j=3: (-2/5) = (3/5) = -1
+
+
+def check_paley_orthogonal(o):
+    for q in (3, 7, 11, 19, 23, 43, 103):
+        h = o.paley1(q)
+        n = q + 1
+        assert h.shape == (n, n) and set(np.unique(h)) == {-1, 1}
+        assert np.array_equal(h @ h.T, n * np.eye(n, dtype=np.int64))
+    for q in (5, 13, 17, 29, 73):
+        h = o.paley2(q)
+        n = 2 * (q + 1)
+        assert h.shape == (n, n) and set(np.unique(h)) == {-1, 1}
+        assert np.array_equal(h @ h.T, n * np.eye(n, dtype=np.int64))
+        assert np.array_equal(h, h.T)          # Paley II matrices are symmetric
+
+
+def check_paley_guards(o):
+    for bad in (5, 13, 9, 15):                  # = 1 (mod 4), or not prime
+        try:
+            o.paley1(bad)
+        except ValueError:
+            pass
+        else:
+            raise AssertionError(f"paley1({bad}) must be refused")
+    for bad in (3, 7, 9, 25):
+        try:
+            o.paley2(bad)
+        except ValueError:
+            pass
+        else:
+            raise AssertionError(f"paley2({bad}) must be refused")
+
+
+def check_order_rules(o):
+    # the orders the benchmark configurations use
+    assert o.factor_order(4096) == (1, 0, 0, 12)
+    assert o.factor_order(256) == (1, 0, 0, 8)
+    assert o.factor_order(128) == (1, 0, 0, 7)
+    assert o.factor_order(3584) == (28, 2, 13, 7)
+    assert o.factor_order(18944) == (148, 2, 73, 7)
+    assert o.factor_order(3072) == (12, 1, 11, 8)
+    assert o.factor_order(1536) == (12, 1, 11, 7)
+    assert o.factor_order(3000) is None and o.factor_order(3008) is None
+    assert o.next_order(3000) == 3072
+    assert o.next_order(4096) == 4096
+    # q+1 for q = 3 (mod 4), 2(q+1) for q = 1 (mod 4); Paley I wins where both exist (12)
+    assert o.paley_kind(12) == (1, 11) and o.paley_kind(28) == (2, 13)
+    assert o.paley_kind(148) == (2, 73) and o.paley_kind(20) == (1, 19)
+    assert o.paley_kind(16) is None and o.paley_kind(40) is None and o.paley_kind(56) is None
+
+
+def check_composite_orthogonal(o):
+    for n in (12, 24, 48, 56, 96, 296, 384):
+        h = o.hadamard_dense(n)
+        assert h.shape == (n, n)
+        assert np.array_equal(h @ h.T, n * np.eye(n, dtype=np.int64))
+    # Kronecker index convention: flat index = a * 2^k + c
+    hp, hs = o.hadamard_factors(48)
+    h = o.hadamard_dense(48)
+    m = hs.shape[0]
+    for (i, j) in ((0, 0), (5, 17), (47, 3), (13, 46), (31, 31)):
+        assert h[i, j] == hp[i // m, j // m] * hs[i % m, j % m]
+
+
+# ----------------------------------------------------------------------------- P4 rotation
+
+def check_rotate_bruteforce(o):
+    # y_i = sum_j H[i,j] x_j / sqrt(n), by explicit loops over the dense matrix (catches a
+    # transposed operand: Paley I matrices are not symmetric)
+    rng = np.random.default_rng(1)
+    for n, d in ((12, 12), (24, 20), (48, 48), (56, 50), (32, 32)):
+        h = o.hadamard_dense(n)
+        x = rng.standard_normal((3, d))
+        y = o.rotate(x, n)
+        for r in range(3):
+            for i in range(n):
+                s = 0.0
+                for j in range(d):
+                    s += h[i, j] * x[r, j]
+                assert abs(y[r, i] - s / math.sqrt(n)) < 1e-12
+
+
+def check_rotate_fwht(o):
+    rng = np.random.default_rng(2)
+    for k in (1, 3, 6, 10):
+        n = 1 << k
+        x = rng.standard_normal((4, n))
+        assert np.allclose(o.rotate(x, n), fwht_reference(x) / math.sqrt(n), rtol=0, atol=1e-11)
+
+
+def check_rotate_norm_and_involution(o):
+    rng = np.random.default_rng(3)
+    for n in (64, 96, 224, 1184, 3072):
+        x = rng.standard_normal((2, n)) * 3
+        y = o.rotate(x, n)
+        assert np.allclose(np.linalg.norm(y, axis=1), np.linalg.norm(x, axis=1), rtol=1e-12)
+    for n in (64, 224, 1184):                     # symmetric H (Sylvester, Paley II): H(Hx)/n = x
+        x = rng.standard_normal((2, n))
+        assert np.allclose(o.rotate(o.rotate(x, n), n), x, atol=1e-12)
+
+
+def check_rotate_onehot(o):
+    # Lemma "Hadamard incoherence" / Theorem "Hadamard optimality": |y_i| = c / sqrt(n) for all i
+    for n in (16, 48, 224, 4096):
+        for j in (0, n // 3, n - 1):
+            x = np.zeros((1, n))
+            x[0, j] = 7.5
+            y = o.rotate(x, n)
+            assert np.allclose(np.abs(y), 7.5 / math.sqrt(n), rtol=1e-14)
+
+
+def check_rotate_zero_pad(o):
+    # Eq. 2: order 4, rows [x0, x1] padded with two zeros -> (x0+x1, x0-x1, x0+x1, x0-x1)/2
+    g = _read_matrices("eq2_expand.txt")["M"]
+    assert np.array_equal(o.hadamard_dense(4), g)
+    x = np.array([[3.0, 5.0], [-2.0, 0.25]])
+    y = o.rotate(x, 4)
+    for r in range(2):
+        a, c = x[r]
+        assert np.allclose(y[r], np.array([a + c, a - c, a + c, a - c]) / 2.0)
+    # padding explicitly with zeros gives the same result, at a Paley order too
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((2, 40))
+    xp = np.concatenate([x, np.zeros((2, 8))], axis=1)
+    assert np.array_equal(o.rotate(x, 48), o.rotate(xp, 48))
+
+
+def check_rotate_peak_experiment(o):
+    # Appendix A.1.2: N(0, 0.1^2) vector plus a peak of 200 -> max|Hx| tracks 200/sqrt(n)
+    rng = np.random.default_rng(5)
+    for n in (64, 256, 1024, 4096):
+        x = rng.normal(0.0, 0.1, size=(1, n))
+        x[0, 17] += 200.0
+        m = np.max(np.abs(o.rotate(x, n)))
+        assert abs(m - 200.0 / math.sqrt(n)) < 0.5
+
+
+def check_bf16_widening(o):
+    bits = np.array([0x3F80, 0xBF80, 0x4049, 0x0000, 0x8000, 0x7F7F, 0x0001], dtype=np.uint16)
+    want = [1.0, -1.0, 3.140625, 0.0, -0.0, 3.3895313892515355e38, 2.0 ** -133]
+    assert np.array_equal(o.bf16_bits_to_f64(bits), np.array(want))
+
+
+# ----------------------------------------------------------------------------- P5 quantizer
+
+def check_quant_params(o):
+    assert o.quant_params(3) == (7, -4, 3)
+    assert o.quant_params(4) == (15, -8, 7)
+
+
+def check_quantize_properties(o):
+    rng = np.random.default_rng(6)
+    y = rng.standard_t(3.0, size=(16, 96))
+    for b in (3, 4):
+        lvl, qmin, qmax = o.quant_params(b)
+        for clip in (1.0, 0.9, 0.5):
+            q, delta, t = o.quantize(y, b, clip)
+            c64 = float(np.float32(clip))
+            assert q.min() >= qmin and q.max() <= qmax
+            assert np.allclose(delta, c64 * np.abs(y).max(axis=1) / lvl, rtol=1e-15)
+            yh = o.dequantize(q, delta)
+            inside = (t >= qmin - 0.5) & (t <= qmax + 0.5)
+            assert np.all(np.abs(yh - y)[inside] <= delta[:, None].repeat(96, 1)[inside] * 0.5 * (1 + 1e-12))
+            # clamped elements sit on the range ends
+            assert np.all(q[t > qmax + 0.5] == qmax) and np.all(q[t < qmin - 0.5] == qmin)
+            # idempotence with the scale held fixed
+            q2 = np.clip(np.rint(yh / delta[:, None]), qmin, qmax).astype(np.int8)
+            assert np.array_equal(q2, q)
+            # scale equivariance (power of two: bit exact)
+            q3, d3, _ = o.quantize(4.0 * y, b, clip)
+            assert np.array_equal(q3, q) and np.array_equal(d3, 4.0 * delta)
+
+
+def check_quantize_ties_and_zero(o):
+    # ties go to even; zero row -> zero scale and codes
+    y = np.array([[7.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.5], [0.0] * 8])
+    q, delta, _ = o.quantize(y, 3, 1.0)            # delta = 1 for the first row
+    assert delta[0] == 1.0 and delta[1] == 0.0
+    assert q[0].tolist() == [3, 0, 2, 2, 0, -2, -2, 3]
+    assert q[1].tolist() == [0] * 8
+
+
+def check_quantize_onehot(o):
+    # one-hot through Sylvester: all |y| equal, t = +-L/clip, codes = qmax / qmin by sign,
+    # delta = clip * c / (sqrt(n) L)
+    n, c = 256, 12.0
+    x = np.zeros((1, n))
+    x[0, 5] = c
+    for b in (3, 4):
+        lvl, qmin, qmax = o.quant_params(b)
+        q, delta, t, y = o.rotate_quantize(x, n, b, 0.9)
+        c64 = float(np.float32(0.9))
+        assert np.allclose(delta, c64 * c / (math.sqrt(n) * lvl), rtol=1e-14)
+        assert np.all(q[y > 0] == qmax) and np.all(q[y < 0] == qmin)
+        assert np.allclose(np.abs(t), lvl / c64, rtol=1e-14)
+
+
+# ----------------------------------------------------------------------------- P6 quant_error
+
+def check_quant_error_bruteforce(o):
+    rng = np.random.default_rng(7)
+    n, d, b = 24, 22, 3
+    x = rng.standard_normal((3, d))
+    clips = np.array([0.5, 0.75, 1.0], dtype=np.float32)
+    got = o.quant_error(x, n, b, clips)
+    h = o.hadamard_dense(n)
+    lvl, qmin, qmax = (1 << b) - 1, -(1 << (b - 1)), (1 << (b - 1)) - 1
+    for k, c in enumerate(clips):
+        tot = 0.0
+        for r in range(3):
+            y = [sum(h[i, j] * x[r, j] for j in range(d)) / math.sqrt(n) for i in range(n)]
+            amax = max(abs(v) for v in y)
+            dl = float(c) * amax / lvl
+            for v in y:
+                code = min(max(round(v / dl), qmin), qmax)      # Python round = half to even
+                tot += (code * dl - v) ** 2
+        assert abs(got[k] - tot / (3 * n)) < 1e-13
+
+
+def check_quant_error_closed_form(o):
+    # one-hot: every |y| = c/sqrt(n) =: a; positive entries saturate at qmax, negative at qmin:
+    # err+ = a (1 - qmax clip / L), err- = a (1 - |qmin| clip / L) (negative side may not clamp)
+    n, c, b = 64, 3.0, 3
+    x = np.zeros((2, n))
+    x[:, 9] = c
+    clips = np.array([0.5, 0.9, 0.9, 1.0], dtype=np.float32)
+    mse = o.quant_error(x, n, b, clips)
+    assert mse[1] == mse[2]
+    a = c / math.sqrt(n)
+    y = o.rotate(x, n)
+    npos = np.sum(y > 0) / y.size
+    for k, cl in enumerate(clips):
+        cl = float(cl)
+        tpos = 7.0 / cl                      # > 3.5 always -> code 3
+        tneg = -7.0 / cl                     # code max(-4, rint(tneg))
+        qneg = max(-4, round(tneg))
+        want = npos * (a - 3 * cl * a / 7) ** 2 + (1 - npos) * (-a - qneg * cl * a / 7) ** 2
+        assert tpos > 3.5
+        assert abs(mse[k] - want) < 1e-14
+
+
+def check_quant_error_rotation_invariance(o):
+    # orthonormal rotation: error measured after rotating back equals error in the rotated domain
+    rng = np.random.default_rng(8)
+    n = 64
+    x = rng.standard_normal((4, n))
+    y = o.rotate(x, n)
+    q, delta, _ = o.quantize(y, 4, 0.8)
+    back = o.rotate(o.dequantize(q, delta), n)          # Sylvester is symmetric: inverse = itself
+    e1 = np.mean((back - x) ** 2)
+    assert abs(e1 - o.quant_error(x, n, 4, np.array([0.8], dtype=np.float32))[0]) < 1e-13
+
+
+# ----------------------------------------------------------------------------- P7 packing
+
+def check_pack_examples(o):
+    for b, codes, by in _read_pack_examples():
+        got = o.pack_codes(np.array([codes], dtype=np.int8), b)
+        assert got.tolist() == [by], (b, got.tolist(), by)
+        assert o.unpack_codes(np.array([by], dtype=np.uint8), b, len(codes)).tolist() == [codes]
+
+
+def check_pack_roundtrip(o):
+    rng = np.random.default_rng(9)
+    for b in (3, 4):
+        _, qmin, qmax = o.quant_params(b)
+        q = rng.integers(qmin, qmax + 1, size=(5, 96)).astype(np.int8)
+        pk = o.pack_codes(q, b)
+        assert pk.shape == (5, 96 * b // 8) and pk.dtype == np.uint8
+        assert np.array_equal(o.unpack_codes(pk, b, 96), q)
+        # bit-level definition, element by element
+        for r in (0, 4):
+            for j in (0, 1, 37, 95):
+                f = 0
+                for i in range(b):
+                    s = j * b + i
+                    f |= ((int(pk[r, s // 8]) >> (s % 8)) & 1) << i
+                assert f == (int(q[r, j]) & ((1 << b) - 1))
+
+
+def check_boundary_mask(o):
+    t = np.array([[0.5, 0.5 + 5e-7, 0.5 + 2e-6, 2.5 - 9e-7, 3.5, -3.5, -4.5, 7.5, 1.0]])
+    m3 = o.boundary_exempt(t, 3)
+    assert m3.tolist() == [[True, True, False, True, False, True, False, False, False]]
+    m4 = o.boundary_exempt(t, 4)
+    assert m4.tolist() == [[True, True, False, True, True, True, True, False, False]]
+
+
+ALL_CHECKS = [v for k, v in sorted(globals().items()) if k.startswith("check_")]

@@ -1,0 +1,96 @@
+"""CPU-only: the oracle against its pins, and the pins against planted mistakes."""
+import importlib.util
+import os
+
+import numpy as np
+import pytest
+
+import oracle_pins as pins
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ORACLE_PATH = os.path.join(ROOT, "oracle", "rotq_oracle.py")
+
+
+def load_oracle(patch=None):
+    """A fresh copy of the oracle module, optionally with source text replaced (to plant a bug)."""
+    with open(ORACLE_PATH) as f:
+        src = f.read()
+    if patch is not None:
+        old, new = patch
+        assert src.count(old) >= 1, f"mutation anchor not found: {old!r}"
+        src = src.replace(old, new)
+    spec = importlib.util.spec_from_loader("rotq_oracle_copy", loader=None)
+    mod = importlib.util.module_from_spec(spec)
+    exec(compile(src, ORACLE_PATH, "exec"), mod.__dict__)
+    return mod
+
+
+@pytest.fixture(scope="module")
+def oracle():
+    return load_oracle()
+
+
+@pytest.mark.parametrize("check", pins.ALL_CHECKS, ids=lambda c: c.__name__)
+def test_pin(oracle, check):
+    check(oracle)
+
+
+# Each entry: a plausible mistake planted in the oracle's source; some pin must fail.
+MUTATIONS = {
+    "sylvester_sign": ("np.block([[h, h], [h, -h]])", "np.block([[h, h], [-h, h]])"),
+    "legendre_flipped": ("return 1 if a in squares else -1", "return -1 if a in squares else 1"),
+    "paley1_diag_plus": ("h[i, j] = -1 if i == j else", "h[i, j] = 1 if i == j else"),
+    "paley1_transposed": ("legendre_symbol((i - 1) - (j - 1), p)", "legendre_symbol((j - 1) - (i - 1), p)"),
+    "paley1_border": ("h[0, i] = -1", "h[0, i] = 1"),
+    "paley1_no_guard": ("if not is_prime(p) or p % 4 != 3:", "if not is_prime(p):"),
+    "paley2_b_sign": ("b = np.array([[1, -1], [-1, -1]]", "b = np.array([[1, -1], [-1, 1]]"),
+    "paley2_border": ("c[1:, 0] = 1", "c[1:, 0] = -1"),
+    "paley2_kron_order": ("return np.kron(c, a) + np.kron(np.eye(m, dtype=np.int64), b)",
+                          "return np.kron(a, c) + np.kron(b, np.eye(m, dtype=np.int64))"),
+    "paley_kind_priority": ("if p >= 4 and is_prime(p - 1) and (p - 1) % 4 == 3:\n        return 1, p - 1",
+                            "if False:\n        return 1, p - 1"),
+    "factor_smallest_pow2": ("    while n % (1 << (k + 1)) == 0:\n        k += 1\n", "    k = 5\n"),
+    "kron_swapped": ("return np.kron(hp, hs)", "return np.kron(hs, hp)"),
+    "rotate_transposed_block": ('np.einsum("ab,rbc->rac"', 'np.einsum("ba,rbc->rac"'),
+    "rotate_axes_swapped": ("xm = xp.reshape(rows, p, m)", "xm = xp.reshape(rows, m, p).transpose(0, 2, 1)"),
+    "rotate_no_norm": ("return y.reshape(rows, n) / math.sqrt(n)", "return y.reshape(rows, n) / n"),
+    "bf16_shift": ("<< np.uint32(16)", "<< np.uint32(15)"),
+    "levels_pow2": ("return (1 << b) - 1, -(1 << (b - 1)), (1 << (b - 1)) - 1",
+                    "return (1 << b), -(1 << (b - 1)), (1 << (b - 1)) - 1"),
+    "range_symmetric": ("return (1 << b) - 1, -(1 << (b - 1)), (1 << (b - 1)) - 1",
+                        "return (1 << b) - 1, -(1 << (b - 1)) + 1, (1 << (b - 1)) - 1"),
+    "clip_dropped": ("delta = clip64 * amax / lvl", "delta = amax / lvl"),
+    "clip_not_f32": ("clip64 = float(np.float32(clip))", "clip64 = float(clip)"),
+    "round_floor": ("codes = np.clip(np.rint(t), qmin, qmax)", "codes = np.clip(np.floor(t + 0.5), qmin, qmax)"),
+    "amax_signed": ("amax = np.max(np.abs(y), axis=1)", "amax = np.max(y, axis=1)"),
+    "mse_sum": ("out[k] = np.mean((dequantize(codes, delta) - y) ** 2)",
+                "out[k] = np.sum((dequantize(codes, delta) - y) ** 2)"),
+    "mse_abs": ("out[k] = np.mean((dequantize(codes, delta) - y) ** 2)",
+                "out[k] = np.mean(np.abs(dequantize(codes, delta) - y))"),
+    "pack_big_endian": ('np.packbits(bits, axis=1, bitorder="little")', 'np.packbits(bits, axis=1, bitorder="big")'),
+    "pack_field_msb_first": ("(field[:, :, None] >> np.arange(b)) & 1", "(field[:, :, None] >> np.arange(b)[::-1]) & 1"),
+    "unpack_no_sign": ("field = np.where(field >= (1 << (b - 1)), field - (1 << b), field)", "field = field"),
+    "boundary_tol": ("return (frac < tol)", "return (frac < 10 * tol)"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MUTATIONS))
+def test_planted_mistake_is_caught(name):
+    broken = load_oracle(MUTATIONS[name])
+    failed = []
+    for check in pins.ALL_CHECKS:
+        try:
+            check(broken)
+        except AssertionError:
+            failed.append(check.__name__)
+        except Exception:
+            failed.append(check.__name__)
+    assert failed, f"no pin notices the planted mistake {name!r}"
+
+
+def test_clip_is_taken_as_float32(oracle):
+    # the library receives clip as a C float; 0.9 is not representable, so the widened value differs
+    y = np.array([[1.0, -0.3, 0.7, 0.2]])
+    _, d32, _ = oracle.quantize(y, 4, 0.9)
+    assert d32[0] == float(np.float32(0.9)) / 15
+    assert d32[0] != 0.9 / 15
