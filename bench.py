@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the rotate-and-quantize hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one rq_rotate_quantize call (load, zero-pad, rotate, absmax, scale, round/clip, pack)
+over one batch of the Llama-shaped configuration: X bf16 [2048 x 4096], H_4096, b = 4,
+clip = 0.9.  Batches live in a ring of distinct HBM buffers larger than the last-level cache,
+so every step reads cold data; the K steps are replayed from one HIP graph so the timed region
+is kernel work, not Python launch overhead (the eager per-call rate is reported next to it).
+The last line printed is one JSON object (see the field notes in the design doc).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+RING_BYTES = 1536 << 20         # ring of batches: well above the 256 MB last-level cache
+
+
+def algorithmic_bytes_per_row(d: int, n: int, bits: int, elem: int = 2) -> int:
+    """Bytes in + out per row: the input row, the packed codes, one fp32 scale."""
+    return elem * d + n * bits // 8 + 4
+
+
+def bytes_view(t):
+    return t.numel() * t.element_size()
+
+
+def time_steady_state(torch, binding, h, base, bits, clip, rows_total):
+    """One large launch (input >= 1 GiB): the kernel's sustained rate without launch effects."""
+    reps = rows_total // base.shape[0]
+    x = base.repeat(reps, 1)
+    codes = torch.empty((x.shape[0], h.n * bits // 8), dtype=torch.uint8, device="cuda")
+    scales = torch.empty((x.shape[0],), dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        binding.rotate_quantize(h, x, bits, clip, codes=codes, scales=scales)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_it = 5
+    e0.record()
+    for _ in range(n_it):
+        binding.rotate_quantize(h, x, bits, clip, codes=codes, scales=scales)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / n_it
+    nbytes = x.shape[0] * algorithmic_bytes_per_row(x.shape[1], h.n, bits)
+    return {"rows": int(x.shape[0]), "ms_per_launch": ms, "GBps": nbytes / ms / 1e6,
+            "frac_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBPS,
+            "tokens_per_s": x.shape[0] / ms * 1e3}
+
+
+def cpu_baseline(x_bits, n, bits, clip):
+    """The oracle as it stands, timed on the host cores on the same batch."""
+    sys.path.insert(0, os.path.join(ROOT, "oracle"))
+    import rotq_oracle as oracle
+    threads = os.cpu_count() or 1
+    try:
+        from threadpoolctl import threadpool_info
+        nt = [p.get("num_threads") for p in threadpool_info() if p.get("user_api") == "blas"]
+        if nt:
+            threads = max(nt)
+    except Exception:
+        pass
+    try:
+        threads = min(threads, len(os.sched_getaffinity(0)))
+    except Exception:
+        pass
+    t0 = time.perf_counter()
+    q, _, _, _ = oracle.rotate_quantize(x_bits, n, bits, clip)
+    oracle.pack_codes(q, bits)
+    dt = time.perf_counter() - t0
+    rows, d = x_bits.shape
+    nbytes = rows * algorithmic_bytes_per_row(d, n, bits)
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"one full batch [{rows} x {d}] bf16, fp64 dense H_{n} product + quantize + pack, "
+                      f"{dt:.2f} s", "tokens_per_s": rows / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-steady-state", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (rows are independent, "
+              "so N GPUs would each run this same kernel on their share of the rows); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2504_13989_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs the GPU", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS["llama_hidden"]
+    bits, clip = 4, w.clip
+    x_bits = wl.generate(w)
+    base = torch.from_numpy(x_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    h = binding.hadamard_build(w.n)
+
+    row_bytes = algorithmic_bytes_per_row(w.d, w.n, bits)
+    batch_bytes = w.rows * row_bytes
+    ring = max(2, RING_BYTES // batch_bytes)
+    # same rows in every slot, rolled so that slots differ; only the addresses need to be distinct
+    xs = [torch.roll(base, shifts=i, dims=0).contiguous() for i in range(ring)]
+    codes = [torch.empty((w.rows, w.n * bits // 8), dtype=torch.uint8, device="cuda") for _ in range(ring)]
+    scales = [torch.empty((w.rows,), dtype=torch.float32, device="cuda") for _ in range(ring)]
+
+    def step(i):
+        s = i % ring
+        binding.rotate_quantize(h, xs[s], bits, clip, codes=codes[s], scales=scales[s])
+
+    # eager: one C-ABI call per step from Python
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    eager_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # graph: the same K steps captured once, replayed inside the timed region
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(0)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for i in range(args.steps):
+            step(i)
+    for _ in range(max(1, args.warmup // max(1, args.steps)) + 1):
+        graph.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    kernel_ms = e0.elapsed_time(e1) / args.steps          # average launch duration, HIP events
+    ms_per_step = wall_ms / args.steps
+    kernel_name = h.last_kernel
+
+    value = batch_bytes / ms_per_step / 1e6                # GB/s over the timed region
+    achieved = batch_bytes / kernel_ms / 1e6
+    out = {
+        "metric": "rotate+quantize GB/s (bytes in+out)",
+        "value": value,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "llama_hidden: X bf16 [2048 x 4096], H_4096, b=4, clip=0.9, "
+                               "Student-t(3) + 8 outlier channels x50 + 2 massive tokens x500, seed 100",
+                   "rows": w.rows, "d": w.d, "n": w.n, "bits": bits, "clip": clip,
+                   "ring_buffers": ring, "launch": "hip graph replay of K steps"},
+        "tokens_per_s": w.rows / ms_per_step * 1e3,
+        "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
+        "eager_ms_per_step": eager_ms,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "kernel": kernel_name,
+                     "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": batch_bytes},
+    }
+    if not args.no_steady_state:
+        out["steady_state"] = time_steady_state(torch, binding, h, base, bits, clip, 131072)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(x_bits, w.n, bits, clip)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,158 @@
+/*
+ * rotq - online Hadamard rotate-and-quantize for MI355X (gfx950).
+ *
+ * C ABI of the inference-time hot path of rotation-based W/A/KV quantization
+ * (arXiv 2504.13989): every token row is multiplied by a normalised Hadamard
+ * matrix (section 2.3.2 Eq. 1 for orders 2^k; section 2.3.3 / Appendix B
+ * Algorithm 2 for Paley orders; zero-padding of section 4.2 Eq. 2 when the row is
+ * narrower than the order) and then quantized per token with the symmetric uniform
+ * quantizer of section 2.1 under a clip ratio (section 3.1).
+ *
+ * Conventions
+ *   - Order n = p * 2^k, where 2^k is the largest power of two for which p is 1 or a
+ *     Paley order <= 256: p = q+1 with q prime, q = 3 (mod 4) (Algorithm 2), or
+ *     p = 2(q+1) with q prime, q = 1 (mod 4) (Paley II; not in the paper, standard
+ *     construction H = C (x) [[1,1],[1,-1]] + I (x) [[1,-1],[-1,-1]]).  Where both
+ *     exist for one p the first is used.  n must be a multiple of 32.
+ *   - H_n = H_p (x) H_{2^k}: flat index j = a * 2^k + c (a < p, c < 2^k),
+ *     H_n[i, j] = H_p[i / 2^k, j / 2^k] * (-1)^popcount((i % 2^k) & (j % 2^k)).
+ *   - Rotated row: y = H_n pad(x) / sqrt(n), pad() appends n - d zeros.
+ *   - Quantizer: amax = max_j |y_j|; Delta = clip * amax / (2^b - 1);
+ *     code_j = clamp(round_half_even(y_j / Delta), -2^(b-1), 2^(b-1) - 1);
+ *     amax == 0 gives Delta = 0 and all-zero codes.  Arithmetic is fp32.
+ *   - Packed codes: row r starts at byte r * n * b / 8; element j of the rotated row is
+ *     the b-bit field at bits [j*b, (j+1)*b) of the row's little-endian bit stream (stream
+ *     bit i = bit i % 8 of byte i / 8), holding the code's low b bits (two's complement).
+ *   - scales[r] = Delta of row r, so that y^_j = code_j * scales[r].
+ *
+ * All functions return RQ_OK (0) or a negative error code; none throws or aborts.
+ * Argument errors are detected on the host before any HIP call.  Data values are not
+ * validated (NaN / Inf propagate).  The hot-path calls enqueue work on the caller's
+ * stream and return without synchronising and without allocating.
+ */
+#ifndef ROTQ_H
+#define ROTQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RQ_OK             0
+#define RQ_ERR_ARG       -1   /* bad pointer, size, stride, bit-width, clip, alignment, workspace */
+#define RQ_ERR_NO_ORDER  -2   /* n has no supported factorisation p * 2^k, or n % 32 != 0 */
+#define RQ_ERR_HIP       -3   /* HIP allocation / launch failure, or the handle has no device table */
+#define RQ_ERR_NOMEM     -4   /* host allocation failure */
+
+#define RQ_BF16 0             /* X elements are bfloat16 (2 bytes) */
+#define RQ_F32  1             /* X elements are float (4 bytes) */
+
+#define RQ_KIND_SYLVESTER 0
+#define RQ_KIND_PALEY1    1
+#define RQ_KIND_PALEY2    2
+
+#define RQ_MAX_CLIPS 64
+
+typedef struct rq_hadamard rq_hadamard_t;   /* opaque; immutable after build */
+
+/*
+ * Build the rotation of order n (sections 2.3.2, 2.3.3, Appendix B Algorithm 2): factor
+ * n = p * 2^k, build the +-1 block H_p from Legendre symbols in integer arithmetic on the
+ * host, and, when a GPU is present, upload the block tables to the current device.
+ * Without a GPU the handle is host-only: the info/dense calls work, the hot-path calls
+ * return RQ_ERR_HIP.
+ *   n    [in]  rotation order, multiple of 32
+ *   out  [out] host pointer receiving the handle; owned by the caller, released with
+ *              rq_hadamard_free.  Untouched on error.
+ * Errors: RQ_ERR_ARG (out NULL, n < 32), RQ_ERR_NO_ORDER, RQ_ERR_NOMEM, RQ_ERR_HIP.
+ */
+int rq_hadamard_build(int n, rq_hadamard_t** out);
+
+/* Release a handle and its device tables (NULL is a no-op).  Work already enqueued that
+ * uses the handle must have completed. */
+void rq_hadamard_free(rq_hadamard_t* h);
+
+/*
+ * Factorisation held by a handle.  Any output pointer may be NULL.
+ *   n      order;  p  block order (1 = pure Sylvester);  kind  RQ_KIND_*;
+ *   q      the prime of the Paley construction (0 for Sylvester);  log2m  k.
+ * Errors: RQ_ERR_ARG (h NULL).
+ */
+int rq_hadamard_info(const rq_hadamard_t* h, int* n, int* p, int* kind, int* q, int* log2m);
+
+/*
+ * Test hook: the dense un-normalised matrix H_n, n*n entries of +-1, row-major, written
+ * to HOST memory host_out (caller-owned, n*n bytes).  Refused for n > 8192.
+ * Errors: RQ_ERR_ARG.
+ */
+int rq_hadamard_dense(const rq_hadamard_t* h, int8_t* host_out);
+
+/*
+ * Dimension expansion helper (section 4.2): the smallest order n >= d that
+ * rq_hadamard_build accepts with 2^k >= 32.  n_out is a host pointer.
+ * Errors: RQ_ERR_ARG (d < 1, n_out NULL), RQ_ERR_NO_ORDER (none below 2^30).
+ */
+int rq_next_order(int d, int* n_out);
+
+/*
+ * Rotate and quantize `rows` token rows (sections 2.1, 2.3, 3.1, 4.2; see Conventions).
+ *   h       [in]  handle of order n >= d, with device tables on the current device
+ *   X       [in]  DEVICE pointer, rows x d elements of `dtype`, row-major with leading
+ *                 dimension ld >= d (in elements); aligned to the element size.  A row of
+ *                 width d < n is treated as zero-padded to n.  Not modified.
+ *   bits    [in]  3 or 4
+ *   clip    [in]  clip ratio in (0, 1]
+ *   codes   [out] DEVICE pointer, rows * n * bits / 8 bytes, 4-byte aligned, caller-owned
+ *   scales  [out] DEVICE pointer, rows floats, caller-owned
+ *   stream  [in]  hipStream_t (NULL = the null stream)
+ * rows == 0 is a successful no-op (X, codes and scales may then be NULL).
+ * Errors: RQ_ERR_ARG (NULL pointer, rows < 0, d < 1, d > n, ld < d, bits not 3/4, clip not in
+ * (0,1] or NaN, misaligned pointer, unknown dtype), RQ_ERR_HIP.
+ */
+int rq_rotate_quantize(const rq_hadamard_t* h,
+                       const void* X, int dtype, int64_t rows, int d, int64_t ld,
+                       int bits, float clip,
+                       void* codes, float* scales, void* stream);
+
+/* Bytes of device workspace rq_quant_error needs for (rows, n_clips); 0 on bad arguments. */
+size_t rq_quant_error_workspace(int64_t rows, int n_clips);
+
+/*
+ * Quantization error of the rotated rows for several clip ratios in one pass (the
+ * objective a clip-ratio search evaluates repeatedly; sections 3.1, 4.1):
+ *   mse[k] = (1 / (rows * n)) * sum over rows, j of (code_j * Delta_k - y_j)^2,
+ * with y, Delta_k = clips[k] * amax / (2^b - 1) and code_j as in rq_rotate_quantize.
+ *   clips     [in]  HOST pointer, n_clips floats in (0, 1]; read before the call returns
+ *   n_clips   [in]  1 .. RQ_MAX_CLIPS
+ *   mse       [out] DEVICE pointer, n_clips floats, caller-owned
+ *   workspace [in]  DEVICE pointer, at least rq_quant_error_workspace(rows, n_clips) bytes,
+ *                   8-byte aligned, caller-owned; contents are scratch
+ * Other arguments as in rq_rotate_quantize.  rows == 0 writes zeros to mse (X may then be NULL).
+ * The result is deterministic (fixed reduction order).
+ * Errors: RQ_ERR_ARG (as above, n_clips out of range, a clip not in (0,1], workspace too small
+ * or misaligned), RQ_ERR_HIP.
+ */
+int rq_quant_error(const rq_hadamard_t* h,
+                   const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits,
+                   const float* clips, int n_clips,
+                   float* mse, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Select the kernel family for subsequent hot-path calls on this handle (testing /
+ * measurement): 0 = automatic (fastest available), 1 = the general LDS kernel.
+ * Errors: RQ_ERR_ARG.
+ */
+int rq_hadamard_set_variant(rq_hadamard_t* h, int variant);
+
+/* Name of the kernel family the last hot-path call on this handle used ("" if none). */
+const char* rq_hadamard_last_kernel(const rq_hadamard_t* h);
+
+/* Static description of an error code. */
+const char* rq_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROTQ_H */

@@ -1,0 +1,208 @@
+// General rotate-and-quantize kernels: one 256-thread workgroup per row, the row held in LDS
+// as fp32.  They cover every supported order p * 2^k that fits in LDS and both input types,
+// and serve as the fallback for shapes the specialised wave kernels do not handle.
+//
+// Per row: load + zero-pad (section 4.2, Eq. 2) -> butterflies along the 2^k axis
+// (section 2.3.2, Eq. 1) -> dense +-1 block product along the p axis (section 2.3.3) ->
+// absmax -> scale -> round/clamp/pack (section 2.1 with the clip ratio of section 3.1).
+#include "rotq_internal.h"
+
+namespace rq {
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ float load_f32(const void* X, int dtype, int64_t idx) {
+    if (dtype == RQ_BF16) {
+        uint32_t b = static_cast<const uint16_t*>(X)[idx];
+        return __uint_as_float(b << 16);
+    }
+    return static_cast<const float*>(X)[idx];
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+// Rotates one row into LDS (un-normalised: y_u = H_n pad(x)) and returns the buffer that holds
+// it; also returns the row's max |y_u| in *amax (same value in every thread).
+__device__ float* rotate_row_lds(const RowArgs& a, int64_t row, float* buf0, float* buf1,
+                                 float* red, float* amax) {
+    const int tid = threadIdx.x;
+    const int n = a.n;
+    const int64_t base = row * a.ld;
+    for (int j = tid; j < n; j += kThreads) buf0[j] = (j < a.d) ? load_f32(a.X, a.dtype, base + j) : 0.0f;
+    __syncthreads();
+    for (int s = 0; s < a.log2m; ++s) {
+        const int h = 1 << s;
+        for (int idx = tid; idx < n / 2; idx += kThreads) {
+            const int i = ((idx >> s) << (s + 1)) | (idx & (h - 1));
+            const float u = buf0[i], v = buf0[i + h];
+            buf0[i] = u + v;
+            buf0[i + h] = u - v;
+        }
+        __syncthreads();
+    }
+    float* y = buf0;
+    if (a.p > 1) {
+        const int m = 1 << a.log2m;
+        for (int o = tid; o < n; o += kThreads) {
+            const int ao = o >> a.log2m, c = o & (m - 1);
+            const int8_t* hrow = a.block + (size_t)ao * a.p;
+            double acc = 0.0;
+            for (int ai = 0; ai < a.p; ++ai) {
+                const float v = buf0[ai * m + c];
+                acc += (hrow[ai] > 0) ? (double)v : -(double)v;
+            }
+            buf1[o] = (float)acc;
+        }
+        __syncthreads();
+        y = buf1;
+    }
+    float mx = 0.0f;
+    for (int j = tid; j < n; j += kThreads) mx = fmaxf(mx, fabsf(y[j]));
+    mx = wave_max(mx);
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+    *amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    return y;
+}
+
+__global__ __launch_bounds__(kThreads) void k_generic_rotate_quantize(RowArgs a, float clip,
+                                                                      uint32_t* codes,
+                                                                      float* scales) {
+    extern __shared__ float lds[];
+    __shared__ float red[4];
+    const int64_t row = blockIdx.x;
+    float amax;
+    const float* y = rotate_row_lds(a, row, lds, lds + a.n, red, &amax);
+    const int bits = a.bits;
+    const double lvl = (double)((1 << bits) - 1);
+    const float qmax = (float)((1 << (bits - 1)) - 1), qmin = -(float)(1 << (bits - 1));
+    const float s = amax > 0.0f ? (float)(lvl / ((double)clip * (double)amax)) : 0.0f;
+    if (threadIdx.x == 0)
+        scales[row] = (float)((double)clip * (double)amax / (sqrt((double)a.n) * lvl));
+    const uint32_t mask = (1u << bits) - 1u;
+    uint32_t* out = codes + row * (int64_t)(a.n / 32 * bits);
+    for (int g = threadIdx.x; g < a.n / 32; g += kThreads) {
+        uint64_t acc = 0;
+        int nb = 0, w = 0;
+        for (int e = 0; e < 32; ++e) {
+            const float t = y[g * 32 + e] * s;
+            const int q = (int)fminf(fmaxf(rintf(t), qmin), qmax);
+            acc |= (uint64_t)((uint32_t)q & mask) << nb;
+            nb += bits;
+            if (nb >= 32) {
+                out[g * bits + w++] = (uint32_t)acc;
+                acc >>= 32;
+                nb -= 32;
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void k_generic_quant_error(RowArgs a, ClipList clips,
+                                                                  int n_clips, double* partial) {
+    extern __shared__ float lds[];
+    __shared__ float red[4];
+    __shared__ double dred[4];
+    const int64_t row = blockIdx.x;
+    float amax;
+    const float* y = rotate_row_lds(a, row, lds, lds + a.n, red, &amax);
+    const int bits = a.bits;
+    const double lvl = (double)((1 << bits) - 1);
+    const float qmax = (float)((1 << (bits - 1)) - 1), qmin = -(float)(1 << (bits - 1));
+    for (int k = 0; k < n_clips; ++k) {
+        const double dk64 = (double)clips.v[k] * (double)amax / lvl;
+        const float dk = (float)dk64;
+        const float ik = amax > 0.0f ? (float)(1.0 / dk64) : 0.0f;
+        float acc = 0.0f;
+        for (int j = threadIdx.x; j < a.n; j += kThreads) {
+            const float v = y[j];
+            const float q = fminf(fmaxf(rintf(v * ik), qmin), qmax);
+            const float e = fmaf(-q, dk, v);
+            acc = fmaf(e, e, acc);
+        }
+        double tot = wave_sum((double)acc);
+        if ((threadIdx.x & 63) == 0) dred[threadIdx.x >> 6] = tot;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            partial[row * n_clips + k] =
+                (dred[0] + dred[1] + dred[2] + dred[3]) / ((double)a.n * (double)a.n);
+        __syncthreads();
+    }
+}
+
+// partial[row][k] is the row's mean squared error in the normalised domain (un-normalised sum
+// divided by n twice); mse[k] is its mean over rows, summed in a fixed order.
+__global__ __launch_bounds__(kThreads) void k_reduce_partials(const double* partial, int64_t rows,
+                                                              int n_clips, float* mse) {
+    __shared__ double dred[4];
+    const int k = blockIdx.x;
+    double acc = 0.0;
+    for (int64_t r = threadIdx.x; r < rows; r += kThreads) acc += partial[r * n_clips + k];
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) dred[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        mse[k] = rows > 0 ? (float)((dred[0] + dred[1] + dred[2] + dred[3]) / (double)rows) : 0.0f;
+}
+
+size_t lds_bytes(const rq_hadamard* h) {
+    return (size_t)h->f.n * sizeof(float) * (h->f.p > 1 ? 2 : 1);
+}
+
+template <typename K>
+int prepare(K kernel, size_t bytes) {
+    if (bytes > 48 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return RQ_ERR_HIP;
+    }
+    return RQ_OK;
+}
+
+}  // namespace
+
+bool generic_supports(const rq_hadamard* h) { return h->device >= 0 && h->generic_ok; }
+
+// Called once when the handle is built (never on the hot path): checks that the row fits in
+// LDS and raises the kernels' dynamic-LDS limit where the default does not cover it.
+bool generic_prepare(const rq_hadamard* h) {
+    const size_t bytes = lds_bytes(h);
+    if (bytes + 256 > (size_t)h->max_lds) return false;
+    return prepare(k_generic_rotate_quantize, bytes) == RQ_OK &&
+           prepare(k_generic_quant_error, bytes) == RQ_OK;
+}
+
+int generic_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
+                            float* scales, hipStream_t s) {
+    const size_t bytes = lds_bytes(h);
+    if (a.rows > 0x7fffffffLL) return RQ_ERR_ARG;
+    hipLaunchKernelGGL(k_generic_rotate_quantize, dim3((unsigned)a.rows), dim3(kThreads), bytes, s, a,
+                       clip, codes, scales);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+int generic_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
+                        float* mse, double* partial, hipStream_t s) {
+    const size_t bytes = lds_bytes(h);
+    if (a.rows > 0x7fffffffLL) return RQ_ERR_ARG;
+    if (a.rows > 0) {
+        hipLaunchKernelGGL(k_generic_quant_error, dim3((unsigned)a.rows), dim3(kThreads), bytes, s, a,
+                           clips, n_clips, partial);
+        if (hipGetLastError() != hipSuccess) return RQ_ERR_HIP;
+    }
+    hipLaunchKernelGGL(k_reduce_partials, dim3(n_clips), dim3(kThreads), 0, s, partial, a.rows,
+                       n_clips, mse);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+}  // namespace rq

@@ -1,0 +1,178 @@
+// C ABI: argument validation, handle management and kernel dispatch.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "rotq_internal.h"
+
+namespace {
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_rows(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d, int64_t ld,
+               int bits) {
+    if (!h) return RQ_ERR_ARG;
+    if (dtype != RQ_BF16 && dtype != RQ_F32) return RQ_ERR_ARG;
+    if (rows < 0 || d < 1 || d > h->f.n || ld < d) return RQ_ERR_ARG;
+    if (bits != 3 && bits != 4) return RQ_ERR_ARG;
+    // with no rows nothing is read or written through X / codes / scales: they may be NULL
+    if (rows > 0 && (!X || !aligned(X, dtype == RQ_BF16 ? 2 : 4))) return RQ_ERR_ARG;
+    return RQ_OK;
+}
+
+bool clip_ok(float c) { return c > 0.0f && c <= 1.0f; }   // false for NaN
+
+rq::RowArgs row_args(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
+                     int64_t ld, int bits) {
+    return rq::RowArgs{X, dtype, rows, d, ld, h->f.n, h->f.p, h->f.log2m, h->d_block, bits};
+}
+
+}  // namespace
+
+extern "C" {
+
+int rq_hadamard_build(int n, rq_hadamard_t** out) {
+    if (!out || n < 32) return RQ_ERR_ARG;
+    if (n % 32 != 0) return RQ_ERR_NO_ORDER;
+    rq::Factorisation f;
+    if (!rq::factor_order(n, &f)) return RQ_ERR_NO_ORDER;
+    rq_hadamard* h = new (std::nothrow) rq_hadamard;
+    if (!h) return RQ_ERR_NOMEM;
+    h->f = f;
+    try {
+        h->block = rq::build_block(f);
+    } catch (const std::bad_alloc&) {
+        delete h;
+        return RQ_ERR_NOMEM;
+    }
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || count == 0) {
+        (void)hipGetLastError();
+        *out = h;   // host-only handle
+        return RQ_OK;
+    }
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        delete h;
+        return RQ_ERR_HIP;
+    }
+    h->max_lds = (int)prop.sharedMemPerBlock;
+    h->num_cu = prop.multiProcessorCount;
+    const size_t bytes = h->block.size();
+    if (hipMalloc((void**)&h->d_block, bytes) != hipSuccess ||
+        hipMemcpy(h->d_block, h->block.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+        if (h->d_block) (void)hipFree(h->d_block);
+        delete h;
+        return RQ_ERR_HIP;
+    }
+    h->device = dev;
+    h->generic_ok = rq::generic_prepare(h);
+    *out = h;
+    return RQ_OK;
+}
+
+void rq_hadamard_free(rq_hadamard_t* h) {
+    if (!h) return;
+    if (h->d_block) (void)hipFree(h->d_block);
+    if (h->d_tiles) (void)hipFree(h->d_tiles);
+    delete h;
+}
+
+int rq_hadamard_info(const rq_hadamard_t* h, int* n, int* p, int* kind, int* q, int* log2m) {
+    if (!h) return RQ_ERR_ARG;
+    if (n) *n = h->f.n;
+    if (p) *p = h->f.p;
+    if (kind) *kind = h->f.kind;
+    if (q) *q = h->f.q;
+    if (log2m) *log2m = h->f.log2m;
+    return RQ_OK;
+}
+
+int rq_hadamard_dense(const rq_hadamard_t* h, int8_t* host_out) {
+    if (!h || !host_out || h->f.n > 8192) return RQ_ERR_ARG;
+    const int n = h->f.n, p = h->f.p, m = 1 << h->f.log2m;
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j)
+            host_out[(size_t)i * n + j] = (int8_t)(h->block[(size_t)(i / m) * p + (j / m)] *
+                                                   rq::sylvester_entry(i % m, j % m));
+    return RQ_OK;
+}
+
+int rq_next_order(int d, int* n_out) {
+    if (d < 1 || !n_out) return RQ_ERR_ARG;
+    for (int64_t n = ((int64_t)d + 31) / 32 * 32; n <= (1 << 30); n += 32) {
+        rq::Factorisation f;
+        if (rq::factor_order((int)n, &f) && f.log2m >= 5) {
+            *n_out = (int)n;
+            return RQ_OK;
+        }
+    }
+    return RQ_ERR_NO_ORDER;
+}
+
+int rq_hadamard_set_variant(rq_hadamard_t* h, int variant) {
+    if (!h || variant < 0 || variant > 1) return RQ_ERR_ARG;
+    h->variant = variant;
+    return RQ_OK;
+}
+
+const char* rq_hadamard_last_kernel(const rq_hadamard_t* h) { return h ? h->last_kernel : ""; }
+
+int rq_rotate_quantize(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
+                       int64_t ld, int bits, float clip, void* codes, float* scales, void* stream) {
+    int rc = check_rows(h, X, dtype, rows, d, ld, bits);
+    if (rc != RQ_OK) return rc;
+    if (!clip_ok(clip)) return RQ_ERR_ARG;
+    if (rows == 0) return RQ_OK;
+    if (!codes || !scales || !aligned(codes, 4) || !aligned(scales, 4)) return RQ_ERR_ARG;
+    if (h->device < 0) return RQ_ERR_HIP;
+    rq_hadamard* hm = const_cast<rq_hadamard*>(h);
+    const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, bits);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
+    hm->last_kernel = "generic_lds";
+    return rq::generic_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
+}
+
+size_t rq_quant_error_workspace(int64_t rows, int n_clips) {
+    if (rows < 0 || n_clips < 1 || n_clips > RQ_MAX_CLIPS) return 0;
+    size_t r = rows > 0 ? (size_t)rows : 1;
+    return r * (size_t)n_clips * sizeof(double);
+}
+
+int rq_quant_error(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
+                   int64_t ld, int bits, const float* clips, int n_clips, float* mse,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_rows(h, X, dtype, rows, d, ld, bits);
+    if (rc != RQ_OK) return rc;
+    if (!clips || n_clips < 1 || n_clips > RQ_MAX_CLIPS) return RQ_ERR_ARG;
+    if (!mse || !aligned(mse, 4) || !workspace || !aligned(workspace, 8)) return RQ_ERR_ARG;
+    if (workspace_bytes < rq_quant_error_workspace(rows, n_clips)) return RQ_ERR_ARG;
+    rq::ClipList cl;
+    std::memset(&cl, 0, sizeof cl);
+    for (int k = 0; k < n_clips; ++k) {
+        if (!clip_ok(clips[k])) return RQ_ERR_ARG;
+        cl.v[k] = clips[k];
+    }
+    if (h->device < 0) return RQ_ERR_HIP;
+    rq_hadamard* hm = const_cast<rq_hadamard*>(h);
+    const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, bits);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
+    hm->last_kernel = "generic_lds";
+    return rq::generic_quant_error(h, a, cl, n_clips, mse, static_cast<double*>(workspace), s);
+}
+
+const char* rq_strerror(int code) {
+    switch (code) {
+        case RQ_OK: return "ok";
+        case RQ_ERR_ARG: return "invalid argument";
+        case RQ_ERR_NO_ORDER: return "no supported Hadamard order";
+        case RQ_ERR_HIP: return "HIP failure or handle without device tables";
+        case RQ_ERR_NOMEM: return "out of host memory";
+        default: return "unknown error";
+    }
+}
+
+}  // extern "C"

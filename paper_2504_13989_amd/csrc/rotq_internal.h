@@ -1,0 +1,50 @@
+// Internal declarations shared by the C ABI layer and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <vector>
+
+#include "../../include/rotq.h"
+#include "hadamard.h"
+
+struct rq_hadamard {
+    rq::Factorisation f;
+    std::vector<int8_t> block;       // host copy of H_p, row-major p x p
+    int device = -1;                 // device the tables live on; -1 = host-only handle
+    int8_t* d_block = nullptr;       // device copy of `block`
+    void* d_tiles = nullptr;         // device MFMA operand tiles of the block stage (bf16)
+    int max_lds = 0;                 // bytes of LDS one workgroup may use on `device`
+    int num_cu = 0;
+    bool generic_ok = false;         // the general LDS kernel can hold a row of this order
+    int variant = 0;                 // 0 auto, 1 general LDS kernel
+    const char* last_kernel = "";
+};
+
+namespace rq {
+
+struct RowArgs {
+    const void* X;
+    int dtype;
+    int64_t rows;
+    int d;
+    int64_t ld;
+    int n, p, log2m;
+    const int8_t* block;
+    int bits;
+};
+
+struct ClipList {
+    float v[RQ_MAX_CLIPS];
+};
+
+// General LDS kernels: one workgroup per row, any supported order that fits in LDS.
+// Return RQ_OK / RQ_ERR_*.
+int generic_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
+                            float* scales, hipStream_t s);
+int generic_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
+                        float* mse, double* partial, hipStream_t s);
+bool generic_supports(const rq_hadamard* h);
+bool generic_prepare(const rq_hadamard* h);
+
+}  // namespace rq

@@ -1,0 +1,79 @@
+"""Comparison of the HIP path's outputs with the oracle's, under the stated parity rule.
+
+  * packed codes are unpacked and compared element by element; a code may differ from the
+    oracle's only where the oracle's pre-round value t lies within 1e-6 of a rounding
+    boundary k + 1/2, and then by exactly one step; such differences (and the exempt set
+    itself, on inputs large enough for the fraction to mean something) must stay within
+    1e-5 of all elements;
+  * scales agree within 1e-5 relative;
+  * dequantized values agree within 1e-5 of the row's max |y| away from the exempt set.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+import rotq_oracle as oracle
+
+T_TOL = 1e-6
+FRAC_TOL = 1e-5
+REL_TOL = 1e-5
+
+
+def to_device(x_np, device="cuda"):
+    """numpy float32 or uint16 (bf16 bits) -> torch tensor on the device, same bits."""
+    import torch
+    if x_np.dtype == np.uint16:
+        return torch.from_numpy(x_np.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(x_np).to(device)
+
+
+def check_rotate_quantize(x_np, n, b, clip, codes_gpu, scales_gpu, what=""):
+    """x_np: the rows given to the GPU; codes_gpu uint8 [rows, n*b/8]; scales_gpu float32 [rows]."""
+    q, delta, t, y = oracle.rotate_quantize(x_np, n, b, clip)
+    rows = q.shape[0]
+    codes_gpu = np.asarray(codes_gpu).reshape(rows, n * b // 8)
+    scales_gpu = np.asarray(scales_gpu, dtype=np.float64).reshape(rows)
+    q_gpu = oracle.unpack_codes(codes_gpu, b, n)
+    _, qmin, qmax = oracle.quant_params(b)
+    assert q_gpu.min() >= qmin and q_gpu.max() <= qmax
+    mism = q_gpu != q
+    exempt = oracle.boundary_exempt(t, b, T_TOL)
+    bad = mism & ~exempt
+    nbad = int(bad.sum())
+    if nbad:
+        r, j = np.argwhere(bad)[0]
+        raise AssertionError(
+            f"{what}: {nbad} code mismatches away from rounding boundaries; first at row {r} col {j}: "
+            f"gpu {q_gpu[r, j]} oracle {q[r, j]} t {t[r, j]!r}")
+    if mism.any():
+        assert np.all(np.abs(q_gpu.astype(np.int32) - q.astype(np.int32))[mism] == 1)
+    total = q.size
+    allowed = max(1, int(np.ceil(FRAC_TOL * total)))
+    assert int(mism.sum()) <= allowed, f"{what}: {int(mism.sum())} boundary mismatches > {allowed}"
+    if total >= 1_000_000:
+        assert exempt.sum() <= FRAC_TOL * total, f"{what}: exempt fraction {exempt.mean():.3g}"
+    # scales
+    zero = delta == 0
+    assert np.all(scales_gpu[zero] == 0)
+    rel = np.abs(scales_gpu[~zero] - delta[~zero]) / delta[~zero]
+    assert rel.size == 0 or rel.max() <= REL_TOL, f"{what}: scale rel err {rel.max():.3g}"
+    # dequantized values
+    amax = np.abs(y).max(axis=1)
+    dq_gpu = q_gpu.astype(np.float64) * scales_gpu[:, None]
+    dq = oracle.dequantize(q, delta)
+    err = np.abs(dq_gpu - dq)
+    err[exempt] = 0
+    assert np.all(err <= REL_TOL * amax[:, None] + 0.0), f"{what}: dequantized values differ"
+    # byte-exact packing where no code differs
+    if not mism.any():
+        assert np.array_equal(codes_gpu, oracle.pack_codes(q, b)), f"{what}: packed bytes differ"
+    return {"elements": int(total), "mismatches": int(mism.sum()), "exempt": int(exempt.sum()),
+            "max_scale_rel": float(rel.max()) if rel.size else 0.0}
+
+
+def check_quant_error(x_np, n, b, clips, mse_gpu, rtol=REL_TOL, what=""):
+    want = oracle.quant_error(x_np, n, b, clips)
+    got = np.asarray(mse_gpu, dtype=np.float64)
+    rel = np.abs(got - want) / np.maximum(want, 1e-300)
+    assert np.all(rel <= rtol), f"{what}: mse rel err {rel.max():.3g} (got {got}, want {want})"
+    return float(rel.max())

@@ -1,0 +1,147 @@
+"""CPU-only: the C ABI loads, exports what the header declares, validates arguments before any
+HIP call, and its host-side Hadamard construction equals the oracle's matrices."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import rotq_oracle as oracle
+from paper_2504_13989_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    return binding.lib()
+
+
+def test_exports_every_declared_symbol(L):
+    with open(os.path.join(ROOT, "include", "rotq.h")) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(rq_[a-z_0-9]+)\s*\(", text))
+    assert {"rq_hadamard_build", "rq_rotate_quantize", "rq_quant_error"} <= names
+    for name in names:
+        assert hasattr(L, name), name
+
+
+@pytest.mark.parametrize("n", [32, 64, 96, 128, 224, 384, 448, 1184, 1536])
+def test_dense_matrix_equals_oracle(n):
+    h = binding.hadamard_build(n)
+    p, kind, q, k = oracle.factor_order(n)
+    assert (h.p, h.kind, h.q, h.log2m) == (p, kind, q, k)
+    assert np.array_equal(h.dense(), oracle.hadamard_dense(n))
+    h.close()
+
+
+def test_orders_of_the_configurations():
+    for n, want in ((4096, (1, 0, 0, 12)), (3584, (28, 2, 13, 7)), (18944, (148, 2, 73, 7)),
+                    (3072, (12, 1, 11, 8)), (256, (1, 0, 0, 8)), (128, (1, 0, 0, 7))):
+        h = binding.hadamard_build(n)
+        assert (h.p, h.kind, h.q, h.log2m) == want
+        h.close()
+
+
+def test_build_errors(L):
+    out = C.c_void_p()
+    assert L.rq_hadamard_build(4096, None) == binding.RQ_ERR_ARG
+    assert L.rq_hadamard_build(16, C.byref(out)) == binding.RQ_ERR_ARG
+    assert L.rq_hadamard_build(100, C.byref(out)) == binding.RQ_ERR_NO_ORDER      # not a multiple of 32
+    assert L.rq_hadamard_build(3008, C.byref(out)) == binding.RQ_ERR_NO_ORDER     # 94 * 32: no order
+    assert L.rq_hadamard_build(32 * 257, C.byref(out)) == binding.RQ_ERR_NO_ORDER
+    assert out.value is None
+    L.rq_hadamard_free(None)
+    assert L.rq_strerror(binding.RQ_ERR_NO_ORDER) not in (None, b"")
+
+
+def test_next_order_matches_oracle():
+    for d in (1, 31, 100, 128, 1536, 3000, 3073, 4096, 5000, 18944, 11008):
+        n = binding.next_order(d)
+        assert n == oracle.next_order(d)
+        assert n >= d and n % 32 == 0
+    assert binding.next_order(3000) == 3072
+    out = C.c_int()
+    assert binding.lib().rq_next_order(0, C.byref(out)) == binding.RQ_ERR_ARG
+    assert binding.lib().rq_next_order(5, None) == binding.RQ_ERR_ARG
+
+
+def _call_rq(L, h, X=0x1000, dtype=0, rows=4, d=128, ld=128, bits=3, clip=0.9, codes=0x2000,
+             scales=0x3000):
+    return L.rq_rotate_quantize(h, C.c_void_p(X), dtype, rows, d, ld, bits, C.c_float(clip),
+                                C.c_void_p(codes), C.c_void_p(scales), None)
+
+
+def test_rotate_quantize_argument_errors(L):
+    # fake non-null "device" pointers: every call below must be refused before any launch
+    h = binding.hadamard_build(128)
+    E = binding.RQ_ERR_ARG
+    assert _call_rq(L, None) == E
+    assert _call_rq(L, h._h, X=0) == E
+    assert _call_rq(L, h._h, codes=0) == E
+    assert _call_rq(L, h._h, scales=0) == E
+    assert _call_rq(L, h._h, dtype=7) == E
+    assert _call_rq(L, h._h, rows=-1) == E
+    assert _call_rq(L, h._h, d=0) == E
+    assert _call_rq(L, h._h, d=129, ld=129) == E
+    assert _call_rq(L, h._h, d=100, ld=99) == E
+    for bits in (0, 2, 5, 8):
+        assert _call_rq(L, h._h, bits=bits) == E
+    for clip in (0.0, -0.5, 1.5, float("nan"), float("inf")):
+        assert _call_rq(L, h._h, clip=clip) == E
+    assert _call_rq(L, h._h, X=0x1001) == E                 # bf16 needs 2-byte alignment
+    assert _call_rq(L, h._h, X=0x1002, dtype=1) == E        # float needs 4-byte alignment
+    assert _call_rq(L, h._h, codes=0x2002) == E
+    assert _call_rq(L, h._h, scales=0x3001) == E
+    assert _call_rq(L, h._h, rows=0) == binding.RQ_OK       # empty input: no-op
+    assert _call_rq(L, h._h, rows=0, X=0, codes=0, scales=0) == binding.RQ_OK
+    assert _call_rq(L, h._h, rows=0, bits=9) == E
+    h.close()
+
+
+def test_quant_error_argument_errors(L):
+    h = binding.hadamard_build(128)
+    E = binding.RQ_ERR_ARG
+    clips = (C.c_float * 3)(0.5, 0.75, 1.0)
+
+    def call(hh=h._h, X=0x1000, rows=4, d=128, ld=128, bits=3, cl=clips, k=3, mse=0x4000, ws=0x5000,
+             wsb=1 << 20):
+        return L.rq_quant_error(hh, C.c_void_p(X), 0, rows, d, ld, bits, cl, k, C.c_void_p(mse),
+                                C.c_void_p(ws), wsb, None)
+
+    assert call(hh=None) == E
+    assert call(X=0) == E
+    assert call(cl=None) == E
+    assert call(k=0) == E and call(k=65) == E
+    assert call(mse=0) == E and call(ws=0) == E
+    assert call(ws=0x5004) == E
+    assert call(wsb=8) == E
+    assert call(bits=5) == E
+    assert call(d=200, ld=200) == E
+    bad = (C.c_float * 3)(0.5, 1.25, 1.0)
+    assert call(cl=bad) == E
+    bad = (C.c_float * 3)(0.5, float("nan"), 1.0)
+    assert call(cl=bad) == E
+    assert L.rq_quant_error_workspace(-1, 3) == 0
+    assert L.rq_quant_error_workspace(4, 0) == 0
+    assert L.rq_quant_error_workspace(512, 32) >= 32 * 4
+    h.close()
+
+
+def test_info_and_variant_errors(L):
+    assert L.rq_hadamard_info(None, None, None, None, None, None) == binding.RQ_ERR_ARG
+    h = binding.hadamard_build(256)
+    assert L.rq_hadamard_info(h._h, None, None, None, None, None) == binding.RQ_OK
+    assert L.rq_hadamard_set_variant(h._h, 9) == binding.RQ_ERR_ARG
+    assert L.rq_hadamard_dense(h._h, None) == binding.RQ_ERR_ARG
+    assert h.last_kernel == ""
+    h.close()
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "librotq.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.lib()

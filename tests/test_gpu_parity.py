@@ -1,0 +1,235 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Small cases compare every element; the full-size configurations run the launch the benchmark
+times and compare either everything (when the oracle finishes in seconds) or sampled row
+blocks (rows are independent, so a sampled row is checked exactly like any other).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import parity
+import rotq_oracle as oracle
+from paper_2504_13989_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[parity] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+_handles = {}
+
+
+def handle(n):
+    if n not in _handles:
+        _handles[n] = binding.hadamard_build(n)
+    return _handles[n]
+
+
+def run_rq(torch, x_np, n, b, clip, variant=0, ld=None):
+    h = handle(n)
+    h.set_variant(variant)
+    x = parity.to_device(x_np)
+    if ld is not None:
+        buf = torch.zeros((x.shape[0], ld), dtype=x.dtype, device="cuda")
+        buf[:, : x.shape[1]] = x
+        x = buf[:, : x.shape[1]]
+    codes, scales = binding.rotate_quantize(h, x, b, clip)
+    torch.cuda.synchronize()
+    h.set_variant(0)
+    return codes.cpu().numpy(), scales.cpu().numpy(), h.last_kernel
+
+
+SMALL = [
+    # workload, rows, variants
+    ("tiny", 64), ("llama_hidden", 333), ("qwen_hidden", 333), ("ffn_expand", 333),
+    ("ffn_down", 37), ("kv_k", 1029), ("kv_v", 515), ("calib", 130),
+]
+
+
+@pytest.mark.parametrize("variant", [0, 1], ids=["auto", "general"])
+@pytest.mark.parametrize("name,rows", SMALL)
+def test_small_cases(torch, name, rows, variant):
+    w = wl.WORKLOADS[name].with_rows(rows)
+    x = wl.generate(w)
+    for b in w.bits:
+        say(f"small {name} rows={rows} n={w.n} b={b} variant={variant}")
+        codes, scales, kern = run_rq(torch, x, w.n, b, w.clip, variant)
+        st = parity.check_rotate_quantize(x, w.n, b, w.clip, codes, scales, f"{name} b={b} [{kern}]")
+        say(f"  ok kernel={kern} {st}")
+
+
+@pytest.mark.parametrize("n,d,dtype", [(256, 256, "f32"), (128, 100, "bf16"), (4096, 4000, "f32"),
+                                       (3584, 3500, "bf16"), (3072, 3000, "f32"), (1536, 1536, "bf16"),
+                                       (2048, 2048, "bf16"), (8192, 8192, "bf16"), (512, 512, "bf16"),
+                                       (640, 640, "bf16"), (64, 64, "bf16"), (32, 20, "f32")])
+@pytest.mark.parametrize("b", [3, 4])
+def test_other_orders_and_padding(torch, n, d, dtype, b):
+    rng = np.random.default_rng(n * 7 + d + b)
+    x = rng.standard_t(3.0, size=(67, d)).astype(np.float32)
+    x[:, rng.choice(d, 3, replace=False)] *= 40
+    if dtype == "bf16":
+        x = wl.f32_to_bf16_bits(x)
+    say(f"order n={n} d={d} {dtype} b={b}")
+    codes, scales, kern = run_rq(torch, x, n, b, 0.85)
+    parity.check_rotate_quantize(x, n, b, 0.85, codes, scales, f"n={n} d={d} {dtype} b={b} [{kern}]")
+
+
+def test_leading_dimension_and_row_views(torch):
+    w = wl.WORKLOADS["llama_hidden"].with_rows(70)
+    x = wl.generate(w)
+    say("ld > d")
+    codes, scales, kern = run_rq(torch, x, w.n, 4, 0.9, ld=w.d + 24)
+    parity.check_rotate_quantize(x, w.n, 4, 0.9, codes, scales, f"ld [{kern}]")
+    w = wl.WORKLOADS["ffn_expand"].with_rows(70)
+    x = wl.generate(w)
+    codes, scales, kern = run_rq(torch, x, w.n, 3, 0.9, ld=w.d + 8)
+    parity.check_rotate_quantize(x, w.n, 3, 0.9, codes, scales, f"ld [{kern}]")
+    # 4-D KV view [B, H, S, 128]
+    w = wl.WORKLOADS["kv_k"].with_rows(2 * 3 * 40)
+    x = wl.generate(w)
+    xt = parity.to_device(x).reshape(2, 3, 40, 128)
+    codes, scales = binding.rotate_quantize(handle(128), xt, 3, 0.9)
+    torch.cuda.synchronize()
+    parity.check_rotate_quantize(x, 128, 3, 0.9, codes.cpu().numpy(), scales.cpu().numpy(), "kv view")
+
+
+def test_degenerate_rows(torch):
+    # empty input, single row, all-zero rows, one-hot rows (closed form: all codes at the range ends)
+    h = handle(4096)
+    x0 = torch.empty((0, 4096), dtype=torch.bfloat16, device="cuda")
+    codes, scales = binding.rotate_quantize(h, x0, 4, 0.9)
+    assert codes.shape == (0, 2048) and scales.shape == (0,)
+    for n in (4096, 3584, 128, 256):
+        x = np.zeros((5, n), dtype=np.float32)
+        x[1, 7] = 12.0
+        x[3, n - 1] = -3.0
+        x[4, :] = 1.0
+        for dtype in ("f32", "bf16"):
+            xx = x if dtype == "f32" else wl.f32_to_bf16_bits(x)
+            for b in (3, 4):
+                say(f"degenerate n={n} {dtype} b={b}")
+                codes, scales, kern = run_rq(torch, xx, n, b, 0.9)
+                parity.check_rotate_quantize(xx, n, b, 0.9, codes, scales, f"degenerate n={n} [{kern}]")
+                assert scales[0] == 0 and not codes[0].any()
+                q = oracle.unpack_codes(codes, b, n)
+                _, qmin, qmax = oracle.quant_params(b)
+                assert set(np.unique(q[1])) <= {qmin, qmax}
+                if n in (4096, 256, 128):   # Sylvester: closed-form scale c * clip / (sqrt(n) L)
+                    want = float(np.float32(0.9)) * 12.0 / (np.sqrt(n) * ((1 << b) - 1))
+                    assert abs(scales[1] - want) <= 1e-6 * want
+        x1 = wl.generate(wl.WORKLOADS["calib"].with_rows(1)) if n == 4096 else None
+        if x1 is not None:
+            codes, scales, kern = run_rq(torch, x1, n, 4, 0.9)
+            parity.check_rotate_quantize(x1, n, 4, 0.9, codes, scales, "single row")
+
+
+def test_deterministic_and_output_bounds(torch):
+    # two runs give identical bytes; bytes after the outputs stay untouched
+    w = wl.WORKLOADS["qwen_hidden"].with_rows(257)
+    x = parity.to_device(wl.generate(w))
+    h = handle(w.n)
+    nb = w.n * 3 // 8
+    codes = torch.full((257 * nb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    scales = torch.full((257 + 16,), -7.0, dtype=torch.float32, device="cuda")
+    binding.rotate_quantize(h, x, 3, 0.9, codes=codes[: 257 * nb].view(257, nb), scales=scales[:257])
+    torch.cuda.synchronize()
+    first = codes.clone(), scales.clone()
+    binding.rotate_quantize(h, x, 3, 0.9, codes=codes[: 257 * nb].view(257, nb), scales=scales[:257])
+    torch.cuda.synchronize()
+    assert torch.equal(first[0], codes) and torch.equal(first[1], scales)
+    assert bool((codes[257 * nb:] == 0xA5).all()) and bool((scales[257:] == -7.0).all())
+
+
+# ------------------------------------------------------------------ full-size configurations
+
+@pytest.mark.parametrize("name", ["tiny", "llama_hidden", "qwen_hidden", "ffn_expand"])
+def test_full_size_all_rows(torch, name):
+    w = wl.WORKLOADS[name]
+    x = wl.generate(w)
+    for b in w.bits:
+        say(f"full {name} [{w.rows} x {w.d}] n={w.n} b={b}")
+        codes, scales, kern = run_rq(torch, x, w.n, b, w.clip)
+        st = parity.check_rotate_quantize(x, w.n, b, w.clip, codes, scales, f"{name} b={b} [{kern}]")
+        say(f"  ok kernel={kern} {st}")
+
+
+def _full_run_sampled_check(torch, name, blocks):
+    w = wl.WORKLOADS[name]
+    say(f"full {name} [{w.rows} x {w.d}] n={w.n}: generating")
+    x = wl.generate(w)
+    b = w.bits[0]
+    say(f"full {name}: launching")
+    h = handle(w.n)
+    xt = parity.to_device(x)
+    codes, scales = binding.rotate_quantize(h, xt, b, w.clip)
+    torch.cuda.synchronize()
+    rows = wl.block_row_index(blocks, w)
+    idx = torch.from_numpy(rows).to("cuda")
+    c = codes[idx].cpu().numpy()
+    s = scales[idx].cpu().numpy()
+    xs = wl.generate_blocks(w, blocks)
+    assert np.array_equal(xs, x[rows])          # block regeneration gives the same rows
+    st = parity.check_rotate_quantize(xs, w.n, b, w.clip, c, s, f"{name} sampled [{h.last_kernel}]")
+    say(f"  ok kernel={h.last_kernel} sampled_rows={len(rows)} {st}")
+
+
+def test_full_size_ffn_down_sampled(torch):
+    _full_run_sampled_check(torch, "ffn_down", [0, 6, 15])
+
+
+@pytest.mark.parametrize("name", ["kv_k", "kv_v"])
+def test_full_size_kv_sampled(torch, name):
+    nb = wl.n_blocks(wl.WORKLOADS[name])
+    _full_run_sampled_check(torch, name, [0, 1, 31, 32, nb // 2 + 5, nb - 1])
+
+
+# ------------------------------------------------------------------ quant_error
+
+@pytest.mark.parametrize("variant", [0, 1], ids=["auto", "general"])
+@pytest.mark.parametrize("name,rows,b", [("calib", 512, 3), ("calib", 77, 4), ("qwen_hidden", 50, 3),
+                                         ("ffn_expand", 50, 3), ("tiny", 64, 3), ("kv_k", 300, 3),
+                                         ("ffn_down", 9, 3)])
+def test_quant_error(torch, name, rows, b, variant):
+    w = wl.WORKLOADS[name].with_rows(rows)
+    x = wl.generate(w)
+    clips = wl.clip_grid()
+    h = handle(w.n)
+    h.set_variant(variant)
+    say(f"quant_error {name} rows={rows} n={w.n} b={b} variant={variant}")
+    mse = binding.quant_error(h, parity.to_device(x), b, clips)
+    torch.cuda.synchronize()
+    h.set_variant(0)
+    rel = parity.check_quant_error(x, w.n, b, clips, mse.cpu().numpy(), what=f"{name} [{h.last_kernel}]")
+    say(f"  ok kernel={h.last_kernel} max rel err {rel:.2e}")
+
+
+def test_quant_error_consistent_with_rotate_quantize(torch):
+    # the two entry points agree: mse[k] equals the error of dequantized rotate_quantize output
+    w = wl.WORKLOADS["calib"].with_rows(64)
+    x = wl.generate(w)
+    xt = parity.to_device(x)
+    h = handle(w.n)
+    clips = np.array([0.6, 0.6, 0.95], dtype=np.float32)
+    mse = binding.quant_error(h, xt, 3, clips).cpu().numpy()
+    assert mse[0] == mse[1]
+    y = oracle.rotate(x, w.n)
+    for k in (0, 2):
+        codes, scales = binding.rotate_quantize(h, xt, 3, float(clips[k]))
+        q = oracle.unpack_codes(codes.cpu().numpy(), 3, w.n)
+        err = np.mean((q * scales.cpu().numpy().astype(np.float64)[:, None] - y) ** 2)
+        assert abs(err - mse[k]) <= 1e-5 * err
+    # empty input -> zeros
+    x0 = torch.empty((0, 4096), dtype=torch.bfloat16, device="cuda")
+    assert not binding.quant_error(h, x0, 3, clips).cpu().numpy().any()
