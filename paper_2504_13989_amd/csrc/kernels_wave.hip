@@ -1,0 +1,266 @@
+// Wave-per-row rotate-and-quantize kernels for bf16 rows and Sylvester orders 128 .. 8192.
+//
+// One 64-lane wave owns a row (or 16 >> CB short rows).  Per row (paper sections in brackets):
+//   1. coalesced 16-byte loads, zero beyond d                         [4.2, Eq. 2]
+//   2. five butterfly stages at once as a +-1 32x32 product on the matrix cores, straight
+//      from the bf16 registers (exact products, fp32 accumulation)   [2.3.2, Eq. 1]
+//   3. the remaining stages on the vector ALU: across registers, then across lanes with
+//      DPP row permutations                                           [2.3.2, Eq. 1]
+//   4. absmax (wave reduction), scale, round/clamp, bit-pack, store   [2.1, 3.1]
+//
+// Index layout.  An element index j of the row splits into
+//   [ t | g | c | i ]   i: 3 bits inside a 16-byte chunk, c: CB bits (lane, within a 16-lane DPP
+//                       row), g: 2 bits (which DPP row), t: log2(T) bits (which load)
+// The matrix-core product transforms the (g, i) bits, register butterflies the t bits, DPP
+// butterflies the c bits.  The transform is in place: an output index has the same layout, so
+// a lane ends up holding 8 consecutive codes per load - whole dwords for b = 4, 3 bytes for
+// b = 3 (merged into dwords inside each quad of lanes).
+//
+// DPP stages use xor-1, xor-2 (quad_perm), half-row mirror (xor-7) and a rotation by 8 (xor-8),
+// each one instruction.  With the mirror, a lane's logical column index is its lane number
+// with the two low bits complemented when bit 2 is set.  A cross-lane stage computes
+// self + sign * partner; on "upper" lanes that is the negated butterfly output, and the
+// negations commute with the later stages, so they are undone once, in the sign of the
+// per-lane quantization multiplier.
+#include "rotq_internal.h"
+
+namespace rq {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kDppXor1 = 0xB1;         // quad_perm:[1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm:[2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // row_half_mirror: lane i <-> 7 - i
+constexpr int kDppRor8 = 0x128;        // row_ror:8: lane i <-> i ^ 8
+constexpr int kDppNext = 0xF9;         // quad_perm:[1,2,3,3]: value of the next lane of the quad
+constexpr int kDppPrev = 0x90;         // quad_perm:[0,0,1,2]: value of the previous lane
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+
+// One cross-lane butterfly stage in place: self + sign * partner.
+template <int CTRL>
+__device__ __forceinline__ void lane_stage(f32x4& v, float sign) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = fmaf(dpp_f<CTRL>(v[i]), sign, v[i]);
+}
+
+__device__ __forceinline__ u32x4 load_chunk(const uint16_t* row, int e0, int d) {
+    if (e0 + 8 <= d) return *reinterpret_cast<const u32x4*>(row + e0);
+    u32x4 r = {0u, 0u, 0u, 0u};
+    if (e0 < d) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t v = (e0 + i < d) ? row[e0 + i] : 0u;
+            r[i >> 1] |= v << ((i & 1) * 16);
+        }
+    }
+    return r;
+}
+
+struct WaveArgs {
+    const uint16_t* X;
+    int64_t rows;
+    int d;
+    int64_t ld;
+    const u32x4* tiles;   // matrix-core operand of the 32x32 +-1 block: [2][64] x 16 bytes
+    uint32_t* codes;
+    float* scales;
+    double c1;            // (2^b - 1) / clip
+    double c2;            // clip / (sqrt(n) (2^b - 1))
+};
+
+// T loads per row (n = 512 T when CB = 4); CB column bits per DPP row (n = 32 << CB when T = 1).
+template <int T, int CB, int BITS>
+__global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
+    static_assert(CB >= 2 && CB <= 4 && (T == 1 || CB == 4), "unsupported shape");
+    constexpr int RPW = 16 >> CB;                      // rows per wave iteration
+    constexpr int N = (T > 1) ? 512 * T : (32 << CB);
+    constexpr int ROW_DWORDS = N * BITS / 32;
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, nnl = lane & 15;
+    const int cphys = nnl & ((1 << CB) - 1);
+    const int rsub = nnl >> CB;
+    const bool mirrored = (CB >= 3) && (cphys & 4);
+    const int c = mirrored ? (cphys ^ 3) : cphys;       // logical column index
+    const int chunk = (g << CB) + c;                    // 16-byte chunk inside a load segment
+
+    const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
+    float sg[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) sg[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
+    const float flip = (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;
+
+    constexpr float kMagic = 12582912.0f;               // 1.5 * 2^23: integer lattice of fp32
+    constexpr float kLo = kMagic, kHi = kMagic + (float)((1 << BITS) - 1);
+    constexpr float kBias = kMagic + (float)(1 << (BITS - 1));
+    constexpr uint32_t kMagicBits = 0x4B400000u;
+    uint32_t csum = 0, msb = 0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        csum += kMagicBits << (BITS * r);
+        msb |= 1u << (BITS * r + BITS - 1);
+    }
+
+    const int64_t n_groups = (a.rows + RPW - 1) / RPW;
+    for (int64_t grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
+        const int64_t row = grp * RPW + rsub;
+        const bool live = row < a.rows;
+        const uint16_t* xr = a.X + (live ? row : 0) * a.ld;
+        const int dd = live ? a.d : 0;
+
+        f32x4 acc[T][2];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const u32x4 raw = load_chunk(xr, (t * 64 + chunk) * 8, dd);
+            const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
+            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), bm, z, 0, 0, 0);
+        }
+        // register stages over the t bits
+#pragma unroll
+        for (int s = 1; s < T; s <<= 1)
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+                if (!(t & s))
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const f32x4 u = acc[t][h], v = acc[t | s][h];
+                        acc[t][h] = u + v;
+                        acc[t | s][h] = u - v;
+                    }
+        // lane stages over the c bits, and the running absmax
+        float m = 0.0f;
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                f32x4 v = acc[t][h];
+                lane_stage<kDppXor1>(v, sg[0]);
+                lane_stage<kDppXor2>(v, sg[1]);
+                if (CB >= 3) lane_stage<kDppHalfMirror>(v, sg[2]);
+                if (CB >= 4) lane_stage<kDppRor8>(v, sg[3]);
+                acc[t][h] = v;
+                m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(v[0]), __builtin_fabsf(v[1])));
+                m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(v[2]), __builtin_fabsf(v[3])));
+            }
+        // absmax over the lanes that share the row
+        m = fmaxf(m, dpp_f<kDppXor1>(m));
+        m = fmaxf(m, dpp_f<kDppXor2>(m));
+        if (CB >= 3) m = fmaxf(m, dpp_f<kDppHalfMirror>(m));
+        if (CB >= 4) m = fmaxf(m, dpp_f<kDppRor8>(m));
+        m = fmaxf(m, __shfl_xor(m, 16, 64));
+        m = fmaxf(m, __shfl_xor(m, 32, 64));
+
+        float s, scale;
+        if (T > 1) {
+            s = m > 0.0f ? (float)(a.c1 / (double)m) : 0.0f;
+            scale = (float)(a.c2 * (double)m);
+        } else {
+            // short rows: fp32 division plus a first-order correction for the rounding of c1
+            const float c1h = (float)a.c1, c1l = (float)(a.c1 - (double)c1h);
+            s = m > 0.0f ? fmaf(c1l, __builtin_amdgcn_rcpf(m), c1h / m) : 0.0f;
+            const float c2h = (float)a.c2, c2l = (float)(a.c2 - (double)c2h);
+            scale = fmaf(m, c2l, m * c2h);
+        }
+        const float sl = s * flip;
+
+        uint32_t* out = a.codes + (live ? row : 0) * (int64_t)ROW_DWORDS;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int r = 7; r >= 0; --r) {
+                float u = fmaf(acc[t][r >> 2][r & 3], sl, kBias);
+                u = __builtin_amdgcn_fmed3f(u, kLo, kHi);
+                w = (w << BITS) + __builtin_bit_cast(uint32_t, u);
+            }
+            w = (w - csum) ^ msb;
+            const int word = t * 64 + chunk;            // 8-element group index inside the row
+            if (BITS == 4) {
+                if (live) out[word] = w;
+            } else {
+                // three bytes per lane: four lanes of a quad make three dwords
+                uint32_t nxt = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppNext, 0xf, 0x5, true);
+                if (CB >= 3)
+                    nxt = (uint32_t)__builtin_amdgcn_update_dpp((int)nxt, (int)w, kDppPrev, 0xf, 0xa, false);
+                const int qpos = c & 3;
+                const uint32_t dw = (w >> (8 * qpos)) | (nxt << (24 - 8 * qpos));
+                if (live && qpos < 3) out[(word >> 2) * 3 + qpos] = dw;
+            }
+        }
+        if (live && g == 0 && c == 0) a.scales[row] = scale;
+    }
+}
+
+template <int T, int CB>
+int launch(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
+    constexpr int RPW = 16 >> CB;
+    const int64_t groups = (a.rows + RPW - 1) / RPW;
+    const int64_t cap = (int64_t)h->num_cu * 4 * 8 * 4;    // a few waves per SIMD slot
+    const unsigned grid = (unsigned)(groups < cap ? groups : cap);
+    if (bits == 4)
+        hipLaunchKernelGGL((k_wave_sylvester<T, CB, 4>), dim3(grid), dim3(64), 0, s, a);
+    else
+        hipLaunchKernelGGL((k_wave_sylvester<T, CB, 3>), dim3(grid), dim3(64), 0, s, a);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+}  // namespace
+
+// The +-1 32x32 block as matrix-core operands.  Operand lane (gA, mm) holds row mm of one
+// 16-row half for the 8 contraction slots (gA, i).  Row mm = 4 go + io of half hh produces the
+// output whose transformed bits are (go, 4 hh + io); the entry is the Sylvester sign between
+// that output index and the input slot (gA, i).
+std::vector<uint32_t> wave_sylvester_tiles() {
+    std::vector<uint32_t> t(2 * 64 * 4, 0u);
+    for (int hh = 0; hh < 2; ++hh)
+        for (int lane = 0; lane < 64; ++lane) {
+            const int gA = lane >> 4, mm = lane & 15, go = mm >> 2, io = mm & 3;
+            const int low3 = 4 * hh + io;
+            for (int i = 0; i < 8; ++i) {
+                const int par = (__builtin_popcount(low3 & i) + __builtin_popcount(go & gA)) & 1;
+                const uint32_t v = par ? 0xBF80u : 0x3F80u;   // bf16 -1 / +1
+                t[(hh * 64 + lane) * 4 + (i >> 1)] |= v << ((i & 1) * 16);
+            }
+        }
+    return t;
+}
+
+bool wave_supports(const rq_hadamard* h, const RowArgs& a) {
+    if (h->device < 0 || !h->d_tiles || a.dtype != RQ_BF16 || a.p != 1) return false;
+    if (a.log2m < 7 || a.log2m > 13) return false;
+    if ((reinterpret_cast<uintptr_t>(a.X) & 15) != 0 || (a.ld & 7) != 0) return false;
+    return true;
+}
+
+int wave_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
+                         float* scales, hipStream_t s) {
+    const double lvl = (double)((1 << a.bits) - 1);
+    WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
+               static_cast<const u32x4*>(h->d_tiles), codes, scales,
+               lvl / (double)clip, (double)clip / (std::sqrt((double)a.n) * lvl)};
+    switch (a.log2m) {
+        case 7: return launch<1, 2>(h, w, a.bits, s);
+        case 8: return launch<1, 3>(h, w, a.bits, s);
+        case 9: return launch<1, 4>(h, w, a.bits, s);
+        case 10: return launch<2, 4>(h, w, a.bits, s);
+        case 11: return launch<4, 4>(h, w, a.bits, s);
+        case 12: return launch<8, 4>(h, w, a.bits, s);
+        case 13: return launch<16, 4>(h, w, a.bits, s);
+        default: return RQ_ERR_NO_ORDER;
+    }
+}
+
+}  // namespace rq

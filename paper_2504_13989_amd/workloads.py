@@ -96,7 +96,7 @@ def _structure(w: Workload):
     if w.recipe in ("normal_outlier", "student_t") and w.n_outlier_ch:
         ch = np.sort(rng.choice(w.d, w.n_outlier_ch, replace=False))
     if w.n_massive_rows:
-        rows = np.sort(rng.choice(w.rows, w.n_massive_rows, replace=False))
+        rows = np.sort(rng.choice(w.rows, min(w.n_massive_rows, w.rows), replace=False))
     if w.recipe == "kv_k":
         # outlier channels differ per (batch, head)
         n_heads = max(1, w.rows // w.head_rows)
