@@ -9,12 +9,14 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "librotq.so")
 
-SOURCES = ["hadamard.cpp", "rotq_api.cpp", "kernels_generic.hip"]
+SOURCES = ["hadamard.cpp", "rotq_api.cpp", "kernels_generic.hip", "kernels_wave.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
     # packed-fp32 VALU forms are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # matrix-core results go straight to VGPRs (no AGPR copies in the wave kernels)
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-attributes",
 ]
 

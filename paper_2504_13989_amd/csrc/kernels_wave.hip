@@ -17,11 +17,8 @@
 // b = 3 (merged into dwords inside each quad of lanes).
 //
 // DPP stages use xor-1, xor-2 (quad_perm), half-row mirror (xor-7) and a rotation by 8 (xor-8),
-// each one instruction.  With the mirror, a lane's logical column index is its lane number
-// with the two low bits complemented when bit 2 is set.  A cross-lane stage computes
-// self + sign * partner; on "upper" lanes that is the negated butterfly output, and the
-// negations commute with the later stages, so they are undone once, in the sign of the
-// per-lane quantization multiplier.
+// each a single DPP-modified add.  With the mirror, a lane's logical column index is its lane
+// number with the two low bits complemented when bit 2 is set.
 #include "rotq_internal.h"
 
 namespace rq {
@@ -48,23 +45,24 @@ __device__ __forceinline__ uint32_t dpp_u(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
 }
 
-// One cross-lane butterfly stage in place: self + sign * partner.
+// One cross-lane butterfly stage in place: partner + (upper lane ? -self : self), i.e. a + b on
+// the lower lane of a pair and a - b on the upper one (one sign flip plus one DPP add).
 template <int CTRL>
-__device__ __forceinline__ void lane_stage(f32x4& v, float sign) {
+__device__ __forceinline__ void lane_stage(f32x4& v, uint32_t signbit) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = fmaf(dpp_f<CTRL>(v[i]), sign, v[i]);
+    for (int i = 0; i < 4; ++i) {
+        const float x = v[i];   // scalar copy: bit-casting a vector element in place is not reliable
+        const float self = __uint_as_float(__float_as_uint(x) ^ signbit);
+        v[i] = dpp_f<CTRL>(x) + self;
+    }
 }
 
+// 16-byte chunk starting at element e0 of a row whose width d is a multiple of 8: whole chunks
+// only, zero beyond d.
 __device__ __forceinline__ u32x4 load_chunk(const uint16_t* row, int e0, int d) {
-    if (e0 + 8 <= d) return *reinterpret_cast<const u32x4*>(row + e0);
-    u32x4 r = {0u, 0u, 0u, 0u};
-    if (e0 < d) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t v = (e0 + i < d) ? row[e0 + i] : 0u;
-            r[i >> 1] |= v << ((i & 1) * 16);
-        }
-    }
+    const bool in = e0 < d;
+    u32x4 r = *reinterpret_cast<const u32x4*>(row + (in ? e0 : 0));
+    if (!in) r = u32x4{0u, 0u, 0u, 0u};
     return r;
 }
 
@@ -96,10 +94,9 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
     const int chunk = (g << CB) + c;                    // 16-byte chunk inside a load segment
 
     const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
-    float sg[4];
+    uint32_t sg[4];
 #pragma unroll
-    for (int b = 0; b < 4; ++b) sg[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
-    const float flip = (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;
+    for (int b = 0; b < 4; ++b) sg[b] = ((c >> b) & 1) ? 0x80000000u : 0u;
 
     constexpr float kMagic = 12582912.0f;               // 1.5 * 2^23: integer lattice of fp32
     constexpr float kLo = kMagic, kHi = kMagic + (float)((1 << BITS) - 1);
@@ -117,7 +114,7 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
         const int64_t row = grp * RPW + rsub;
         const bool live = row < a.rows;
         const uint16_t* xr = a.X + (live ? row : 0) * a.ld;
-        const int dd = live ? a.d : 0;
+        const int dd = live ? a.d : 0;   // rows past the end read as zeros and store nothing
 
         f32x4 acc[T][2];
 #pragma unroll
@@ -174,7 +171,6 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
             const float c2h = (float)a.c2, c2l = (float)(a.c2 - (double)c2h);
             scale = fmaf(m, c2l, m * c2h);
         }
-        const float sl = s * flip;
 
         uint32_t* out = a.codes + (live ? row : 0) * (int64_t)ROW_DWORDS;
 #pragma unroll
@@ -182,7 +178,7 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
             uint32_t w = 0;
 #pragma unroll
             for (int r = 7; r >= 0; --r) {
-                float u = fmaf(acc[t][r >> 2][r & 3], sl, kBias);
+                float u = fmaf(acc[t][r >> 2][r & 3], s, kBias);
                 u = __builtin_amdgcn_fmed3f(u, kLo, kHi);
                 w = (w << BITS) + __builtin_bit_cast(uint32_t, u);
             }
@@ -192,15 +188,136 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
                 if (live) out[word] = w;
             } else {
                 // three bytes per lane: four lanes of a quad make three dwords
-                uint32_t nxt = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppNext, 0xf, 0x5, true);
-                if (CB >= 3)
+                // the lane holding the next 8 columns: lane + 1, or lane - 1 in mirrored quads
+                uint32_t nxt;
+                if constexpr (CB >= 3) {
+                    nxt = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppNext, 0xf, 0x5, true);
                     nxt = (uint32_t)__builtin_amdgcn_update_dpp((int)nxt, (int)w, kDppPrev, 0xf, 0xa, false);
+                } else {
+                    nxt = dpp_u<kDppNext>(w);
+                }
                 const int qpos = c & 3;
                 const uint32_t dw = (w >> (8 * qpos)) | (nxt << (24 - 8 * qpos));
                 if (live && qpos < 3) out[(word >> 2) * 3 + qpos] = dw;
             }
         }
         if (live && g == 0 && c == 0) a.scales[row] = scale;
+    }
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Block kernel: n = PB * 128 with a +-1 block of order PB <= 32 along the strided axis
+// (H_n = B (x) H_128, B = H_p (x) H_{2^(k-7)}; sections 2.3.2, 2.3.3).  Index layout [ a | c | i ]:
+// a = block row (stride 128 elements), c = 4 lane bits, i = 3 bits inside a 16-byte chunk.
+// Lane (g, c) loads the chunks of block rows a = 8 g + t, t = 0..7.  The matrix cores contract
+// over a, so the eight values a lane holds for one column are first gathered from the eight
+// loads into one operand (a 16-bit transpose inside the lane, v_perm_b32).  Outputs come back
+// with 8 block rows x 8 consecutive columns per lane; butterflies over i (registers) and c
+// (DPP), quantization and packing then work exactly as in the Sylvester kernel.
+template <int BITS>
+__global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
+    constexpr int ROW_DWORDS_PER_A = 128 * BITS / 32;
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, cphys = lane & 15;
+    const int c = (cphys & 4) ? (cphys ^ 3) : cphys;     // logical column chunk
+    const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
+    uint32_t sg[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) sg[b] = ((c >> b) & 1) ? 0x80000000u : 0u;
+
+    constexpr float kMagic = 12582912.0f;
+    constexpr float kLo = kMagic, kHi = kMagic + (float)((1 << BITS) - 1);
+    constexpr float kBias = kMagic + (float)(1 << (BITS - 1));
+    constexpr uint32_t kMagicBits = 0x4B400000u;
+    uint32_t csum = 0, msb = 0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        csum += kMagicBits << (BITS * r);
+        msb |= 1u << (BITS * r + BITS - 1);
+    }
+
+    for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
+        const uint16_t* xr = a.X + row * a.ld;
+        u32x4 R[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int ar = 8 * g + t;
+            R[t] = load_chunk(xr, ar * 128 + c * 8, ar < pb ? a.d : 0);
+        }
+        f32x4 acc[8][2];                                  // [column i][half]: 4 block rows each
+#pragma unroll
+        for (int ic = 0; ic < 8; ++ic) {
+            u32x4 bm;
+            const uint32_t sel = (ic & 1) ? 0x07060302u : 0x05040100u;
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                bm[w] = __builtin_amdgcn_perm(R[2 * w + 1][ic >> 1], R[2 * w][ic >> 1], sel);
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            const bf16x8 b8 = __builtin_bit_cast(bf16x8, bm);
+            acc[ic][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), b8, z, 0, 0, 0);
+            acc[ic][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), b8, z, 0, 0, 0);
+        }
+#pragma unroll
+        for (int s = 1; s < 8; s <<= 1)
+#pragma unroll
+            for (int ic = 0; ic < 8; ++ic)
+                if (!(ic & s))
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const f32x4 u = acc[ic][h], v = acc[ic | s][h];
+                        acc[ic][h] = u + v;
+                        acc[ic | s][h] = u - v;
+                    }
+        float m = 0.0f;
+#pragma unroll
+        for (int ic = 0; ic < 8; ++ic)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                f32x4 v = acc[ic][h];
+                lane_stage<kDppXor1>(v, sg[0]);
+                lane_stage<kDppXor2>(v, sg[1]);
+                lane_stage<kDppHalfMirror>(v, sg[2]);
+                lane_stage<kDppRor8>(v, sg[3]);
+                acc[ic][h] = v;
+                m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(v[0]), __builtin_fabsf(v[1])));
+                m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(v[2]), __builtin_fabsf(v[3])));
+            }
+        m = fmaxf(m, dpp_f<kDppXor1>(m));
+        m = fmaxf(m, dpp_f<kDppXor2>(m));
+        m = fmaxf(m, dpp_f<kDppHalfMirror>(m));
+        m = fmaxf(m, dpp_f<kDppRor8>(m));
+        m = fmaxf(m, __shfl_xor(m, 16, 64));
+        m = fmaxf(m, __shfl_xor(m, 32, 64));
+        const float s = m > 0.0f ? (float)(a.c1 / (double)m) : 0.0f;
+        const float scale = (float)(a.c2 * (double)m);
+
+        uint32_t* out = a.codes + row * (int64_t)(ROW_DWORDS_PER_A * pb);
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int ip = 0; ip < 4; ++ip) {
+                const int ao = 16 * h + 4 * ip + g;        // output block row of this register
+                uint32_t w = 0;
+#pragma unroll
+                for (int r = 7; r >= 0; --r) {
+                    float u = fmaf(acc[r][h][ip], s, kBias);
+                    u = __builtin_amdgcn_fmed3f(u, kLo, kHi);
+                    w = (w << BITS) + __builtin_bit_cast(uint32_t, u);
+                }
+                w = (w - csum) ^ msb;
+                const int word = ao * 16 + c;
+                if (BITS == 4) {
+                    if (ao < pb) out[word] = w;
+                } else {
+                    uint32_t nxt = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppNext, 0xf, 0x5, true);
+                    nxt = (uint32_t)__builtin_amdgcn_update_dpp((int)nxt, (int)w, kDppPrev, 0xf, 0xa, false);
+                    const int qpos = c & 3;
+                    const uint32_t dw = (w >> (8 * qpos)) | (nxt << (24 - 8 * qpos));
+                    if (ao < pb && qpos < 3) out[(word >> 2) * 3 + qpos] = dw;
+                }
+            }
+        if (lane == 0) a.scales[row] = scale;
     }
 }
 
@@ -238,10 +355,52 @@ std::vector<uint32_t> wave_sylvester_tiles() {
     return t;
 }
 
+// Matrix-core operand of a 32x32 zero-padded +-1 block `bm` (row-major, order pb) for the block
+// kernel: operand lane (gA, mm) holds, for half hh, row 16 hh + 4 (mm & 3) + (mm >> 2) of the
+// block at the 8 contraction slots a = 8 gA + t.
+std::vector<uint32_t> wave_block_tiles(const std::vector<int8_t>& bm, int pb) {
+    std::vector<uint32_t> t(2 * 64 * 4, 0u);
+    for (int hh = 0; hh < 2; ++hh)
+        for (int lane = 0; lane < 64; ++lane) {
+            const int gA = lane >> 4, mm = lane & 15;
+            const int ao = 16 * hh + 4 * (mm & 3) + (mm >> 2);
+            for (int i = 0; i < 8; ++i) {
+                const int ai = 8 * gA + i;
+                uint32_t v = 0;
+                if (ao < pb && ai < pb) v = bm[(size_t)ao * pb + ai] > 0 ? 0x3F80u : 0xBF80u;
+                t[(hh * 64 + lane) * 4 + (i >> 1)] |= v << ((i & 1) * 16);
+            }
+        }
+    return t;
+}
+
+bool wave_block_supports(const rq_hadamard* h, const RowArgs& a) {
+    if (h->device < 0 || !h->d_tiles || a.dtype != RQ_BF16 || a.p == 1) return false;
+    if (a.log2m < 7 || (a.p << (a.log2m - 7)) > 32) return false;
+    if ((reinterpret_cast<uintptr_t>(a.X) & 15) != 0 || (a.ld & 7) != 0 || (a.d & 7) != 0) return false;
+    return true;
+}
+
+int wave_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
+                               float* scales, hipStream_t s) {
+    const double lvl = (double)((1 << a.bits) - 1);
+    WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
+               static_cast<const u32x4*>(h->d_tiles), codes, scales,
+               lvl / (double)clip, (double)clip / (std::sqrt((double)a.n) * lvl)};
+    const int pb = a.p << (a.log2m - 7);
+    const int64_t cap = (int64_t)h->num_cu * 4 * 8 * 4;
+    const unsigned grid = (unsigned)(a.rows < cap ? a.rows : cap);
+    if (a.bits == 4)
+        hipLaunchKernelGGL((k_wave_block<4>), dim3(grid), dim3(64), 0, s, w, pb);
+    else
+        hipLaunchKernelGGL((k_wave_block<3>), dim3(grid), dim3(64), 0, s, w, pb);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
 bool wave_supports(const rq_hadamard* h, const RowArgs& a) {
     if (h->device < 0 || !h->d_tiles || a.dtype != RQ_BF16 || a.p != 1) return false;
     if (a.log2m < 7 || a.log2m > 13) return false;
-    if ((reinterpret_cast<uintptr_t>(a.X) & 15) != 0 || (a.ld & 7) != 0) return false;
+    if ((reinterpret_cast<uintptr_t>(a.X) & 15) != 0 || (a.ld & 7) != 0 || (a.d & 7) != 0) return false;
     return true;
 }
 

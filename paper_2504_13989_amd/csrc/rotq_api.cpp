@@ -66,6 +66,29 @@ int rq_hadamard_build(int n, rq_hadamard_t** out) {
         delete h;
         return RQ_ERR_HIP;
     }
+    const bool sylv = f.p == 1 && f.log2m >= 7 && f.log2m <= 13;
+    const bool blk = f.p > 1 && f.log2m >= 7 && (f.p << (f.log2m - 7)) <= 32;
+    if (sylv || blk) {
+        std::vector<uint32_t> tiles;
+        if (sylv) {
+            tiles = rq::wave_sylvester_tiles();
+        } else {
+            // block of the strided axis: H_p (x) H_{2^(k-7)}, index a * 2^(k-7) + (high bits of c)
+            const int e = 1 << (f.log2m - 7), pb = f.p * e;
+            std::vector<int8_t> bm((size_t)pb * pb);
+            for (int i = 0; i < pb; ++i)
+                for (int j = 0; j < pb; ++j)
+                    bm[(size_t)i * pb + j] = (int8_t)(h->block[(size_t)(i / e) * f.p + j / e] *
+                                                      rq::sylvester_entry(i % e, j % e));
+            tiles = rq::wave_block_tiles(bm, pb);
+        }
+        const size_t tb = tiles.size() * sizeof(uint32_t);
+        if (hipMalloc(&h->d_tiles, tb) != hipSuccess ||
+            hipMemcpy(h->d_tiles, tiles.data(), tb, hipMemcpyHostToDevice) != hipSuccess) {
+            rq_hadamard_free(h);
+            return RQ_ERR_HIP;
+        }
+    }
     h->device = dev;
     h->generic_ok = rq::generic_prepare(h);
     *out = h;
@@ -130,6 +153,14 @@ int rq_rotate_quantize(const rq_hadamard_t* h, const void* X, int dtype, int64_t
     rq_hadamard* hm = const_cast<rq_hadamard*>(h);
     const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, bits);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (h->variant == 0 && rq::wave_supports(h, a)) {
+        hm->last_kernel = "wave_sylvester";
+        return rq::wave_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
+    }
+    if (h->variant == 0 && rq::wave_block_supports(h, a)) {
+        hm->last_kernel = "wave_block";
+        return rq::wave_block_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
+    }
     if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
     hm->last_kernel = "generic_lds";
     return rq::generic_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);

@@ -47,4 +47,16 @@ int generic_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& 
 bool generic_supports(const rq_hadamard* h);
 bool generic_prepare(const rq_hadamard* h);
 
+// Wave-per-row kernels (bf16 rows, Sylvester orders 128 .. 8192, 16-byte aligned rows).
+std::vector<uint32_t> wave_sylvester_tiles();
+bool wave_supports(const rq_hadamard* h, const RowArgs& a);
+int wave_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
+                         float* scales, hipStream_t s);
+// Block kernel: bf16 rows, n = pb * 128 with a +-1 block of order pb <= 32 (Paley (x) small
+// Sylvester) on the matrix cores.
+std::vector<uint32_t> wave_block_tiles(const std::vector<int8_t>& bm, int pb);
+bool wave_block_supports(const rq_hadamard* h, const RowArgs& a);
+int wave_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
+                               float* scales, hipStream_t s);
+
 }  // namespace rq
