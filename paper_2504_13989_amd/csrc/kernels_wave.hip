@@ -57,6 +57,43 @@ __device__ __forceinline__ void lane_stage(f32x4& v, uint32_t signbit) {
     }
 }
 
+// The four cross-lane stages (xor-1, xor-2, half mirror, xor-8) on four independent values, one
+// v_fmac_f32 with a DPP-permuted operand per value and stage: x <- x + sign * partner(x), sign
+// = -1 on the upper lane of a pair.  The upper lane thus receives b - a instead of a - b; these
+// negations commute with all later stages and are undone once, in the sign of the lane's
+// quantization multiplier.  (The compiler does not fold a DPP operand into an fma, hence the
+// assembly.)  A DPP read needs two wait states after the VALU write of its source: the leading
+// s_nop covers the producer of the inputs, and inside the block three instructions separate a
+// value's consecutive stages.
+__device__ __forceinline__ void lane_stages_fused(f32x4& v, float s0, float s1, float s2, float s3) {
+    float x0 = v[0], x1 = v[1], x2 = v[2], x3 = v[3];
+    asm("s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %0, %4 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %4 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %4 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %4 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %0, %5 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %5 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %5 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %5 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %0, %6 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %6 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %6 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %6 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %0, %7 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %7 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %7 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %7 row_ror:8 row_mask:0xf bank_mask:0xf"
+        : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3)
+        : "v"(s0), "v"(s1), "v"(s2), "v"(s3));
+    v[0] = x0; v[1] = x1; v[2] = x2; v[3] = x3;
+}
+
+__device__ __forceinline__ float absmax4(float m, const f32x4& v) {
+    m = __builtin_fmaxf(__builtin_fmaxf(m, __builtin_fabsf(v[0])), __builtin_fabsf(v[1]));
+    return __builtin_fmaxf(__builtin_fmaxf(m, __builtin_fabsf(v[2])), __builtin_fabsf(v[3]));
+}
+
 // 16-byte chunk starting at element e0 of a row whose width d is a multiple of 8: whole chunks
 // only, zero beyond d.
 __device__ __forceinline__ u32x4 load_chunk(const uint16_t* row, int e0, int d) {
@@ -94,9 +131,15 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
     const int chunk = (g << CB) + c;                    // 16-byte chunk inside a load segment
 
     const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
+    constexpr bool kFused = (T >= 2);                   // inputs of the fused stages come from VALU ops
     uint32_t sg[4];
+    float sf[4];
 #pragma unroll
-    for (int b = 0; b < 4; ++b) sg[b] = ((c >> b) & 1) ? 0x80000000u : 0u;
+    for (int b = 0; b < 4; ++b) {
+        sg[b] = ((c >> b) & 1) ? 0x80000000u : 0u;
+        sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
+    }
+    const float flip = (kFused && (__builtin_popcount(c) & 1)) ? -1.0f : 1.0f;
 
     constexpr float kMagic = 12582912.0f;               // 1.5 * 2^23: integer lattice of fp32
     constexpr float kLo = kMagic, kHi = kMagic + (float)((1 << BITS) - 1);
@@ -144,13 +187,16 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 f32x4 v = acc[t][h];
-                lane_stage<kDppXor1>(v, sg[0]);
-                lane_stage<kDppXor2>(v, sg[1]);
-                if (CB >= 3) lane_stage<kDppHalfMirror>(v, sg[2]);
-                if (CB >= 4) lane_stage<kDppRor8>(v, sg[3]);
+                if constexpr (kFused) {
+                    lane_stages_fused(v, sf[0], sf[1], sf[2], sf[3]);
+                } else {
+                    lane_stage<kDppXor1>(v, sg[0]);
+                    lane_stage<kDppXor2>(v, sg[1]);
+                    if (CB >= 3) lane_stage<kDppHalfMirror>(v, sg[2]);
+                    if (CB >= 4) lane_stage<kDppRor8>(v, sg[3]);
+                }
                 acc[t][h] = v;
-                m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(v[0]), __builtin_fabsf(v[1])));
-                m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(v[2]), __builtin_fabsf(v[3])));
+                m = absmax4(m, v);
             }
         // absmax over the lanes that share the row
         m = fmaxf(m, dpp_f<kDppXor1>(m));
@@ -171,6 +217,7 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
             const float c2h = (float)a.c2, c2l = (float)(a.c2 - (double)c2h);
             scale = fmaf(m, c2l, m * c2h);
         }
+        s *= flip;
 
         uint32_t* out = a.codes + (live ? row : 0) * (int64_t)ROW_DWORDS;
 #pragma unroll
@@ -222,9 +269,10 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
     const int g = lane >> 4, cphys = lane & 15;
     const int c = (cphys & 4) ? (cphys ^ 3) : cphys;     // logical column chunk
     const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
-    uint32_t sg[4];
+    float sf[4];
 #pragma unroll
-    for (int b = 0; b < 4; ++b) sg[b] = ((c >> b) & 1) ? 0x80000000u : 0u;
+    for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
+    const float flip = (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;
 
     constexpr float kMagic = 12582912.0f;
     constexpr float kLo = kMagic, kHi = kMagic + (float)((1 << BITS) - 1);
@@ -275,13 +323,9 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 f32x4 v = acc[ic][h];
-                lane_stage<kDppXor1>(v, sg[0]);
-                lane_stage<kDppXor2>(v, sg[1]);
-                lane_stage<kDppHalfMirror>(v, sg[2]);
-                lane_stage<kDppRor8>(v, sg[3]);
+                lane_stages_fused(v, sf[0], sf[1], sf[2], sf[3]);
                 acc[ic][h] = v;
-                m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(v[0]), __builtin_fabsf(v[1])));
-                m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(v[2]), __builtin_fabsf(v[3])));
+                m = absmax4(m, v);
             }
         m = fmaxf(m, dpp_f<kDppXor1>(m));
         m = fmaxf(m, dpp_f<kDppXor2>(m));
@@ -289,7 +333,7 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
         m = fmaxf(m, dpp_f<kDppRor8>(m));
         m = fmaxf(m, __shfl_xor(m, 16, 64));
         m = fmaxf(m, __shfl_xor(m, 32, 64));
-        const float s = m > 0.0f ? (float)(a.c1 / (double)m) : 0.0f;
+        const float s = m > 0.0f ? flip * (float)(a.c1 / (double)m) : 0.0f;
         const float scale = (float)(a.c2 * (double)m);
 
         uint32_t* out = a.codes + row * (int64_t)(ROW_DWORDS_PER_A * pb);
