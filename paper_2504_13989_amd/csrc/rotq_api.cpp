@@ -67,7 +67,7 @@ int rq_hadamard_build(int n, rq_hadamard_t** out) {
         return RQ_ERR_HIP;
     }
     const bool sylv = f.p == 1 && f.log2m >= 7 && f.log2m <= 13;
-    const bool blk = f.p > 1 && f.log2m >= 7 && (f.p << (f.log2m - 7)) <= 32;
+    const bool blk = f.p > 1 && f.log2m >= 7 && (f.p << (f.log2m - 7)) <= 256;
     if (sylv || blk) {
         std::vector<uint32_t> tiles;
         if (sylv) {
@@ -80,7 +80,8 @@ int rq_hadamard_build(int n, rq_hadamard_t** out) {
                 for (int j = 0; j < pb; ++j)
                     bm[(size_t)i * pb + j] = (int8_t)(h->block[(size_t)(i / e) * f.p + j / e] *
                                                       rq::sylvester_entry(i % e, j % e));
-            tiles = rq::wave_block_tiles(bm, pb);
+            tiles = pb <= 32 ? rq::wave_block_tiles(bm, pb) : rq::wg_block_tiles(bm, pb);
+            if (pb > 32) h->wg_ok = rq::wg_block_prepare(pb);
         }
         const size_t tb = tiles.size() * sizeof(uint32_t);
         if (hipMalloc(&h->d_tiles, tb) != hipSuccess ||
@@ -160,6 +161,10 @@ int rq_rotate_quantize(const rq_hadamard_t* h, const void* X, int dtype, int64_t
     if (h->variant == 0 && rq::wave_block_supports(h, a)) {
         hm->last_kernel = "wave_block";
         return rq::wave_block_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
+    }
+    if (h->variant == 0 && rq::wg_block_supports(h, a)) {
+        hm->last_kernel = "wg_block";
+        return rq::wg_block_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
     }
     if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
     hm->last_kernel = "generic_lds";

@@ -16,6 +16,7 @@ struct rq_hadamard {
     void* d_tiles = nullptr;         // device MFMA operand tiles of the block stage (bf16)
     int max_lds = 0;                 // bytes of LDS one workgroup may use on `device`
     int num_cu = 0;
+    bool wg_ok = false;              // the workgroup block kernel is usable for this order
     bool generic_ok = false;         // the general LDS kernel can hold a row of this order
     int variant = 0;                 // 0 auto, 1 general LDS kernel
     const char* last_kernel = "";
@@ -58,5 +59,12 @@ std::vector<uint32_t> wave_block_tiles(const std::vector<int8_t>& bm, int pb);
 bool wave_block_supports(const rq_hadamard* h, const RowArgs& a);
 int wave_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                                float* scales, hipStream_t s);
+
+// Workgroup block kernel: bf16 rows, n = pb * 128 with 32 < pb <= 256 (e.g. 18944 = 148 * 128).
+std::vector<uint32_t> wg_block_tiles(const std::vector<int8_t>& bm, int pb);
+bool wg_block_prepare(int pb);
+bool wg_block_supports(const rq_hadamard* h, const RowArgs& a);
+int wg_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
+                             float* scales, hipStream_t s);
 
 }  // namespace rq

@@ -1,0 +1,161 @@
+// Device helpers shared by the wave-level kernels: DPP permutations, the fused cross-lane
+// butterfly stages, chunk loads, and the launch-argument block.
+#pragma once
+#include "rotq_internal.h"
+
+namespace rq {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kDppXor1 = 0xB1;         // quad_perm:[1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm:[2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // row_half_mirror: lane i <-> 7 - i
+constexpr int kDppRor8 = 0x128;        // row_ror:8: lane i <-> i ^ 8
+constexpr int kDppNext = 0xF9;         // quad_perm:[1,2,3,3]: value of the next lane of the quad
+constexpr int kDppPrev = 0x90;         // quad_perm:[0,0,1,2]: value of the previous lane
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+
+// One cross-lane butterfly stage in place: partner + (upper lane ? -self : self), i.e. a + b on
+// the lower lane of a pair and a - b on the upper one (one sign flip plus one DPP add).
+template <int CTRL>
+__device__ __forceinline__ void lane_stage(f32x4& v, uint32_t signbit) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float x = v[i];   // scalar copy: bit-casting a vector element in place is not reliable
+        const float self = __uint_as_float(__float_as_uint(x) ^ signbit);
+        v[i] = dpp_f<CTRL>(x) + self;
+    }
+}
+
+// The four cross-lane stages (xor-1, xor-2, half mirror, xor-8) on four independent values, one
+// v_fmac_f32 with a DPP-permuted operand per value and stage: x <- x + sign * partner(x), sign
+// = -1 on the upper lane of a pair.  The upper lane thus receives b - a instead of a - b; these
+// negations commute with all later stages and are undone once, in the sign of the lane's
+// quantization multiplier.  (The compiler does not fold a DPP operand into an fma, hence the
+// assembly.)  A DPP read needs two wait states after the VALU write of its source: the leading
+// s_nop covers the producer of the inputs, and inside the block three instructions separate a
+// value's consecutive stages.
+__device__ __forceinline__ void lane_stages_fused(f32x4& v, float s0, float s1, float s2, float s3) {
+    float x0 = v[0], x1 = v[1], x2 = v[2], x3 = v[3];
+    asm("s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %0, %4 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %4 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %4 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %4 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %0, %5 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %5 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %5 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %5 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %0, %6 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %6 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %6 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %6 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %0, %7 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %7 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %7 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %7 row_ror:8 row_mask:0xf bank_mask:0xf"
+        : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3)
+        : "v"(s0), "v"(s1), "v"(s2), "v"(s3));
+    v[0] = x0; v[1] = x1; v[2] = x2; v[3] = x3;
+}
+
+__device__ __forceinline__ float absmax4(float m, const f32x4& v) {
+    m = __builtin_fmaxf(__builtin_fmaxf(m, __builtin_fabsf(v[0])), __builtin_fabsf(v[1]));
+    return __builtin_fmaxf(__builtin_fmaxf(m, __builtin_fabsf(v[2])), __builtin_fabsf(v[3]));
+}
+
+// 16-byte chunk starting at element e0 of a row whose width d is a multiple of 8: whole chunks
+// only, zero beyond d.
+__device__ __forceinline__ u32x4 load_chunk(const uint16_t* row, int e0, int d) {
+    const bool in = e0 < d;
+    u32x4 r = *reinterpret_cast<const u32x4*>(row + (in ? e0 : 0));
+    if (!in) r = u32x4{0u, 0u, 0u, 0u};
+    return r;
+}
+
+struct WaveArgs {
+    const uint16_t* X;
+    int64_t rows;
+    int d;
+    int64_t ld;
+    const u32x4* tiles;   // matrix-core operand of the 32x32 +-1 block: [2][64] x 16 bytes
+    uint32_t* codes;
+    float* scales;
+    double c1;            // (2^b - 1) / clip
+    double c2;            // clip / (sqrt(n) (2^b - 1))
+};
+
+
+// Quantizer constants for b-bit codes (section 2.1 with the clip ratio of section 3.1).
+// u = fma(y, s, kBias) rounds y*s + 2^(b-1) to the nearest-even integer on the fp32 lattice
+// above 1.5 * 2^23; v_med3 clamps it to [kLo, kHi]; the code (offset binary) is the low
+// mantissa bits.  Eight codes are chained with shift-adds, the accumulated exponent bits
+// (kCsum) are subtracted once and one xor (kMsb) turns offset binary into two's complement.
+template <int BITS>
+struct Quant {
+    static constexpr float kMagic = 12582912.0f;   // 1.5 * 2^23
+    static constexpr float kLo = kMagic, kHi = kMagic + (float)((1 << BITS) - 1);
+    static constexpr float kBias = kMagic + (float)(1 << (BITS - 1));
+    static constexpr uint32_t csum() {
+        uint32_t c = 0;
+        for (int r = 0; r < 8; ++r) c += 0x4B400000u << (BITS * r);
+        return c;
+    }
+    static constexpr uint32_t msb() {
+        uint32_t m = 0;
+        for (int r = 0; r < 8; ++r) m |= 1u << (BITS * r + BITS - 1);
+        return m;
+    }
+    // packs codes of y0..y7 (y0 in the low bits) into 8*BITS bits
+    static __device__ __forceinline__ uint32_t pack8(float y0, float y1, float y2, float y3, float y4,
+                                                     float y5, float y6, float y7, float s) {
+        const float y[8] = {y0, y1, y2, y3, y4, y5, y6, y7};
+        uint32_t w = 0;
+#pragma unroll
+        for (int r = 7; r >= 0; --r) {
+            float u = fmaf(y[r], s, kBias);
+            u = __builtin_amdgcn_fmed3f(u, kLo, kHi);
+            w = (w << BITS) + __float_as_uint(u);
+        }
+        return (w - csum()) ^ msb();
+    }
+};
+
+// b = 3: a lane's 24 bits and those of the lane holding the next 8 columns (lane + 1, or
+// lane - 1 in mirrored quads) make the dword for quad position qpos (0..2).
+template <bool MIRROR>
+__device__ __forceinline__ uint32_t merge24(uint32_t w, int qpos) {
+    uint32_t nxt;
+    if constexpr (MIRROR) {
+        nxt = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppNext, 0xf, 0x5, true);
+        nxt = (uint32_t)__builtin_amdgcn_update_dpp((int)nxt, (int)w, kDppPrev, 0xf, 0xa, false);
+    } else {
+        nxt = dpp_u<kDppNext>(w);
+    }
+    return (w >> (8 * qpos)) | (nxt << (24 - 8 * qpos));
+}
+
+// Max over the 64 lanes of a wave (all four DPP row patterns, then the two cross-row steps).
+__device__ __forceinline__ float wave_absmax(float m) {
+    m = fmaxf(m, dpp_f<kDppXor1>(m));
+    m = fmaxf(m, dpp_f<kDppXor2>(m));
+    m = fmaxf(m, dpp_f<kDppHalfMirror>(m));
+    m = fmaxf(m, dpp_f<kDppRor8>(m));
+    m = fmaxf(m, __shfl_xor(m, 16, 64));
+    return fmaxf(m, __shfl_xor(m, 32, 64));
+}
+
+}  // namespace
+}  // namespace rq

@@ -73,11 +73,16 @@ def test_small_cases(torch, name, rows, variant):
 @pytest.mark.parametrize("n,d,dtype", [(256, 256, "f32"), (128, 100, "bf16"), (4096, 4000, "f32"),
                                        (3584, 3500, "bf16"), (3072, 3000, "f32"), (1536, 1536, "bf16"),
                                        (2048, 2048, "bf16"), (8192, 8192, "bf16"), (512, 512, "bf16"),
-                                       (640, 640, "bf16"), (64, 64, "bf16"), (32, 20, "f32")])
+                                       (640, 640, "bf16"), (64, 64, "bf16"), (32, 20, "f32"),
+                                       # blocks above 32: 44 (q=43), 60 (II, q=29), 84, 108, 168, 200, 252
+                                       (44 * 128, 44 * 128, "bf16"), (60 * 128, 7600, "bf16"),
+                                       (84 * 128, 84 * 128, "bf16"), (108 * 128, 108 * 128, "bf16"),
+                                       (168 * 128, 168 * 128, "bf16"), (200 * 128, 25000, "bf16"),
+                                       (252 * 128, 252 * 128, "bf16"), (38 * 256, 38 * 256, "bf16")])
 @pytest.mark.parametrize("b", [3, 4])
 def test_other_orders_and_padding(torch, n, d, dtype, b):
     rng = np.random.default_rng(n * 7 + d + b)
-    x = rng.standard_t(3.0, size=(67, d)).astype(np.float32)
+    x = rng.standard_t(3.0, size=(67 if n <= 8192 else 19, d)).astype(np.float32)
     x[:, rng.choice(d, 3, replace=False)] *= 40
     if dtype == "bf16":
         x = wl.f32_to_bf16_bits(x)
