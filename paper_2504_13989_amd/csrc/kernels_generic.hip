@@ -191,6 +191,12 @@ int generic_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, 
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 
+int reduce_partials(const double* partial, int64_t rows, int n_clips, float* mse, hipStream_t s) {
+    hipLaunchKernelGGL(k_reduce_partials, dim3(n_clips), dim3(kThreads), 0, s, partial, rows, n_clips,
+                       mse);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
 int generic_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
                         float* mse, double* partial, hipStream_t s) {
     const size_t bytes = lds_bytes(h);
@@ -200,9 +206,7 @@ int generic_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& 
                            clips, n_clips, partial);
         if (hipGetLastError() != hipSuccess) return RQ_ERR_HIP;
     }
-    hipLaunchKernelGGL(k_reduce_partials, dim3(n_clips), dim3(kThreads), 0, s, partial, a.rows,
-                       n_clips, mse);
-    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+    return reduce_partials(partial, a.rows, n_clips, mse, s);
 }
 
 }  // namespace rq

@@ -274,6 +274,97 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// quant_error for bf16 rows of Sylvester order n = 512 T (1024 .. 8192): the rotation of
+// k_wave_sylvester, then for each clip ratio of this wave's share [k0, k1) the row's squared
+// quantization error (sections 2.1, 3.1): t = y / Delta_k, r = clamp(round(t)),
+// e = y - r Delta_k, sum e^2.  The grid is rows x ksplit: with few rows the candidates of one
+// row are spread over several waves (each repeats the rotation) so the chip is filled.
+// partial[row][k] receives sum e^2 / n^2, the row's mean squared error in the normalised domain.
+template <int T, int BITS>
+__global__ __launch_bounds__(64) void k_wave_quant_error(WaveArgs a, ClipList clips, int n_clips,
+                                                         int ksplit, double* partial) {
+    constexpr int N = 512 * T;
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, cphys = lane & 15;
+    const int c = (cphys & 4) ? (cphys ^ 3) : cphys;
+    const int chunk = (g << 4) + c;
+    const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
+    float sf[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
+    const float flip = (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;
+    constexpr float kQmax = (float)((1 << (BITS - 1)) - 1), kQmin = -(float)(1 << (BITS - 1));
+    const double lvl = (double)((1 << BITS) - 1);
+
+    const int64_t n_items = a.rows * ksplit;
+    for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int64_t row = item / ksplit;
+        const int part = (int)(item - row * ksplit);
+        const int per = (n_clips + ksplit - 1) / ksplit;
+        const int k0 = part * per, k1 = (k0 + per < n_clips) ? k0 + per : n_clips;
+        const uint16_t* xr = a.X + row * a.ld;
+
+        f32x4 acc[T][2];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const u32x4 raw = load_chunk(xr, (t * 64 + chunk) * 8, a.d);
+            const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
+            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), bm, z, 0, 0, 0);
+        }
+#pragma unroll
+        for (int s = 1; s < T; s <<= 1)
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+                if (!(t & s))
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const f32x4 u = acc[t][h], v = acc[t | s][h];
+                        acc[t][h] = u + v;
+                        acc[t | s][h] = u - v;
+                    }
+        float m = 0.0f;
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                f32x4 v = acc[t][h];
+                lane_stages_fused(v, sf[0], sf[1], sf[2], sf[3]);
+                acc[t][h] = v;
+                m = absmax4(m, v);
+            }
+        m = wave_absmax(m);
+
+        for (int k = k0; k < k1; ++k) {
+            const double dk64 = (double)clips.v[k] * (double)m / lvl;
+            const float sk = m > 0.0f ? flip * (float)(1.0 / dk64) : 0.0f;   // lane sign folded in
+            const float ndk = -flip * (float)dk64;
+            float e2 = 0.0f;
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float y = acc[t][h][i];
+                        const float r = __builtin_amdgcn_fmed3f(__builtin_rintf(y * sk), kQmin, kQmax);
+                        const float e = fmaf(r, ndk, y);
+                        e2 = fmaf(e, e, e2);
+                    }
+            e2 += dpp_f<kDppXor1>(e2);
+            e2 += dpp_f<kDppXor2>(e2);
+            e2 += dpp_f<kDppHalfMirror>(e2);
+            e2 += dpp_f<kDppRor8>(e2);
+            e2 += __shfl_xor(e2, 16, 64);
+            e2 += __shfl_xor(e2, 32, 64);
+            if (lane == 0) partial[row * n_clips + k] = (double)e2 / ((double)N * (double)N);
+        }
+    }
+}
+
 template <int T, int CB>
 int launch(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
     constexpr int RPW = 16 >> CB;
@@ -355,6 +446,42 @@ bool wave_supports(const rq_hadamard* h, const RowArgs& a) {
     if (a.log2m < 7 || a.log2m > 13) return false;
     if ((reinterpret_cast<uintptr_t>(a.X) & 15) != 0 || (a.ld & 7) != 0 || (a.d & 7) != 0) return false;
     return true;
+}
+
+bool wave_quant_error_supports(const rq_hadamard* h, const RowArgs& a) {
+    return wave_supports(h, a) && a.log2m >= 10;
+}
+
+template <int T>
+static int launch_qe(const rq_hadamard* h, const WaveArgs& w, const ClipList& clips, int n_clips,
+                     int bits, double* partial, hipStream_t s) {
+    // spread one row's candidates over several waves when there are few rows
+    const int64_t target = (int64_t)h->num_cu * 4 * 4;
+    int ksplit = (int)((target + w.rows - 1) / w.rows);
+    if (ksplit < 1) ksplit = 1;
+    if (ksplit > n_clips) ksplit = n_clips;
+    if (ksplit > 8) ksplit = 8;
+    const int64_t items = w.rows * ksplit;
+    const int64_t cap = (int64_t)h->num_cu * 4 * 8;
+    const unsigned grid = (unsigned)(items < cap ? items : cap);
+    if (bits == 4)
+        hipLaunchKernelGGL((k_wave_quant_error<T, 4>), dim3(grid), dim3(64), 0, s, w, clips, n_clips, ksplit, partial);
+    else
+        hipLaunchKernelGGL((k_wave_quant_error<T, 3>), dim3(grid), dim3(64), 0, s, w, clips, n_clips, ksplit, partial);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+int wave_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
+                     double* partial, hipStream_t s) {
+    WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
+               static_cast<const u32x4*>(h->d_tiles), nullptr, nullptr, 0.0, 0.0};
+    switch (a.log2m) {
+        case 10: return launch_qe<2>(h, w, clips, n_clips, a.bits, partial, s);
+        case 11: return launch_qe<4>(h, w, clips, n_clips, a.bits, partial, s);
+        case 12: return launch_qe<8>(h, w, clips, n_clips, a.bits, partial, s);
+        case 13: return launch_qe<16>(h, w, clips, n_clips, a.bits, partial, s);
+        default: return RQ_ERR_NO_ORDER;
+    }
 }
 
 int wave_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,

@@ -195,6 +195,12 @@ int rq_quant_error(const rq_hadamard_t* h, const void* X, int dtype, int64_t row
     rq_hadamard* hm = const_cast<rq_hadamard*>(h);
     const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, bits);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (h->variant == 0 && rows > 0 && rq::wave_quant_error_supports(h, a)) {
+        hm->last_kernel = "wave_quant_error";
+        rc = rq::wave_quant_error(h, a, cl, n_clips, static_cast<double*>(workspace), s);
+        if (rc != RQ_OK) return rc;
+        return rq::reduce_partials(static_cast<double*>(workspace), rows, n_clips, mse, s);
+    }
     if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
     hm->last_kernel = "generic_lds";
     return rq::generic_quant_error(h, a, cl, n_clips, mse, static_cast<double*>(workspace), s);

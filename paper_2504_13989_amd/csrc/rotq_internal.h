@@ -53,6 +53,12 @@ std::vector<uint32_t> wave_sylvester_tiles();
 bool wave_supports(const rq_hadamard* h, const RowArgs& a);
 int wave_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                          float* scales, hipStream_t s);
+// quant_error on the wave path (bf16, Sylvester orders 1024 .. 8192): fills partial[rows][n_clips];
+// reduce_partials then averages over rows.
+bool wave_quant_error_supports(const rq_hadamard* h, const RowArgs& a);
+int wave_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
+                     double* partial, hipStream_t s);
+int reduce_partials(const double* partial, int64_t rows, int n_clips, float* mse, hipStream_t s);
 // Block kernel: bf16 rows, n = pb * 128 with a +-1 block of order pb <= 32 (Paley (x) small
 // Sylvester) on the matrix cores.
 std::vector<uint32_t> wave_block_tiles(const std::vector<int8_t>& bm, int pb);
