@@ -24,54 +24,28 @@
 namespace rq {
 namespace {
 
-// T loads per row (n = 512 T when CB = 4); CB column bits per DPP row (n = 32 << CB when T = 1).
-template <int T, int CB, int BITS>
+// Long rows: n = 512 T (T = 2 .. 16), one wave per row.  FULL: d == n (no zero padding).
+template <int T, int BITS, bool FULL>
 __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
-    static_assert(CB >= 2 && CB <= 4 && (T == 1 || CB == 4), "unsupported shape");
-    constexpr int RPW = 16 >> CB;                      // rows per wave iteration
-    constexpr int N = (T > 1) ? 512 * T : (32 << CB);
-    constexpr int ROW_DWORDS = N * BITS / 32;
+    constexpr int ROW_DWORDS = 512 * T * BITS / 32;
     const int lane = threadIdx.x;
-    const int g = lane >> 4, nnl = lane & 15;
-    const int cphys = nnl & ((1 << CB) - 1);
-    const int rsub = nnl >> CB;
-    const bool mirrored = (CB >= 3) && (cphys & 4);
-    const int c = mirrored ? (cphys ^ 3) : cphys;       // logical column index
-    const int chunk = (g << CB) + c;                    // 16-byte chunk inside a load segment
+    const int g = lane >> 4, cphys = lane & 15;
+    const int c = (cphys & 4) ? (cphys ^ 3) : cphys;    // logical column index
+    const int chunk = (g << 4) + c;                     // 16-byte chunk inside a 1 KB load segment
 
     const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
-    constexpr bool kFused = (T >= 2);                   // inputs of the fused stages come from VALU ops
-    uint32_t sg[4];
     float sf[4];
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-        sg[b] = ((c >> b) & 1) ? 0x80000000u : 0u;
-        sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
-    }
-    const float flip = (kFused && (__builtin_popcount(c) & 1)) ? -1.0f : 1.0f;
+    for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
+    const float flip = (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;
 
-    constexpr float kMagic = 12582912.0f;               // 1.5 * 2^23: integer lattice of fp32
-    constexpr float kLo = kMagic, kHi = kMagic + (float)((1 << BITS) - 1);
-    constexpr float kBias = kMagic + (float)(1 << (BITS - 1));
-    constexpr uint32_t kMagicBits = 0x4B400000u;
-    uint32_t csum = 0, msb = 0;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        csum += kMagicBits << (BITS * r);
-        msb |= 1u << (BITS * r + BITS - 1);
-    }
-
-    const int64_t n_groups = (a.rows + RPW - 1) / RPW;
-    for (int64_t grp = blockIdx.x; grp < n_groups; grp += gridDim.x) {
-        const int64_t row = grp * RPW + rsub;
-        const bool live = row < a.rows;
-        const uint16_t* xr = a.X + (live ? row : 0) * a.ld;
-        const int dd = live ? a.d : 0;   // rows past the end read as zeros and store nothing
-
+    for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
+        const uint16_t* xr = a.X + row * a.ld;
         f32x4 acc[T][2];
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            const u32x4 raw = load_chunk(xr, (t * 64 + chunk) * 8, dd);
+            const int e0 = (t * 64 + chunk) * 8;
+            const u32x4 raw = FULL ? load16(xr + e0) : load_chunk(xr, e0, a.d);
             const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
             acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
@@ -96,71 +70,128 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 f32x4 v = acc[t][h];
-                if constexpr (kFused) {
-                    lane_stages_fused(v, sf[0], sf[1], sf[2], sf[3]);
-                } else {
-                    lane_stage<kDppXor1>(v, sg[0]);
-                    lane_stage<kDppXor2>(v, sg[1]);
-                    if (CB >= 3) lane_stage<kDppHalfMirror>(v, sg[2]);
-                    if (CB >= 4) lane_stage<kDppRor8>(v, sg[3]);
-                }
+                lane_stages_fused(v, sf[0], sf[1], sf[2], sf[3]);
                 acc[t][h] = v;
                 m = absmax4(m, v);
             }
-        // absmax over the lanes that share the row
-        m = fmaxf(m, dpp_f<kDppXor1>(m));
-        m = fmaxf(m, dpp_f<kDppXor2>(m));
-        if (CB >= 3) m = fmaxf(m, dpp_f<kDppHalfMirror>(m));
-        if (CB >= 4) m = fmaxf(m, dpp_f<kDppRor8>(m));
-        m = fmaxf(m, __shfl_xor(m, 16, 64));
-        m = fmaxf(m, __shfl_xor(m, 32, 64));
+        m = wave_absmax<4>(m);
+        const float s = m > 0.0f ? flip * (float)(a.c1 / (double)m) : 0.0f;
 
-        float s, scale;
-        if (T > 1) {
-            s = m > 0.0f ? (float)(a.c1 / (double)m) : 0.0f;
-            scale = (float)(a.c2 * (double)m);
-        } else {
-            // short rows: fp32 division plus a first-order correction for the rounding of c1
-            const float c1h = (float)a.c1, c1l = (float)(a.c1 - (double)c1h);
-            s = m > 0.0f ? fmaf(c1l, __builtin_amdgcn_rcpf(m), c1h / m) : 0.0f;
-            const float c2h = (float)a.c2, c2l = (float)(a.c2 - (double)c2h);
-            scale = fmaf(m, c2l, m * c2h);
-        }
-        s *= flip;
-
-        uint32_t* out = a.codes + (live ? row : 0) * (int64_t)ROW_DWORDS;
+        uint32_t* out = a.codes + row * (int64_t)ROW_DWORDS;
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            uint32_t w = 0;
-#pragma unroll
-            for (int r = 7; r >= 0; --r) {
-                float u = fmaf(acc[t][r >> 2][r & 3], s, kBias);
-                u = __builtin_amdgcn_fmed3f(u, kLo, kHi);
-                w = (w << BITS) + __builtin_bit_cast(uint32_t, u);
-            }
-            w = (w - csum) ^ msb;
+            const uint32_t w = Quant<BITS>::pack8(acc[t][0][0], acc[t][0][1], acc[t][0][2], acc[t][0][3],
+                                                  acc[t][1][0], acc[t][1][1], acc[t][1][2], acc[t][1][3], s);
             const int word = t * 64 + chunk;            // 8-element group index inside the row
             if (BITS == 4) {
-                if (live) out[word] = w;
+                store_codes(out + word, w);
             } else {
-                // three bytes per lane: four lanes of a quad make three dwords
-                // the lane holding the next 8 columns: lane + 1, or lane - 1 in mirrored quads
-                uint32_t nxt;
-                if constexpr (CB >= 3) {
-                    nxt = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppNext, 0xf, 0x5, true);
-                    nxt = (uint32_t)__builtin_amdgcn_update_dpp((int)nxt, (int)w, kDppPrev, 0xf, 0xa, false);
-                } else {
-                    nxt = dpp_u<kDppNext>(w);
-                }
                 const int qpos = c & 3;
-                const uint32_t dw = (w >> (8 * qpos)) | (nxt << (24 - 8 * qpos));
-                if (live && qpos < 3) out[(word >> 2) * 3 + qpos] = dw;
+                const uint32_t dw = merge24<true>(w, qpos);
+                if (qpos < 3) store_codes(out + (word >> 2) * 3 + qpos, dw);
             }
         }
-        if (live && g == 0 && c == 0) a.scales[row] = scale;
+        if (lane == 0) a.scales[row] = (float)(a.c2 * (double)m);
     }
 }
 
+// Short rows: n = 32 << CB (128, 256, 512), 16 >> CB rows per wave pass, U passes in flight.
+// Lane (g, r, c): DPP row g holds contraction slots, r selects the row of the pass, c the
+// column chunk; the matrix cores transform the (g, i) bits, CB DPP stages the c bits.
+// GUARD: the super-group may be ragged (rows missing at the end) or d < n.
+template <int CB, int BITS, int U, bool GUARD>
+__device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_t* base, uint32_t* obase,
+                                                float* sbase, int rem, const u32x4& A0, const u32x4& A1,
+                                                const uint32_t (&sg)[4], int g, int c, int rsub, int chunk,
+                                                float c1h, float c1l, float c2h, float c2l) {
+    constexpr int RPW = 16 >> CB;
+    constexpr int ROW_DWORDS = (32 << CB) * BITS / 32;
+    u32x4 raw[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int rr = u * RPW + rsub;
+        const uint16_t* p = base + (int64_t)rr * a.ld + chunk * 8;
+        if (GUARD) {
+            const bool in = rr < rem && chunk * 8 < a.d;
+            raw[u] = load16(in ? p : base);
+            if (!in) raw[u] = u32x4{0u, 0u, 0u, 0u};
+        } else {
+            raw[u] = load16(p);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int rr = u * RPW + rsub;
+        const bool live = !GUARD || rr < rem;
+        const bf16x8 bm = __builtin_bit_cast(bf16x8, raw[u]);
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        f32x4 v0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
+        f32x4 v1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), bm, z, 0, 0, 0);
+        lane_stage<kDppXor1>(v0, sg[0]);
+        lane_stage<kDppXor1>(v1, sg[0]);
+        lane_stage<kDppXor2>(v0, sg[1]);
+        lane_stage<kDppXor2>(v1, sg[1]);
+        if (CB >= 3) {
+            lane_stage<kDppHalfMirror>(v0, sg[2]);
+            lane_stage<kDppHalfMirror>(v1, sg[2]);
+        }
+        if (CB >= 4) {
+            lane_stage<kDppRor8>(v0, sg[3]);
+            lane_stage<kDppRor8>(v1, sg[3]);
+        }
+        float m = absmax4(absmax4(0.0f, v0), v1);
+        m = wave_absmax<CB>(m);                          // over the lanes that share the row
+        const float s = m > 0.0f ? div_pair(c1h, c1l, m) : 0.0f;
+        const uint32_t w = Quant<BITS>::pack8(v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3], s);
+        uint32_t* out = obase + rr * ROW_DWORDS;
+        if (BITS == 4) {
+            if (live) store_codes(out + chunk, w);
+        } else {
+            const int qpos = c & 3;
+            const uint32_t dw = merge24<(CB >= 3)>(w, qpos);
+            if (live && qpos < 3) store_codes(out + (chunk >> 2) * 3 + qpos, dw);
+        }
+        if (live && g == 0 && c == 0) sbase[rr] = fmaf(m, c2l, m * c2h);
+    }
+}
+
+template <int CB, int BITS, int U>
+__global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
+    static_assert(CB >= 2 && CB <= 4, "unsupported shape");
+    constexpr int RPW = 16 >> CB;
+    constexpr int N = 32 << CB;
+    constexpr int ROW_DWORDS = N * BITS / 32;
+    constexpr int SUPER = RPW * U;                      // rows per wave iteration
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, nnl = lane & 15;
+    const int cphys = nnl & ((1 << CB) - 1);
+    const int rsub = nnl >> CB;
+    const int c = (CB >= 3 && (cphys & 4)) ? (cphys ^ 3) : cphys;
+    const int chunk = (g << CB) + c;
+    const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
+    uint32_t sg[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) sg[b] = ((c >> b) & 1) ? 0x80000000u : 0u;
+    const float c1h = (float)a.c1, c1l = (float)(a.c1 - (double)c1h);
+    const float c2h = (float)a.c2, c2l = (float)(a.c2 - (double)c2h);
+    const bool full_d = a.d == N;
+
+    const int64_t n_super = (a.rows + SUPER - 1) / SUPER;
+    for (int64_t sgi = blockIdx.x; sgi < n_super; sgi += gridDim.x) {
+        const int64_t row0 = sgi * SUPER;
+        const int64_t left = a.rows - row0;
+        const int rem = left < SUPER ? (int)left : SUPER;
+        const uint16_t* base = a.X + row0 * a.ld;
+        uint32_t* obase = a.codes + row0 * ROW_DWORDS;
+        float* sbase = a.scales + row0;
+        if (rem == SUPER && full_d)
+            short_rows_pass<CB, BITS, U, false>(a, base, obase, sbase, rem, A0, A1, sg, g, c, rsub, chunk,
+                                                c1h, c1l, c2h, c2l);
+        else
+            short_rows_pass<CB, BITS, U, true>(a, base, obase, sbase, rem, A0, A1, sg, g, c, rsub, chunk,
+                                               c1h, c1l, c2h, c2l);
+    }
+}
 
 // ---------------------------------------------------------------------------------------------
 // Block kernel: n = PB * 128 with a +-1 block of order PB <= 32 along the strided axis
@@ -171,7 +202,7 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
 // loads into one operand (a 16-bit transpose inside the lane, v_perm_b32).  Outputs come back
 // with 8 block rows x 8 consecutive columns per lane; butterflies over i (registers) and c
 // (DPP), quantization and packing then work exactly as in the Sylvester kernel.
-template <int BITS>
+template <int BITS, bool FULL>
 __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
     constexpr int ROW_DWORDS_PER_A = 128 * BITS / 32;
     const int lane = threadIdx.x;
@@ -194,14 +225,16 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
         msb |= 1u << (BITS * r + BITS - 1);
     }
 
+    // block rows at or beyond pb meet zero columns of the block operand, so what is loaded for
+    // them does not matter as long as it is in bounds: reuse the last real block row
+    int eoff[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) eoff[t] = (8 * g + t < pb ? 8 * g + t : pb - 1) * 128 + c * 8;
     for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
         const uint16_t* xr = a.X + row * a.ld;
         u32x4 R[8];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int ar = 8 * g + t;
-            R[t] = load_chunk(xr, ar * 128 + c * 8, ar < pb ? a.d : 0);
-        }
+        for (int t = 0; t < 8; ++t) R[t] = FULL ? load16(xr + eoff[t]) : load_chunk(xr, eoff[t], a.d);
         f32x4 acc[8][2];                                  // [column i][half]: 4 block rows each
 #pragma unroll
         for (int ic = 0; ic < 8; ++ic) {
@@ -236,12 +269,7 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
                 acc[ic][h] = v;
                 m = absmax4(m, v);
             }
-        m = fmaxf(m, dpp_f<kDppXor1>(m));
-        m = fmaxf(m, dpp_f<kDppXor2>(m));
-        m = fmaxf(m, dpp_f<kDppHalfMirror>(m));
-        m = fmaxf(m, dpp_f<kDppRor8>(m));
-        m = fmaxf(m, __shfl_xor(m, 16, 64));
-        m = fmaxf(m, __shfl_xor(m, 32, 64));
+        m = wave_absmax<4>(m);
         const float s = m > 0.0f ? flip * (float)(a.c1 / (double)m) : 0.0f;
         const float scale = (float)(a.c2 * (double)m);
 
@@ -261,13 +289,13 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
                 w = (w - csum) ^ msb;
                 const int word = ao * 16 + c;
                 if (BITS == 4) {
-                    if (ao < pb) out[word] = w;
+                    if (ao < pb) store_codes(out + word, w);
                 } else {
                     uint32_t nxt = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppNext, 0xf, 0x5, true);
                     nxt = (uint32_t)__builtin_amdgcn_update_dpp((int)nxt, (int)w, kDppPrev, 0xf, 0xa, false);
                     const int qpos = c & 3;
                     const uint32_t dw = (w >> (8 * qpos)) | (nxt << (24 - 8 * qpos));
-                    if (ao < pb && qpos < 3) out[(word >> 2) * 3 + qpos] = dw;
+                    if (ao < pb && qpos < 3) store_codes(out + (word >> 2) * 3 + qpos, dw);
                 }
             }
         if (lane == 0) a.scales[row] = scale;
@@ -365,17 +393,36 @@ __global__ __launch_bounds__(64) void k_wave_quant_error(WaveArgs a, ClipList cl
     }
 }
 
-template <int T, int CB>
-int launch(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
-    constexpr int RPW = 16 >> CB;
-    const int64_t groups = (a.rows + RPW - 1) / RPW;
-    const int64_t cap = (int64_t)h->num_cu * 4 * 8 * 4;    // a few waves per SIMD slot
-    const unsigned grid = (unsigned)(groups < cap ? groups : cap);
-    if (bits == 4)
-        hipLaunchKernelGGL((k_wave_sylvester<T, CB, 4>), dim3(grid), dim3(64), 0, s, a);
-    else
-        hipLaunchKernelGGL((k_wave_sylvester<T, CB, 3>), dim3(grid), dim3(64), 0, s, a);
+template <typename K>
+int launch_wave(K kernel, const rq_hadamard* h, const WaveArgs& a, int64_t items, int waves_per_simd,
+                hipStream_t s) {
+    // one wave per item: a fresh wave starts with its loads, which hides memory latency better
+    // than a resident wave looping over rows (measured); the loop only serves huge inputs
+    (void)h;
+    (void)waves_per_simd;
+    const int64_t cap = 1 << 24;
+    const unsigned grid = (unsigned)(items < cap ? items : cap);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(64), 0, s, a);
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+template <int T>
+int launch_long(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
+    const bool full = a.d == 512 * T;
+    if (bits == 4)
+        return full ? launch_wave(k_wave_sylvester<T, 4, true>, h, a, a.rows, 4, s)
+                    : launch_wave(k_wave_sylvester<T, 4, false>, h, a, a.rows, 4, s);
+    return full ? launch_wave(k_wave_sylvester<T, 3, true>, h, a, a.rows, 4, s)
+                : launch_wave(k_wave_sylvester<T, 3, false>, h, a, a.rows, 4, s);
+}
+
+template <int CB>
+int launch_short(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
+    constexpr int U = 4;
+    constexpr int SUPER = (16 >> CB) * U;
+    const int64_t items = (a.rows + SUPER - 1) / SUPER;
+    return bits == 4 ? launch_wave(k_wave_short<CB, 4, U>, h, a, items, 8, s)
+                     : launch_wave(k_wave_short<CB, 3, U>, h, a, items, 8, s);
 }
 
 }  // namespace
@@ -432,12 +479,16 @@ int wave_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float cli
                static_cast<const u32x4*>(h->d_tiles), codes, scales,
                lvl / (double)clip, (double)clip / (std::sqrt((double)a.n) * lvl)};
     const int pb = a.p << (a.log2m - 7);
-    const int64_t cap = (int64_t)h->num_cu * 4 * 8 * 4;
+    const int64_t cap = 1 << 24;
     const unsigned grid = (unsigned)(a.rows < cap ? a.rows : cap);
-    if (a.bits == 4)
-        hipLaunchKernelGGL((k_wave_block<4>), dim3(grid), dim3(64), 0, s, w, pb);
-    else
-        hipLaunchKernelGGL((k_wave_block<3>), dim3(grid), dim3(64), 0, s, w, pb);
+    const bool full = a.d == a.n;
+    if (a.bits == 4) {
+        if (full) hipLaunchKernelGGL((k_wave_block<4, true>), dim3(grid), dim3(64), 0, s, w, pb);
+        else hipLaunchKernelGGL((k_wave_block<4, false>), dim3(grid), dim3(64), 0, s, w, pb);
+    } else {
+        if (full) hipLaunchKernelGGL((k_wave_block<3, true>), dim3(grid), dim3(64), 0, s, w, pb);
+        else hipLaunchKernelGGL((k_wave_block<3, false>), dim3(grid), dim3(64), 0, s, w, pb);
+    }
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 
@@ -491,13 +542,13 @@ int wave_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uin
                static_cast<const u32x4*>(h->d_tiles), codes, scales,
                lvl / (double)clip, (double)clip / (std::sqrt((double)a.n) * lvl)};
     switch (a.log2m) {
-        case 7: return launch<1, 2>(h, w, a.bits, s);
-        case 8: return launch<1, 3>(h, w, a.bits, s);
-        case 9: return launch<1, 4>(h, w, a.bits, s);
-        case 10: return launch<2, 4>(h, w, a.bits, s);
-        case 11: return launch<4, 4>(h, w, a.bits, s);
-        case 12: return launch<8, 4>(h, w, a.bits, s);
-        case 13: return launch<16, 4>(h, w, a.bits, s);
+        case 7: return launch_short<2>(h, w, a.bits, s);
+        case 8: return launch_short<3>(h, w, a.bits, s);
+        case 9: return launch_short<4>(h, w, a.bits, s);
+        case 10: return launch_long<2>(h, w, a.bits, s);
+        case 11: return launch_long<4>(h, w, a.bits, s);
+        case 12: return launch_long<8>(h, w, a.bits, s);
+        case 13: return launch_long<16>(h, w, a.bits, s);
         default: return RQ_ERR_NO_ORDER;
     }
 }

@@ -119,11 +119,11 @@ __global__ __launch_bounds__(64 * W) void k_wg_block(WaveArgs a, int pb) {
                                                       acc[6][h][ip], acc[7][h][ip], s);
                 const int word = ao * 16 + c;
                 if (BITS == 4) {
-                    if (ao < pb) out[word] = w;
+                    if (ao < pb) store_codes(out + word, w);
                 } else {
                     const int qpos = c & 3;
                     const uint32_t dw = merge24<true>(w, qpos);
-                    if (ao < pb && qpos < 3) out[(word >> 2) * 3 + qpos] = dw;
+                    if (ao < pb && qpos < 3) store_codes(out + (word >> 2) * 3 + qpos, dw);
                 }
             }
         if (threadIdx.x == 0) a.scales[row] = (float)(a.c2 * (double)m);

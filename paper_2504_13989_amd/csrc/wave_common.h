@@ -80,7 +80,8 @@ __device__ __forceinline__ float absmax4(float m, const f32x4& v) {
 // only, zero beyond d.
 __device__ __forceinline__ u32x4 load_chunk(const uint16_t* row, int e0, int d) {
     const bool in = e0 < d;
-    u32x4 r = *reinterpret_cast<const u32x4*>(row + (in ? e0 : 0));
+    // streamed once: non-temporal, so the row does not displace anything in the caches
+    u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (in ? e0 : 0)));
     if (!in) r = u32x4{0u, 0u, 0u, 0u};
     return r;
 }
@@ -147,14 +148,39 @@ __device__ __forceinline__ uint32_t merge24(uint32_t w, int qpos) {
     return (w >> (8 * qpos)) | (nxt << (24 - 8 * qpos));
 }
 
-// Max over the 64 lanes of a wave (all four DPP row patterns, then the two cross-row steps).
-__device__ __forceinline__ float wave_absmax(float m) {
-    m = fmaxf(m, dpp_f<kDppXor1>(m));
-    m = fmaxf(m, dpp_f<kDppXor2>(m));
-    m = fmaxf(m, dpp_f<kDppHalfMirror>(m));
-    m = fmaxf(m, dpp_f<kDppRor8>(m));
-    m = fmaxf(m, __shfl_xor(m, 16, 64));
-    return fmaxf(m, __shfl_xor(m, 32, 64));
+// Packed codes are written once and not read back by this kernel: non-temporal store.
+__device__ __forceinline__ void store_codes(uint32_t* p, uint32_t v) { __builtin_nontemporal_store(v, p); }
+
+// Max of a non-negative float over lanes: non-negative floats order like their bit patterns,
+// so the reduction runs on unsigned integers (one DPP-fused v_max_u32 per step).  ROW_BITS of
+// the four DPP row patterns are used (lanes that share a row differ in those bits), then the two
+// cross-row steps.
+template <int ROW_BITS = 4>
+__device__ __forceinline__ float wave_absmax(float mf) {
+    uint32_t m = __float_as_uint(mf);
+    m = max(m, dpp_u<kDppXor1>(m));
+    m = max(m, dpp_u<kDppXor2>(m));
+    if (ROW_BITS >= 3) m = max(m, dpp_u<kDppHalfMirror>(m));
+    if (ROW_BITS >= 4) m = max(m, dpp_u<kDppRor8>(m));
+    m = max(m, (uint32_t)__shfl_xor((int)m, 16, 64));
+    m = max(m, (uint32_t)__shfl_xor((int)m, 32, 64));
+    return __uint_as_float(m);
+}
+
+// c / m for m > 0 with c = ch + cl (float pair): reciprocal, one Newton step, one correction of
+// the quotient, then the low part; about half an ulp.  Used where a full IEEE division per
+// row would be a visible cost (short rows).
+__device__ __forceinline__ float div_pair(float ch, float cl, float m) {
+    float r = __builtin_amdgcn_rcpf(m);
+    r = fmaf(fmaf(-m, r, 1.0f), r, r);
+    float q = ch * r;
+    q = fmaf(fmaf(-q, m, ch), r, q);
+    return fmaf(cl, r, q);
+}
+
+// 16-byte non-temporal load of a whole chunk (no bounds handling).
+__device__ __forceinline__ u32x4 load16(const uint16_t* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
 }
 
 }  // namespace
