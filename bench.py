@@ -25,6 +25,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 RING_BYTES = 1536 << 20         # ring of batches: well above the 256 MB last-level cache
+# HBM bytes per timed launch measured with rocprofv3 PMC counters (FETCH_SIZE, WRITE_SIZE, each scaled
+# by what the same counter reads for a 256 MiB copy); it does not depend on timing, so it is recorded
+# here from profiles/hbm_traffic_wave_sylvester_llama_hidden_b4.txt rather than re-measured per run
+TRAFFIC_BYTES_PER_LAUNCH = {"wave_sylvester": 21_160_770}
 
 
 def algorithmic_bytes_per_row(d: int, n: int, bits: int, elem: int = 2) -> int:
@@ -93,6 +97,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-steady-state", action="store_true")
+    ap.add_argument("--pmc-calibrate", action="store_true",
+                    help="also run one 256 MiB device-to-device copy, the known-size reference that "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (rows are independent, "
@@ -183,9 +190,15 @@ def main():
         "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "eager_ms_per_step": eager_ms,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "kernel": kernel_name,
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(kernel_name), "kernel": kernel_name,
                      "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": batch_bytes},
     }
+    if args.pmc_calibrate:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(7)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_steady_state:
         out["steady_state"] = time_steady_state(torch, binding, h, base, bits, clip, 131072)
     if not args.no_cpu_baseline:
