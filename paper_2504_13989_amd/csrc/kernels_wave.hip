@@ -28,6 +28,7 @@ namespace {
 template <int T, int BITS, bool FULL>
 __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
     constexpr int ROW_DWORDS = 512 * T * BITS / 32;
+    __shared__ __attribute__((aligned(16))) uint8_t stage[BITS == 3 ? ROW_DWORDS * 4 : 16];
     const int lane = threadIdx.x;
     const int g = lane >> 4, cphys = lane & 15;
     const int c = (cphys & 4) ? (cphys ^ 3) : cphys;    // logical column index
@@ -83,13 +84,15 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
             const uint32_t w = Quant<BITS>::pack8(acc[t][0][0], acc[t][0][1], acc[t][0][2], acc[t][0][3],
                                                   acc[t][1][0], acc[t][1][1], acc[t][1][2], acc[t][1][3], s);
             const int word = t * 64 + chunk;            // 8-element group index inside the row
-            if (BITS == 4) {
+            if (BITS == 4)
                 store_codes(out + word, w);
-            } else {
-                const int qpos = c & 3;
-                const uint32_t dw = merge24<true>(w, qpos);
-                if (qpos < 3) store_codes(out + (word >> 2) * 3 + qpos, dw);
-            }
+            else
+                stage24(stage, word, w);
+        }
+        if (BITS == 3) {
+            __syncthreads();
+            copy_out16<ROW_DWORDS / 4>(stage, out, ROW_DWORDS / 4, lane);
+            __syncthreads();
         }
         if (lane == 0) a.scales[row] = (float)(a.c2 * (double)m);
     }
@@ -202,9 +205,28 @@ __global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
 // loads into one operand (a 16-bit transpose inside the lane, v_perm_b32).  Outputs come back
 // with 8 block rows x 8 consecutive columns per lane; butterflies over i (registers) and c
 // (DPP), quantization and packing then work exactly as in the Sylvester kernel.
-template <int BITS, bool FULL>
+// The four fused cross-lane stages on N (1..4) consecutive values.
+template <int N>
+__device__ __forceinline__ void fused_group(float* v, const float (&sf)[4]) {
+    if constexpr (N == 4) {
+        f32x4 q = {v[0], v[1], v[2], v[3]};
+        lane_stages_fused(q, sf[0], sf[1], sf[2], sf[3]);
+        v[0] = q[0]; v[1] = q[1]; v[2] = q[2]; v[3] = q[3];
+    } else if constexpr (N == 3) {
+        lane_stages_fused3(v[0], v[1], v[2], sf[0], sf[1], sf[2], sf[3]);
+    } else if constexpr (N == 2) {
+        lane_stages_fused2(v[0], v[1], sf[0], sf[1], sf[2], sf[3]);
+    } else {
+        lane_stages_fused1(v[0], sf[0], sf[1], sf[2], sf[3]);
+    }
+}
+
+template <int BITS, bool FULL, int NV>
 __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
     constexpr int ROW_DWORDS_PER_A = 128 * BITS / 32;
+    constexpr int NH1 = NV > 4 ? NV - 4 : 0;              // live registers of the second half
+    constexpr int NH0 = NV > 4 ? 4 : NV;
+    __shared__ __attribute__((aligned(16))) uint8_t stage[BITS == 3 ? 32 * 48 : 16];
     const int lane = threadIdx.x;
     const int g = lane >> 4, cphys = lane & 15;
     const int c = (cphys & 4) ? (cphys ^ 3) : cphys;     // logical column chunk
@@ -214,28 +236,20 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
     for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
     const float flip = (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;
 
-    constexpr float kMagic = 12582912.0f;
-    constexpr float kLo = kMagic, kHi = kMagic + (float)((1 << BITS) - 1);
-    constexpr float kBias = kMagic + (float)(1 << (BITS - 1));
-    constexpr uint32_t kMagicBits = 0x4B400000u;
-    uint32_t csum = 0, msb = 0;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        csum += kMagicBits << (BITS * r);
-        msb |= 1u << (BITS * r + BITS - 1);
-    }
-
-    // block rows at or beyond pb meet zero columns of the block operand, so what is loaded for
-    // them does not matter as long as it is in bounds: reuse the last real block row
-    int eoff[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) eoff[t] = (8 * g + t < pb ? 8 * g + t : pb - 1) * 128 + c * 8;
+    // DPP row g loads the 8 block rows base_g .. base_g + 7, base_g = min(8 g, pb - 8): always inside
+    // the row, at constant offsets from one address.  Where that overlaps the rows of g - 1 the
+    // block operand has zero columns, so the duplicates contribute nothing.
+    const int base_g = 8 * g < pb - 8 ? 8 * g : pb - 8;
+    const int e_base = base_g * 128 + c * 8;
     for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
-        const uint16_t* xr = a.X + row * a.ld;
+        const uint16_t* xr = a.X + row * a.ld + e_base;
         u32x4 R[8];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) R[t] = FULL ? load16(xr + eoff[t]) : load_chunk(xr, eoff[t], a.d);
-        f32x4 acc[8][2];                                  // [column i][half]: 4 block rows each
+        for (int t = 0; t < 8; ++t)
+            R[t] = FULL ? load16(xr + t * 128) : load_chunk(xr - e_base, e_base + t * 128, a.d);
+        // y[column i][j]: register j = 4 h + ip holds block rows 4 j .. 4 j + 3 (one per DPP row g);
+        // only the NV = ceil(pb / 4) registers that hold real block rows are carried further
+        float y[8][NV];
 #pragma unroll
         for (int ic = 0; ic < 8; ++ic) {
             u32x4 bm;
@@ -245,8 +259,14 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
                 bm[w] = __builtin_amdgcn_perm(R[2 * w + 1][ic >> 1], R[2 * w][ic >> 1], sel);
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
             const bf16x8 b8 = __builtin_bit_cast(bf16x8, bm);
-            acc[ic][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), b8, z, 0, 0, 0);
-            acc[ic][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), b8, z, 0, 0, 0);
+            const f32x4 d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), b8, z, 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < NH0; ++j) y[ic][j] = d0[j];
+            if constexpr (NH1 > 0) {
+                const f32x4 d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), b8, z, 0, 0, 0);
+#pragma unroll
+                for (int j = 0; j < NH1; ++j) y[ic][4 + j] = d1[j];
+            }
         }
 #pragma unroll
         for (int s = 1; s < 8; s <<= 1)
@@ -254,54 +274,44 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
             for (int ic = 0; ic < 8; ++ic)
                 if (!(ic & s))
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const f32x4 u = acc[ic][h], v = acc[ic | s][h];
-                        acc[ic][h] = u + v;
-                        acc[ic | s][h] = u - v;
+                    for (int j = 0; j < NV; ++j) {
+                        const float u = y[ic][j], v = y[ic | s][j];
+                        y[ic][j] = u + v;
+                        y[ic | s][j] = u - v;
                     }
         float m = 0.0f;
 #pragma unroll
-        for (int ic = 0; ic < 8; ++ic)
+        for (int ic = 0; ic < 8; ++ic) {
+            fused_group<NH0>(&y[ic][0], sf);
+            if constexpr (NH1 > 0) fused_group<NH1>(&y[ic][4], sf);
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                f32x4 v = acc[ic][h];
-                lane_stages_fused(v, sf[0], sf[1], sf[2], sf[3]);
-                acc[ic][h] = v;
-                m = absmax4(m, v);
-            }
+            for (int j = 0; j < NV; ++j) m = __builtin_fmaxf(m, __builtin_fabsf(y[ic][j]));
+        }
         m = wave_absmax<4>(m);
         const float s = m > 0.0f ? flip * (float)(a.c1 / (double)m) : 0.0f;
         const float scale = (float)(a.c2 * (double)m);
 
         uint32_t* out = a.codes + row * (int64_t)(ROW_DWORDS_PER_A * pb);
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int ip = 0; ip < 4; ++ip) {
-                const int ao = 16 * h + 4 * ip + g;        // output block row of this register
-                uint32_t w = 0;
-#pragma unroll
-                for (int r = 7; r >= 0; --r) {
-                    float u = fmaf(acc[r][h][ip], s, kBias);
-                    u = __builtin_amdgcn_fmed3f(u, kLo, kHi);
-                    w = (w << BITS) + __builtin_bit_cast(uint32_t, u);
-                }
-                w = (w - csum) ^ msb;
-                const int word = ao * 16 + c;
-                if (BITS == 4) {
-                    if (ao < pb) store_codes(out + word, w);
-                } else {
-                    uint32_t nxt = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, kDppNext, 0xf, 0x5, true);
-                    nxt = (uint32_t)__builtin_amdgcn_update_dpp((int)nxt, (int)w, kDppPrev, 0xf, 0xa, false);
-                    const int qpos = c & 3;
-                    const uint32_t dw = (w >> (8 * qpos)) | (nxt << (24 - 8 * qpos));
-                    if (ao < pb && qpos < 3) store_codes(out + (word >> 2) * 3 + qpos, dw);
-                }
+        for (int j = 0; j < NV; ++j) {
+            const int ao = 4 * j + g;                      // output block row of this register
+            const uint32_t w = Quant<BITS>::pack8(y[0][j], y[1][j], y[2][j], y[3][j], y[4][j], y[5][j],
+                                                  y[6][j], y[7][j], s);
+            const int word = ao * 16 + c;
+            if (BITS == 4) {
+                if (ao < pb) store_codes(out + word, w);
+            } else {
+                stage24(stage, word, w);                   // block rows >= pb land beyond the copied part
             }
+        }
+        if (BITS == 3) {
+            __syncthreads();
+            copy_out16<32 * 3>(stage, out, pb * 3, lane);
+            __syncthreads();
+        }
         if (lane == 0) a.scales[row] = scale;
     }
 }
-
 
 // ---------------------------------------------------------------------------------------------
 // quant_error for bf16 rows of Sylvester order n = 512 T (1024 .. 8192): the rotation of
@@ -446,19 +456,33 @@ std::vector<uint32_t> wave_sylvester_tiles() {
     return t;
 }
 
-// Matrix-core operand of a 32x32 zero-padded +-1 block `bm` (row-major, order pb) for the block
-// kernel: operand lane (gA, mm) holds, for half hh, row 16 hh + 4 (mm & 3) + (mm >> 2) of the
-// block at the 8 contraction slots a = 8 gA + t.
+template <int NV>
+static void launch_block_nv(int bits, bool full, unsigned grid, hipStream_t s, const WaveArgs& w, int pb) {
+    if (bits == 4) {
+        if (full) hipLaunchKernelGGL((k_wave_block<4, true, NV>), dim3(grid), dim3(64), 0, s, w, pb);
+        else hipLaunchKernelGGL((k_wave_block<4, false, NV>), dim3(grid), dim3(64), 0, s, w, pb);
+    } else {
+        if (full) hipLaunchKernelGGL((k_wave_block<3, true, NV>), dim3(grid), dim3(64), 0, s, w, pb);
+        else hipLaunchKernelGGL((k_wave_block<3, false, NV>), dim3(grid), dim3(64), 0, s, w, pb);
+    }
+}
+
+// Matrix-core operand of a +-1 block `bm` (row-major, order 8 <= pb <= 32) for the block kernel.
+// Contraction slot (gA, i) carries block row r = min(8 gA, pb - 8) + i of the input, and counts
+// only where r >= 8 gA (below that it duplicates a row of the previous slot group): other
+// columns are zero.  Operand lane (gA, mm) holds, for half hh, row 16 hh + 4 (mm & 3) + (mm >> 2)
+// of the block.
 std::vector<uint32_t> wave_block_tiles(const std::vector<int8_t>& bm, int pb) {
     std::vector<uint32_t> t(2 * 64 * 4, 0u);
     for (int hh = 0; hh < 2; ++hh)
         for (int lane = 0; lane < 64; ++lane) {
             const int gA = lane >> 4, mm = lane & 15;
             const int ao = 16 * hh + 4 * (mm & 3) + (mm >> 2);
+            const int base = 8 * gA < pb - 8 ? 8 * gA : pb - 8;
             for (int i = 0; i < 8; ++i) {
-                const int ai = 8 * gA + i;
+                const int ai = base + i;
                 uint32_t v = 0;
-                if (ao < pb && ai < pb) v = bm[(size_t)ao * pb + ai] > 0 ? 0x3F80u : 0xBF80u;
+                if (ao < pb && ai >= 8 * gA && ai < pb) v = bm[(size_t)ao * pb + ai] > 0 ? 0x3F80u : 0xBF80u;
                 t[(hh * 64 + lane) * 4 + (i >> 1)] |= v << ((i & 1) * 16);
             }
         }
@@ -467,7 +491,7 @@ std::vector<uint32_t> wave_block_tiles(const std::vector<int8_t>& bm, int pb) {
 
 bool wave_block_supports(const rq_hadamard* h, const RowArgs& a) {
     if (h->device < 0 || !h->d_tiles || a.dtype != RQ_BF16 || a.p == 1) return false;
-    if (a.log2m < 7 || (a.p << (a.log2m - 7)) > 32) return false;
+    if (a.log2m < 7 || (a.p << (a.log2m - 7)) > 32 || (a.p << (a.log2m - 7)) < 8) return false;
     if ((reinterpret_cast<uintptr_t>(a.X) & 15) != 0 || (a.ld & 7) != 0 || (a.d & 7) != 0) return false;
     return true;
 }
@@ -482,12 +506,15 @@ int wave_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float cli
     const int64_t cap = 1 << 24;
     const unsigned grid = (unsigned)(a.rows < cap ? a.rows : cap);
     const bool full = a.d == a.n;
-    if (a.bits == 4) {
-        if (full) hipLaunchKernelGGL((k_wave_block<4, true>), dim3(grid), dim3(64), 0, s, w, pb);
-        else hipLaunchKernelGGL((k_wave_block<4, false>), dim3(grid), dim3(64), 0, s, w, pb);
-    } else {
-        if (full) hipLaunchKernelGGL((k_wave_block<3, true>), dim3(grid), dim3(64), 0, s, w, pb);
-        else hipLaunchKernelGGL((k_wave_block<3, false>), dim3(grid), dim3(64), 0, s, w, pb);
+    switch ((pb + 3) / 4) {
+        case 2: launch_block_nv<2>(a.bits, full, grid, s, w, pb); break;
+        case 3: launch_block_nv<3>(a.bits, full, grid, s, w, pb); break;
+        case 4: launch_block_nv<4>(a.bits, full, grid, s, w, pb); break;
+        case 5: launch_block_nv<5>(a.bits, full, grid, s, w, pb); break;
+        case 6: launch_block_nv<6>(a.bits, full, grid, s, w, pb); break;
+        case 7: launch_block_nv<7>(a.bits, full, grid, s, w, pb); break;
+        case 8: launch_block_nv<8>(a.bits, full, grid, s, w, pb); break;
+        default: return RQ_ERR_NO_ORDER;
     }
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }

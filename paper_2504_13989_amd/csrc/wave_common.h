@@ -71,6 +71,54 @@ __device__ __forceinline__ void lane_stages_fused(f32x4& v, float s0, float s1, 
     v[0] = x0; v[1] = x1; v[2] = x2; v[3] = x3;
 }
 
+// The same on one, two or three values; with fewer than three values in flight an s_nop keeps
+// two wait states between a value's consecutive stages.
+__device__ __forceinline__ void lane_stages_fused1(float& x0, float s0, float s1, float s2, float s3) {
+    asm("s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %0, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %0, %2 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %0, %3 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %0, %4 row_ror:8 row_mask:0xf bank_mask:0xf"
+        : "+v"(x0)
+        : "v"(s0), "v"(s1), "v"(s2), "v"(s3));
+}
+__device__ __forceinline__ void lane_stages_fused2(float& x0, float& x1, float s0, float s1, float s2, float s3) {
+    asm("s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %0, %2 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %2 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_fmac_f32_dpp %0, %0, %3 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %3 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_fmac_f32_dpp %0, %0, %4 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %4 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_fmac_f32_dpp %0, %0, %5 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %5 row_ror:8 row_mask:0xf bank_mask:0xf"
+        : "+v"(x0), "+v"(x1)
+        : "v"(s0), "v"(s1), "v"(s2), "v"(s3));
+}
+__device__ __forceinline__ void lane_stages_fused3(float& x0, float& x1, float& x2, float s0, float s1, float s2, float s3) {
+    asm("s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %0, %3 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %3 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %3 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %0, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %0, %5 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %5 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %5 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %0, %6 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %6 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %6 row_ror:8 row_mask:0xf bank_mask:0xf"
+        : "+v"(x0), "+v"(x1), "+v"(x2)
+        : "v"(s0), "v"(s1), "v"(s2), "v"(s3));
+}
+
 __device__ __forceinline__ float absmax4(float m, const f32x4& v) {
     m = __builtin_fmaxf(__builtin_fmaxf(m, __builtin_fabsf(v[0])), __builtin_fabsf(v[1]));
     return __builtin_fmaxf(__builtin_fmaxf(m, __builtin_fabsf(v[2])), __builtin_fabsf(v[3]));
@@ -146,6 +194,28 @@ __device__ __forceinline__ uint32_t merge24(uint32_t w, int qpos) {
         nxt = dpp_u<kDppNext>(w);
     }
     return (w >> (8 * qpos)) | (nxt << (24 - 8 * qpos));
+}
+
+// b = 3 output path.  A lane holds 24 bits per group of 8 columns, which is not a whole dword;
+// the row's packed bytes are therefore assembled in LDS (three byte writes per group, no
+// cross-lane merging, no per-group predicates) and then copied to memory as 16-byte units by
+// all lanes.  `stage` is private to the wave's workgroup and 16-byte aligned.
+__device__ __forceinline__ void stage24(uint8_t* stage, int group, uint32_t w) {
+    uint8_t* p = stage + group * 3;
+    p[0] = (uint8_t)w;
+    p[1] = (uint8_t)(w >> 8);
+    p[2] = (uint8_t)(w >> 16);
+}
+
+template <int MAX_UNITS>
+__device__ __forceinline__ void copy_out16(const uint8_t* stage, uint32_t* out, int units, int lane) {
+#pragma unroll
+    for (int k = 0; k * 64 < MAX_UNITS; ++k) {
+        const int idx = k * 64 + lane;
+        if (idx < units)
+            __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(stage + idx * 16),
+                                        reinterpret_cast<u32x4*>(out) + idx);
+    }
 }
 
 // Packed codes are written once and not read back by this kernel: non-temporal store.

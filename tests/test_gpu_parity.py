@@ -74,6 +74,7 @@ def test_small_cases(torch, name, rows, variant):
                                        (3584, 3500, "bf16"), (3072, 3000, "f32"), (1536, 1536, "bf16"),
                                        (2048, 2048, "bf16"), (8192, 8192, "bf16"), (512, 512, "bf16"),
                                        (640, 640, "bf16"), (64, 64, "bf16"), (32, 20, "f32"),
+                                       (2560, 2560, "bf16"), (2560, 2400, "bf16"), (5120, 5120, "bf16"),
                                        # blocks above 32: 44 (q=43), 60 (II, q=29), 84, 108, 168, 200, 252
                                        (44 * 128, 44 * 128, "bf16"), (60 * 128, 7600, "bf16"),
                                        (84 * 128, 84 * 128, "bf16"), (108 * 128, 108 * 128, "bf16"),
