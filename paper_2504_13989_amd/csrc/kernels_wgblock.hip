@@ -3,79 +3,103 @@
 // 2.3.2, 2.3.3) - e.g. 18944 = 148 * 128 with the order-148 Paley II block.
 //
 // The dense block product Y1[pb x 128] = B * X[pb x 128] is a real contraction (pb adds per
-// output), so it runs on the matrix cores; W = ceil(pb / 32) waves share a row:
-//   phase 1  wave w loads block rows 32w .. 32w+31 (16-byte chunks), transposes 16-bit values
-//            inside each lane (v_perm_b32) so that 8 consecutive block rows of one column sit in
-//            one 16-byte operand, and writes the operands to LDS laid out [column][block row],
-//            16-byte units xor-swizzled by the lane's column group so that writes and reads
-//            are free of bank conflicts;
-//   phase 2  wave w computes output block rows 32w .. 32w+31 for all 128 columns:
-//            2 (row halves) x 8 (column tiles) x W (contraction steps) v_mfma_f32_16x16x32_bf16,
-//            its 2 W operand tiles of B resident in registers, the data operands read from LDS;
+// output), so it runs on the matrix cores.  NW = ceil(pb / 16) waves share a row, wave w owning
+// the 16 block rows 16 w .. 16 w + 15 on input and on output:
+//   phase 1  the wave loads its block rows (16-byte chunks, 4 per lane), transposes 16-bit
+//            values inside each lane (v_perm_b32) so that consecutive block rows of one column are
+//            adjacent, and writes them to LDS laid out [column][block row]; 16-byte units are
+//            xor-swizzled by the lane's column group so that writes and reads avoid bank
+//            conflicts;
+//   phase 2  the wave computes its 16 output block rows for all 128 columns: 8 column tiles x
+//            KK = ceil(pb / 32) contraction steps of v_mfma_f32_16x16x32_bf16, its KK operand tiles of
+//            B resident in registers, the data operands read from LDS (16 bytes per lane);
 //   phase 3  128-point transform along the columns: three register stages, four fused DPP
 //            stages, absmax; workgroup absmax through LDS;
-//   phase 4  scale, round/clamp, pack, store (as in the one-wave block kernel).
-// Column tile nt holds columns {8 c + nt}, so a lane ends up with 8 consecutive columns of 8
-// block rows.  A workgroup loops over rows; two barriers per row order the LDS reuse.
+//   phase 4  scale, round/clamp, pack; b = 4 stores dwords, b = 3 assembles the row's bytes in LDS
+//            and all waves copy them out in 16-byte units.
+// Column tile nt holds columns {8 c + nt}, so a lane ends up with 8 consecutive columns of 4
+// block rows.  One wave per 16 block rows keeps a wave near 100 VGPRs, so two workgroups share a
+// CU.  A workgroup loops over rows; barriers order the LDS reuse.
 #include "wave_common.h"
 
 namespace rq {
 namespace {
 
-template <int W>
-constexpr int wg_chunks() { return ((4 * W + 7) / 8) * 8; }   // 16-byte units per LDS column
+template <int KK>
+constexpr int wg_chunks() { return ((4 * KK + 7) / 8) * 8; }   // 16-byte units per LDS column
 
-template <int W, int BITS>
-__global__ __launch_bounds__(64 * W) void k_wg_block(WaveArgs a, int pb) {
-    constexpr int NCH = wg_chunks<W>();
-    extern __shared__ u32x4 lds[];                     // [128 columns][NCH]
-    __shared__ float wmax[8];
+template <int KK>
+constexpr size_t wg_lds_bytes() { return (size_t)128 * wg_chunks<KK>() * 16 + (size_t)KK * 32 * 48; }
+
+// Waves of a workgroup are placed on the four SIMDs round robin from SIMD 0, so two resident
+// workgroups of 9 or 10 waves put 6 waves on a SIMD: each wave may then hold at most 80 VGPRs.
+// The register budget is requested accordingly (6 waves per SIMD up to pb = 160, 4 above).
+template <int KK, int BITS, bool FULL>
+__global__ __launch_bounds__(128 * KK) __attribute__((amdgpu_waves_per_eu(KK <= 5 ? 6 : 4)))
+void k_wg_block(WaveArgs a, int pb) {
+    constexpr int NCH = wg_chunks<KK>();
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
+    uint8_t* const ops = lds_raw;                        // [128 columns][NCH] x 16 bytes
+    uint8_t* const stage = lds_raw + 128 * NCH * 16;     // packed codes of the row (b = 3)
+    __shared__ float wmax[16];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nw = blockDim.x >> 6;                      // ceil(pb / 16)
     const int g = lane >> 4, cphys = lane & 15;
     const int c = (cphys & 4) ? (cphys ^ 3) : cphys;    // logical column group (8 columns)
     const int swz = c & 7;
 
-    u32x4 A[2][W];
+    u32x4 A[KK];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int kk = 0; kk < W; ++kk) A[h][kk] = a.tiles[((wave * 2 + h) * W + kk) * 64 + lane];
+    for (int kk = 0; kk < KK; ++kk) A[kk] = a.tiles[(wave * KK + kk) * 64 + lane];
     float sf[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
     const float flip = (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;
 
+    // phase-1 geometry: lane (g, c) loads block rows 16 wave + 4 g + t, t = 0..3 (rows at or beyond pb
+    // meet zero columns of B: any in-bounds data will do, the last real row is reused)
+    int eoff[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int r = 16 * wave + 4 * g + t;
+        eoff[t] = (r < pb ? r : pb - 1) * 128 + c * 8;
+    }
+    // 8-byte half of the 16-byte unit that holds block rows 8 q .. 8 q + 7, q = 2 wave + g / 2
+    const int wr_unit = ((2 * wave + (g >> 1)) ^ swz) * 16 + (g & 1) * 8;
+
+    // Units for block rows at or beyond 16 nw are never written by phase 1 but are read by the last
+    // contraction step (against zero columns of B): clear the buffer once so they hold zeros.
+    for (int i = threadIdx.x; i < 128 * NCH; i += blockDim.x)
+        reinterpret_cast<u32x4*>(ops)[i] = u32x4{0u, 0u, 0u, 0u};
+    __syncthreads();
+
     for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
         const uint16_t* xr = a.X + row * a.ld;
         // ---- phase 1
-        u32x4 R[8];
+        u32x4 R[4];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int ar = 32 * wave + 8 * g + t;
-            R[t] = load_chunk(xr, ar * 128 + c * 8, ar < pb ? a.d : 0);
-        }
+        for (int t = 0; t < 4; ++t) R[t] = FULL ? load16(xr + eoff[t]) : load_chunk(xr, eoff[t], a.d);
 #pragma unroll
         for (int ic = 0; ic < 8; ++ic) {
-            u32x4 bm;
             const uint32_t sel = (ic & 1) ? 0x07060302u : 0x05040100u;
-#pragma unroll
-            for (int w = 0; w < 4; ++w)
-                bm[w] = __builtin_amdgcn_perm(R[2 * w + 1][ic >> 1], R[2 * w][ic >> 1], sel);
-            lds[(8 * c + ic) * NCH + ((4 * wave + g) ^ swz)] = bm;
+            uint2 v;
+            v.x = __builtin_amdgcn_perm(R[1][ic >> 1], R[0][ic >> 1], sel);
+            v.y = __builtin_amdgcn_perm(R[3][ic >> 1], R[2][ic >> 1], sel);
+            *reinterpret_cast<uint2*>(ops + (8 * c + ic) * (NCH * 16) + wr_unit) = v;
         }
         __syncthreads();
         // ---- phase 2
-        f32x4 acc[8][2];
+        f32x4 acc[8];
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) {
-            acc[nt][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-            acc[nt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+            acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int kk = 0; kk < W; ++kk) {
-                const bf16x8 b8 = __builtin_bit_cast(bf16x8, lds[(8 * c + nt) * NCH + ((4 * kk + g) ^ swz)]);
-                acc[nt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[0][kk]), b8, acc[nt][0], 0, 0, 0);
-                acc[nt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[1][kk]), b8, acc[nt][1], 0, 0, 0);
+            for (int kk = 0; kk < KK; ++kk) {
+                const u32x4 raw = *reinterpret_cast<const u32x4*>(ops + (8 * c + nt) * (NCH * 16) +
+                                                                  ((4 * kk + g) ^ swz) * 16);
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[kk]),
+                                                                   __builtin_bit_cast(bf16x8, raw), acc[nt], 0, 0, 0);
             }
         }
         // ---- phase 3
@@ -83,112 +107,118 @@ __global__ __launch_bounds__(64 * W) void k_wg_block(WaveArgs a, int pb) {
         for (int s = 1; s < 8; s <<= 1)
 #pragma unroll
             for (int nt = 0; nt < 8; ++nt)
-                if (!(nt & s))
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const f32x4 u = acc[nt][h], v = acc[nt | s][h];
-                        acc[nt][h] = u + v;
-                        acc[nt | s][h] = u - v;
-                    }
+                if (!(nt & s)) {
+                    const f32x4 u = acc[nt], v = acc[nt | s];
+                    acc[nt] = u + v;
+                    acc[nt | s] = u - v;
+                }
         float m = 0.0f;
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                f32x4 v = acc[nt][h];
-                lane_stages_fused(v, sf[0], sf[1], sf[2], sf[3]);
-                acc[nt][h] = v;
-                m = absmax4(m, v);
-            }
-        m = wave_absmax(m);
+        for (int nt = 0; nt < 8; ++nt) {
+            f32x4 v = acc[nt];
+            lane_stages_fused(v, sf[0], sf[1], sf[2], sf[3]);
+            acc[nt] = v;
+            m = absmax4(m, v);
+        }
+        m = wave_absmax<4>(m);
         if (lane == 0) wmax[wave] = m;
         __syncthreads();    // also: every wave is done reading this row's operands from LDS
         m = wmax[0];
-#pragma unroll
-        for (int w = 1; w < W; ++w) m = fmaxf(m, wmax[w]);
+        for (int w = 1; w < nw; ++w) m = fmaxf(m, wmax[w]);
         // ---- phase 4
         const float s = m > 0.0f ? flip * (float)(a.c1 / (double)m) : 0.0f;
         uint32_t* out = a.codes + row * (int64_t)(128 * BITS / 32) * pb;
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int ip = 0; ip < 4; ++ip) {
-                const int ao = 32 * wave + 16 * h + 4 * ip + g;   // output block row of this register
-                const uint32_t w = Quant<BITS>::pack8(acc[0][h][ip], acc[1][h][ip], acc[2][h][ip],
-                                                      acc[3][h][ip], acc[4][h][ip], acc[5][h][ip],
-                                                      acc[6][h][ip], acc[7][h][ip], s);
-                const int word = ao * 16 + c;
-                if (BITS == 4) {
-                    if (ao < pb) store_codes(out + word, w);
-                } else {
-                    const int qpos = c & 3;
-                    const uint32_t dw = merge24<true>(w, qpos);
-                    if (ao < pb && qpos < 3) store_codes(out + (word >> 2) * 3 + qpos, dw);
-                }
+        for (int ip = 0; ip < 4; ++ip) {
+            const int ao = 16 * wave + 4 * ip + g;      // output block row of this register
+            const uint32_t w = Quant<BITS>::pack8(acc[0][ip], acc[1][ip], acc[2][ip], acc[3][ip],
+                                                  acc[4][ip], acc[5][ip], acc[6][ip], acc[7][ip], s);
+            const int word = ao * 16 + c;
+            if (BITS == 4) {
+                if (ao < pb) store_codes(out + word, w);
+            } else {
+                stage24(stage, word, w);                // block rows >= pb land beyond the copied part
             }
+        }
+        if (BITS == 3) {
+            __syncthreads();
+            const int units = pb * 3;                   // 16-byte units of the packed row
+            for (int idx = threadIdx.x; idx < units; idx += blockDim.x)
+                __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(stage + idx * 16),
+                                            reinterpret_cast<u32x4*>(out) + idx);
+            // the next row's stage writes come after two more barriers: no barrier needed here
+        }
         if (threadIdx.x == 0) a.scales[row] = (float)(a.c2 * (double)m);
     }
 }
 
-template <int W>
-size_t wg_lds_bytes() { return (size_t)128 * wg_chunks<W>() * 16; }
-
-template <int W>
-int launch_w(const rq_hadamard* h, const WaveArgs& a, int bits, int pb, hipStream_t s) {
-    const size_t lds = wg_lds_bytes<W>();
-    const int per_cu = (int)((size_t)h->max_lds / (lds + 64));
-    const int64_t cap = (int64_t)h->num_cu * (per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu));
+template <int KK>
+int launch_kk(const rq_hadamard* h, const WaveArgs& a, int bits, int pb, hipStream_t s) {
+    const size_t lds = wg_lds_bytes<KK>();
+    const int nw = (pb + 15) / 16;
+    int per_cu = (int)((size_t)h->max_lds / (lds + 128));
+    const int by_waves = nw <= 10 ? 2 : 1;               // see the register budget note at the kernel
+    if (per_cu > by_waves) per_cu = by_waves;
+    if (per_cu < 1) per_cu = 1;
+    const int64_t cap = (int64_t)h->num_cu * per_cu;
     const unsigned grid = (unsigned)(a.rows < cap ? a.rows : cap);
-    if (bits == 4)
-        hipLaunchKernelGGL((k_wg_block<W, 4>), dim3(grid), dim3(64 * W), lds, s, a, pb);
-    else
-        hipLaunchKernelGGL((k_wg_block<W, 3>), dim3(grid), dim3(64 * W), lds, s, a, pb);
+    const bool full = a.d == 128 * pb;
+    if (bits == 4) {
+        if (full) hipLaunchKernelGGL((k_wg_block<KK, 4, true>), dim3(grid), dim3(64 * nw), lds, s, a, pb);
+        else hipLaunchKernelGGL((k_wg_block<KK, 4, false>), dim3(grid), dim3(64 * nw), lds, s, a, pb);
+    } else {
+        if (full) hipLaunchKernelGGL((k_wg_block<KK, 3, true>), dim3(grid), dim3(64 * nw), lds, s, a, pb);
+        else hipLaunchKernelGGL((k_wg_block<KK, 3, false>), dim3(grid), dim3(64 * nw), lds, s, a, pb);
+    }
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 
-template <int W>
-bool prepare_w() {
-    const int lds = (int)wg_lds_bytes<W>();
-    if (lds <= 48 * 1024) return true;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(k_wg_block<W, 4>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, lds) == hipSuccess &&
-           hipFuncSetAttribute(reinterpret_cast<const void*>(k_wg_block<W, 3>),
+template <typename K>
+bool raise_lds(K kernel, int lds) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                hipFuncAttributeMaxDynamicSharedMemorySize, lds) == hipSuccess;
+}
+
+template <int KK>
+bool prepare_kk() {
+    const int lds = (int)wg_lds_bytes<KK>();
+    if (lds <= 48 * 1024) return true;
+    return raise_lds(k_wg_block<KK, 4, true>, lds) && raise_lds(k_wg_block<KK, 4, false>, lds) &&
+           raise_lds(k_wg_block<KK, 3, true>, lds) && raise_lds(k_wg_block<KK, 3, false>, lds);
 }
 
 }  // namespace
 
-// Operand tiles of the zero-padded block `bm` (order pb) for W = ceil(pb/32) waves:
-// [wave][half][kk][lane] x 16 bytes; operand lane (gA, mm) of (wave, half, kk) holds block row
-// 32 wave + 16 half + 4 (mm & 3) + (mm >> 2) at the contraction slots a = 32 kk + 8 gA + i.
+// Operand tiles of the zero-padded block `bm` (order pb): [wave][kk][lane] x 16 bytes, wave <
+// ceil(pb/16), kk < ceil(pb/32); operand lane (gA, mm) of (wave, kk) holds block row
+// 16 wave + 4 (mm & 3) + (mm >> 2) at the contraction slots a = 32 kk + 8 gA + i.
 std::vector<uint32_t> wg_block_tiles(const std::vector<int8_t>& bm, int pb) {
-    const int W = (pb + 31) / 32;
-    std::vector<uint32_t> t((size_t)W * 2 * W * 64 * 4, 0u);
-    for (int w = 0; w < W; ++w)
-        for (int hh = 0; hh < 2; ++hh)
-            for (int kk = 0; kk < W; ++kk)
-                for (int lane = 0; lane < 64; ++lane) {
-                    const int gA = lane >> 4, mm = lane & 15;
-                    const int ao = 32 * w + 16 * hh + 4 * (mm & 3) + (mm >> 2);
-                    for (int i = 0; i < 8; ++i) {
-                        const int ai = 32 * kk + 8 * gA + i;
-                        uint32_t v = 0;
-                        if (ao < pb && ai < pb) v = bm[(size_t)ao * pb + ai] > 0 ? 0x3F80u : 0xBF80u;
-                        t[((((size_t)w * 2 + hh) * W + kk) * 64 + lane) * 4 + (i >> 1)] |= v << ((i & 1) * 16);
-                    }
+    const int NW = (pb + 15) / 16, KK = (pb + 31) / 32;
+    std::vector<uint32_t> t((size_t)NW * KK * 64 * 4, 0u);
+    for (int w = 0; w < NW; ++w)
+        for (int kk = 0; kk < KK; ++kk)
+            for (int lane = 0; lane < 64; ++lane) {
+                const int gA = lane >> 4, mm = lane & 15;
+                const int ao = 16 * w + 4 * (mm & 3) + (mm >> 2);
+                for (int i = 0; i < 8; ++i) {
+                    const int ai = 32 * kk + 8 * gA + i;
+                    uint32_t v = 0;
+                    if (ao < pb && ai < pb) v = bm[(size_t)ao * pb + ai] > 0 ? 0x3F80u : 0xBF80u;
+                    t[(((size_t)w * KK + kk) * 64 + lane) * 4 + (i >> 1)] |= v << ((i & 1) * 16);
                 }
+            }
     return t;
 }
 
 bool wg_block_prepare(int pb) {
     switch ((pb + 31) / 32) {
-        case 2: return prepare_w<2>();
-        case 3: return prepare_w<3>();
-        case 4: return prepare_w<4>();
-        case 5: return prepare_w<5>();
-        case 6: return prepare_w<6>();
-        case 7: return prepare_w<7>();
-        case 8: return prepare_w<8>();
+        case 2: return prepare_kk<2>();
+        case 3: return prepare_kk<3>();
+        case 4: return prepare_kk<4>();
+        case 5: return prepare_kk<5>();
+        case 6: return prepare_kk<6>();
+        case 7: return prepare_kk<7>();
+        case 8: return prepare_kk<8>();
         default: return false;
     }
 }
@@ -209,13 +239,13 @@ int wg_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip,
                lvl / (double)clip, (double)clip / (std::sqrt((double)a.n) * lvl)};
     const int pb = a.p << (a.log2m - 7);
     switch ((pb + 31) / 32) {
-        case 2: return launch_w<2>(h, w, a.bits, pb, s);
-        case 3: return launch_w<3>(h, w, a.bits, pb, s);
-        case 4: return launch_w<4>(h, w, a.bits, pb, s);
-        case 5: return launch_w<5>(h, w, a.bits, pb, s);
-        case 6: return launch_w<6>(h, w, a.bits, pb, s);
-        case 7: return launch_w<7>(h, w, a.bits, pb, s);
-        case 8: return launch_w<8>(h, w, a.bits, pb, s);
+        case 2: return launch_kk<2>(h, w, a.bits, pb, s);
+        case 3: return launch_kk<3>(h, w, a.bits, pb, s);
+        case 4: return launch_kk<4>(h, w, a.bits, pb, s);
+        case 5: return launch_kk<5>(h, w, a.bits, pb, s);
+        case 6: return launch_kk<6>(h, w, a.bits, pb, s);
+        case 7: return launch_kk<7>(h, w, a.bits, pb, s);
+        case 8: return launch_kk<8>(h, w, a.bits, pb, s);
         default: return RQ_ERR_NO_ORDER;
     }
 }
