@@ -376,11 +376,18 @@ __global__ __launch_bounds__(64) void k_wave_quant_error(WaveArgs a, ClipList cl
             }
         m = wave_absmax(m);
 
-        for (int k = k0; k < k1; ++k) {
-            const double dk64 = (double)clips.v[k] * (double)m / lvl;
-            const float sk = m > 0.0f ? flip * (float)(1.0 / dk64) : 0.0f;   // lane sign folded in
-            const float ndk = -flip * (float)dk64;
-            float e2 = 0.0f;
+        // candidates four at a time: four independent chains per element, reductions interleaved
+        const double inv_m = m > 0.0f ? 1.0 / (double)m : 0.0;
+        for (int kb = k0; kb < k1; kb += 4) {
+            float sk[4], ndk[4], e2[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int k = kb + j < k1 ? kb + j : k1 - 1;
+                const double cl = (double)clips.v[k];
+                sk[j] = flip * (float)(lvl / cl * inv_m);          // lane sign folded in
+                ndk[j] = -flip * (float)(cl * (double)m / lvl);
+                e2[j] = 0.0f;
+            }
 #pragma unroll
             for (int t = 0; t < T; ++t)
 #pragma unroll
@@ -388,17 +395,29 @@ __global__ __launch_bounds__(64) void k_wave_quant_error(WaveArgs a, ClipList cl
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const float y = acc[t][h][i];
-                        const float r = __builtin_amdgcn_fmed3f(__builtin_rintf(y * sk), kQmin, kQmax);
-                        const float e = fmaf(r, ndk, y);
-                        e2 = fmaf(e, e, e2);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const float r = __builtin_amdgcn_fmed3f(__builtin_rintf(y * sk[j]), kQmin, kQmax);
+                            const float e = fmaf(r, ndk[j], y);
+                            e2[j] = fmaf(e, e, e2[j]);
+                        }
                     }
-            e2 += dpp_f<kDppXor1>(e2);
-            e2 += dpp_f<kDppXor2>(e2);
-            e2 += dpp_f<kDppHalfMirror>(e2);
-            e2 += dpp_f<kDppRor8>(e2);
-            e2 += __shfl_xor(e2, 16, 64);
-            e2 += __shfl_xor(e2, 32, 64);
-            if (lane == 0) partial[row * n_clips + k] = (double)e2 / ((double)N * (double)N);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppXor1>(e2[j]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppXor2>(e2[j]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppHalfMirror>(e2[j]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppRor8>(e2[j]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 16, 64);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 32, 64);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (lane == 0 && kb + j < k1)
+                    partial[row * n_clips + kb + j] = (double)e2[j] / ((double)N * (double)N);
         }
     }
 }
@@ -533,14 +552,16 @@ bool wave_quant_error_supports(const rq_hadamard* h, const RowArgs& a) {
 template <int T>
 static int launch_qe(const rq_hadamard* h, const WaveArgs& w, const ClipList& clips, int n_clips,
                      int bits, double* partial, hipStream_t s) {
-    // spread one row's candidates over several waves when there are few rows
-    const int64_t target = (int64_t)h->num_cu * 4 * 4;
+    // Spread one row's candidates over several waves when there are few rows, aiming at about one
+    // wave per SIMD: every extra wave of a row repeats the rotation (about two candidates' worth
+    // of work), so splitting further than that costs more than it balances.
+    const int64_t target = (int64_t)h->num_cu * 4;
     int ksplit = (int)((target + w.rows - 1) / w.rows);
     if (ksplit < 1) ksplit = 1;
     if (ksplit > n_clips) ksplit = n_clips;
     if (ksplit > 8) ksplit = 8;
     const int64_t items = w.rows * ksplit;
-    const int64_t cap = (int64_t)h->num_cu * 4 * 8;
+    const int64_t cap = 1 << 24;
     const unsigned grid = (unsigned)(items < cap ? items : cap);
     if (bits == 4)
         hipLaunchKernelGGL((k_wave_quant_error<T, 4>), dim3(grid), dim3(64), 0, s, w, clips, n_clips, ksplit, partial);
