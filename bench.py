@@ -63,6 +63,71 @@ def time_steady_state(torch, binding, h, base, bits, clip, rows_total):
             "tokens_per_s": x.shape[0] / ms * 1e3}
 
 
+VALU_PEAK_TLANEOPS = 39.3       # 256 CUs x 64 lanes x 2.4 GHz, packed fp32 excluded (T lane-ops/s)
+
+
+def _min_ms(torch, fn, n=10, rounds=4):
+    for _ in range(2):
+        fn()
+    torch.cuda.synchronize()
+    best = float("inf")
+    for _ in range(rounds):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1) / n)
+    return best
+
+
+def time_all_configs(torch, binding, wl):
+    """Every configuration's rotate_quantize at its own row count and at a steady-state row count
+    (input >= 1 GiB, rows tiled from a 2048-row seeded sample), plus quant_error on the
+    calibration tensor.  Best of 4 rounds of 10 launches, HIP events, inputs resident and reused
+    (warm caches for the small shapes): context next to the cold-ring headline figure."""
+    res = {}
+    for name in ("llama_hidden", "qwen_hidden", "ffn_expand", "ffn_down", "kv_k"):
+        w = wl.WORKLOADS[name]
+        base_rows = min(w.rows, 2048)
+        xb = wl.generate(w.with_rows(base_rows))
+        x0 = torch.from_numpy(xb.view(np.int16)).cuda().view(torch.bfloat16)
+        h = binding.hadamard_build(w.n)
+        steady_rows = w.rows if name.startswith("kv") else max(w.rows, ((1 << 30) // (2 * w.d)) // base_rows * base_rows)
+        for b in w.bits:
+            row_bytes = algorithmic_bytes_per_row(w.d, w.n, b)
+            entry = {"n": w.n, "d": w.d, "bits": b}
+            for label, rows in (("config_rows", w.rows), ("steady_rows", steady_rows)):
+                x = x0.repeat(max(1, rows // base_rows), 1)
+                codes = torch.empty((x.shape[0], w.n * b // 8), dtype=torch.uint8, device="cuda")
+                scales = torch.empty((x.shape[0],), dtype=torch.float32, device="cuda")
+                ms = _min_ms(torch, lambda: binding.rotate_quantize(h, x, b, w.clip, codes=codes, scales=scales))
+                gbps = x.shape[0] * row_bytes / ms / 1e6
+                entry[label] = {"rows": int(x.shape[0]), "us": ms * 1e3, "GBps": gbps,
+                                "frac_hbm_peak": gbps / HBM_PEAK_GBPS}
+                entry["kernel"] = h.last_kernel
+                del x, codes, scales
+            res[f"{name}_b{b}"] = entry
+        del x0
+        torch.cuda.empty_cache()
+    w = wl.WORKLOADS["calib"]
+    x = torch.from_numpy(wl.generate(w).view(np.int16)).cuda().view(torch.bfloat16)
+    h = binding.hadamard_build(w.n)
+    clips = wl.clip_grid()
+    mse = torch.empty(len(clips), dtype=torch.float32, device="cuda")
+    ws = torch.empty(binding.quant_error_workspace(w.rows, len(clips)) // 8, dtype=torch.float64, device="cuda")
+    ms = _min_ms(torch, lambda: binding.quant_error(h, x, 3, clips, mse=mse, workspace=ws))
+    ec = w.rows * w.n * len(clips)
+    res["quant_error_calib_b3"] = {
+        "rows": w.rows, "n": w.n, "clips": len(clips), "us": ms * 1e3, "kernel": h.last_kernel,
+        "element_candidates_per_s": ec / ms * 1e3,
+        "roofline": {"bound": "alu", "unit": "T lane-ops/s", "achieved": 5 * ec / ms / 1e9,
+                     "peak": VALU_PEAK_TLANEOPS, "frac": 5 * ec / ms / 1e9 / VALU_PEAK_TLANEOPS,
+                     "note": "5 VALU lane-ops per element-candidate; two launches (row sums, reduction)"}}
+    return res
+
+
 def cpu_baseline(x_bits, n, bits, clip):
     """The oracle as it stands, timed on the host cores on the same batch."""
     sys.path.insert(0, os.path.join(ROOT, "oracle"))
@@ -97,6 +162,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-steady-state", action="store_true")
+    ap.add_argument("--no-configs", action="store_true", help="skip the per-configuration table")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also run one 256 MiB device-to-device copy, the known-size reference that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -201,6 +267,10 @@ def main():
         torch.cuda.synchronize()
     if not args.no_steady_state:
         out["steady_state"] = time_steady_state(torch, binding, h, base, bits, clip, 131072)
+    if not args.no_configs:
+        del xs, codes, scales
+        torch.cuda.empty_cache()
+        out["configs"] = time_all_configs(torch, binding, wl)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(x_bits, w.n, bits, clip)
     print(json.dumps(out))
