@@ -139,6 +139,34 @@ int rq_quant_error(const rq_hadamard_t* h,
                    const float* clips, int n_clips,
                    float* mse, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Bytes of device workspace rq_gbs_search needs for `rows` rows; 0 on bad arguments. */
+size_t rq_gbs_workspace(int64_t rows);
+
+/*
+ * Clip-ratio search for one projection: the inner loop of the Gradual Binary Search
+ * (section 4.1, Algorithm 1) with f(clip) = rq_quant_error of X at that single clip ratio as
+ * the objective (the paper's objective, perplexity of a model, is not available here).
+ * a = 0, b = 1, m = 1/2; iterations alternate the probes (a + m)/2 and (b + m)/2; a probe with
+ * f(x) < f(m) becomes the new middle and the far bracket end moves to the old middle, otherwise
+ * the bracket end on the probe's side moves to the probe; stops when b - a <= eps or after
+ * max_evals evaluations of f.  Every evaluation enqueues rq_quant_error on `stream`,
+ * synchronises the stream and reads one float back: a calibration call, not a hot-path call.
+ *   eps          [in]  bracket width to stop at, > 0
+ *   max_evals    [in]  1 .. 256
+ *   workspace    [in]  DEVICE, >= rq_gbs_workspace(rows) bytes, 8-byte aligned, scratch
+ *   clip_out     [out] HOST, the final middle m
+ *   mse_out      [out] HOST, f(m)
+ *   trace_clips  [out] HOST, max_evals floats or NULL: the probes in evaluation order
+ *   trace_mse    [out] HOST, max_evals floats or NULL: f at those probes
+ *   n_evals      [out] HOST or NULL: number of evaluations made
+ * X, dtype, rows (>= 1), d, ld, bits as in rq_rotate_quantize.
+ * Errors: RQ_ERR_ARG, RQ_ERR_NO_ORDER, RQ_ERR_HIP.
+ */
+int rq_gbs_search(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d, int64_t ld,
+                  int bits, float eps, int max_evals, void* workspace, size_t workspace_bytes,
+                  void* stream, float* clip_out, float* mse_out, float* trace_clips,
+                  float* trace_mse, int* n_evals);
+
 /*
  * Select the kernel family for subsequent hot-path calls on this handle (testing /
  * measurement): 0 = automatic (fastest available), 1 = the general LDS kernel.

@@ -273,3 +273,50 @@ def boundary_exempt(t: np.ndarray, b: int, tol: float = 1e-6) -> np.ndarray:
     _, qmin, qmax = quant_params(b)
     frac = np.abs(t - np.floor(t) - 0.5)
     return (frac < tol) & (t >= qmin + 0.5 - tol) & (t <= qmax - 0.5 + tol)
+
+
+# --------------------------------------------------------------------------- gradual binary search
+
+def gbs_search(f, eps: float, max_evals: int = 64):
+    """Clip-ratio search for ONE projection: the inner loop of Algorithm 1 (section 4.1).
+
+    a = 0, b = 1, m = 1/2 with f_m = f(m); iterations alternate a left probe x = (a + m)/2 (even
+    iteration) and a right probe x = (b + m)/2 (odd).  If f(x) < f_m the probe becomes the new
+    middle and the bracket end on the far side of the old middle moves to the old middle; else
+    the bracket end on the probe's side moves to the probe.  Stops when b - a <= eps.
+    Returns (m, f_m, trace) with trace = [(x, f(x)), ...] in evaluation order (first entry is
+    the initial middle).  The paper leaves eps open; max_evals only guards against eps <= 0."""
+    a, b = 0.0, 1.0
+    m = (a + b) / 2
+    fm = f(m)
+    trace = [(m, fm)]
+    it = 0
+    while b - a > eps and len(trace) < max_evals:
+        x = (a + m) / 2 if it % 2 == 0 else (b + m) / 2
+        fx = f(x)
+        trace.append((x, fx))
+        if fx < fm:
+            if x < m:
+                b = m
+            else:
+                a = m
+            m, fm = x, fx
+        else:
+            if x < m:
+                a = x
+            else:
+                b = x
+        it += 1
+    return m, fm, trace
+
+
+def gbs(objectives, eps: float):
+    """Algorithm 1 over a list of projections: one search per projection, in order, each appended to
+    the list L.  Reading: the loop runs over all projections (the listing's upper bound n - 1 is
+    taken as an off-by-one), and with a quantization-error objective the projections do not
+    interact, so objectives[i] is a function of its own clip ratio only."""
+    out = []
+    for f in objectives:
+        m, _, _ = gbs_search(f, eps)
+        out.append(m)
+    return out

@@ -4,5 +4,5 @@
 seeded synthetic input generators; `build` compiles the library in-tree.
 """
 from . import workloads  # noqa: F401
-from .binding import (Hadamard, RotqError, hadamard_build, next_order, quant_error,  # noqa: F401
-                      quant_error_workspace, rotate_quantize)
+from .binding import (Hadamard, RotqError, gbs_search, hadamard_build, next_order,  # noqa: F401
+                      quant_error, quant_error_workspace, rotate_quantize)

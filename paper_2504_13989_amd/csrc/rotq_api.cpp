@@ -206,6 +206,62 @@ int rq_quant_error(const rq_hadamard_t* h, const void* X, int dtype, int64_t row
     return rq::generic_quant_error(h, a, cl, n_clips, mse, static_cast<double*>(workspace), s);
 }
 
+size_t rq_gbs_workspace(int64_t rows) {
+    const size_t q = rq_quant_error_workspace(rows, 1);
+    return q ? q + 256 : 0;
+}
+
+int rq_gbs_search(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d, int64_t ld,
+                  int bits, float eps, int max_evals, void* workspace, size_t workspace_bytes,
+                  void* stream, float* clip_out, float* mse_out, float* trace_clips,
+                  float* trace_mse, int* n_evals) {
+    int rc = check_rows(h, X, dtype, rows, d, ld, bits);
+    if (rc != RQ_OK) return rc;
+    if (rows < 1 || !(eps > 0.0f) || max_evals < 1 || max_evals > 256) return RQ_ERR_ARG;
+    if (!clip_out || !mse_out || !workspace || !aligned(workspace, 8)) return RQ_ERR_ARG;
+    if (workspace_bytes < rq_gbs_workspace(rows)) return RQ_ERR_ARG;
+    if (h->device < 0) return RQ_ERR_HIP;
+    // layout of the workspace: [0, 256) one float for the objective, then the quant_error scratch
+    float* d_mse = static_cast<float*>(workspace);
+    void* qws = static_cast<char*>(workspace) + 256;
+    const size_t qws_bytes = workspace_bytes - 256;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int evals = 0;
+    auto f = [&](double x, float* out) -> int {
+        const float c = (float)x;
+        int r = rq_quant_error(h, X, dtype, rows, d, ld, bits, &c, 1, d_mse, qws, qws_bytes, stream);
+        if (r != RQ_OK) return r;
+        if (hipStreamSynchronize(s) != hipSuccess ||
+            hipMemcpy(out, d_mse, sizeof(float), hipMemcpyDeviceToHost) != hipSuccess)
+            return RQ_ERR_HIP;
+        if (trace_clips) trace_clips[evals] = c;
+        if (trace_mse) trace_mse[evals] = *out;
+        ++evals;
+        return RQ_OK;
+    };
+    double a = 0.0, b = 1.0, m = 0.5;
+    float fm = 0.0f;
+    rc = f(m, &fm);
+    if (rc != RQ_OK) return rc;
+    for (int it = 0; b - a > (double)eps && evals < max_evals; ++it) {
+        const double x = (it % 2 == 0) ? (a + m) / 2 : (b + m) / 2;
+        float fx = 0.0f;
+        rc = f(x, &fx);
+        if (rc != RQ_OK) return rc;
+        if (fx < fm) {
+            if (x < m) b = m; else a = m;
+            m = x;
+            fm = fx;
+        } else {
+            if (x < m) a = x; else b = x;
+        }
+    }
+    *clip_out = (float)m;
+    *mse_out = fm;
+    if (n_evals) *n_evals = evals;
+    return RQ_OK;
+}
+
 const char* rq_strerror(int code) {
     switch (code) {
         case RQ_OK: return "ok";

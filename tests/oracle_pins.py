@@ -426,4 +426,34 @@ def check_boundary_mask(o):
     assert m4.tolist() == [[True, True, False, True, True, True, True, False, False]]
 
 
+# ----------------------------------------------------------------------------- Algorithm 1
+
+def check_gbs_trace(o):
+    # hand-worked run of Algorithm 1 on f(x) = (x - 0.3)^2 with eps = 0.1 (tests/golden/alg1_trace.txt)
+    rows = []
+    with open(os.path.join(GOLDEN, "alg1_trace.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                rows.append([float(v) for v in line.split()])
+    m, fm, trace = o.gbs_search(lambda x: (x - 0.3) ** 2, 0.1)
+    assert [t[0] for t in trace] == [r[0] for r in rows]
+    assert m == rows[-1][3] and fm == (m - 0.3) ** 2
+
+
+def check_gbs_converges(o):
+    # unimodal objectives: the result is within the final bracket width of the minimiser, the
+    # objective never increases along the accepted middles, probes stay inside (0, 1)
+    for cstar in (0.07, 0.3, 0.5, 0.61, 0.93, 1.0):
+        for eps in (1 / 16, 1 / 64, 1 / 1024):
+            f = lambda x, c=cstar: abs(x - c) ** 1.5
+            m, fm, trace = o.gbs_search(f, eps)
+            assert abs(m - cstar) <= 2 * eps + 1e-12, (cstar, eps, m)
+            assert all(0.0 < x < 1.0 for x, _ in trace)
+            assert fm == min(v for _, v in trace)
+    # a flat objective never moves the middle; the bracket still closes
+    m, fm, trace = o.gbs_search(lambda x: 1.0, 1 / 32)
+    assert m == 0.5 and len(trace) > 4
+    assert o.gbs([lambda x: (x - 0.25) ** 2, lambda x: (x - 0.75) ** 2], 1 / 256) == [0.25, 0.75]
+
+
 ALL_CHECKS = [v for k, v in sorted(globals().items()) if k.startswith("check_")]

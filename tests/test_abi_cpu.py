@@ -130,6 +130,29 @@ def test_quant_error_argument_errors(L):
     h.close()
 
 
+def test_gbs_search_argument_errors(L):
+    h = binding.hadamard_build(128)
+    E = binding.RQ_ERR_ARG
+    clip, mse = C.c_float(), C.c_float()
+
+    def call(hh=h._h, X=0x1000, rows=4, bits=3, eps=0.01, me=16, ws=0x5000, wsb=1 << 20, co=clip, mo=mse):
+        return L.rq_gbs_search(hh, C.c_void_p(X), 0, rows, 128, 128, bits, C.c_float(eps), me,
+                               C.c_void_p(ws), wsb, None, C.byref(co) if co is not None else None,
+                               C.byref(mo) if mo is not None else None, None, None, None)
+
+    assert call(hh=None) == E
+    assert call(X=0) == E
+    assert call(rows=0) == E
+    assert call(bits=7) == E
+    assert call(eps=0.0) == E and call(eps=float("nan")) == E
+    assert call(me=0) == E and call(me=1000) == E
+    assert call(ws=0) == E and call(ws=0x5004) == E and call(wsb=64) == E
+    assert call(co=None) == E and call(mo=None) == E
+    assert L.rq_gbs_workspace(0) > 0 and L.rq_gbs_workspace(-2) == 0
+    assert call() == binding.RQ_ERR_HIP           # host-only handle: refused after validation
+    h.close()
+
+
 def test_info_and_variant_errors(L):
     assert L.rq_hadamard_info(None, None, None, None, None, None) == binding.RQ_ERR_ARG
     h = binding.hadamard_build(256)

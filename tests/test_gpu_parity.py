@@ -239,3 +239,34 @@ def test_quant_error_consistent_with_rotate_quantize(torch):
     # empty input -> zeros
     x0 = torch.empty((0, 4096), dtype=torch.bfloat16, device="cuda")
     assert not binding.quant_error(h, x0, 3, clips).cpu().numpy().any()
+
+
+# ------------------------------------------------------------------ gradual binary search
+
+@pytest.mark.parametrize("name,rows,b", [("calib", 512, 3), ("calib", 64, 4), ("qwen_hidden", 40, 3), ("tiny", 64, 3)])
+def test_gbs_search_follows_algorithm_1(torch, name, rows, b):
+    # the HIP-side search (host loop over rq_quant_error) against the oracle's Algorithm 1 with the
+    # oracle's fp64 quant_error as objective: same probes in the same order, same result
+    w = wl.WORKLOADS[name].with_rows(rows)
+    x = wl.generate(w)
+    eps = 1.0 / 64
+    say(f"gbs {name} rows={rows} b={b}")
+    clip, mse, trace = binding.gbs_search(handle(w.n), parity.to_device(x), b, eps)
+    y = oracle.rotate(x, w.n)
+
+    def f(c):
+        q, delta, _ = oracle.quantize(y, b, np.float32(c))
+        return float(np.mean((oracle.dequantize(q, delta) - y) ** 2))
+
+    m, fm, otrace = oracle.gbs_search(f, eps)
+    assert len(trace) == len(otrace)
+    for (cg, fg), (co, fo) in zip(trace, otrace):
+        assert cg == co, (trace, otrace)
+        assert abs(fg - fo) <= 1e-5 * fo
+    assert clip == m and abs(mse - fm) <= 1e-5 * fm
+    # consistency with the grid: the found clip is no worse than the best of a 32-point grid
+    # evaluated by the same entry point, up to the grid's own resolution
+    grid = wl.clip_grid()
+    gm = binding.quant_error(handle(w.n), parity.to_device(x), b, grid).cpu().numpy()
+    assert mse <= gm.min() * 1.05
+    say(f"  ok clip={clip} mse={mse:.4g} evals={len(trace)} grid argmin={grid[gm.argmin()]}")

@@ -71,6 +71,10 @@ MUTATIONS = {
     "pack_field_msb_first": ("(field[:, :, None] >> np.arange(b)) & 1", "(field[:, :, None] >> np.arange(b)[::-1]) & 1"),
     "unpack_no_sign": ("field = np.where(field >= (1 << (b - 1)), field - (1 << b), field)", "field = field"),
     "boundary_tol": ("return (frac < tol)", "return (frac < 10 * tol)"),
+    "gbs_probe_parity": ("x = (a + m) / 2 if it % 2 == 0 else (b + m) / 2", "x = (a + m) / 2 if it % 2 == 1 else (b + m) / 2"),
+    "gbs_keep_worse": ("        if fx < fm:\n            if x < m:\n                b = m", "        if fx > fm:\n            if x < m:\n                b = m"),
+    "gbs_bracket_swap": ("            if x < m:\n                a = x\n            else:\n                b = x", "            if x < m:\n                b = x\n            else:\n                a = x"),
+    "gbs_stop": ("while b - a > eps and", "while b - a > 4 * eps and"),
 }
 
 
