@@ -242,6 +242,49 @@ def quant_error(x: np.ndarray, n: int, b: int, clips) -> np.ndarray:
     return out
 
 
+# --------------------------------------------------------------------------- asymmetric groups
+
+GROUP = 128
+
+
+def quantize_asym(y: np.ndarray, b: int, clip, group: int = GROUP) -> tuple:
+    """Asymmetric uniform quantization of rotated rows in groups of `group` consecutive values
+    (the KV-cache setting of section 5.1: "asymmetric quantization with a group size of 128").
+
+    The paper names the scheme without a formula; the reading taken: per group, lo = clip * min,
+    hi = clip * max (the clip ratio of section 3.1 shrinks the range towards zero),
+    delta = (hi - lo) / (2^b - 1), code = clamp(round_half_even((y - lo) / delta), 0, 2^b - 1),
+    y^ = code * delta + lo.  The offset is kept as the real number lo, not as a rounded integer
+    zero point.  A constant group has delta = 0 and all-zero codes (y^ = lo).
+    Returns (codes uint8 [rows, n], delta f64 [rows, n/group], lo f64 [rows, n/group], t f64)."""
+    rows, n = y.shape
+    if n % group:
+        raise ValueError("row length must be a multiple of the group size")
+    lvl = (1 << b) - 1
+    clip64 = float(np.float32(clip))
+    yg = y.reshape(rows, n // group, group)
+    lo = clip64 * yg.min(axis=2)
+    hi = clip64 * yg.max(axis=2)
+    delta = (hi - lo) / lvl
+    safe = np.where(delta > 0, delta, 1.0)
+    t = (yg - lo[:, :, None]) / safe[:, :, None]
+    t[delta == 0] = 0.0
+    codes = np.clip(np.rint(t), 0, lvl).astype(np.uint8)
+    return codes.reshape(rows, n), delta, lo, t.reshape(rows, n)
+
+
+def dequantize_asym(codes: np.ndarray, delta: np.ndarray, lo: np.ndarray, group: int = GROUP) -> np.ndarray:
+    rows, n = codes.shape
+    cg = codes.reshape(rows, n // group, group).astype(np.float64)
+    return (cg * delta[:, :, None] + lo[:, :, None]).reshape(rows, n)
+
+
+def quantize_plain(x: np.ndarray, b: int, clip) -> tuple:
+    """Per-token symmetric quantization of rows as they are (no rotation): the quantizer of
+    section 2.1 applied to activations whose rotation was fused into the weights offline."""
+    return quantize(as_f64(x), b, clip)
+
+
 # --------------------------------------------------------------------------- packing
 
 def pack_codes(codes: np.ndarray, b: int) -> np.ndarray:
@@ -256,16 +299,26 @@ def pack_codes(codes: np.ndarray, b: int) -> np.ndarray:
     return np.packbits(bits, axis=1, bitorder="little")
 
 
-def unpack_codes(packed: np.ndarray, b: int, n: int) -> np.ndarray:
-    """Inverse of pack_codes: int8 codes [rows, n] (sign-extended)."""
+def unpack_codes(packed: np.ndarray, b: int, n: int, signed: bool = True) -> np.ndarray:
+    """Inverse of pack_codes: int8 codes [rows, n] (sign-extended), or uint8 fields as stored
+    when signed is False."""
     rows = packed.shape[0]
     bits = np.unpackbits(np.asarray(packed, dtype=np.uint8), axis=1, bitorder="little")[:, : n * b]
     field = (bits.reshape(rows, n, b).astype(np.int64) << np.arange(b)).sum(axis=2)
+    if not signed:
+        return field.astype(np.uint8)
     field = np.where(field >= (1 << (b - 1)), field - (1 << b), field)
     return field.astype(np.int8)
 
 
 # --------------------------------------------------------------------------- checker helpers
+
+def boundary_exempt_asym(t: np.ndarray, b: int, tol: float = 1e-6) -> np.ndarray:
+    """As boundary_exempt, for unsigned codes 0 .. 2^b - 1 (boundaries 1/2 .. 2^b - 3/2)."""
+    lvl = (1 << b) - 1
+    frac = np.abs(t - np.floor(t) - 0.5)
+    return (frac < tol) & (t >= 0.5 - tol) & (t <= lvl - 0.5 + tol)
+
 
 def boundary_exempt(t: np.ndarray, b: int, tol: float = 1e-6) -> np.ndarray:
     """Mask of elements whose pre-round value t lies within ``tol`` of a rounding boundary

@@ -426,6 +426,77 @@ def check_boundary_mask(o):
     assert m4.tolist() == [[True, True, False, True, True, True, True, False, False]]
 
 
+# ----------------------------------------------------------------------------- asymmetric groups
+
+def check_asym_properties(o):
+    rng = np.random.default_rng(11)
+    y = rng.standard_t(3.0, size=(6, 256)) + 0.7
+    for b in (3, 4):
+        lvl = (1 << b) - 1
+        for clip in (1.0, 0.9):
+            q, delta, lo, t = o.quantize_asym(y, b, clip)
+            c64 = float(np.float32(clip))
+            assert q.dtype == np.uint8 and q.min() >= 0 and q.max() <= lvl
+            yg = y.reshape(6, 2, 128)
+            assert np.allclose(lo, c64 * yg.min(axis=2), rtol=1e-15)
+            assert np.allclose(delta, c64 * (yg.max(axis=2) - yg.min(axis=2)) / lvl, rtol=1e-14)
+            yh = o.dequantize_asym(q, delta, lo)
+            dfull = np.repeat(delta, 128, axis=1)
+            inside = (t >= -0.5) & (t <= lvl + 0.5)
+            assert np.all(np.abs(yh - y)[inside] <= 0.5 * dfull[inside] * (1 + 1e-12))
+            assert np.all(q[t > lvl + 0.5] == lvl) and np.all(q[t < -0.5] == 0)
+            if clip == 1.0:
+                # the extremes of every group land on the end codes and are reproduced exactly
+                for r in range(6):
+                    for g in range(2):
+                        seg = slice(128 * g, 128 * g + 128)
+                        assert q[r, seg][np.argmin(y[r, seg])] == 0 and q[r, seg][np.argmax(y[r, seg])] == lvl
+                        assert abs(yh[r, seg].min() - y[r, seg].min()) < 1e-12
+                        assert abs(yh[r, seg].max() - y[r, seg].max()) < 1e-12
+            # idempotence with the group parameters held fixed
+            q2 = np.clip(np.rint((yh.reshape(6, 2, 128) - lo[:, :, None]) / delta[:, :, None]), 0, lvl)
+            assert np.array_equal(q2.reshape(6, 256).astype(np.uint8), q)
+            # scaling by a power of two: same codes, scaled parameters
+            q3, d3, l3, _ = o.quantize_asym(8.0 * y, b, clip)
+            assert np.array_equal(q3, q) and np.array_equal(d3, 8 * delta) and np.array_equal(l3, 8 * lo)
+
+
+def check_asym_closed_forms(o):
+    # a group that is an exact arithmetic progression over the levels is reproduced exactly
+    for b in (3, 4):
+        lvl = (1 << b) - 1
+        base = np.arange(128) % (lvl + 1)
+        y = (base * 0.25 - 1.0)[None, :]
+        q, delta, lo, _ = o.quantize_asym(y, b, 1.0)
+        assert np.array_equal(q[0], base.astype(np.uint8))
+        assert delta[0, 0] == 0.25 and lo[0, 0] == -1.0
+        assert np.array_equal(o.dequantize_asym(q, delta, lo), y)
+    # a shift moves only the offset; a constant group has delta 0, codes 0, y^ = clip * value
+    y = np.linspace(-1, 2, 128)[None, :]
+    q, delta, lo, _ = o.quantize_asym(y, 4, 1.0)
+    q2, d2, l2, _ = o.quantize_asym(y + 4.0, 4, 1.0)
+    assert np.array_equal(q, q2) and np.allclose(d2, delta, rtol=1e-15) and np.allclose(l2, lo + 4.0)
+    qc, dc, lc, _ = o.quantize_asym(np.full((1, 128), 3.0), 3, 0.5)
+    assert not qc.any() and dc[0, 0] == 0 and lc[0, 0] == 1.5
+    # unsigned fields round-trip through the packer
+    rng = np.random.default_rng(12)
+    qq = rng.integers(0, 8, size=(3, 128)).astype(np.uint8)
+    assert np.array_equal(o.unpack_codes(o.pack_codes(qq, 3), 3, 128, signed=False), qq)
+    tt = np.array([[0.5, 6.5, 7.5, -0.5, 14.5, 3.2]])
+    assert o.boundary_exempt_asym(tt, 3).tolist() == [[True, True, False, False, False, False]]
+    assert o.boundary_exempt_asym(tt, 4).tolist() == [[True, True, True, False, True, False]]
+
+
+def check_quantize_plain(o):
+    # no rotation: the section 2.1 quantizer on the row itself
+    x = np.array([[0.0, 1.0, -2.0, 7.0, -7.0, 3.5, 0.4, -0.6]])
+    q, delta, t = o.quantize_plain(x, 3, 1.0)
+    assert delta[0] == 1.0 and q[0].tolist() == [0, 1, -2, 3, -4, 3, 0, -1]
+    bits = np.array([[0x3F80, 0xC000, 0x40E0, 0x0000]], dtype=np.uint16)      # 1, -2, 7, 0
+    q, delta, _ = o.quantize_plain(bits, 4, 1.0)
+    assert delta[0] == 7.0 / 15 and q[0].tolist() == [2, -4, 7, 0]
+
+
 # ----------------------------------------------------------------------------- Algorithm 1
 
 def check_gbs_trace(o):

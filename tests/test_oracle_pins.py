@@ -71,6 +71,11 @@ MUTATIONS = {
     "pack_field_msb_first": ("(field[:, :, None] >> np.arange(b)) & 1", "(field[:, :, None] >> np.arange(b)[::-1]) & 1"),
     "unpack_no_sign": ("field = np.where(field >= (1 << (b - 1)), field - (1 << b), field)", "field = field"),
     "boundary_tol": ("return (frac < tol)", "return (frac < 10 * tol)"),
+    "asym_clip_one_side": ("    hi = clip64 * yg.max(axis=2)", "    hi = yg.max(axis=2)"),
+    "asym_levels": ("    delta = (hi - lo) / lvl\n", "    delta = (hi - lo) / (lvl + 1)\n"),
+    "asym_offset_dropped": ("return (cg * delta[:, :, None] + lo[:, :, None]).reshape(rows, n)", "return (cg * delta[:, :, None]).reshape(rows, n)"),
+    "asym_signed_range": ("codes = np.clip(np.rint(t), 0, lvl).astype(np.uint8)", "codes = np.clip(np.rint(t), 0, lvl - 1).astype(np.uint8)"),
+    "asym_group_axis": ("yg = y.reshape(rows, n // group, group)\n    lo = clip64", "yg = y.reshape(rows, group, n // group).transpose(0, 2, 1)\n    lo = clip64"),
     "gbs_probe_parity": ("x = (a + m) / 2 if it % 2 == 0 else (b + m) / 2", "x = (a + m) / 2 if it % 2 == 1 else (b + m) / 2"),
     "gbs_keep_worse": ("        if fx < fm:\n            if x < m:\n                b = m", "        if fx > fm:\n            if x < m:\n                b = m"),
     "gbs_bracket_swap": ("            if x < m:\n                a = x\n            else:\n                b = x", "            if x < m:\n                b = x\n            else:\n                a = x"),
