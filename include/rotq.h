@@ -54,6 +54,7 @@ extern "C" {
 #define RQ_KIND_PALEY2    2
 
 #define RQ_MAX_CLIPS 64
+#define RQ_GROUP 128
 
 typedef struct rq_hadamard rq_hadamard_t;   /* opaque; immutable after build */
 
@@ -115,6 +116,42 @@ int rq_rotate_quantize(const rq_hadamard_t* h,
                        const void* X, int dtype, int64_t rows, int d, int64_t ld,
                        int bits, float clip,
                        void* codes, float* scales, void* stream);
+
+/*
+ * Rotate, then quantize asymmetrically in groups of RQ_GROUP consecutive rotated values (the
+ * KV-cache setting of section 5.1: 3-bit asymmetric quantization with a group size of 128;
+ * rotation as in sections 2.3, 4.2).  The paper names the scheme without a formula; per group g
+ * of the rotated row y:
+ *   lo = clip * min(y_g), hi = clip * max(y_g), Delta = (hi - lo) / (2^b - 1),
+ *   code_j = clamp(round_half_even((y_j - lo) / Delta), 0, 2^b - 1),  y^_j = code_j * Delta + lo.
+ * A constant group has Delta = 0 and all-zero codes.
+ *   h       [in]  handle whose order n is a multiple of RQ_GROUP
+ *   codes   [out] DEVICE, rows * n * bits / 8 bytes: unsigned b-bit fields, bitstream layout as
+ *                 in rq_rotate_quantize
+ *   scales  [out] DEVICE, rows * (n / RQ_GROUP) floats: Delta, row-major [row][group]
+ *   mins    [out] DEVICE, rows * (n / RQ_GROUP) floats: lo
+ * Other arguments, ownership and the rows == 0 rule as in rq_rotate_quantize.
+ * Errors: RQ_ERR_ARG (as rq_rotate_quantize, or n not a multiple of RQ_GROUP), RQ_ERR_NO_ORDER
+ * (no kernel can hold a row of this order), RQ_ERR_HIP.
+ */
+int rq_rotate_quantize_asym(const rq_hadamard_t* h,
+                            const void* X, int dtype, int64_t rows, int d, int64_t ld,
+                            int bits, float clip,
+                            void* codes, float* scales, float* mins, void* stream);
+
+/*
+ * The per-token symmetric quantizer of section 2.1 (with the clip ratio of section 3.1) on the
+ * rows as they are, without a rotation: for activations whose rotation has been fused into the
+ * neighbouring weights offline (section 2.2), so that only the quantizer remains online.
+ *   X       [in]  DEVICE, rows x d elements of `dtype`, leading dimension ld >= d
+ *   d       [in]  row width, a multiple of 32
+ *   codes   [out] DEVICE, rows * d * bits / 8 bytes, 4-byte aligned (signed fields, same layout)
+ *   scales  [out] DEVICE, rows floats: Delta = clip * max|x| / (2^b - 1)
+ * Runs on the current device.  rows == 0 is a successful no-op.
+ * Errors: RQ_ERR_ARG, RQ_ERR_HIP.
+ */
+int rq_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld,
+                int bits, float clip, void* codes, float* scales, void* stream);
 
 /* Bytes of device workspace rq_quant_error needs for (rows, n_clips); 0 on bad arguments. */
 size_t rq_quant_error_workspace(int64_t rows, int n_clips);

@@ -45,6 +45,8 @@ def lib() -> C.CDLL:
     L.rq_hadamard_dense.argtypes = [vp, vp]
     L.rq_next_order.argtypes = [i32, ip]
     L.rq_rotate_quantize.argtypes = [vp, vp, i32, i64, i32, i64, i32, C.c_float, vp, vp, vp]
+    L.rq_rotate_quantize_asym.argtypes = [vp, vp, i32, i64, i32, i64, i32, C.c_float, vp, vp, vp, vp]
+    L.rq_quantize.argtypes = [vp, i32, i64, i32, i64, i32, C.c_float, vp, vp, vp]
     L.rq_quant_error_workspace.argtypes = [i64, i32]
     L.rq_quant_error_workspace.restype = C.c_size_t
     L.rq_quant_error.argtypes = [vp, vp, i32, i64, i32, i64, i32, f32p, i32, vp, vp, C.c_size_t, vp]
@@ -158,6 +160,50 @@ def rotate_quantize(h: Hadamard, x, bits: int, clip: float, codes=None, scales=N
                                   int(bits), C.c_float(clip), C.c_void_p(codes.data_ptr()),
                                   C.c_void_p(scales.data_ptr()), _stream_ptr(stream))
     _check(rc, "rq_rotate_quantize")
+    return codes, scales
+
+
+GROUP = 128
+
+
+def rotate_quantize_asym(h: Hadamard, x, bits: int, clip: float, codes=None, scales=None, mins=None,
+                         stream=None):
+    """rq_rotate_quantize_asym on a CUDA tensor x [..., d]; returns (codes uint8 [rows, n*bits/8],
+    scales float32 [rows, n/128], mins float32 [rows, n/128])."""
+    import torch
+    if not x.is_cuda:
+        raise ValueError("x must be a device tensor")
+    x2, rows, d, ld = _rows_view(x)
+    groups = max(h.n // GROUP, 1)
+    if codes is None:
+        codes = torch.empty((rows, h.n * bits // 8), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty((rows, groups), dtype=torch.float32, device=x.device)
+    if mins is None:
+        mins = torch.empty((rows, groups), dtype=torch.float32, device=x.device)
+    rc = lib().rq_rotate_quantize_asym(h._h, C.c_void_p(x2.data_ptr()), _dtype_code(x2), rows, d, ld,
+                                       int(bits), C.c_float(clip), C.c_void_p(codes.data_ptr()),
+                                       C.c_void_p(scales.data_ptr()), C.c_void_p(mins.data_ptr()),
+                                       _stream_ptr(stream))
+    _check(rc, "rq_rotate_quantize_asym")
+    return codes, scales, mins
+
+
+def quantize(x, bits: int, clip: float, codes=None, scales=None, stream=None):
+    """rq_quantize (no rotation) on a CUDA tensor x [..., d]; returns (codes uint8 [rows, d*bits/8],
+    scales float32 [rows])."""
+    import torch
+    if not x.is_cuda:
+        raise ValueError("x must be a device tensor")
+    x2, rows, d, ld = _rows_view(x)
+    if codes is None:
+        codes = torch.empty((rows, d * bits // 8), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty((rows,), dtype=torch.float32, device=x.device)
+    rc = lib().rq_quantize(C.c_void_p(x2.data_ptr()), _dtype_code(x2), rows, d, ld, int(bits),
+                           C.c_float(clip), C.c_void_p(codes.data_ptr()),
+                           C.c_void_p(scales.data_ptr()), _stream_ptr(stream))
+    _check(rc, "rq_quantize")
     return codes, scales
 
 

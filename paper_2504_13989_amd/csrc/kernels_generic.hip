@@ -11,6 +11,7 @@ namespace rq {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kMaxGroups = 320;      // groups of 128 in the longest row LDS can hold
 
 __device__ __forceinline__ float load_f32(const void* X, int dtype, int64_t idx) {
     if (dtype == RQ_BF16) {
@@ -107,6 +108,108 @@ __global__ __launch_bounds__(kThreads) void k_generic_rotate_quantize(RowArgs a,
     }
 }
 
+// Asymmetric quantization in groups of 128 rotated values (section 5.1, KV cache): per group
+// lo = clip * min, delta = clip * (max - min) / (2^b - 1), code = clamp(rne((y - lo) / delta), 0,
+// 2^b - 1).  The decision is taken in fp64 here; this kernel is the general fallback.
+__global__ __launch_bounds__(kThreads) void k_generic_rotate_quantize_asym(RowArgs a, float clip,
+                                                                           uint32_t* codes,
+                                                                           float* scales, float* mins) {
+    extern __shared__ float lds[];
+    __shared__ float red[4];
+    __shared__ float gmn[kMaxGroups], gmx[kMaxGroups];
+    const int64_t row = blockIdx.x;
+    float amax;
+    const float* y = rotate_row_lds(a, row, lds, lds + a.n, red, &amax);
+    const int bits = a.bits;
+    const int n_groups = a.n / 128;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int gi = wave; gi < n_groups; gi += kThreads / 64) {
+        const float u = y[gi * 128 + lane], v = y[gi * 128 + 64 + lane];
+        float mn = fminf(u, v), mx = fmaxf(u, v);
+        for (int m = 32; m >= 1; m >>= 1) {
+            mn = fminf(mn, __shfl_xor(mn, m, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+        }
+        if (lane == 0) {
+            gmn[gi] = mn;
+            gmx[gi] = mx;
+        }
+    }
+    __syncthreads();
+    const double lvl = (double)((1 << bits) - 1);
+    const double rn = sqrt((double)a.n);
+    for (int gi = threadIdx.x; gi < n_groups; gi += kThreads) {
+        const double r = (double)gmx[gi] - (double)gmn[gi];
+        scales[row * n_groups + gi] = (float)((double)clip * r / (rn * lvl));
+        mins[row * n_groups + gi] = (float)((double)clip * (double)gmn[gi] / rn);
+    }
+    const uint32_t mask = (1u << bits) - 1u;
+    uint32_t* out = codes + row * (int64_t)(a.n / 32 * bits);
+    for (int g = threadIdx.x; g < a.n / 32; g += kThreads) {
+        const double mn = (double)gmn[g >> 2];
+        const double r = (double)gmx[g >> 2] - mn;
+        const double lo = (double)clip * mn;
+        const double inv = r > 0.0 ? lvl / ((double)clip * r) : 0.0;
+        uint64_t acc = 0;
+        int nb = 0, w = 0;
+        for (int e = 0; e < 32; ++e) {
+            const double t = ((double)y[g * 32 + e] - lo) * inv;
+            const int q = (int)fmin(fmax(rint(t), 0.0), lvl);
+            acc |= (uint64_t)((uint32_t)q & mask) << nb;
+            nb += bits;
+            if (nb >= 32) {
+                out[g * bits + w++] = (uint32_t)acc;
+                acc >>= 32;
+                nb -= 32;
+            }
+        }
+    }
+}
+
+// Per-token symmetric quantization of rows as they are (section 2.1; no rotation, for layers
+// whose rotation is fused into the weights).  One workgroup per row, two passes over the row:
+// absmax, then round / clamp / pack (the second pass is served by the caches).
+__global__ __launch_bounds__(kThreads) void k_plain_quantize(const void* X, int dtype, int d, int64_t ld,
+                                                             int bits, float clip, uint32_t* codes,
+                                                             float* scales) {
+    __shared__ float red[4];
+    const int64_t row = blockIdx.x;
+    const int64_t base = row * ld;
+    float mx = 0.0f;
+    for (int j = threadIdx.x; j < d; j += kThreads) mx = fmaxf(mx, fabsf(load_f32(X, dtype, base + j)));
+    mx = wave_max(mx);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    const float amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const double lvl = (double)((1 << bits) - 1);
+    const float qmax = (float)((1 << (bits - 1)) - 1), qmin = -(float)(1 << (bits - 1));
+    const float s = amax > 0.0f ? (float)(lvl / ((double)clip * (double)amax)) : 0.0f;
+    const double delta = (double)clip * (double)amax / lvl;
+    if (threadIdx.x == 0) scales[row] = (float)delta;
+    const uint32_t mask = (1u << bits) - 1u;
+    uint32_t* out = codes + row * (int64_t)(d / 32 * bits);
+    for (int g = threadIdx.x; g < d / 32; g += kThreads) {
+        uint64_t acc = 0;
+        int nb = 0, w = 0;
+        for (int e = 0; e < 32; ++e) {
+            const float x = load_f32(X, dtype, base + g * 32 + e);
+            const float t = x * s;
+            float r = rintf(t);
+            // un-rotated bf16 inputs sit on a coarse grid and hit rounding ties often: near a tie
+            // the decision is retaken with the exact quotient x / Delta in fp64
+            if (fabsf(t - r) > 0.499f) r = (float)rint((double)x / delta);
+            const int q = (int)fminf(fmaxf(r, qmin), qmax);
+            acc |= (uint64_t)((uint32_t)q & mask) << nb;
+            nb += bits;
+            if (nb >= 32) {
+                out[g * bits + w++] = (uint32_t)acc;
+                acc >>= 32;
+                nb -= 32;
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void k_generic_quant_error(RowArgs a, ClipList clips,
                                                                   int n_clips, double* partial) {
     extern __shared__ float lds[];
@@ -178,6 +281,9 @@ bool generic_supports(const rq_hadamard* h) { return h->device >= 0 && h->generi
 bool generic_prepare(const rq_hadamard* h) {
     const size_t bytes = lds_bytes(h);
     if (bytes + 256 > (size_t)h->max_lds) return false;
+    if (h->f.n % 128 == 0 && (h->f.n / 128 > kMaxGroups ||
+                              prepare(k_generic_rotate_quantize_asym, bytes) != RQ_OK))
+        return false;
     return prepare(k_generic_rotate_quantize, bytes) == RQ_OK &&
            prepare(k_generic_quant_error, bytes) == RQ_OK;
 }
@@ -188,6 +294,23 @@ int generic_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, 
     if (a.rows > 0x7fffffffLL) return RQ_ERR_ARG;
     hipLaunchKernelGGL(k_generic_rotate_quantize, dim3((unsigned)a.rows), dim3(kThreads), bytes, s, a,
                        clip, codes, scales);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+int generic_rotate_quantize_asym(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
+                                 float* scales, float* mins, hipStream_t s) {
+    const size_t bytes = lds_bytes(h);
+    if (a.rows > 0x7fffffffLL || a.n % 128 != 0) return RQ_ERR_ARG;
+    hipLaunchKernelGGL(k_generic_rotate_quantize_asym, dim3((unsigned)a.rows), dim3(kThreads), bytes, s,
+                       a, clip, codes, scales, mins);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+int plain_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
+                   uint32_t* codes, float* scales, hipStream_t s) {
+    if (rows > 0x7fffffffLL) return RQ_ERR_ARG;
+    hipLaunchKernelGGL(k_plain_quantize, dim3((unsigned)rows), dim3(kThreads), 0, s, X, dtype, d, ld,
+                       bits, clip, codes, scales);
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 

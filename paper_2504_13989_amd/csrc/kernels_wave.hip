@@ -102,9 +102,9 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
 // Lane (g, r, c): DPP row g holds contraction slots, r selects the row of the pass, c the
 // column chunk; the matrix cores transform the (g, i) bits, CB DPP stages the c bits.
 // GUARD: the super-group may be ragged (rows missing at the end) or d < n.
-template <int CB, int BITS, int U, bool GUARD>
+template <int CB, int BITS, int U, bool GUARD, bool ASYM>
 __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_t* base, uint32_t* obase,
-                                                float* sbase, int rem, const u32x4& A0, const u32x4& A1,
+                                                float* sbase, int64_t row0, int rem, const u32x4& A0, const u32x4& A1,
                                                 const uint32_t (&sg)[4], int g, int c, int rsub, int chunk,
                                                 float c1h, float c1l, float c2h, float c2l) {
     constexpr int RPW = 16 >> CB;
@@ -142,10 +142,37 @@ __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_
             lane_stage<kDppRor8>(v0, sg[3]);
             lane_stage<kDppRor8>(v1, sg[3]);
         }
-        float m = absmax4(absmax4(0.0f, v0), v1);
-        m = wave_absmax<CB>(m);                          // over the lanes that share the row
-        const float s = m > 0.0f ? div_pair(c1h, c1l, m) : 0.0f;
-        const uint32_t w = Quant<BITS>::pack8(v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3], s);
+        uint32_t w;
+        float m = 0.0f;
+        if constexpr (ASYM) {
+            // one group of 128 = the whole row (section 5.1, KV cache): min / max instead of absmax
+            static_assert(!ASYM || CB == 2, "asymmetric groups: rows of 128 only");
+            const float yv[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+            float mn = yv[0], mx = yv[0];
+#pragma unroll
+            for (int i = 1; i < 8; ++i) {
+                mn = __builtin_fminf(mn, yv[i]);
+                mx = __builtin_fmaxf(mx, yv[i]);
+            }
+            wave_minmax<CB>(mn, mx);
+            const double r64 = (double)mx - (double)mn;           // exact
+            const float rh = (float)r64, rl = (float)(r64 - (double)rh);
+            const bool flat = !(rh > 0.0f);
+            const float s = flat ? 0.0f : div_pair2(c1h, c1l, rh, rl);
+            constexpr double kMid = (double)(1 << (BITS - 1)) / (double)((1 << BITS) - 1);
+            const float cen = (float)(a.clip * fma(r64, kMid, (double)mn));
+            const float bias = flat ? Quant<BITS>::kMagic : Quant<BITS>::kBias;
+            w = Quant<BITS>::pack8u(yv, cen, s, bias);
+            if (live && g == 0 && c == 0) {
+                sbase[rr] = (float)(r64 * a.c2);
+                a.mins[row0 + rr] = (float)((double)mn * a.c3);
+            }
+        } else {
+            m = absmax4(absmax4(0.0f, v0), v1);
+            m = wave_absmax<CB>(m);                          // over the lanes that share the row
+            const float s = m > 0.0f ? div_pair(c1h, c1l, m) : 0.0f;
+            w = Quant<BITS>::pack8(v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3], s);
+        }
         uint32_t* out = obase + rr * ROW_DWORDS;
         if (BITS == 4) {
             if (live) store_codes(out + chunk, w);
@@ -154,11 +181,11 @@ __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_
             const uint32_t dw = merge24<(CB >= 3)>(w, qpos);
             if (live && qpos < 3) store_codes(out + (chunk >> 2) * 3 + qpos, dw);
         }
-        if (live && g == 0 && c == 0) sbase[rr] = fmaf(m, c2l, m * c2h);
+        if (!ASYM && live && g == 0 && c == 0) sbase[rr] = fmaf(m, c2l, m * c2h);
     }
 }
 
-template <int CB, int BITS, int U>
+template <int CB, int BITS, int U, bool ASYM = false>
 __global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
     static_assert(CB >= 2 && CB <= 4, "unsupported shape");
     constexpr int RPW = 16 >> CB;
@@ -188,10 +215,10 @@ __global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
         uint32_t* obase = a.codes + row0 * ROW_DWORDS;
         float* sbase = a.scales + row0;
         if (rem == SUPER && full_d)
-            short_rows_pass<CB, BITS, U, false>(a, base, obase, sbase, rem, A0, A1, sg, g, c, rsub, chunk,
+            short_rows_pass<CB, BITS, U, false, ASYM>(a, base, obase, sbase, row0, rem, A0, A1, sg, g, c, rsub, chunk,
                                                 c1h, c1l, c2h, c2l);
         else
-            short_rows_pass<CB, BITS, U, true>(a, base, obase, sbase, rem, A0, A1, sg, g, c, rsub, chunk,
+            short_rows_pass<CB, BITS, U, true, ASYM>(a, base, obase, sbase, row0, rem, A0, A1, sg, g, c, rsub, chunk,
                                                c1h, c1l, c2h, c2l);
     }
 }
@@ -454,6 +481,14 @@ int launch_short(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t 
                      : launch_wave(k_wave_short<CB, 3, U>, h, a, items, 8, s);
 }
 
+int launch_short_asym(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
+    constexpr int U = 4;
+    constexpr int SUPER = 4 * U;
+    const int64_t items = (a.rows + SUPER - 1) / SUPER;
+    return bits == 4 ? launch_wave(k_wave_short<2, 4, U, true>, h, a, items, 8, s)
+                     : launch_wave(k_wave_short<2, 3, U, true>, h, a, items, 8, s);
+}
+
 }  // namespace
 
 // The +-1 32x32 block as matrix-core operands.  Operand lane (gA, mm) holds row mm of one
@@ -599,6 +634,20 @@ int wave_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uin
         case 13: return launch_long<16>(h, w, a.bits, s);
         default: return RQ_ERR_NO_ORDER;
     }
+}
+
+bool wave_asym_supports(const rq_hadamard* h, const RowArgs& a) {
+    return wave_supports(h, a) && a.log2m == 7;
+}
+
+int wave_rotate_quantize_asym(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
+                              float* scales, float* mins, hipStream_t s) {
+    const double lvl = (double)((1 << a.bits) - 1);
+    const double rn = std::sqrt((double)a.n);
+    WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
+               static_cast<const u32x4*>(h->d_tiles), codes, scales,
+               lvl / (double)clip, (double)clip / (rn * lvl), mins, (double)clip, (double)clip / rn};
+    return launch_short_asym(h, w, a.bits, s);
 }
 
 }  // namespace rq

@@ -171,6 +171,41 @@ int rq_rotate_quantize(const rq_hadamard_t* h, const void* X, int dtype, int64_t
     return rq::generic_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
 }
 
+int rq_rotate_quantize_asym(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
+                            int64_t ld, int bits, float clip, void* codes, float* scales,
+                            float* mins, void* stream) {
+    int rc = check_rows(h, X, dtype, rows, d, ld, bits);
+    if (rc != RQ_OK) return rc;
+    if (!clip_ok(clip) || h->f.n % RQ_GROUP != 0) return RQ_ERR_ARG;
+    if (rows == 0) return RQ_OK;
+    if (!codes || !scales || !mins || !aligned(codes, 4) || !aligned(scales, 4) || !aligned(mins, 4))
+        return RQ_ERR_ARG;
+    if (h->device < 0) return RQ_ERR_HIP;
+    rq_hadamard* hm = const_cast<rq_hadamard*>(h);
+    const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, bits);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (h->variant == 0 && rq::wave_asym_supports(h, a)) {
+        hm->last_kernel = "wave_short_asym";
+        return rq::wave_rotate_quantize_asym(h, a, clip, static_cast<uint32_t*>(codes), scales, mins, s);
+    }
+    if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
+    hm->last_kernel = "generic_lds_asym";
+    return rq::generic_rotate_quantize_asym(h, a, clip, static_cast<uint32_t*>(codes), scales, mins, s);
+}
+
+int rq_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
+                void* codes, float* scales, void* stream) {
+    if (dtype != RQ_BF16 && dtype != RQ_F32) return RQ_ERR_ARG;
+    if (rows < 0 || d < 32 || d % 32 != 0 || ld < d) return RQ_ERR_ARG;
+    if (bits != 3 && bits != 4) return RQ_ERR_ARG;
+    if (!clip_ok(clip)) return RQ_ERR_ARG;
+    if (rows == 0) return RQ_OK;
+    if (!X || !aligned(X, dtype == RQ_BF16 ? 2 : 4)) return RQ_ERR_ARG;
+    if (!codes || !scales || !aligned(codes, 4) || !aligned(scales, 4)) return RQ_ERR_ARG;
+    return rq::plain_quantize(X, dtype, rows, d, ld, bits, clip, static_cast<uint32_t*>(codes), scales,
+                              static_cast<hipStream_t>(stream));
+}
+
 size_t rq_quant_error_workspace(int64_t rows, int n_clips) {
     if (rows < 0 || n_clips < 1 || n_clips > RQ_MAX_CLIPS) return 0;
     size_t r = rows > 0 ? (size_t)rows : 1;

@@ -45,6 +45,11 @@ int generic_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, 
                             float* scales, hipStream_t s);
 int generic_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
                         float* mse, double* partial, hipStream_t s);
+int generic_rotate_quantize_asym(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
+                                 float* scales, float* mins, hipStream_t s);
+// Rotation-free per-token quantizer (any d that is a multiple of 32).
+int plain_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
+                   uint32_t* codes, float* scales, hipStream_t s);
 bool generic_supports(const rq_hadamard* h);
 bool generic_prepare(const rq_hadamard* h);
 
@@ -53,6 +58,10 @@ std::vector<uint32_t> wave_sylvester_tiles();
 bool wave_supports(const rq_hadamard* h, const RowArgs& a);
 int wave_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                          float* scales, hipStream_t s);
+// Asymmetric group-128 variant on the wave path: bf16 rows of order 128 (one group per row).
+bool wave_asym_supports(const rq_hadamard* h, const RowArgs& a);
+int wave_rotate_quantize_asym(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
+                              float* scales, float* mins, hipStream_t s);
 // quant_error on the wave path (bf16, Sylvester orders 1024 .. 8192): fills partial[rows][n_clips];
 // reduce_partials then averages over rows.
 bool wave_quant_error_supports(const rq_hadamard* h, const RowArgs& a);

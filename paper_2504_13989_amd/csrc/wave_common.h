@@ -144,6 +144,10 @@ struct WaveArgs {
     float* scales;
     double c1;            // (2^b - 1) / clip
     double c2;            // clip / (sqrt(n) (2^b - 1))
+    // asymmetric group variant only
+    float* mins = nullptr;
+    double clip = 0.0;
+    double c3 = 0.0;      // clip / sqrt(n)
 };
 
 
@@ -179,6 +183,19 @@ struct Quant {
             w = (w << BITS) + __float_as_uint(u);
         }
         return (w - csum()) ^ msb();
+    }
+    // Unsigned codes 0 .. 2^b - 1 of (y - cen) * s + bias - kMagic: the asymmetric group
+    // quantizer, centred on the value `cen` that maps to the middle code so that the fp32
+    // products stay as small as in the symmetric case.
+    static __device__ __forceinline__ uint32_t pack8u(const float (&y)[8], float cen, float s, float bias) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int r = 7; r >= 0; --r) {
+            float u = fmaf(y[r] - cen, s, bias);
+            u = __builtin_amdgcn_fmed3f(u, kLo, kHi);
+            w = (w << BITS) + __float_as_uint(u);
+        }
+        return w - csum();
     }
 };
 
@@ -237,6 +254,27 @@ __device__ __forceinline__ float wave_absmax(float mf) {
     return __uint_as_float(m);
 }
 
+// Min and max of a float over the lanes that share a row (same lane pattern as wave_absmax).
+template <int ROW_BITS = 4>
+__device__ __forceinline__ void wave_minmax(float& mn, float& mx) {
+    mn = __builtin_fminf(mn, dpp_f<kDppXor1>(mn));
+    mx = __builtin_fmaxf(mx, dpp_f<kDppXor1>(mx));
+    mn = __builtin_fminf(mn, dpp_f<kDppXor2>(mn));
+    mx = __builtin_fmaxf(mx, dpp_f<kDppXor2>(mx));
+    if (ROW_BITS >= 3) {
+        mn = __builtin_fminf(mn, dpp_f<kDppHalfMirror>(mn));
+        mx = __builtin_fmaxf(mx, dpp_f<kDppHalfMirror>(mx));
+    }
+    if (ROW_BITS >= 4) {
+        mn = __builtin_fminf(mn, dpp_f<kDppRor8>(mn));
+        mx = __builtin_fmaxf(mx, dpp_f<kDppRor8>(mx));
+    }
+    mn = __builtin_fminf(mn, __shfl_xor(mn, 16, 64));
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mn = __builtin_fminf(mn, __shfl_xor(mn, 32, 64));
+    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+}
+
 // c / m for m > 0 with c = ch + cl (float pair): reciprocal, one Newton step, one correction of
 // the quotient, then the low part; about half an ulp.  Used where a full IEEE division per
 // row would be a visible cost (short rows).
@@ -246,6 +284,16 @@ __device__ __forceinline__ float div_pair(float ch, float cl, float m) {
     float q = ch * r;
     q = fmaf(fmaf(-q, m, ch), r, q);
     return fmaf(cl, r, q);
+}
+
+// (ch + cl) / (mh + ml), mh > 0, |ml| <= ulp(mh) / 2: as div_pair with the divisor's low part
+// folded into the last correction.
+__device__ __forceinline__ float div_pair2(float ch, float cl, float mh, float ml) {
+    float r = __builtin_amdgcn_rcpf(mh);
+    r = fmaf(fmaf(-mh, r, 1.0f), r, r);
+    float q = ch * r;
+    q = fmaf(fmaf(-q, mh, ch), r, q);
+    return fmaf(fmaf(-q, ml, cl), r, q);
 }
 
 // 16-byte non-temporal load of a whole chunk (no bounds handling).

@@ -71,6 +71,71 @@ def check_rotate_quantize(x_np, n, b, clip, codes_gpu, scales_gpu, what=""):
             "max_scale_rel": float(rel.max()) if rel.size else 0.0}
 
 
+def check_rotate_quantize_asym(x_np, n, b, clip, codes_gpu, scales_gpu, mins_gpu, what=""):
+    """Asymmetric group-128 variant: codes exact away from rounding boundaries, Delta within 1e-5
+    relative, lo within 1e-5 of the group's range, dequantized values within 1e-5 of the range."""
+    y = oracle.rotate(x_np, n)
+    q, delta, lo, t = oracle.quantize_asym(y, b, clip)
+    rows = q.shape[0]
+    groups = n // oracle.GROUP
+    lvl = (1 << b) - 1
+    codes_gpu = np.asarray(codes_gpu).reshape(rows, n * b // 8)
+    scales_gpu = np.asarray(scales_gpu, dtype=np.float64).reshape(rows, groups)
+    mins_gpu = np.asarray(mins_gpu, dtype=np.float64).reshape(rows, groups)
+    q_gpu = oracle.unpack_codes(codes_gpu, b, n, signed=False)
+    assert q_gpu.max() <= lvl
+    mism = q_gpu != q
+    exempt = oracle.boundary_exempt_asym(t, b, T_TOL)
+    bad = mism & ~exempt
+    if bad.any():
+        r, j = np.argwhere(bad)[0]
+        raise AssertionError(
+            f"{what}: {int(bad.sum())} code mismatches away from rounding boundaries; first at row {r} "
+            f"col {j}: gpu {q_gpu[r, j]} oracle {q[r, j]} t {t[r, j]!r}")
+    if mism.any():
+        assert np.all(np.abs(q_gpu.astype(np.int32) - q.astype(np.int32))[mism] == 1)
+    total = q.size
+    allowed = max(1, int(np.ceil(FRAC_TOL * total)))
+    assert int(mism.sum()) <= allowed, f"{what}: {int(mism.sum())} boundary mismatches > {allowed}"
+    if total >= 1_000_000:
+        assert exempt.sum() <= FRAC_TOL * total, f"{what}: exempt fraction {exempt.mean():.3g}"
+    zero = delta == 0
+    assert np.all(scales_gpu[zero] == 0)
+    rel = np.abs(scales_gpu[~zero] - delta[~zero]) / delta[~zero]
+    assert rel.size == 0 or rel.max() <= REL_TOL, f"{what}: scale rel err {rel.max():.3g}"
+    span = np.maximum(delta * lvl, np.abs(lo))
+    assert np.all(np.abs(mins_gpu - lo) <= REL_TOL * span), f"{what}: group minima differ"
+    dq_gpu = oracle.dequantize_asym(q_gpu, scales_gpu, mins_gpu)
+    dq = oracle.dequantize_asym(q, delta, lo)
+    err = np.abs(dq_gpu - dq)
+    err[exempt] = 0
+    assert np.all(err <= REL_TOL * np.repeat(span, oracle.GROUP, axis=1)), f"{what}: dequantized values differ"
+    if not mism.any():
+        assert np.array_equal(codes_gpu, oracle.pack_codes(q, b)), f"{what}: packed bytes differ"
+    return {"elements": int(total), "mismatches": int(mism.sum()), "exempt": int(exempt.sum())}
+
+
+def check_quantize_plain(x_np, b, clip, codes_gpu, scales_gpu, what=""):
+    """Rotation-free quantizer: same rule as check_rotate_quantize with y = x."""
+    q, delta, t = oracle.quantize_plain(x_np, b, clip)
+    rows, d = q.shape
+    codes_gpu = np.asarray(codes_gpu).reshape(rows, d * b // 8)
+    scales_gpu = np.asarray(scales_gpu, dtype=np.float64).reshape(rows)
+    q_gpu = oracle.unpack_codes(codes_gpu, b, d)
+    mism = q_gpu != q
+    exempt = oracle.boundary_exempt(t, b, T_TOL)
+    bad = mism & ~exempt
+    assert not bad.any(), f"{what}: {int(bad.sum())} code mismatches away from rounding boundaries"
+    assert int(mism.sum()) <= max(1, int(np.ceil(FRAC_TOL * q.size)))
+    zero = delta == 0
+    assert np.all(scales_gpu[zero] == 0)
+    rel = np.abs(scales_gpu[~zero] - delta[~zero]) / delta[~zero]
+    assert rel.size == 0 or rel.max() <= REL_TOL, f"{what}: scale rel err {rel.max():.3g}"
+    if not mism.any():
+        assert np.array_equal(codes_gpu, oracle.pack_codes(q, b)), f"{what}: packed bytes differ"
+    return {"elements": int(q.size), "mismatches": int(mism.sum())}
+
+
 def check_quant_error(x_np, n, b, clips, mse_gpu, rtol=REL_TOL, what=""):
     want = oracle.quant_error(x_np, n, b, clips)
     got = np.asarray(mse_gpu, dtype=np.float64)

@@ -101,6 +101,37 @@ def test_rotate_quantize_argument_errors(L):
     h.close()
 
 
+def test_asym_and_plain_argument_errors(L):
+    import ctypes as C
+    vp = C.c_void_p
+    E = binding.RQ_ERR_ARG
+
+    def asym(h, X=0x1000, dtype=0, rows=4, d=128, ld=128, bits=3, clip=1.0, codes=0x2000, scales=0x3000,
+             mins=0x4000):
+        return L.rq_rotate_quantize_asym(h, vp(X), dtype, rows, d, ld, bits, C.c_float(clip), vp(codes),
+                                         vp(scales), vp(mins), None)
+
+    h = binding.hadamard_build(128)
+    h96 = binding.hadamard_build(96)                 # 3 * 32: not a multiple of the group size
+    assert asym(None) == E
+    assert asym(h._h, mins=0) == E and asym(h._h, scales=0) == E and asym(h._h, codes=0) == E
+    assert asym(h._h, mins=0x4002) == E
+    assert asym(h._h, bits=2) == E and asym(h._h, clip=0.0) == E and asym(h._h, d=129, ld=129) == E
+    assert asym(h96._h, d=96, ld=96) == E
+    assert asym(h._h, rows=0, X=0, codes=0, scales=0, mins=0) == binding.RQ_OK
+    h.close()
+    h96.close()
+
+    def plain(X=0x1000, dtype=0, rows=4, d=128, ld=128, bits=4, clip=1.0, codes=0x2000, scales=0x3000):
+        return L.rq_quantize(vp(X), dtype, rows, d, ld, bits, C.c_float(clip), vp(codes), vp(scales), None)
+
+    assert plain(X=0) == E and plain(codes=0) == E and plain(scales=0) == E
+    assert plain(d=100, ld=100) == E and plain(d=0) == E and plain(ld=64) == E
+    assert plain(dtype=2) == E and plain(bits=5) == E and plain(clip=float("nan")) == E
+    assert plain(X=0x1001) == E and plain(rows=-1) == E
+    assert plain(rows=0, X=0, codes=0, scales=0) == binding.RQ_OK
+
+
 def test_quant_error_argument_errors(L):
     h = binding.hadamard_build(128)
     E = binding.RQ_ERR_ARG

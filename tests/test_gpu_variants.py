@@ -1,0 +1,128 @@
+"""GPU parity of the widened entry points against the oracle: the asymmetric group-128 variant
+(section 5.1, KV cache) and the rotation-free quantizer (section 2.1 alone)."""
+import sys
+
+import numpy as np
+import pytest
+
+import parity
+from paper_2504_13989_amd import binding, workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[variants] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+_handles = {}
+
+
+def handle(n):
+    if n not in _handles:
+        _handles[n] = binding.hadamard_build(n)
+    return _handles[n]
+
+
+def run_asym(torch, x_np, n, b, clip, variant=0):
+    h = handle(n)
+    h.set_variant(variant)
+    codes, scales, mins = binding.rotate_quantize_asym(h, parity.to_device(x_np), b, clip)
+    torch.cuda.synchronize()
+    h.set_variant(0)
+    return codes.cpu().numpy(), scales.cpu().numpy(), mins.cpu().numpy(), h.last_kernel
+
+
+@pytest.mark.parametrize("variant", [0, 1], ids=["auto", "general"])
+@pytest.mark.parametrize("name,rows", [("kv_k", 1029), ("kv_v", 515), ("tiny", 64), ("llama_hidden", 41),
+                                       ("qwen_hidden", 23)])
+@pytest.mark.parametrize("b", [3, 4])
+def test_asym_small(torch, name, rows, b, variant):
+    w = wl.WORKLOADS[name].with_rows(rows)
+    x = wl.generate(w)
+    for clip in (1.0, 0.9):
+        say(f"asym {name} rows={rows} n={w.n} b={b} clip={clip} variant={variant}")
+        codes, scales, mins, kern = run_asym(torch, x, w.n, b, clip, variant)
+        st = parity.check_rotate_quantize_asym(x, w.n, b, clip, codes, scales, mins, f"{name} b={b} [{kern}]")
+        say(f"  ok kernel={kern} {st}")
+        if variant == 0 and w.n == 128 and x.dtype == np.uint16:
+            assert kern == "wave_short_asym"
+
+
+def test_asym_shifted_and_degenerate_groups(torch):
+    # rows far from zero (all-positive groups), constant rows, zero rows, a short ragged tail
+    rng = np.random.default_rng(5)
+    rows = 37
+    xf = rng.standard_normal((rows, 128)).astype(np.float32)
+    xf[3] = 0.0
+    xf[4] = 2.5                      # constant input: rotated row is one spike, not a flat group
+    xf[5, 1:] = 0.0                  # one non-zero input: rotated row has constant magnitude
+    xf[6] += 40.0
+    x = wl.f32_to_bf16_bits(xf)
+    for b in (3, 4):
+        for variant in (0, 1):
+            say(f"asym degenerate b={b} variant={variant}")
+            codes, scales, mins, kern = run_asym(torch, x, 128, b, 0.95, variant)
+            parity.check_rotate_quantize_asym(x, 128, b, 0.95, codes, scales, mins, f"degenerate [{kern}]")
+            assert scales[3, 0] == 0 and mins[3, 0] == 0 and not codes[3].any()
+    # padded width
+    say("asym d=100 of n=128")
+    codes, scales, mins, kern = run_asym(torch, x[:, :100].copy(), 128, 3, 1.0)
+    parity.check_rotate_quantize_asym(x[:, :100], 128, 3, 1.0, codes, scales, mins, f"padded [{kern}]")
+
+
+@pytest.mark.parametrize("name", ["kv_k", "kv_v"])
+def test_asym_full_size_kv_sampled(torch, name):
+    w = wl.WORKLOADS[name]
+    nb = wl.n_blocks(w)
+    blocks = [0, 1, 31, nb // 2 + 5, nb - 1]
+    say(f"asym full {name} [{w.rows} x {w.d}]: generating")
+    x = wl.generate(w)
+    b = w.bits[0]
+    h = handle(w.n)
+    say(f"asym full {name}: launching")
+    codes, scales, mins = binding.rotate_quantize_asym(h, parity.to_device(x), b, w.clip)
+    torch.cuda.synchronize()
+    rows = wl.block_row_index(blocks, w)
+    idx = torch.from_numpy(rows).to("cuda")
+    st = parity.check_rotate_quantize_asym(x[rows], w.n, b, w.clip, codes[idx].cpu().numpy(),
+                                           scales[idx].cpu().numpy(), mins[idx].cpu().numpy(),
+                                           f"{name} asym sampled [{h.last_kernel}]")
+    say(f"  ok kernel={h.last_kernel} sampled_rows={len(rows)} {st}")
+
+
+@pytest.mark.parametrize("name,rows", [("tiny", 64), ("llama_hidden", 333), ("qwen_hidden", 100),
+                                       ("ffn_down", 19), ("kv_k", 1029)])
+@pytest.mark.parametrize("b", [3, 4])
+def test_plain_quantize(torch, name, rows, b):
+    w = wl.WORKLOADS[name].with_rows(rows)
+    x = wl.generate(w)
+    if x.shape[1] % 32:
+        x = np.ascontiguousarray(x[:, : x.shape[1] // 32 * 32])
+    say(f"plain {name} rows={rows} d={x.shape[1]} b={b}")
+    codes, scales = binding.quantize(parity.to_device(x), b, w.clip)
+    torch.cuda.synchronize()
+    st = parity.check_quantize_plain(x, b, w.clip, codes.cpu().numpy(), scales.cpu().numpy(), name)
+    say(f"  ok {st}")
+
+
+def test_plain_quantize_views_and_zero_rows(torch):
+    rng = np.random.default_rng(6)
+    xf = rng.standard_normal((50, 96)).astype(np.float32)
+    xf[7] = 0.0
+    buf = torch.zeros((50, 160), dtype=torch.float32, device="cuda")
+    buf[:, :96] = torch.from_numpy(xf).cuda()
+    codes, scales = binding.quantize(buf[:, :96], 4, 0.8)
+    torch.cuda.synchronize()
+    parity.check_quantize_plain(xf, 4, 0.8, codes.cpu().numpy(), scales.cpu().numpy(), "ld view")
+    assert scales[7].item() == 0 and not codes[7].any().item()
+    c0, s0 = binding.quantize(buf[:0, :96], 4, 0.8)
+    assert c0.shape[0] == 0
