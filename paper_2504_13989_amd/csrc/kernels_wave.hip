@@ -105,7 +105,8 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
 template <int CB, int BITS, int U, bool GUARD, bool ASYM>
 __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_t* base, uint32_t* obase,
                                                 float* sbase, int64_t row0, int rem, const u32x4& A0, const u32x4& A1,
-                                                const uint32_t (&sg)[4], int g, int c, int rsub, int chunk,
+                                                uint32_t sg0, const float (&sf)[4], float flip, int g, int c, int rsub,
+                                                int chunk,
                                                 float c1h, float c1l, float c2h, float c2l) {
     constexpr int RPW = 16 >> CB;
     constexpr int ROW_DWORDS = (32 << CB) * BITS / 32;
@@ -130,47 +131,38 @@ __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
         f32x4 v0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
         f32x4 v1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), bm, z, 0, 0, 0);
-        lane_stage<kDppXor1>(v0, sg[0]);
-        lane_stage<kDppXor1>(v1, sg[0]);
-        lane_stage<kDppXor2>(v0, sg[1]);
-        lane_stage<kDppXor2>(v1, sg[1]);
-        if (CB >= 3) {
-            lane_stage<kDppHalfMirror>(v0, sg[2]);
-            lane_stage<kDppHalfMirror>(v1, sg[2]);
-        }
-        if (CB >= 4) {
-            lane_stage<kDppRor8>(v0, sg[3]);
-            lane_stage<kDppRor8>(v1, sg[3]);
-        }
+        lane_stage<kDppXor1>(v0, sg0);
+        lane_stage<kDppXor1>(v1, sg0);
+        lane_stages_tail<CB>(v0, sf);
+        lane_stages_tail<CB>(v1, sf);
         uint32_t w;
         float m = 0.0f;
         if constexpr (ASYM) {
             // one group of 128 = the whole row (section 5.1, KV cache): min / max instead of absmax
             static_assert(!ASYM || CB == 2, "asymmetric groups: rows of 128 only");
+            // the lane holds flip * y (see lane_stages_fused): its own extremes swap with the sign
             const float yv[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-            float mn = yv[0], mx = yv[0];
-#pragma unroll
-            for (int i = 1; i < 8; ++i) {
-                mn = __builtin_fminf(mn, yv[i]);
-                mx = __builtin_fmaxf(mx, yv[i]);
-            }
-            wave_minmax<CB>(mn, mx);
+            const float lo = min8(yv), hi = max8(yv);
+            float mx = flip > 0.0f ? hi : -lo;
+            float nm = flip > 0.0f ? -lo : hi;                    // -min
+            quad_rows_max_pair(mx, nm);
+            const float mn = -nm;
             const double r64 = (double)mx - (double)mn;           // exact
             const float rh = (float)r64, rl = (float)(r64 - (double)rh);
             const bool flat = !(rh > 0.0f);
-            const float s = flat ? 0.0f : div_pair2(c1h, c1l, rh, rl);
+            const float s = flat ? 0.0f : flip * div_pair2(c1h, c1l, rh, rl);
             constexpr double kMid = (double)(1 << (BITS - 1)) / (double)((1 << BITS) - 1);
-            const float cen = (float)(a.clip * fma(r64, kMid, (double)mn));
+            const float cen = flip * (float)(a.clip * fma(r64, kMid, (double)mn));
             const float bias = flat ? Quant<BITS>::kMagic : Quant<BITS>::kBias;
             w = Quant<BITS>::pack8u(yv, cen, s, bias);
             if (live && g == 0 && c == 0) {
-                sbase[rr] = (float)(r64 * a.c2);
-                a.mins[row0 + rr] = (float)((double)mn * a.c3);
+                sbase[rr] = rh * (float)a.c2;
+                a.mins[row0 + rr] = mn * (float)a.c3;
             }
         } else {
             m = absmax4(absmax4(0.0f, v0), v1);
             m = wave_absmax<CB>(m);                          // over the lanes that share the row
-            const float s = m > 0.0f ? div_pair(c1h, c1l, m) : 0.0f;
+            const float s = m > 0.0f ? flip * div_pair(c1h, c1l, m) : 0.0f;
             w = Quant<BITS>::pack8(v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3], s);
         }
         uint32_t* out = obase + rr * ROW_DWORDS;
@@ -199,9 +191,11 @@ __global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
     const int c = (CB >= 3 && (cphys & 4)) ? (cphys ^ 3) : cphys;
     const int chunk = (g << CB) + c;
     const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
-    uint32_t sg[4];
+    float sf[4];
 #pragma unroll
-    for (int b = 0; b < 4; ++b) sg[b] = ((c >> b) & 1) ? 0x80000000u : 0u;
+    for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
+    const uint32_t sg0 = (c & 1) ? 0x80000000u : 0u;
+    const float flip = (__builtin_popcount(c >> 1) & 1) ? -1.0f : 1.0f;   // stages 2.. are the fused ones
     const float c1h = (float)a.c1, c1l = (float)(a.c1 - (double)c1h);
     const float c2h = (float)a.c2, c2l = (float)(a.c2 - (double)c2h);
     const bool full_d = a.d == N;
@@ -215,10 +209,10 @@ __global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
         uint32_t* obase = a.codes + row0 * ROW_DWORDS;
         float* sbase = a.scales + row0;
         if (rem == SUPER && full_d)
-            short_rows_pass<CB, BITS, U, false, ASYM>(a, base, obase, sbase, row0, rem, A0, A1, sg, g, c, rsub, chunk,
+            short_rows_pass<CB, BITS, U, false, ASYM>(a, base, obase, sbase, row0, rem, A0, A1, sg0, sf, flip, g, c, rsub, chunk,
                                                 c1h, c1l, c2h, c2l);
         else
-            short_rows_pass<CB, BITS, U, true, ASYM>(a, base, obase, sbase, row0, rem, A0, A1, sg, g, c, rsub, chunk,
+            short_rows_pass<CB, BITS, U, true, ASYM>(a, base, obase, sbase, row0, rem, A0, A1, sg0, sf, flip, g, c, rsub, chunk,
                                                c1h, c1l, c2h, c2l);
     }
 }
@@ -449,6 +443,101 @@ __global__ __launch_bounds__(64) void k_wave_quant_error(WaveArgs a, ClipList cl
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Rotation-free quantizer (section 2.1 with the clip ratio of section 3.1 on the row itself): one
+// wave per bf16 row of d <= 512 T values, the row held in registers between the absmax pass and
+// the quantization pass.  Un-rotated bf16 values sit on a coarse grid, so x / Delta lands on or
+// next to a rounding tie far more often than rotated values do; every code whose fp32 residual
+// is within 0.001 of a tie is therefore retaken with the exact fp64 quotient.
+struct PlainArgs {
+    const uint16_t* X;
+    int64_t rows;
+    int d;
+    int64_t ld;
+    uint32_t* codes;
+    float* scales;
+    double clip;
+};
+
+template <int T, int BITS>
+__global__ __launch_bounds__(64) void k_plain_wave(PlainArgs a) {
+    const int lane = threadIdx.x;
+    const int nchunks = a.d >> 3;
+    const int row_dwords = a.d * BITS / 32;
+    constexpr double kLvl = (double)((1 << BITS) - 1);
+    constexpr float kQmin = -(float)(1 << (BITS - 1)), kQmax = (float)((1 << (BITS - 1)) - 1);
+    for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
+        const uint16_t* xr = a.X + row * a.ld;
+        u32x4 raw[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int idx = t * 64 + lane;
+            const bool in = idx < nchunks;
+            raw[t] = load16(xr + (in ? idx * 8 : 0));
+            if (!in) raw[t] = u32x4{0u, 0u, 0u, 0u};
+        }
+        float m = 0.0f;
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t w = raw[t][k];
+                m = __builtin_fmaxf(m, __builtin_fabsf(__uint_as_float(w << 16)));
+                m = __builtin_fmaxf(m, __builtin_fabsf(__uint_as_float(w & 0xffff0000u)));
+            }
+        m = wave_absmax<4>(m);
+        const double delta = a.clip * (double)m / kLvl;
+        const float s = m > 0.0f ? (float)(kLvl / (a.clip * (double)m)) : 0.0f;
+        uint32_t* out = a.codes + row * (int64_t)row_dwords;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int idx = t * 64 + lane;
+            float x[8];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                x[2 * k] = __uint_as_float(raw[t][k] << 16);
+                x[2 * k + 1] = __uint_as_float(raw[t][k] & 0xffff0000u);
+            }
+            uint32_t w = 0;
+            bool near = false;
+#pragma unroll
+            for (int r = 7; r >= 0; --r) {
+                float u = fmaf(x[r], s, Quant<BITS>::kBias);
+                const float e = fmaf(x[r], s, Quant<BITS>::kBias - u);     // t - round(t)
+                near |= __builtin_fabsf(e) > 0.499f;
+                u = __builtin_amdgcn_fmed3f(u, Quant<BITS>::kLo, Quant<BITS>::kHi);
+                w = (w << BITS) + __float_as_uint(u);
+            }
+            w = (w - Quant<BITS>::csum()) ^ Quant<BITS>::msb();
+            if (near) {
+                w = 0;
+#pragma unroll
+                for (int r = 7; r >= 0; --r) {
+                    const float q = fminf(fmaxf((float)rint((double)x[r] / delta), kQmin), kQmax);
+                    w = (w << BITS) | ((uint32_t)(int)q & ((1u << BITS) - 1u));
+                }
+            }
+            if (BITS == 4) {
+                if (idx < nchunks) store_codes(out + idx, w);
+            } else {
+                const int qpos = lane & 3;
+                const uint32_t dw = merge24<false>(w, qpos);
+                if (idx < nchunks && qpos < 3) store_codes(out + (idx >> 2) * 3 + qpos, dw);
+            }
+        }
+        if (lane == 0) a.scales[row] = (float)delta;
+    }
+}
+
+template <int T>
+int launch_plain(const PlainArgs& a, int bits, hipStream_t s) {
+    const int64_t cap = 1 << 24;
+    const unsigned grid = (unsigned)(a.rows < cap ? a.rows : cap);
+    if (bits == 4) hipLaunchKernelGGL((k_plain_wave<T, 4>), dim3(grid), dim3(64), 0, s, a);
+    else hipLaunchKernelGGL((k_plain_wave<T, 3>), dim3(grid), dim3(64), 0, s, a);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
 template <typename K>
 int launch_wave(K kernel, const rq_hadamard* h, const WaveArgs& a, int64_t items, int waves_per_simd,
                 hipStream_t s) {
@@ -634,6 +723,24 @@ int wave_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uin
         case 13: return launch_long<16>(h, w, a.bits, s);
         default: return RQ_ERR_NO_ORDER;
     }
+}
+
+bool plain_wave_supports(const void* X, int dtype, int d, int64_t ld) {
+    return dtype == RQ_BF16 && d % 32 == 0 && d <= 512 * 40 && ld % 8 == 0 &&
+           (reinterpret_cast<uintptr_t>(X) % 16) == 0;
+}
+
+int plain_wave_quantize(const void* X, int64_t rows, int d, int64_t ld, int bits, float clip,
+                        uint32_t* codes, float* scales, hipStream_t s) {
+    const PlainArgs a{static_cast<const uint16_t*>(X), rows, d, ld, codes, scales, (double)clip};
+    const int t = (d + 511) / 512;
+    if (t <= 1) return launch_plain<1>(a, bits, s);
+    if (t <= 2) return launch_plain<2>(a, bits, s);
+    if (t <= 4) return launch_plain<4>(a, bits, s);
+    if (t <= 8) return launch_plain<8>(a, bits, s);
+    if (t <= 16) return launch_plain<16>(a, bits, s);
+    if (t <= 24) return launch_plain<24>(a, bits, s);
+    return launch_plain<40>(a, bits, s);
 }
 
 bool wave_asym_supports(const rq_hadamard* h, const RowArgs& a) {

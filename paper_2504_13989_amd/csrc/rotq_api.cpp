@@ -202,6 +202,9 @@ int rq_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int b
     if (rows == 0) return RQ_OK;
     if (!X || !aligned(X, dtype == RQ_BF16 ? 2 : 4)) return RQ_ERR_ARG;
     if (!codes || !scales || !aligned(codes, 4) || !aligned(scales, 4)) return RQ_ERR_ARG;
+    if (rq::plain_wave_supports(X, dtype, d, ld))
+        return rq::plain_wave_quantize(X, rows, d, ld, bits, clip, static_cast<uint32_t*>(codes), scales,
+                                       static_cast<hipStream_t>(stream));
     return rq::plain_quantize(X, dtype, rows, d, ld, bits, clip, static_cast<uint32_t*>(codes), scales,
                               static_cast<hipStream_t>(stream));
 }

@@ -50,6 +50,10 @@ int generic_rotate_quantize_asym(const rq_hadamard* h, const RowArgs& a, float c
 // Rotation-free per-token quantizer (any d that is a multiple of 32).
 int plain_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
                    uint32_t* codes, float* scales, hipStream_t s);
+// The same on the wave path: bf16 rows up to 20480 wide, 16-byte aligned.
+bool plain_wave_supports(const void* X, int dtype, int d, int64_t ld);
+int plain_wave_quantize(const void* X, int64_t rows, int d, int64_t ld, int bits, float clip,
+                        uint32_t* codes, float* scales, hipStream_t s);
 bool generic_supports(const rq_hadamard* h);
 bool generic_prepare(const rq_hadamard* h);
 

@@ -71,6 +71,63 @@ __device__ __forceinline__ void lane_stages_fused(f32x4& v, float s0, float s1, 
     v[0] = x0; v[1] = x1; v[2] = x2; v[3] = x3;
 }
 
+// Stages 2 .. CB (xor-2, half mirror, xor-8) fused as above, for values that come straight from
+// the matrix cores: stage 1 is then taken with lane_stage, whose instructions the compiler sees
+// and separates from the matrix-core write by the required wait states (it does not look inside
+// an assembly block).
+__device__ __forceinline__ void lane_stages_tail_1(f32x4& v, float s1) {
+    float x0 = v[0], x1 = v[1], x2 = v[2], x3 = v[3];
+    asm("s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %0, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf"
+        : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3)
+        : "v"(s1));
+    v[0] = x0; v[1] = x1; v[2] = x2; v[3] = x3;
+}
+__device__ __forceinline__ void lane_stages_tail_2(f32x4& v, float s1, float s2) {
+    float x0 = v[0], x1 = v[1], x2 = v[2], x3 = v[3];
+    asm("s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %0, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %0, %5 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %5 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %5 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %5 row_half_mirror row_mask:0xf bank_mask:0xf"
+        : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3)
+        : "v"(s1), "v"(s2));
+    v[0] = x0; v[1] = x1; v[2] = x2; v[3] = x3;
+}
+__device__ __forceinline__ void lane_stages_tail_3(f32x4& v, float s1, float s2, float s3) {
+    float x0 = v[0], x1 = v[1], x2 = v[2], x3 = v[3];
+    asm("s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %0, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %0, %5 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %5 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %5 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %5 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %0, %6 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %1, %6 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %2, %6 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %3, %6 row_ror:8 row_mask:0xf bank_mask:0xf"
+        : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3)
+        : "v"(s1), "v"(s2), "v"(s3));
+    v[0] = x0; v[1] = x1; v[2] = x2; v[3] = x3;
+}
+
+template <int CB>
+__device__ __forceinline__ void lane_stages_tail(f32x4& v, const float (&sf)[4]) {
+    if constexpr (CB == 2) lane_stages_tail_1(v, sf[1]);
+    else if constexpr (CB == 3) lane_stages_tail_2(v, sf[1], sf[2]);
+    else lane_stages_tail_3(v, sf[1], sf[2], sf[3]);
+}
+
 // The same on one, two or three values; with fewer than three values in flight an s_nop keeps
 // two wait states between a value's consecutive stages.
 __device__ __forceinline__ void lane_stages_fused1(float& x0, float s0, float s1, float s2, float s3) {
@@ -238,6 +295,16 @@ __device__ __forceinline__ void copy_out16(const uint8_t* stage, uint32_t* out, 
 // Packed codes are written once and not read back by this kernel: non-temporal store.
 __device__ __forceinline__ void store_codes(uint32_t* p, uint32_t v) { __builtin_nontemporal_store(v, p); }
 
+// Max over the four DPP rows of a wave (lanes l, l ^ 16, l ^ 32, l ^ 48) with the row-swap
+// instructions: v_permlane16_swap(a, b) returns rows [a0 b0 a2 b2] and [a1 b1 a3 b3],
+// v_permlane32_swap(a, b) returns [a0 a1 b0 b1] and [a2 a3 b2 b3]; no LDS traffic.
+__device__ __forceinline__ uint32_t rows_max_u32(uint32_t m) {
+    const auto a = __builtin_amdgcn_permlane16_swap(m, m, false, false);
+    m = max((uint32_t)a[0], (uint32_t)a[1]);
+    const auto b = __builtin_amdgcn_permlane32_swap(m, m, false, false);
+    return max((uint32_t)b[0], (uint32_t)b[1]);
+}
+
 // Max of a non-negative float over lanes: non-negative floats order like their bit patterns,
 // so the reduction runs on unsigned integers (one DPP-fused v_max_u32 per step).  ROW_BITS of
 // the four DPP row patterns are used (lanes that share a row differ in those bits), then the two
@@ -249,30 +316,53 @@ __device__ __forceinline__ float wave_absmax(float mf) {
     m = max(m, dpp_u<kDppXor2>(m));
     if (ROW_BITS >= 3) m = max(m, dpp_u<kDppHalfMirror>(m));
     if (ROW_BITS >= 4) m = max(m, dpp_u<kDppRor8>(m));
-    m = max(m, (uint32_t)__shfl_xor((int)m, 16, 64));
-    m = max(m, (uint32_t)__shfl_xor((int)m, 32, 64));
-    return __uint_as_float(m);
+    return __uint_as_float(rows_max_u32(m));
 }
 
-// Min and max of a float over the lanes that share a row (same lane pattern as wave_absmax).
-template <int ROW_BITS = 4>
-__device__ __forceinline__ void wave_minmax(float& mn, float& mx) {
-    mn = __builtin_fminf(mn, dpp_f<kDppXor1>(mn));
-    mx = __builtin_fmaxf(mx, dpp_f<kDppXor1>(mx));
-    mn = __builtin_fminf(mn, dpp_f<kDppXor2>(mn));
-    mx = __builtin_fmaxf(mx, dpp_f<kDppXor2>(mx));
-    if (ROW_BITS >= 3) {
-        mn = __builtin_fminf(mn, dpp_f<kDppHalfMirror>(mn));
-        mx = __builtin_fmaxf(mx, dpp_f<kDppHalfMirror>(mx));
-    }
-    if (ROW_BITS >= 4) {
-        mn = __builtin_fminf(mn, dpp_f<kDppRor8>(mn));
-        mx = __builtin_fmaxf(mx, dpp_f<kDppRor8>(mx));
-    }
-    mn = __builtin_fminf(mn, __shfl_xor(mn, 16, 64));
-    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mn = __builtin_fminf(mn, __shfl_xor(mn, 32, 64));
-    mx = __builtin_fmaxf(mx, __shfl_xor(mx, 32, 64));
+// Min / max of eight floats as three-operand instructions.  Written in assembly because the
+// values come out of an assembly block: the compiler would first pass each of them through a
+// canonicalizing v_max_f32 x, x, which costs as much as the reduction itself.
+__device__ __forceinline__ float max8(const float (&y)[8]) {
+    float m;
+    asm("v_max3_f32 %0, %1, %2, %3\n\t"
+        "v_max3_f32 %0, %0, %4, %5\n\t"
+        "v_max3_f32 %0, %0, %6, %7\n\t"
+        "v_max_f32 %0, %0, %8"
+        : "=&v"(m)
+        : "v"(y[0]), "v"(y[1]), "v"(y[2]), "v"(y[3]), "v"(y[4]), "v"(y[5]), "v"(y[6]), "v"(y[7]));
+    return m;
+}
+__device__ __forceinline__ float min8(const float (&y)[8]) {
+    float m;
+    asm("v_min3_f32 %0, %1, %2, %3\n\t"
+        "v_min3_f32 %0, %0, %4, %5\n\t"
+        "v_min3_f32 %0, %0, %6, %7\n\t"
+        "v_min_f32 %0, %0, %8"
+        : "=&v"(m)
+        : "v"(y[0]), "v"(y[1]), "v"(y[2]), "v"(y[3]), "v"(y[4]), "v"(y[5]), "v"(y[6]), "v"(y[7]));
+    return m;
+}
+
+// Max of two floats at once (mx and nm = -min) over the 4 lanes of a quad and the four DPP rows:
+// the lanes that hold one row of 128 values.  The quad steps are DPP-fused maxima (assembly: the
+// compiler does not fold a DPP operand into a float max); the row steps carry mx in rows 0 / 2
+// and nm in rows 1 / 3, so that three row swaps and two maxima serve both values.
+__device__ __forceinline__ void quad_rows_max_pair(float& mx, float& nm) {
+    asm("s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 3"
+        : "+v"(mx), "+v"(nm));
+    const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(mx), __float_as_uint(nm), false, false);
+    float x = __builtin_fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __builtin_fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+    const auto c = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    mx = __uint_as_float(c[0]);
+    nm = __uint_as_float(c[1]);
 }
 
 // c / m for m > 0 with c = ch + cl (float pair): reciprocal, one Newton step, one correction of
