@@ -196,6 +196,41 @@ def rotate(x: np.ndarray, n: int) -> np.ndarray:
     return y.reshape(rows, n) / math.sqrt(n)
 
 
+def rotate_back(y: np.ndarray, n: int, d: int = None) -> np.ndarray:
+    """x = H_n^T y / sqrt(n), first d columns: the inverse of rotate (H_n^T H_n = n I,
+    section 2.3), which also drops the coordinates that section 4.2 padded with zeros.
+    (H_p (x) H_{2^k})^T = H_p^T (x) H_{2^k}: the Sylvester factor is symmetric, a Paley block
+    in general is not."""
+    y = np.asarray(y, dtype=np.float64)
+    rows, width = y.shape
+    if width != n:
+        raise ValueError("rotated rows have width n")
+    hp, hs = hadamard_factors(n)
+    p, m = hp.shape[0], hs.shape[0]
+    ym = y.reshape(rows, p, m)
+    x = np.matmul(ym, hs.astype(np.float64))                   # along c: H^T[c, c'] = H[c', c]
+    x = np.einsum("ba,rbc->rac", hp.astype(np.float64), x)     # along a: H_p^T
+    x = x.reshape(rows, n) / math.sqrt(n)
+    return x if d is None else x[:, :d]
+
+
+def fuse_weight(w: np.ndarray, n: int) -> np.ndarray:
+    """Offline weight fusion of section 4.2, Eq. 2: W [d, out] is padded with zero rows to
+    [n, out] and multiplied by the Hadamard matrix, W' = H_n pad(W) / sqrt(n), so that
+    rotate(x) @ W' = x @ W for every row x (the 1 / sqrt(n) of both sides included)."""
+    w = as_f64(w)
+    return rotate(w.T, n).T
+
+
+def expand_limit(n: int, b: int, b_prime: int) -> int:
+    """Lemma "Expanding limit" (section 4.2): the largest number d of added dimensions for which
+    the product at b' bits costs no more bit operations than the original at b bits,
+    (n + d) b' <= n b, i.e. floor(n (b - b') / b')."""
+    if not (1 <= b_prime <= b) or n < 1:
+        raise ValueError("need 1 <= b' <= b and n >= 1")
+    return (n * (b - b_prime)) // b_prime
+
+
 # --------------------------------------------------------------------------- quantizer
 
 def quant_params(b: int):

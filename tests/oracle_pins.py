@@ -426,6 +426,55 @@ def check_boundary_mask(o):
     assert m4.tolist() == [[True, True, False, True, True, True, True, False, False]]
 
 
+# ----------------------------------------------------------------------------- inverse, fusion, limit
+
+def check_rotate_back_inverts(o):
+    rng = np.random.default_rng(21)
+    for n, d in ((64, 64), (96, 96), (96, 70), (224, 200), (3584, 3584)):       # 96 = 12*8, 224 = 28*8
+        x = rng.standard_normal((3, d))
+        y = o.rotate(x, n)
+        xb = o.rotate_back(y, n, d)
+        assert np.allclose(xb, x, atol=1e-12), n
+        full = o.rotate_back(y, n)
+        assert np.allclose(full[:, d:], 0.0, atol=1e-12)
+        # against the dense definition: x = H^T y / sqrt(n)
+        if n <= 224:
+            h = o.hadamard_dense(n).astype(np.float64)
+            assert np.allclose(full, (h.T @ y.T).T / np.sqrt(n), atol=1e-12)
+    # a Paley I block is not symmetric: using H instead of H^T must not invert
+    h12 = o.hadamard_dense(96).astype(np.float64)
+    assert not np.array_equal(h12, h12.T)
+    e = np.zeros((1, 96)); e[0, 5] = 1.0
+    assert np.allclose(o.rotate_back(e, 96), h12[5:6, :] / np.sqrt(96))        # row 5 of H = column 5 of H^T
+
+
+def check_fuse_weight(o):
+    # Eq. 2: order 4, W = [[a, b], [c, d]] padded with two zero rows
+    g = _read_matrices("eq2_expand.txt")["M"]
+    a, b, c, d = 3.0, -1.0, 0.5, 2.0
+    w = np.array([[a, b], [c, d]])
+    want = g @ np.array([[a, b], [c, d], [0, 0], [0, 0]]) / 2.0
+    assert np.allclose(o.fuse_weight(w, 4), want)
+    # the product is preserved: rotate(x) @ W' = x @ W, also with padding and a Paley block
+    rng = np.random.default_rng(22)
+    for n, din in ((64, 64), (96, 80), (224, 224)):
+        w = rng.standard_normal((din, 7))
+        x = rng.standard_normal((5, din))
+        assert np.allclose(o.rotate(x, n) @ o.fuse_weight(w, n), x @ w, atol=1e-11)
+        assert o.fuse_weight(w, n).shape == (n, 7)
+
+
+def check_expand_limit(o):
+    # section 4.2's example: n = 4096, 4 -> 3 bits; n (b - b') / b' = 1365.33 (printed rounded up, 1366)
+    assert o.expand_limit(4096, 4, 3) == 1365
+    for n, b, bp in ((4096, 4, 3), (1536, 8, 4), (100, 4, 4), (7, 5, 2)):
+        d = o.expand_limit(n, b, bp)
+        assert (n + d) * bp <= n * b < (n + d + 1) * bp
+        # the lemma's own inequality on the squared cost (m, p cancel)
+        assert (n + d) ** 2 * bp ** 2 <= n ** 2 * b ** 2 < (n + d + 1) ** 2 * bp ** 2
+    assert o.expand_limit(100, 4, 4) == 0 and o.expand_limit(1536, 8, 4) == 1536
+
+
 # ----------------------------------------------------------------------------- asymmetric groups
 
 def check_asym_properties(o):

@@ -71,6 +71,11 @@ MUTATIONS = {
     "pack_field_msb_first": ("(field[:, :, None] >> np.arange(b)) & 1", "(field[:, :, None] >> np.arange(b)[::-1]) & 1"),
     "unpack_no_sign": ("field = np.where(field >= (1 << (b - 1)), field - (1 << b), field)", "field = field"),
     "boundary_tol": ("return (frac < tol)", "return (frac < 10 * tol)"),
+    "back_not_transposed": ('x = np.einsum("ba,rbc->rac", hp.astype(np.float64), x)', 'x = np.einsum("ab,rbc->rac", hp.astype(np.float64), x)'),
+    "back_unnormalised": ("    x = x.reshape(rows, n) / math.sqrt(n)\n", "    x = x.reshape(rows, n) / n\n"),
+    "fuse_wrong_side": ("    return rotate(w.T, n).T\n", "    return rotate_back(np.pad(w.T, ((0, 0), (0, n - w.shape[0]))), n).T\n"),
+    "limit_rounds_up": ("    return (n * (b - b_prime)) // b_prime", "    return -((-n * (b - b_prime)) // b_prime)"),
+    "limit_wrong_divisor": ("    return (n * (b - b_prime)) // b_prime", "    return (n * (b - b_prime)) // b"),
     "asym_clip_one_side": ("    hi = clip64 * yg.max(axis=2)", "    hi = yg.max(axis=2)"),
     "asym_levels": ("    delta = (hi - lo) / lvl\n", "    delta = (hi - lo) / (lvl + 1)\n"),
     "asym_offset_dropped": ("return (cg * delta[:, :, None] + lo[:, :, None]).reshape(rows, n)", "return (cg * delta[:, :, None]).reshape(rows, n)"),
