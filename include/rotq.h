@@ -153,6 +153,44 @@ int rq_rotate_quantize_asym(const rq_hadamard_t* h,
 int rq_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld,
                 int bits, float clip, void* codes, float* scales, void* stream);
 
+/*
+ * Rotation alone with a floating-point result: Y = (H_n pad(x) / sqrt(n))[:d_out] for every row,
+ * or with H_n^T when transpose = 1.  Two uses:
+ *   - offline weight fusion (section 4.2, Eq. 2): W' = H_n pad(W) / sqrt(n) is this call on the
+ *     rows of W^T (input side) or of W (output side), so that rotate(x) W' = x W;
+ *   - the inverse rotation x = H_n^T y / sqrt(n) (H_n^T H_n = n I, section 2.3) with
+ *     transpose = 1 and d_out = the un-padded width.
+ *   X        [in]  DEVICE, rows x d, leading dimension ld, `dtype` (as rq_rotate_quantize)
+ *   Y        [out] DEVICE, rows x d_out elements of out_dtype (RQ_F32, or RQ_BF16 rounded to
+ *                  nearest even), leading dimension ld_out >= d_out; 1 <= d_out <= n
+ * rows == 0 is a successful no-op.
+ * Errors: RQ_ERR_ARG, RQ_ERR_NO_ORDER (the row does not fit the kernel's LDS), RQ_ERR_HIP.
+ */
+int rq_rotate(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d, int64_t ld,
+              int transpose, void* Y, int out_dtype, int d_out, int64_t ld_out, void* stream);
+
+/*
+ * Dequantize packed codes and rotate back (the inverse of rq_rotate_quantize up to the
+ * quantization error): y^ = code * Delta (mins == NULL, signed codes) or code * Delta_g + lo_g
+ * (mins != NULL, unsigned codes in groups of RQ_GROUP as written by rq_rotate_quantize_asym),
+ * then Y = (H_n^T y^ / sqrt(n))[:d_out] with transpose = 1 (transpose = 0 applies H_n).
+ *   codes, scales, mins [in] DEVICE, layouts as the quantizing calls write them
+ *   Y                   [out] as in rq_rotate
+ * Errors: RQ_ERR_ARG, RQ_ERR_NO_ORDER, RQ_ERR_HIP.
+ */
+int rq_dequantize_rotate(const rq_hadamard_t* h, const void* codes, const float* scales,
+                         const float* mins, int64_t rows, int bits, int transpose,
+                         void* Y, int out_dtype, int d_out, int64_t ld_out, void* stream);
+
+/*
+ * Lemma "Expanding limit" (section 4.2): the largest number of added dimensions d for which a
+ * product over n + d dimensions at bits_reduced bits costs no more bit operations than the
+ * product over n dimensions at `bits` bits: (n + d) * bits_reduced <= n * bits, i.e.
+ * floor(n (bits - bits_reduced) / bits_reduced).  Host-only; d_max is a HOST pointer.
+ * Errors: RQ_ERR_ARG (n < 1, bits_reduced < 1, bits_reduced > bits, bits > 64, NULL).
+ */
+int rq_expand_limit(int n, int bits, int bits_reduced, int64_t* d_max);
+
 /* Bytes of device workspace rq_quant_error needs for (rows, n_clips); 0 on bad arguments. */
 size_t rq_quant_error_workspace(int64_t rows, int n_clips);
 

@@ -4,6 +4,6 @@
 seeded synthetic input generators; `build` compiles the library in-tree.
 """
 from . import workloads  # noqa: F401
-from .binding import (Hadamard, RotqError, gbs_search, hadamard_build, next_order,  # noqa: F401
-                      quant_error, quant_error_workspace, quantize, rotate_quantize,
+from .binding import (Hadamard, RotqError, dequantize_rotate, expand_limit, gbs_search, hadamard_build, next_order,  # noqa: F401
+                      quant_error, quant_error_workspace, quantize, rotate, rotate_quantize,
                       rotate_quantize_asym)

@@ -47,6 +47,9 @@ def lib() -> C.CDLL:
     L.rq_rotate_quantize.argtypes = [vp, vp, i32, i64, i32, i64, i32, C.c_float, vp, vp, vp]
     L.rq_rotate_quantize_asym.argtypes = [vp, vp, i32, i64, i32, i64, i32, C.c_float, vp, vp, vp, vp]
     L.rq_quantize.argtypes = [vp, i32, i64, i32, i64, i32, C.c_float, vp, vp, vp]
+    L.rq_rotate.argtypes = [vp, vp, i32, i64, i32, i64, i32, vp, i32, i32, i64, vp]
+    L.rq_dequantize_rotate.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, i32, i32, i64, vp]
+    L.rq_expand_limit.argtypes = [i32, i32, i32, C.POINTER(C.c_int64)]
     L.rq_quant_error_workspace.argtypes = [i64, i32]
     L.rq_quant_error_workspace.restype = C.c_size_t
     L.rq_quant_error.argtypes = [vp, vp, i32, i64, i32, i64, i32, f32p, i32, vp, vp, C.c_size_t, vp]
@@ -205,6 +208,60 @@ def quantize(x, bits: int, clip: float, codes=None, scales=None, stream=None):
                            C.c_void_p(scales.data_ptr()), _stream_ptr(stream))
     _check(rc, "rq_quantize")
     return codes, scales
+
+
+def _out_code(torch, dtype):
+    if dtype == torch.float32:
+        return RQ_F32
+    if dtype == torch.bfloat16:
+        return RQ_BF16
+    raise ValueError("output dtype must be float32 or bfloat16")
+
+
+def rotate(h: Hadamard, x, transpose: bool = False, d_out: Optional[int] = None, out_dtype=None,
+           out=None, stream=None):
+    """rq_rotate on a CUDA tensor x [..., d]: (H_n pad(x) / sqrt(n))[:, :d_out] per row (H_n^T with
+    transpose), as float32 (default) or bfloat16.  Applied to the rows of a weight stored
+    [out_features, in_features] it is the offline input-side fusion of section 4.2."""
+    import torch
+    if not x.is_cuda:
+        raise ValueError("x must be a device tensor")
+    x2, rows, d, ld = _rows_view(x)
+    d_out = h.n if d_out is None else int(d_out)
+    if out is None:
+        out = torch.empty((rows, d_out), dtype=out_dtype or torch.float32, device=x.device)
+    rc = lib().rq_rotate(h._h, C.c_void_p(x2.data_ptr()), _dtype_code(x2), rows, d, ld,
+                         1 if transpose else 0, C.c_void_p(out.data_ptr()), _out_code(torch, out.dtype),
+                         d_out, out.stride(0) if rows > 1 else max(d_out, out.stride(0)),
+                         _stream_ptr(stream))
+    _check(rc, "rq_rotate")
+    return out
+
+
+def dequantize_rotate(h: Hadamard, codes, scales, bits: int, mins=None, transpose: bool = True,
+                      d_out: Optional[int] = None, out_dtype=None, out=None, stream=None):
+    """rq_dequantize_rotate: packed codes (+ scales, + mins for the asymmetric variant) back to
+    rows in the original basis, (H_n^T y^ / sqrt(n))[:, :d_out]."""
+    import torch
+    rows = codes.shape[0]
+    d_out = h.n if d_out is None else int(d_out)
+    if out is None:
+        out = torch.empty((rows, d_out), dtype=out_dtype or torch.float32, device=codes.device)
+    rc = lib().rq_dequantize_rotate(h._h, C.c_void_p(codes.data_ptr()), C.c_void_p(scales.data_ptr()),
+                                    C.c_void_p(mins.data_ptr()) if mins is not None else None, rows,
+                                    int(bits), 1 if transpose else 0, C.c_void_p(out.data_ptr()),
+                                    _out_code(torch, out.dtype), d_out,
+                                    out.stride(0) if rows > 1 else max(d_out, out.stride(0)),
+                                    _stream_ptr(stream))
+    _check(rc, "rq_dequantize_rotate")
+    return out
+
+
+def expand_limit(n: int, bits: int, bits_reduced: int) -> int:
+    """rq_expand_limit: floor(n (bits - bits_reduced) / bits_reduced) (Lemma "Expanding limit")."""
+    out = C.c_int64(0)
+    _check(lib().rq_expand_limit(int(n), int(bits), int(bits_reduced), C.byref(out)), "rq_expand_limit")
+    return int(out.value)
 
 
 def quant_error_workspace(rows: int, n_clips: int) -> int:

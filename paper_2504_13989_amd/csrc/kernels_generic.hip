@@ -31,15 +31,12 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
-// Rotates one row into LDS (un-normalised: y_u = H_n pad(x)) and returns the buffer that holds
-// it; also returns the row's max |y_u| in *amax (same value in every thread).
-__device__ float* rotate_row_lds(const RowArgs& a, int64_t row, float* buf0, float* buf1,
-                                 float* red, float* amax) {
+// Transforms the row held in buf0 (n floats, already visible to the whole workgroup) in place
+// and returns the buffer that holds the un-normalised result H_n v, or H_n^T v when `transpose`
+// is set ((H_p (x) H_m)^T = H_p^T (x) H_m: only the +-1 block changes).
+__device__ float* transform_row_lds(const RowArgs& a, float* buf0, float* buf1, bool transpose) {
     const int tid = threadIdx.x;
     const int n = a.n;
-    const int64_t base = row * a.ld;
-    for (int j = tid; j < n; j += kThreads) buf0[j] = (j < a.d) ? load_f32(a.X, a.dtype, base + j) : 0.0f;
-    __syncthreads();
     for (int s = 0; s < a.log2m; ++s) {
         const int h = 1 << s;
         for (int idx = tid; idx < n / 2; idx += kThreads) {
@@ -50,22 +47,38 @@ __device__ float* rotate_row_lds(const RowArgs& a, int64_t row, float* buf0, flo
         }
         __syncthreads();
     }
-    float* y = buf0;
-    if (a.p > 1) {
-        const int m = 1 << a.log2m;
-        for (int o = tid; o < n; o += kThreads) {
-            const int ao = o >> a.log2m, c = o & (m - 1);
-            const int8_t* hrow = a.block + (size_t)ao * a.p;
-            double acc = 0.0;
-            for (int ai = 0; ai < a.p; ++ai) {
-                const float v = buf0[ai * m + c];
-                acc += (hrow[ai] > 0) ? (double)v : -(double)v;
-            }
-            buf1[o] = (float)acc;
+    if (a.p == 1) return buf0;
+    const int m = 1 << a.log2m;
+    for (int o = tid; o < n; o += kThreads) {
+        const int ao = o >> a.log2m, c = o & (m - 1);
+        const int8_t* hrow = transpose ? a.block + ao : a.block + (size_t)ao * a.p;
+        const int hstep = transpose ? a.p : 1;
+        double acc = 0.0;
+        for (int ai = 0; ai < a.p; ++ai) {
+            const float v = buf0[ai * m + c];
+            acc += (hrow[(size_t)ai * hstep] > 0) ? (double)v : -(double)v;
         }
-        __syncthreads();
-        y = buf1;
+        buf1[o] = (float)acc;
     }
+    __syncthreads();
+    return buf1;
+}
+
+__device__ void load_row_lds(const RowArgs& a, int64_t row, float* buf0) {
+    const int64_t base = row * a.ld;
+    for (int j = threadIdx.x; j < a.n; j += kThreads)
+        buf0[j] = (j < a.d) ? load_f32(a.X, a.dtype, base + j) : 0.0f;
+    __syncthreads();
+}
+
+// Rotates one row into LDS (un-normalised: y_u = H_n pad(x)) and returns the buffer that holds
+// it; also returns the row's max |y_u| in *amax (same value in every thread).
+__device__ float* rotate_row_lds(const RowArgs& a, int64_t row, float* buf0, float* buf1,
+                                 float* red, float* amax) {
+    const int tid = threadIdx.x;
+    const int n = a.n;
+    load_row_lds(a, row, buf0);
+    float* y = transform_row_lds(a, buf0, buf1, false);
     float mx = 0.0f;
     for (int j = tid; j < n; j += kThreads) mx = fmaxf(mx, fabsf(y[j]));
     mx = wave_max(mx);
@@ -73,6 +86,62 @@ __device__ float* rotate_row_lds(const RowArgs& a, int64_t row, float* buf0, flo
     __syncthreads();
     *amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     return y;
+}
+
+// Store of one result value as fp32 or bf16 (round to nearest even).
+__device__ __forceinline__ void store_out(const OutArgs& o, int64_t idx, float v) {
+    if (o.dtype == RQ_BF16) {
+        const uint32_t u = __float_as_uint(v);
+        static_cast<uint16_t*>(o.Y)[idx] = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+    } else {
+        static_cast<float*>(o.Y)[idx] = v;
+    }
+}
+
+// Rotation alone, floating-point result: Y = (H_n pad(x) / sqrt(n))[:d_out], or with H_n^T.
+// Serves the offline weight fusion of section 4.2 (Eq. 2: rows of W^T or of W) and the
+// inverse rotation x = H_n^T y / sqrt(n) (section 2.3).
+__global__ __launch_bounds__(kThreads) void k_generic_rotate(RowArgs a, int transpose, OutArgs o) {
+    extern __shared__ float lds[];
+    const int64_t row = blockIdx.x;
+    load_row_lds(a, row, lds);
+    const float* y = transform_row_lds(a, lds, lds + a.n, transpose != 0);
+    const double inv = 1.0 / sqrt((double)a.n);
+    for (int j = threadIdx.x; j < o.d_out; j += kThreads)
+        store_out(o, row * o.ld_out + j, (float)((double)y[j] * inv));
+}
+
+// Dequantize-and-rotate-back: y^ from packed codes (symmetric: code * Delta, the transform then
+// runs on the integer codes, which fp32 adds exactly; asymmetric groups of 128: code * Delta_g +
+// lo_g), then H_n^T y^ / sqrt(n), first d_out columns.
+__global__ __launch_bounds__(kThreads) void k_generic_dequant_rotate(RowArgs a, const uint32_t* codes,
+                                                                     const float* scales,
+                                                                     const float* mins, int transpose,
+                                                                     OutArgs o) {
+    extern __shared__ float lds[];
+    const int64_t row = blockIdx.x;
+    const int bits = a.bits;
+    const int row_dwords = a.n / 32 * bits;
+    const uint32_t* cr = codes + row * (int64_t)row_dwords;
+    const uint32_t mask = (1u << bits) - 1u;
+    const int n_groups = a.n / 128;
+    for (int j = threadIdx.x; j < a.n; j += kThreads) {
+        const int bit = j * bits, dw = bit >> 5, sh = bit & 31;
+        uint64_t w = cr[dw];
+        if (sh + bits > 32) w |= (uint64_t)cr[dw + 1] << 32;      // never beyond the row's last dword
+        const uint32_t f = (uint32_t)(w >> sh) & mask;
+        if (mins) {
+            const int64_t gi = row * n_groups + (j >> 7);
+            lds[j] = fmaf((float)f, scales[gi], mins[gi]);
+        } else {
+            lds[j] = (float)((int)(f << (32 - bits)) >> (32 - bits));
+        }
+    }
+    __syncthreads();
+    const float* y = transform_row_lds(a, lds, lds + a.n, transpose != 0);
+    const double k = (mins ? 1.0 : (double)scales[row]) / sqrt((double)a.n);
+    for (int j = threadIdx.x; j < o.d_out; j += kThreads)
+        store_out(o, row * o.ld_out + j, (float)((double)y[j] * k));
 }
 
 __global__ __launch_bounds__(kThreads) void k_generic_rotate_quantize(RowArgs a, float clip,
@@ -284,6 +353,8 @@ bool generic_prepare(const rq_hadamard* h) {
     if (h->f.n % 128 == 0 && (h->f.n / 128 > kMaxGroups ||
                               prepare(k_generic_rotate_quantize_asym, bytes) != RQ_OK))
         return false;
+    if (prepare(k_generic_rotate, bytes) != RQ_OK || prepare(k_generic_dequant_rotate, bytes) != RQ_OK)
+        return false;
     return prepare(k_generic_rotate_quantize, bytes) == RQ_OK &&
            prepare(k_generic_quant_error, bytes) == RQ_OK;
 }
@@ -303,6 +374,23 @@ int generic_rotate_quantize_asym(const rq_hadamard* h, const RowArgs& a, float c
     if (a.rows > 0x7fffffffLL || a.n % 128 != 0) return RQ_ERR_ARG;
     hipLaunchKernelGGL(k_generic_rotate_quantize_asym, dim3((unsigned)a.rows), dim3(kThreads), bytes, s,
                        a, clip, codes, scales, mins);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+int generic_rotate(const rq_hadamard* h, const RowArgs& a, int transpose, const OutArgs& o,
+                   hipStream_t s) {
+    if (a.rows > 0x7fffffffLL) return RQ_ERR_ARG;
+    hipLaunchKernelGGL(k_generic_rotate, dim3((unsigned)a.rows), dim3(kThreads), lds_bytes(h), s, a,
+                       transpose, o);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+int generic_dequant_rotate(const rq_hadamard* h, const RowArgs& a, const uint32_t* codes,
+                           const float* scales, const float* mins, int transpose, const OutArgs& o,
+                           hipStream_t s) {
+    if (a.rows > 0x7fffffffLL) return RQ_ERR_ARG;
+    hipLaunchKernelGGL(k_generic_dequant_rotate, dim3((unsigned)a.rows), dim3(kThreads), lds_bytes(h), s,
+                       a, codes, scales, mins, transpose, o);
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 

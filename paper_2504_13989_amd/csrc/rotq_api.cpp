@@ -209,6 +209,50 @@ int rq_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int b
                               static_cast<hipStream_t>(stream));
 }
 
+int rq_rotate(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d, int64_t ld,
+              int transpose, void* Y, int out_dtype, int d_out, int64_t ld_out, void* stream) {
+    int rc = check_rows(h, X, dtype, rows, d, ld, 4);
+    if (rc != RQ_OK) return rc;
+    if (out_dtype != RQ_BF16 && out_dtype != RQ_F32) return RQ_ERR_ARG;
+    if (d_out < 1 || d_out > h->f.n || ld_out < d_out || (transpose != 0 && transpose != 1))
+        return RQ_ERR_ARG;
+    if (rows == 0) return RQ_OK;
+    if (!Y || !aligned(Y, out_dtype == RQ_BF16 ? 2 : 4)) return RQ_ERR_ARG;
+    if (h->device < 0) return RQ_ERR_HIP;
+    if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
+    const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, 4);
+    const rq::OutArgs o{Y, out_dtype, d_out, ld_out};
+    const_cast<rq_hadamard*>(h)->last_kernel = "generic_rotate";
+    return rq::generic_rotate(h, a, transpose, o, static_cast<hipStream_t>(stream));
+}
+
+int rq_dequantize_rotate(const rq_hadamard_t* h, const void* codes, const float* scales,
+                         const float* mins, int64_t rows, int bits, int transpose, void* Y,
+                         int out_dtype, int d_out, int64_t ld_out, void* stream) {
+    if (!h || rows < 0 || (bits != 3 && bits != 4)) return RQ_ERR_ARG;
+    if (out_dtype != RQ_BF16 && out_dtype != RQ_F32) return RQ_ERR_ARG;
+    if (d_out < 1 || d_out > h->f.n || ld_out < d_out || (transpose != 0 && transpose != 1))
+        return RQ_ERR_ARG;
+    if (mins && h->f.n % RQ_GROUP != 0) return RQ_ERR_ARG;
+    if (rows == 0) return RQ_OK;
+    if (!codes || !scales || !Y || !aligned(codes, 4) || !aligned(scales, 4) || !aligned(mins, 4) ||
+        !aligned(Y, out_dtype == RQ_BF16 ? 2 : 4))
+        return RQ_ERR_ARG;
+    if (h->device < 0) return RQ_ERR_HIP;
+    if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
+    const rq::RowArgs a = row_args(h, nullptr, RQ_F32, rows, h->f.n, h->f.n, bits);
+    const rq::OutArgs o{Y, out_dtype, d_out, ld_out};
+    const_cast<rq_hadamard*>(h)->last_kernel = "generic_dequant_rotate";
+    return rq::generic_dequant_rotate(h, a, static_cast<const uint32_t*>(codes), scales, mins, transpose,
+                                      o, static_cast<hipStream_t>(stream));
+}
+
+int rq_expand_limit(int n, int bits, int bits_reduced, int64_t* d_max) {
+    if (!d_max || n < 1 || bits_reduced < 1 || bits_reduced > bits || bits > 64) return RQ_ERR_ARG;
+    *d_max = ((int64_t)n * (bits - bits_reduced)) / bits_reduced;
+    return RQ_OK;
+}
+
 size_t rq_quant_error_workspace(int64_t rows, int n_clips) {
     if (rows < 0 || n_clips < 1 || n_clips > RQ_MAX_CLIPS) return 0;
     size_t r = rows > 0 ? (size_t)rows : 1;

@@ -35,6 +35,13 @@ struct RowArgs {
     int bits;
 };
 
+struct OutArgs {
+    void* Y;          // rows x d_out results, fp32 or bf16
+    int dtype;
+    int d_out;
+    int64_t ld_out;
+};
+
 struct ClipList {
     float v[RQ_MAX_CLIPS];
 };
@@ -47,6 +54,12 @@ int generic_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& 
                         float* mse, double* partial, hipStream_t s);
 int generic_rotate_quantize_asym(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                                  float* scales, float* mins, hipStream_t s);
+// Rotation with a floating-point result (H_n or H_n^T), from rows or from packed codes.
+int generic_rotate(const rq_hadamard* h, const RowArgs& a, int transpose, const OutArgs& o,
+                   hipStream_t s);
+int generic_dequant_rotate(const rq_hadamard* h, const RowArgs& a, const uint32_t* codes,
+                           const float* scales, const float* mins, int transpose, const OutArgs& o,
+                           hipStream_t s);
 // Rotation-free per-token quantizer (any d that is a multiple of 32).
 int plain_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
                    uint32_t* codes, float* scales, hipStream_t s);

@@ -142,3 +142,16 @@ def check_quant_error(x_np, n, b, clips, mse_gpu, rtol=REL_TOL, what=""):
     rel = np.abs(got - want) / np.maximum(want, 1e-300)
     assert np.all(rel <= rtol), f"{what}: mse rel err {rel.max():.3g} (got {got}, want {want})"
     return float(rel.max())
+
+
+def check_float_rows(got, want, rtol=REL_TOL, what="", bf16=False):
+    """Floating-point rows against the oracle's fp64 rows: every element within rtol of the row's
+    largest magnitude (fp32 results), plus one bf16 rounding step of the element for bf16 results."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, f"{what}: shape {got.shape} vs {want.shape}"
+    amax = np.abs(want).max(axis=1, keepdims=True)
+    tol = rtol * amax + (np.abs(want) * 2.0 ** -8 if bf16 else 0.0)
+    err = np.abs(got - want)
+    assert np.all(err <= tol), f"{what}: max err {err.max():.3g} (row max {amax.max():.3g})"
+    return float((err / np.maximum(amax, 1e-300)).max())

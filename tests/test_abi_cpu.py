@@ -132,6 +132,49 @@ def test_asym_and_plain_argument_errors(L):
     assert plain(rows=0, X=0, codes=0, scales=0) == binding.RQ_OK
 
 
+def test_expand_limit_matches_oracle_and_paper_example(L):
+    import ctypes as C
+    assert binding.expand_limit(4096, 4, 3) == 1365          # section 4.2 prints it rounded up, 1366
+    for n, b, bp in ((4096, 4, 3), (3584, 4, 3), (1536, 8, 4), (18944, 16, 4), (128, 4, 4), (7, 5, 2)):
+        assert binding.expand_limit(n, b, bp) == oracle.expand_limit(n, b, bp)
+    out = C.c_int64(0)
+    E = binding.RQ_ERR_ARG
+    assert L.rq_expand_limit(0, 4, 3, C.byref(out)) == E
+    assert L.rq_expand_limit(64, 3, 4, C.byref(out)) == E
+    assert L.rq_expand_limit(64, 4, 0, C.byref(out)) == E
+    assert L.rq_expand_limit(64, 65, 4, C.byref(out)) == E
+    assert L.rq_expand_limit(64, 4, 3, None) == E
+
+
+def test_rotate_and_dequantize_rotate_argument_errors(L):
+    import ctypes as C
+    vp = C.c_void_p
+    E = binding.RQ_ERR_ARG
+    h = binding.hadamard_build(128)
+
+    def rot(hh, X=0x1000, dtype=0, rows=4, d=128, ld=128, tr=0, Y=0x2000, odt=1, d_out=128, ld_out=128):
+        return L.rq_rotate(hh, vp(X), dtype, rows, d, ld, tr, vp(Y), odt, d_out, ld_out, None)
+
+    assert rot(None) == E and rot(h._h, X=0) == E and rot(h._h, Y=0) == E
+    assert rot(h._h, d=129, ld=129) == E and rot(h._h, d_out=0) == E and rot(h._h, d_out=129, ld_out=129) == E
+    assert rot(h._h, ld_out=100) == E and rot(h._h, tr=2) == E and rot(h._h, odt=5) == E and rot(h._h, dtype=3) == E
+    assert rot(h._h, Y=0x2002) == E and rot(h._h, Y=0x2001, odt=0) == E
+    assert rot(h._h, rows=0, X=0, Y=0) == binding.RQ_OK
+
+    def deq(hh, codes=0x1000, scales=0x2000, mins=0, rows=4, bits=3, tr=1, Y=0x3000, odt=1, d_out=128, ld_out=128):
+        return L.rq_dequantize_rotate(hh, vp(codes), vp(scales), vp(mins), rows, bits, tr, vp(Y), odt, d_out,
+                                      ld_out, None)
+
+    assert deq(None) == E and deq(h._h, codes=0) == E and deq(h._h, scales=0) == E and deq(h._h, Y=0) == E
+    assert deq(h._h, bits=5) == E and deq(h._h, rows=-1) == E and deq(h._h, d_out=200, ld_out=200) == E
+    assert deq(h._h, codes=0x1002) == E and deq(h._h, mins=0x4002) == E and deq(h._h, tr=3) == E
+    assert deq(h._h, rows=0, codes=0, scales=0, Y=0) == binding.RQ_OK
+    h96 = binding.hadamard_build(96)
+    assert deq(h96._h, mins=0x4000, d_out=96, ld_out=96) == E     # groups of 128 need n % 128 == 0
+    h.close()
+    h96.close()
+
+
 def test_quant_error_argument_errors(L):
     h = binding.hadamard_build(128)
     E = binding.RQ_ERR_ARG
