@@ -27,8 +27,15 @@ Readings taken where the paper is silent (each also listed in the design notes)
   * "round" is round-half-to-even;
   * an all-zero row gets Delta = 0 and all-zero codes;
   * the mean in the quantization error runs over all rows * n rotated elements.
-  PARITY UNPINNED for the first two readings: the paper prints no worked numeric
-  quantization example, so only internal consistency pins them.
+  * the asymmetric group quantizer of section 5.1 (named there, no formula): lo = clip * min,
+    hi = clip * max per group of 128, Delta = (hi - lo) / (2^b - 1), unsigned codes, real offset;
+  * Algorithm 1 (section 4.1) searches one projection at a time; its objective is a callable;
+  * the expanding limit (lemma of section 4.2) is the floor of n (b - b') / b' (the text prints
+    1366 for 1365.33);
+  * the fused weight of section 4.2, Eq. 2 carries the same 1 / sqrt(n) as the activation side.
+  PARITY UNPINNED for the first two readings and for the asymmetric quantizer's formula: the
+  paper prints no worked numeric quantization example, so only the properties of the stated
+  definitions pin them.
 
 Everything is float64 unless stated.  Rotation is always a dense product of the
 constructed +-1 matrices - never a butterfly.
