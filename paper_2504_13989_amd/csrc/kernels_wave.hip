@@ -42,11 +42,12 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
 
     for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
         const uint16_t* xr = a.X + row * a.ld;
+        const RowView xv = row_view(xr, a.d);
         f32x4 acc[T][2];
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             const int e0 = (t * 64 + chunk) * 8;
-            const u32x4 raw = FULL ? load16(xr + e0) : load_chunk(xr, e0, a.d);
+            const u32x4 raw = FULL ? load16(xr + e0) : load_chunk(xv, e0);
             const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
             acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
@@ -264,10 +265,11 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
     const int e_base = base_g * 128 + c * 8;
     for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
         const uint16_t* xr = a.X + row * a.ld + e_base;
+        const RowView xv = row_view(a.X + row * a.ld, a.d);
         u32x4 R[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t)
-            R[t] = FULL ? load16(xr + t * 128) : load_chunk(xr - e_base, e_base + t * 128, a.d);
+            R[t] = FULL ? load16(xr + t * 128) : load_chunk(xv, e_base + t * 128);
         // y[column i][j]: register j = 4 h + ip holds block rows 4 j .. 4 j + 3 (one per DPP row g);
         // only the NV = ceil(pb / 4) registers that hold real block rows are carried further
         float y[8][NV];
@@ -363,12 +365,12 @@ __global__ __launch_bounds__(64) void k_wave_quant_error(WaveArgs a, ClipList cl
         const int part = (int)(item - row * ksplit);
         const int per = (n_clips + ksplit - 1) / ksplit;
         const int k0 = part * per, k1 = (k0 + per < n_clips) ? k0 + per : n_clips;
-        const uint16_t* xr = a.X + row * a.ld;
+        const RowView xv = row_view(a.X + row * a.ld, a.d);
 
         f32x4 acc[T][2];
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            const u32x4 raw = load_chunk(xr, (t * 64 + chunk) * 8, a.d);
+            const u32x4 raw = load_chunk(xv, (t * 64 + chunk) * 8);
             const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
             acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
@@ -467,14 +469,11 @@ __global__ __launch_bounds__(64) void k_plain_wave(PlainArgs a) {
     constexpr double kLvl = (double)((1 << BITS) - 1);
     constexpr float kQmin = -(float)(1 << (BITS - 1)), kQmax = (float)((1 << (BITS - 1)) - 1);
     for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
-        const uint16_t* xr = a.X + row * a.ld;
+        const RowView xv = row_view(a.X + row * a.ld, a.d);
         u32x4 raw[T];
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            const int idx = t * 64 + lane;
-            const bool in = idx < nchunks;
-            raw[t] = load16(xr + (in ? idx * 8 : 0));
-            if (!in) raw[t] = u32x4{0u, 0u, 0u, 0u};
+            raw[t] = load_chunk(xv, (t * 64 + lane) * 8);
         }
         float m = 0.0f;
 #pragma unroll

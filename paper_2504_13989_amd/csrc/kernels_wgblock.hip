@@ -76,10 +76,11 @@ void k_wg_block(WaveArgs a, int pb) {
 
     for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
         const uint16_t* xr = a.X + row * a.ld;
+        const RowView xv = row_view(xr, a.d);
         // ---- phase 1
         u32x4 R[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) R[t] = FULL ? load16(xr + eoff[t]) : load_chunk(xr, eoff[t], a.d);
+        for (int t = 0; t < 4; ++t) R[t] = FULL ? load16(xr + eoff[t]) : load_chunk(xv, eoff[t]);
 #pragma unroll
         for (int ic = 0; ic < 8; ++ic) {
             const uint32_t sel = (ic & 1) ? 0x07060302u : 0x05040100u;

@@ -181,14 +181,19 @@ __device__ __forceinline__ float absmax4(float m, const f32x4& v) {
     return __builtin_fmaxf(__builtin_fmaxf(m, __builtin_fabsf(v[2])), __builtin_fabsf(v[3]));
 }
 
-// 16-byte chunk starting at element e0 of a row whose width d is a multiple of 8: whole chunks
-// only, zero beyond d.
-__device__ __forceinline__ u32x4 load_chunk(const uint16_t* row, int e0, int d) {
-    const bool in = e0 < d;
-    // streamed once: non-temporal, so the row does not displace anything in the caches
-    u32x4 r = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (in ? e0 : 0)));
-    if (!in) r = u32x4{0u, 0u, 0u, 0u};
-    return r;
+// A row of width d (a multiple of 8) as a raw buffer resource: loads beyond the row's d * 2
+// bytes return zero in hardware, which is the zero padding of section 4.2 with no compare or
+// select in the instruction stream.  `row` must be uniform across the wave.
+struct RowView {
+    __amdgpu_buffer_rsrc_t rs;
+};
+__device__ __forceinline__ RowView row_view(const uint16_t* row, int d) {
+    return RowView{__builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(row), 0, d * 2, 0x00020000)};
+}
+// 16-byte chunk starting at element e0 (a multiple of 8): whole chunks only, zero beyond d.
+// Streamed once: non-temporal, so the row does not displace anything in the caches.
+__device__ __forceinline__ u32x4 load_chunk(const RowView& v, int e0) {
+    return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(v.rs, e0 * 2, 0, 2));
 }
 
 struct WaveArgs {
