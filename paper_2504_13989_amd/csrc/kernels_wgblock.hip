@@ -25,8 +25,15 @@
 namespace rq {
 namespace {
 
+// 16-byte units per LDS column: at least 4 KK (32 block rows per contraction step), a multiple of 8
+// (the swizzle permutes units inside aligned groups of 8) and = 8 (mod 16), so that a column
+// is an odd multiple of 128 bytes: neighbouring columns then start in opposite halves of the
+// 256-byte bank window.
 template <int KK>
-constexpr int wg_chunks() { return ((4 * KK + 7) / 8) * 8; }   // 16-byte units per LDS column
+constexpr int wg_chunks() {
+    int n = ((4 * KK + 7) / 8) * 8;
+    return (n % 16 == 8) ? n : n + 8;
+}
 
 template <int KK>
 constexpr size_t wg_lds_bytes() { return (size_t)128 * wg_chunks<KK>() * 16 + (size_t)KK * 32 * 48; }
@@ -47,7 +54,10 @@ void k_wg_block(WaveArgs a, int pb) {
     const int nw = blockDim.x >> 6;                      // ceil(pb / 16)
     const int g = lane >> 4, cphys = lane & 15;
     const int c = (cphys & 4) ? (cphys ^ 3) : cphys;    // logical column group (8 columns)
-    const int swz = c & 7;
+    // LDS column of (column group c, position ic inside the group) is ic * 16 + c: the 16 lanes of a
+    // DPP row then touch 16 neighbouring columns, whose 16-byte units - start halves alternating
+    // with c & 1, unit index xor-ed with c >> 1 - are 16 different ones of a 256-byte bank window.
+    const int swz = (c >> 1) & 7;
 
     u32x4 A[KK];
 #pragma unroll
@@ -68,28 +78,44 @@ void k_wg_block(WaveArgs a, int pb) {
     // 8-byte half of the 16-byte unit that holds block rows 8 q .. 8 q + 7, q = 2 wave + g / 2
     const int wr_unit = ((2 * wave + (g >> 1)) ^ swz) * 16 + (g & 1) * 8;
 
+    const uint8_t* const rd0 = ops + c * (NCH * 16) + ((g ^ swz) * 16);
+    const uint8_t* const rd1 = ops + c * (NCH * 16) + (((4 + g) ^ swz) * 16);
+    uint8_t* const wr0 = ops + c * (NCH * 16) + wr_unit;
+
     // Units for block rows at or beyond 16 nw are never written by phase 1 but are read by the last
     // contraction step (against zero columns of B): clear the buffer once so they hold zeros.
     for (int i = threadIdx.x; i < 128 * NCH; i += blockDim.x)
         reinterpret_cast<u32x4*>(ops)[i] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
 
-    for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
+    // The loads of a row are issued one iteration ahead, right after the barrier that follows the
+    // LDS writes of the previous row, so that their latency is covered by phases 2 - 4.
+    u32x4 R[4];
+    auto load_row = [&](int64_t row) {
         const uint16_t* xr = a.X + row * a.ld;
         const RowView xv = row_view(xr, a.d);
-        // ---- phase 1
-        u32x4 R[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) R[t] = FULL ? load16(xr + eoff[t]) : load_chunk(xv, eoff[t]);
+    };
+    if ((int64_t)blockIdx.x < a.rows) load_row(blockIdx.x);
+
+    for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
+#ifndef RQ_WG_PREFETCH
+        load_row(row);
+#endif
+        // ---- phase 1
 #pragma unroll
         for (int ic = 0; ic < 8; ++ic) {
             const uint32_t sel = (ic & 1) ? 0x07060302u : 0x05040100u;
             uint2 v;
             v.x = __builtin_amdgcn_perm(R[1][ic >> 1], R[0][ic >> 1], sel);
             v.y = __builtin_amdgcn_perm(R[3][ic >> 1], R[2][ic >> 1], sel);
-            *reinterpret_cast<uint2*>(ops + (8 * c + ic) * (NCH * 16) + wr_unit) = v;
+            *reinterpret_cast<uint2*>(wr0 + ic * 16 * (NCH * 16)) = v;
         }
         __syncthreads();
+#ifdef RQ_WG_PREFETCH
+        if (row + gridDim.x < a.rows) load_row(row + gridDim.x);
+#endif
         // ---- phase 2
         f32x4 acc[8];
 #pragma unroll
@@ -97,8 +123,10 @@ void k_wg_block(WaveArgs a, int pb) {
             acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                const u32x4 raw = *reinterpret_cast<const u32x4*>(ops + (8 * c + nt) * (NCH * 16) +
-                                                                  ((4 * kk + g) ^ swz) * 16);
+                // unit (4 kk + g) ^ swz: the xor touches the low three bits only, so the address is one of
+                // two per-lane bases (kk even / odd) plus a compile-time offset
+                const u32x4 raw = *reinterpret_cast<const u32x4*>(((kk & 1) ? rd1 : rd0) +
+                                                                  nt * 16 * (NCH * 16) + (kk >> 1) * 128);
                 acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[kk]),
                                                                    __builtin_bit_cast(bf16x8, raw), acc[nt], 0, 0, 0);
             }
@@ -142,12 +170,15 @@ void k_wg_block(WaveArgs a, int pb) {
             }
         }
         if (BITS == 3) {
-            __syncthreads();
-            const int units = pb * 3;                   // 16-byte units of the packed row
-            for (int idx = threadIdx.x; idx < units; idx += blockDim.x)
-                __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(stage + idx * 16),
-                                            reinterpret_cast<u32x4*>(out) + idx);
-            // the next row's stage writes come after two more barriers: no barrier needed here
+            // a wave's 16 block rows are 768 contiguous bytes of the packed row, written and read
+            // back by the same wave: no workgroup barrier, only the wave's own LDS ordering
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int unit = 48 * wave + lane;          // 16-byte units; the row has 3 pb of them
+            if (lane < 48 && unit < 3 * pb)
+                __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(stage + unit * 16),
+                                            reinterpret_cast<u32x4*>(out) + unit);
         }
         if (threadIdx.x == 0) a.scales[row] = (float)(a.c2 * (double)m);
     }
