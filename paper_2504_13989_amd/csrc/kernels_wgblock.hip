@@ -88,8 +88,8 @@ void k_wg_block(WaveArgs a, int pb) {
         reinterpret_cast<u32x4*>(ops)[i] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
 
-    // The loads of a row are issued one iteration ahead, right after the barrier that follows the
-    // LDS writes of the previous row, so that their latency is covered by phases 2 - 4.
+    // (Issuing a row's loads one iteration ahead costs 16 more live registers; at the 80-register
+    // budget that means spills whose reloads wait on the same counter as the loads: measured slower.)
     u32x4 R[4];
     auto load_row = [&](int64_t row) {
         const uint16_t* xr = a.X + row * a.ld;
@@ -97,12 +97,8 @@ void k_wg_block(WaveArgs a, int pb) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) R[t] = FULL ? load16(xr + eoff[t]) : load_chunk(xv, eoff[t]);
     };
-    if ((int64_t)blockIdx.x < a.rows) load_row(blockIdx.x);
-
     for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
-#ifndef RQ_WG_PREFETCH
         load_row(row);
-#endif
         // ---- phase 1
 #pragma unroll
         for (int ic = 0; ic < 8; ++ic) {
@@ -113,9 +109,6 @@ void k_wg_block(WaveArgs a, int pb) {
             *reinterpret_cast<uint2*>(wr0 + ic * 16 * (NCH * 16)) = v;
         }
         __syncthreads();
-#ifdef RQ_WG_PREFETCH
-        if (row + gridDim.x < a.rows) load_row(row + gridDim.x);
-#endif
         // ---- phase 2
         f32x4 acc[8];
 #pragma unroll
