@@ -194,6 +194,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-steady-state", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the per-configuration table")
+    ap.add_argument("--variant", type=int, default=0,
+                    help="rq_hadamard_set_variant value for the timed step (0 = automatic kernel choice)")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also run one 256 MiB device-to-device copy, the known-size reference that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -216,6 +218,7 @@ def main():
     x_bits = wl.generate(w)
     base = torch.from_numpy(x_bits.view(np.int16)).cuda().view(torch.bfloat16)
     h = binding.hadamard_build(w.n)
+    h.set_variant(args.variant)
 
     row_bytes = algorithmic_bytes_per_row(w.d, w.n, bits)
     batch_bytes = w.rows * row_bytes

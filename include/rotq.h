@@ -244,7 +244,9 @@ int rq_gbs_search(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows
 
 /*
  * Select the kernel family for subsequent hot-path calls on this handle (testing /
- * measurement): 0 = automatic (fastest available), 1 = the general LDS kernel.
+ * measurement): 0 = automatic (fastest available), 1 = the general LDS kernel; for long
+ * power-of-two rows 2 = one wave per row at any row count, 3 / 4 = a row split over 2 / 4 waves
+ * at any row count (automatic picks by the number of rows).
  * Errors: RQ_ERR_ARG.
  */
 int rq_hadamard_set_variant(rq_hadamard_t* h, int variant);

@@ -99,6 +99,119 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
     }
 }
 
+// Few long rows: the same transform with a row split over S waves of one workgroup, so that a
+// launch of a few thousand rows has enough waves to cover memory latency and a short tail.
+// H_n = H_S (x) H_{n/S} (section 2.3.2, Eq. 1): output segment s is H_{n/S} applied to
+// sum_s' H_S[s][s'] x_seg[s'], and that signed sum costs nothing on the matrix cores - the
+// products of all S input segments accumulate into one accumulator, with the negated operand
+// tile where H_S has -1.  Every wave therefore loads the whole row (S times the L1 traffic, the
+// same HBM traffic) but carries only T / S accumulator sets through the vector-ALU stages; the
+// waves exchange nothing but their absmax.
+template <int T, int BITS, bool FULL, int S>
+__global__ __launch_bounds__(64 * S) void k_wave_sylvester_split(WaveArgs a) {
+    static_assert(T % S == 0 && (S == 2 || S == 4), "unsupported split");
+    constexpr int TS = T / S;
+    constexpr int ROW_DWORDS = 512 * T * BITS / 32;
+    constexpr int SEG_DWORDS = ROW_DWORDS / S;
+    __shared__ __attribute__((aligned(16))) uint8_t stage_all[BITS == 3 ? ROW_DWORDS * 4 : 16];
+    __shared__ float wmax[S];
+    const int lane = threadIdx.x & 63;
+    const int seg = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, cphys = lane & 15;
+    const int c = (cphys & 4) ? (cphys ^ 3) : cphys;
+    const int chunk = (g << 4) + c;
+
+    const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
+    // operand tiles per input segment: negated where H_S[seg][sp] = -1 (Sylvester sign)
+    u32x4 P0[S], P1[S];
+#pragma unroll
+    for (int sp = 0; sp < S; ++sp) {
+        const uint32_t sg = (__builtin_popcount(seg & sp) & 1) ? 0x80008000u : 0u;
+        const u32x4 sgn = {sg, sg, sg, sg};
+        P0[sp] = A0 ^ sgn;
+        P1[sp] = A1 ^ sgn;
+    }
+    float sf[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
+    const float flip = (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;
+
+    const int64_t row = blockIdx.x;
+    if (row >= a.rows) return;                           // whole workgroup: no barrier is skipped
+    const uint16_t* xr = a.X + row * a.ld;
+    const RowView xv = row_view(xr, a.d);
+    f32x4 acc[TS][2];
+#pragma unroll
+    for (int t = 0; t < TS; ++t) {
+        acc[t][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int sp = 0; sp < S; ++sp) {
+            const int e0 = ((sp * TS + t) * 64 + chunk) * 8;
+            const u32x4 raw = FULL ? load16(xr + e0) : load_chunk(xv, e0);
+            const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
+            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, P0[sp]), bm, acc[t][0], 0, 0, 0);
+            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, P1[sp]), bm, acc[t][1], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int s = 1; s < TS; s <<= 1)
+#pragma unroll
+        for (int t = 0; t < TS; ++t)
+            if (!(t & s))
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const f32x4 u = acc[t][h], v = acc[t | s][h];
+                    acc[t][h] = u + v;
+                    acc[t | s][h] = u - v;
+                }
+    float m = 0.0f;
+#pragma unroll
+    for (int t = 0; t < TS; ++t)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            f32x4 v = acc[t][h];
+            if (TS == 1) {                               // straight from the matrix cores: see lane_stages_tail
+                const uint32_t sg0 = (c & 1) ? 0x80000000u : 0u;
+                lane_stage<kDppXor1>(v, sg0);
+                lane_stages_tail<4>(v, sf);
+            } else {
+                lane_stages_fused(v, sf[0], sf[1], sf[2], sf[3]);
+            }
+            acc[t][h] = v;
+            m = absmax4(m, v);
+        }
+    m = wave_absmax<4>(m);
+    if (lane == 0) wmax[seg] = m;
+    __syncthreads();
+    m = wmax[0];
+#pragma unroll
+    for (int w = 1; w < S; ++w) m = __builtin_fmaxf(m, wmax[w]);
+    const float fl = TS == 1 ? ((__builtin_popcount(c >> 1) & 1) ? -1.0f : 1.0f) : flip;
+    const float s = m > 0.0f ? fl * (float)(a.c1 / (double)m) : 0.0f;
+
+    uint32_t* out = a.codes + row * (int64_t)ROW_DWORDS + seg * SEG_DWORDS;
+    uint8_t* stage = stage_all + (BITS == 3 ? seg * SEG_DWORDS * 4 : 0);
+#pragma unroll
+    for (int t = 0; t < TS; ++t) {
+        const uint32_t w = Quant<BITS>::pack8(acc[t][0][0], acc[t][0][1], acc[t][0][2], acc[t][0][3],
+                                              acc[t][1][0], acc[t][1][1], acc[t][1][2], acc[t][1][3], s);
+        const int word = t * 64 + chunk;
+        if (BITS == 4)
+            store_codes(out + word, w);
+        else
+            stage24(stage, word, w);
+    }
+    if (BITS == 3) {
+        // the segment's bytes are written and read back by this wave only
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        copy_out16<SEG_DWORDS / 4>(stage, out, SEG_DWORDS / 4, lane);
+    }
+    if (threadIdx.x == 0) a.scales[row] = (float)(a.c2 * (double)m);
+}
+
 // Short rows: n = 32 << CB (128, 256, 512), 16 >> CB rows per wave pass, U passes in flight.
 // Lane (g, r, c): DPP row g holds contraction slots, r selects the row of the pass, c the
 // column chunk; the matrix cores transform the (g, i) bits, CB DPP stages the c bits.
@@ -550,8 +663,32 @@ int launch_wave(K kernel, const rq_hadamard* h, const WaveArgs& a, int64_t items
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 
+template <int T, int S>
+int launch_split(const WaveArgs& a, int bits, hipStream_t s) {
+    const bool full = a.d == 512 * T;
+    const dim3 grid((unsigned)a.rows), block(64 * S);
+    if (bits == 4) {
+        if (full) hipLaunchKernelGGL((k_wave_sylvester_split<T, 4, true, S>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_wave_sylvester_split<T, 4, false, S>), grid, block, 0, s, a);
+    } else {
+        if (full) hipLaunchKernelGGL((k_wave_sylvester_split<T, 3, true, S>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_wave_sylvester_split<T, 3, false, S>), grid, block, 0, s, a);
+    }
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
 template <int T>
 int launch_long(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
+    // fewer rows than half the SIMDs: a row split over 4 waves finishes sooner (measured on 4096-wide
+    // rows: 64 rows 3.1 -> 2.5 us, 512 rows 4.3 -> 4.0 us; from 1024 rows on one wave per row is faster)
+    if constexpr (T >= 4) {
+        const int64_t simds = (int64_t)h->num_cu * 4;
+        if (h->split >= 0) {
+            const int want = h->split > 0 ? h->split : (a.rows * 2 <= simds ? 4 : 1);
+            if (want == 4) return launch_split<T, 4>(a, bits, s);
+            if (want == 2) return launch_split<T, 2>(a, bits, s);
+        }
+    }
     const bool full = a.d == 512 * T;
     if (bits == 4)
         return full ? launch_wave(k_wave_sylvester<T, 4, true>, h, a, a.rows, 4, s)

@@ -136,8 +136,9 @@ int rq_next_order(int d, int* n_out) {
 }
 
 int rq_hadamard_set_variant(rq_hadamard_t* h, int variant) {
-    if (!h || variant < 0 || variant > 1) return RQ_ERR_ARG;
-    h->variant = variant;
+    if (!h || variant < 0 || variant > 4) return RQ_ERR_ARG;
+    h->variant = variant == 1 ? 1 : 0;
+    h->split = variant == 2 ? -1 : variant == 3 ? 2 : variant == 4 ? 4 : 0;
     return RQ_OK;
 }
 

@@ -19,6 +19,7 @@ struct rq_hadamard {
     bool wg_ok = false;              // the workgroup block kernel is usable for this order
     bool generic_ok = false;         // the general LDS kernel can hold a row of this order
     int variant = 0;                 // 0 auto, 1 general LDS kernel
+    int split = 0;                   // long Sylvester rows: 0 auto, 2 / 4 waves per row, -1 never split
     const char* last_kernel = "";
 };
 

@@ -92,6 +92,22 @@ def test_other_orders_and_padding(torch, n, d, dtype, b):
     parity.check_rotate_quantize(x, n, b, 0.85, codes, scales, f"n={n} d={d} {dtype} b={b} [{kern}]")
 
 
+@pytest.mark.parametrize("variant", [2, 3, 4], ids=["one_wave", "split2", "split4"])
+@pytest.mark.parametrize("n,d", [(2048, 2048), (4096, 4096), (4096, 4000), (8192, 8192), (8192, 6000)])
+def test_long_rows_split_over_waves(torch, n, d, variant):
+    # the same rows through one wave per row and through 2 / 4 waves per row
+    rng = np.random.default_rng(n + d)
+    xf = rng.standard_t(3.0, size=(77, d)).astype(np.float32)
+    xf[:, 5] *= 40.0
+    x = wl.f32_to_bf16_bits(xf)
+    for b in (3, 4):
+        say(f"split n={n} d={d} b={b} variant={variant}")
+        codes, scales, kern = run_rq(torch, x, n, b, 0.9, variant)
+        assert kern == "wave_sylvester"
+        st = parity.check_rotate_quantize(x, n, b, 0.9, codes, scales, f"n={n} d={d} b={b} variant={variant}")
+        say(f"  ok {st}")
+
+
 def test_leading_dimension_and_row_views(torch):
     w = wl.WORKLOADS["llama_hidden"].with_rows(70)
     x = wl.generate(w)
