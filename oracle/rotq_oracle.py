@@ -42,11 +42,13 @@ constructed +-1 matrices - never a butterfly.
 """
 from __future__ import annotations
 
+import functools
 import math
 
 import numpy as np
 
 MAX_PALEY_ORDER = 256
+MAX_LARGE_ORDER = 4096
 
 
 # --------------------------------------------------------------------------- matrices
@@ -74,8 +76,12 @@ def legendre_symbol(a: int, p: int) -> int:
     a %= p
     if a == 0:
         return 0
-    squares = {(x * x) % p for x in range(1, p)}
-    return 1 if a in squares else -1
+    return 1 if a in _nonzero_squares(p) else -1
+
+
+@functools.lru_cache(maxsize=None)
+def _nonzero_squares(p: int) -> frozenset:
+    return frozenset((x * x) % p for x in range(1, p))
 
 
 def paley1(p: int) -> np.ndarray:
@@ -126,8 +132,8 @@ def paley_kind(p: int):
 
 def factor_order(n: int):
     """n = p * 2^k with the largest 2^k such that p is 1 or a constructible Paley order
-    (p <= MAX_PALEY_ORDER).  Returns (p, kind, q, k); kind 0 = pure Sylvester.  None if no
-    such factorisation exists."""
+    (p <= MAX_PALEY_ORDER); failing that, with a large Paley block (p <= MAX_LARGE_ORDER).
+    Returns (p, kind, q, k); kind 0 = pure Sylvester.  None if no such factorisation exists."""
     if n < 1:
         return None
     k = 0
@@ -142,6 +148,19 @@ def factor_order(n: int):
             if kq is not None:
                 return p, kq[0], kq[1], k
         k -= 1
+    # no block of at most MAX_PALEY_ORDER: a large Paley block, up to the whole dimension
+    # (section 5.2.2: 1536 + 8 = 1544 = 1543 + 1 "managed by the Paley algorithm"), again with
+    # the largest 2^k
+    k = 0
+    while n % (1 << (k + 1)) == 0:
+        k += 1
+    while k >= 0:
+        p = n >> k
+        if MAX_PALEY_ORDER < p <= MAX_LARGE_ORDER:
+            kq = paley_kind(p)
+            if kq is not None:
+                return p, kq[0], kq[1], k
+        k -= 1
     return None
 
 
@@ -151,7 +170,7 @@ def next_order(d: int, min_pow2: int = 32) -> int:
     n = d
     while True:
         f = factor_order(n)
-        if f is not None and (1 << f[3]) >= min_pow2:
+        if f is not None and (1 << f[3]) >= min_pow2 and f[0] <= MAX_PALEY_ORDER:
             return n
         n += 1
 

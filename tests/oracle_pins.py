@@ -180,7 +180,10 @@ def check_order_rules(o):
     assert o.factor_order(18944) == (148, 2, 73, 7)
     assert o.factor_order(3072) == (12, 1, 11, 8)
     assert o.factor_order(1536) == (12, 1, 11, 7)
-    assert o.factor_order(3000) is None and o.factor_order(3008) is None
+    # 3000 and 3008 have no block of at most 256 (only large ones: 1500 = 1499 + 1, 752 = 751 + 1),
+    # so the expansion helper, which keeps to small blocks, moves on to 3072
+    assert o.factor_order(3000) == (1500, 1, 1499, 1) and o.factor_order(3008) == (752, 1, 751, 2)
+    assert o.factor_order(3002) is None
     assert o.next_order(3000) == 3072
     assert o.next_order(4096) == 4096
     # q+1 for q = 3 (mod 4), 2(q+1) for q = 1 (mod 4); Paley I wins where both exist (12)
@@ -424,6 +427,29 @@ def check_boundary_mask(o):
     assert m3.tolist() == [[True, True, False, True, False, True, False, False, False]]
     m4 = o.boundary_exempt(t, 4)
     assert m4.tolist() == [[True, True, False, True, True, True, True, False, False]]
+
+
+# ----------------------------------------------------------------------------- large blocks
+
+def check_large_paley_blocks(o):
+    # section 5.2.2: 1536 + 8 = 1544 = 1543 + 1, the whole dimension as one Paley block
+    assert o.is_prime(1543) and 1543 % 4 == 3
+    assert o.factor_order(1544) == (1544, 1, 1543, 0)
+    assert o.factor_order(3088) == (1544, 1, 1543, 1)          # largest 2^k first
+    assert o.factor_order(1540) == (1540, 2, 769, 0)           # 2 (769 + 1), 769 = 1 (mod 4)
+    assert o.factor_order(1536) == (12, 1, 11, 7)              # a small block wins where one exists
+    assert o.factor_order(1542) is None and o.factor_order(1546) is None
+    h = o.hadamard_dense(1544).astype(np.float64)               # exact: integers far below 2^53
+    assert np.array_equal(h @ h.T, 1544 * np.eye(1544))
+    # the expansion helper keeps its cost rule (blocks of at most 256)
+    assert o.next_order(1537) == 1792 and o.next_order(1544) == 1792
+    # rotation through the large block against explicit loops on a few outputs
+    rng = np.random.default_rng(41)
+    x = rng.standard_normal((2, 1544))
+    y = o.rotate(x, 1544)
+    for r, i in ((0, 0), (0, 1), (1, 777), (1, 1543)):
+        assert abs(y[r, i] - sum(int(h[i, j]) * x[r, j] for j in range(1544)) / np.sqrt(1544)) < 1e-10
+    assert np.allclose(o.rotate_back(y, 1544), x, atol=1e-11)
 
 
 # ----------------------------------------------------------------------------- inverse, fusion, limit

@@ -38,7 +38,7 @@ def test_pin(oracle, check):
 # Each entry: a plausible mistake planted in the oracle's source; some pin must fail.
 MUTATIONS = {
     "sylvester_sign": ("np.block([[h, h], [h, -h]])", "np.block([[h, h], [-h, h]])"),
-    "legendre_flipped": ("return 1 if a in squares else -1", "return -1 if a in squares else 1"),
+    "legendre_flipped": ("return 1 if a in _nonzero_squares(p) else -1", "return -1 if a in _nonzero_squares(p) else 1"),
     "paley1_diag_plus": ("h[i, j] = -1 if i == j else", "h[i, j] = 1 if i == j else"),
     "paley1_transposed": ("legendre_symbol((i - 1) - (j - 1), p)", "legendre_symbol((j - 1) - (i - 1), p)"),
     "paley1_border": ("h[0, i] = -1", "h[0, i] = 1"),
@@ -71,6 +71,7 @@ MUTATIONS = {
     "pack_field_msb_first": ("(field[:, :, None] >> np.arange(b)) & 1", "(field[:, :, None] >> np.arange(b)[::-1]) & 1"),
     "unpack_no_sign": ("field = np.where(field >= (1 << (b - 1)), field - (1 << b), field)", "field = field"),
     "boundary_tol": ("return (frac < tol)", "return (frac < 10 * tol)"),
+    "large_block_smallest_k": ("    # (section 5.2.2: 1536 + 8 = 1544 = 1543 + 1 \"managed by the Paley algorithm\"), again with\n    # the largest 2^k\n    k = 0\n    while n % (1 << (k + 1)) == 0:\n        k += 1\n    while k >= 0:", "    kmax = 0\n    while n % (1 << (kmax + 1)) == 0:\n        kmax += 1\n    for k in range(0, kmax + 1):"),
     "back_not_transposed": ('x = np.einsum("ba,rbc->rac", hp.astype(np.float64), x)', 'x = np.einsum("ab,rbc->rac", hp.astype(np.float64), x)'),
     "back_unnormalised": ("    x = x.reshape(rows, n) / math.sqrt(n)\n", "    x = x.reshape(rows, n) / n\n"),
     "fuse_wrong_side": ("    return rotate(w.T, n).T\n", "    return rotate_back(np.pad(w.T, ((0, 0), (0, n - w.shape[0]))), n).T\n"),
