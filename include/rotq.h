@@ -64,7 +64,10 @@ typedef struct rq_hadamard rq_hadamard_t;   /* opaque; immutable after build */
  * host, and, when a GPU is present, upload the block tables to the current device.
  * Without a GPU the handle is host-only: the info/dense calls work, the hot-path calls
  * return RQ_ERR_HIP.
- *   n    [in]  rotation order, multiple of 32
+ * The largest 2^k is taken for which p is 1 or a Paley order of at most 256; where there is none, a
+ * large Paley block of at most 4096 is used, up to the whole dimension (section 5.2.2:
+ * 1544 = 1543 + 1).
+ *   n    [in]  rotation order, multiple of 8 (packed rows are whole bytes)
  *   out  [out] host pointer receiving the handle; owned by the caller, released with
  *              rq_hadamard_free.  Untouched on error.
  * Errors: RQ_ERR_ARG (out NULL, n < 32), RQ_ERR_NO_ORDER, RQ_ERR_NOMEM, RQ_ERR_HIP.
@@ -92,7 +95,8 @@ int rq_hadamard_dense(const rq_hadamard_t* h, int8_t* host_out);
 
 /*
  * Dimension expansion helper (section 4.2): the smallest order n >= d that
- * rq_hadamard_build accepts with 2^k >= 32.  n_out is a host pointer.
+ * rq_hadamard_build accepts with 2^k >= 32 and a block of at most 256 (the orders the fast
+ * kernels serve).  n_out is a host pointer.
  * Errors: RQ_ERR_ARG (d < 1, n_out NULL), RQ_ERR_NO_ORDER (none below 2^30).
  */
 int rq_next_order(int d, int* n_out);

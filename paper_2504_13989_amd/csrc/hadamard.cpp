@@ -45,14 +45,16 @@ void paley_kind(int p, int* kind, int* q) {
 
 bool factor_order(int n, Factorisation* f) {
     if (n < 1) return false;
-    int k = __builtin_ctz((unsigned)n);
-    for (; k >= 0; --k) {
+    // p only grows as k shrinks: the first constructible p met is the smallest one, so blocks of at
+    // most kMaxPaleyOrder are preferred and a large block (up to the whole dimension, e.g.
+    // 1544 = 1543 + 1, section 5.2.2) is used only where no small one exists
+    for (int k = __builtin_ctz((unsigned)n); k >= 0; --k) {
         int p = n >> k;
         if (p == 1) {
             *f = Factorisation{n, 1, 0, 0, k};
             return true;
         }
-        if (p > kMaxPaleyOrder) return false;   // p only grows as k shrinks
+        if (p > kMaxLargeOrder) return false;
         int kind, q;
         paley_kind(p, &kind, &q);
         if (kind) {

@@ -13,14 +13,15 @@ struct Factorisation {
     int log2m = 0;   // k: n = p * 2^k
 };
 
-constexpr int kMaxPaleyOrder = 256;
+constexpr int kMaxPaleyOrder = 256;    // blocks the hot kernels and the expansion helper use
+constexpr int kMaxLargeOrder = 4096;   // largest block at all (general kernel only)
 
 bool is_prime(int v);
 // (a/q) for a prime q by Euler's criterion a^((q-1)/2) mod q; result in {-1, 0, 1}.
 int legendre(int64_t a, int q);
 // kind (1 or 2) and prime for a block order p, or kind 0 if p is not constructible.
 void paley_kind(int p, int* kind, int* q);
-// Largest 2^k with n / 2^k equal to 1 or a constructible block order <= kMaxPaleyOrder.
+// Largest 2^k with n / 2^k equal to 1 or a constructible block order <= kMaxLargeOrder.
 bool factor_order(int n, Factorisation* f);
 // Row-major p x p matrix of +-1.
 std::vector<int8_t> build_block(const Factorisation& f);

@@ -121,15 +121,14 @@ __global__ __launch_bounds__(kThreads) void k_generic_dequant_rotate(RowArgs a, 
     extern __shared__ float lds[];
     const int64_t row = blockIdx.x;
     const int bits = a.bits;
-    const int row_dwords = a.n / 32 * bits;
-    const uint32_t* cr = codes + row * (int64_t)row_dwords;
+    const uint8_t* cr = reinterpret_cast<const uint8_t*>(codes) + row * (int64_t)(a.n / 8 * bits);
     const uint32_t mask = (1u << bits) - 1u;
     const int n_groups = a.n / 128;
     for (int j = threadIdx.x; j < a.n; j += kThreads) {
-        const int bit = j * bits, dw = bit >> 5, sh = bit & 31;
-        uint64_t w = cr[dw];
-        if (sh + bits > 32) w |= (uint64_t)cr[dw + 1] << 32;      // never beyond the row's last dword
-        const uint32_t f = (uint32_t)(w >> sh) & mask;
+        const int bit = j * bits, by = bit >> 3, sh = bit & 7;
+        uint32_t w = cr[by];
+        if (sh + bits > 8) w |= (uint32_t)cr[by + 1] << 8;         // never beyond the row's last byte
+        const uint32_t f = (w >> sh) & mask;
         if (mins) {
             const int64_t gi = row * n_groups + (j >> 7);
             lds[j] = fmaf((float)f, scales[gi], mins[gi]);
@@ -159,6 +158,21 @@ __global__ __launch_bounds__(kThreads) void k_generic_rotate_quantize(RowArgs a,
     if (threadIdx.x == 0)
         scales[row] = (float)((double)clip * (double)amax / (sqrt((double)a.n) * lvl));
     const uint32_t mask = (1u << bits) - 1u;
+    if (a.n % 32 != 0) {
+        // orders that are only a multiple of 8 (whole-dimension blocks such as 1544): a row is a whole
+        // number of bytes but not of dwords, so groups of 8 codes are stored byte by byte
+        uint8_t* outb = reinterpret_cast<uint8_t*>(codes) + row * (int64_t)(a.n / 8 * bits);
+        for (int g = threadIdx.x; g < a.n / 8; g += kThreads) {
+            uint32_t acc = 0;
+            for (int e = 0; e < 8; ++e) {
+                const float t = y[g * 8 + e] * s;
+                const int q = (int)fminf(fmaxf(rintf(t), qmin), qmax);
+                acc |= ((uint32_t)q & mask) << (e * bits);
+            }
+            for (int k = 0; k < bits; ++k) outb[g * bits + k] = (uint8_t)(acc >> (8 * k));
+        }
+        return;
+    }
     uint32_t* out = codes + row * (int64_t)(a.n / 32 * bits);
     for (int g = threadIdx.x; g < a.n / 32; g += kThreads) {
         uint64_t acc = 0;

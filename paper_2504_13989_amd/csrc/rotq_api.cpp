@@ -33,7 +33,7 @@ extern "C" {
 
 int rq_hadamard_build(int n, rq_hadamard_t** out) {
     if (!out || n < 32) return RQ_ERR_ARG;
-    if (n % 32 != 0) return RQ_ERR_NO_ORDER;
+    if (n % 8 != 0) return RQ_ERR_NO_ORDER;     // packed rows are whole bytes for 3 and 4 bits
     rq::Factorisation f;
     if (!rq::factor_order(n, &f)) return RQ_ERR_NO_ORDER;
     rq_hadamard* h = new (std::nothrow) rq_hadamard;
@@ -127,7 +127,7 @@ int rq_next_order(int d, int* n_out) {
     if (d < 1 || !n_out) return RQ_ERR_ARG;
     for (int64_t n = ((int64_t)d + 31) / 32 * 32; n <= (1 << 30); n += 32) {
         rq::Factorisation f;
-        if (rq::factor_order((int)n, &f) && f.log2m >= 5) {
+        if (rq::factor_order((int)n, &f) && f.log2m >= 5 && f.p <= rq::kMaxPaleyOrder) {
             *n_out = (int)n;
             return RQ_OK;
         }

@@ -28,7 +28,7 @@ def test_exports_every_declared_symbol(L):
         assert hasattr(L, name), name
 
 
-@pytest.mark.parametrize("n", [32, 64, 96, 128, 224, 384, 448, 1184, 1536])
+@pytest.mark.parametrize("n", [32, 40, 56, 64, 96, 128, 224, 384, 448, 1184, 1536, 1544, 3008])
 def test_dense_matrix_equals_oracle(n):
     h = binding.hadamard_build(n)
     p, kind, q, k = oracle.factor_order(n)
@@ -39,7 +39,8 @@ def test_dense_matrix_equals_oracle(n):
 
 def test_orders_of_the_configurations():
     for n, want in ((4096, (1, 0, 0, 12)), (3584, (28, 2, 13, 7)), (18944, (148, 2, 73, 7)),
-                    (3072, (12, 1, 11, 8)), (256, (1, 0, 0, 8)), (128, (1, 0, 0, 7))):
+                    (3072, (12, 1, 11, 8)), (256, (1, 0, 0, 8)), (128, (1, 0, 0, 7)),
+                    (1544, (1544, 1, 1543, 0)), (3000, (1500, 1, 1499, 1))):
         h = binding.hadamard_build(n)
         assert (h.p, h.kind, h.q, h.log2m) == want
         h.close()
@@ -49,8 +50,9 @@ def test_build_errors(L):
     out = C.c_void_p()
     assert L.rq_hadamard_build(4096, None) == binding.RQ_ERR_ARG
     assert L.rq_hadamard_build(16, C.byref(out)) == binding.RQ_ERR_ARG
-    assert L.rq_hadamard_build(100, C.byref(out)) == binding.RQ_ERR_NO_ORDER      # not a multiple of 32
-    assert L.rq_hadamard_build(3008, C.byref(out)) == binding.RQ_ERR_NO_ORDER     # 94 * 32: no order
+    assert L.rq_hadamard_build(100, C.byref(out)) == binding.RQ_ERR_NO_ORDER      # not a multiple of 8
+    assert L.rq_hadamard_build(3016, C.byref(out)) == binding.RQ_ERR_NO_ORDER     # 377 * 8: no order
+    assert L.rq_hadamard_build(1542, C.byref(out)) == binding.RQ_ERR_NO_ORDER
     assert L.rq_hadamard_build(32 * 257, C.byref(out)) == binding.RQ_ERR_NO_ORDER
     assert out.value is None
     L.rq_hadamard_free(None)
@@ -58,7 +60,7 @@ def test_build_errors(L):
 
 
 def test_next_order_matches_oracle():
-    for d in (1, 31, 100, 128, 1536, 3000, 3073, 4096, 5000, 18944, 11008):
+    for d in (1, 31, 100, 128, 1536, 1537, 1544, 3000, 3073, 4096, 5000, 18944, 11008):
         n = binding.next_order(d)
         assert n == oracle.next_order(d)
         assert n >= d and n % 32 == 0

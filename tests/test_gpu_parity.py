@@ -108,6 +108,35 @@ def test_long_rows_split_over_waves(torch, n, d, variant):
         say(f"  ok {st}")
 
 
+@pytest.mark.parametrize("n,d,dtype", [(1544, 1544, "bf16"), (1544, 1536, "bf16"), (1544, 1536, "f32"),
+                                       (3088, 3088, "bf16"), (3000, 3000, "bf16"), (56, 56, "f32"),
+                                       (40, 33, "bf16")])
+def test_large_blocks_and_byte_granular_rows(torch, n, d, dtype):
+    # whole-dimension Paley blocks (1544 = 1543 + 1: the 1536 + 8 expansion of section 5.2.2) and
+    # orders that are a multiple of 8 only; packed rows are then not a whole number of dwords
+    rng = np.random.default_rng(n * 7 + d)
+    xf = rng.standard_normal((21, d)).astype(np.float32)
+    xf[:, 3] *= 25.0
+    x = xf if dtype == "f32" else wl.f32_to_bf16_bits(xf)
+    for b in (3, 4):
+        say(f"large/odd order n={n} d={d} {dtype} b={b}")
+        codes, scales, kern = run_rq(torch, x, n, b, 0.9)
+        assert kern == "generic_lds"
+        st = parity.check_rotate_quantize(x, n, b, 0.9, codes, scales, f"n={n} d={d} b={b}")
+        say(f"  ok {st}")
+    h = handle(n)
+    mse = binding.quant_error(h, parity.to_device(x), 3, [0.7, 1.0])
+    torch.cuda.synchronize()
+    parity.check_quant_error(x, n, 3, [0.7, 1.0], mse.cpu().numpy(), what=f"n={n}")
+    # and back: codes -> original basis
+    q, delta, _, y = oracle.rotate_quantize(x, n, 4, 0.9)
+    out = binding.dequantize_rotate(h, torch.from_numpy(oracle.pack_codes(q, 4)).cuda(),
+                                    torch.from_numpy(delta.astype(np.float32)).cuda(), 4, d_out=d)
+    torch.cuda.synchronize()
+    want = oracle.rotate_back(oracle.dequantize(q, delta.astype(np.float32).astype(np.float64)), n, d)
+    parity.check_float_rows(out.cpu().numpy(), want, what=f"n={n} inverse")
+
+
 def test_leading_dimension_and_row_views(torch):
     w = wl.WORKLOADS["llama_hidden"].with_rows(70)
     x = wl.generate(w)
