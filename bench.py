@@ -136,6 +136,24 @@ def time_all_configs(torch, binding, wl):
                                       "kernel": "plain_quantize"}
     del x, codes, scales
     torch.cuda.empty_cache()
+    # whole-dimension Paley block (1536 + 8 = 1544 = 1543 + 1): a dense contraction on the matrix cores
+    w = wl.WORKLOADS["llama_hidden"]
+    xs = wl.generate(w)[:, :1544].copy()
+    for rows in (2048, 16384):
+        x = torch.from_numpy(xs.view(np.int16)).cuda().view(torch.bfloat16).repeat(rows // 2048, 1)
+        h = binding.hadamard_build(1544)
+        codes = torch.empty((rows, 1544 * 4 // 8), dtype=torch.uint8, device="cuda")
+        scales = torch.empty((rows,), dtype=torch.float32, device="cuda")
+        ms = _min_ms(torch, lambda: binding.rotate_quantize(h, x, 4, w.clip, codes=codes, scales=scales), n=5, rounds=3)
+        flops = 2.0 * 1544 * 1544 * rows
+        res[f"dense_1544_b4_rows{rows}"] = {
+            "n": 1544, "bits": 4, "rows": rows, "us": ms * 1e3, "kernel": h.last_kernel,
+            "GBps": rows * algorithmic_bytes_per_row(1544, 1544, 4) / ms / 1e6,
+            "roofline": {"bound": "mfma", "unit": "TFLOP/s", "achieved": flops / ms / 1e9, "peak": 2500.0,
+                         "frac": flops / ms / 1e9 / 2500.0,
+                         "note": "2 n^2 flops per row (dense +-1 matrix, bf16 operands); limited by the "
+                                 "n^2/8 bytes of operand table each 16-row workgroup reads from L2"}}
+        del x, codes, scales
     w = wl.WORKLOADS["calib"]
     x = torch.from_numpy(wl.generate(w).view(np.int16)).cuda().view(torch.bfloat16)
     h = binding.hadamard_build(w.n)

@@ -68,10 +68,19 @@ int rq_hadamard_build(int n, rq_hadamard_t** out) {
     }
     const bool sylv = f.p == 1 && f.log2m >= 7 && f.log2m <= 13;
     const bool blk = f.p > 1 && f.log2m >= 7 && (f.p << (f.log2m - 7)) <= 256;
-    if (sylv || blk) {
+    const bool dense = !sylv && !blk && n <= 4096;
+    if (sylv || blk || dense) {
         std::vector<uint32_t> tiles;
         if (sylv) {
             tiles = rq::wave_sylvester_tiles();
+        } else if (dense) {
+            std::vector<int8_t> hm((size_t)n * n);
+            if (rq_hadamard_dense(h, hm.data()) != RQ_OK) {
+                rq_hadamard_free(h);
+                return RQ_ERR_ARG;
+            }
+            tiles = rq::dense_block_tiles(hm, n);
+            h->dense_ok = true;
         } else {
             // block of the strided axis: H_p (x) H_{2^(k-7)}, index a * 2^(k-7) + (high bits of c)
             const int e = 1 << (f.log2m - 7), pb = f.p * e;
@@ -166,6 +175,10 @@ int rq_rotate_quantize(const rq_hadamard_t* h, const void* X, int dtype, int64_t
     if (h->variant == 0 && rq::wg_block_supports(h, a)) {
         hm->last_kernel = "wg_block";
         return rq::wg_block_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
+    }
+    if (h->variant == 0 && rq::dense_block_supports(h, a)) {
+        hm->last_kernel = "dense_block";
+        return rq::dense_block_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
     }
     if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
     hm->last_kernel = "generic_lds";

@@ -17,6 +17,7 @@ struct rq_hadamard {
     int max_lds = 0;                 // bytes of LDS one workgroup may use on `device`
     int num_cu = 0;
     bool wg_ok = false;              // the workgroup block kernel is usable for this order
+    bool dense_ok = false;           // d_tiles holds the whole matrix for the dense-block kernel
     bool generic_ok = false;         // the general LDS kernel can hold a row of this order
     int variant = 0;                 // 0 auto, 1 general LDS kernel
     int split = 0;                   // long Sylvester rows: 0 auto, 2 / 4 waves per row, -1 never split
@@ -92,6 +93,13 @@ std::vector<uint32_t> wave_block_tiles(const std::vector<int8_t>& bm, int pb);
 bool wave_block_supports(const rq_hadamard* h, const RowArgs& a);
 int wave_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                                float* scales, hipStream_t s);
+
+// Dense-block kernel: bf16 rows, any order n <= 4096 that the wave kernels do not serve (the whole
+// matrix on the matrix cores), e.g. 1544 as one Paley block.
+std::vector<uint32_t> dense_block_tiles(const std::vector<int8_t>& hm, int n);
+bool dense_block_supports(const rq_hadamard* h, const RowArgs& a);
+int dense_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
+                                float* scales, hipStream_t s);
 
 // Workgroup block kernel: bf16 rows, n = pb * 128 with 32 < pb <= 256 (e.g. 18944 = 148 * 128).
 std::vector<uint32_t> wg_block_tiles(const std::vector<int8_t>& bm, int pb);

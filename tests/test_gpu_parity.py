@@ -119,11 +119,13 @@ def test_large_blocks_and_byte_granular_rows(torch, n, d, dtype):
     xf[:, 3] *= 25.0
     x = xf if dtype == "f32" else wl.f32_to_bf16_bits(xf)
     for b in (3, 4):
-        say(f"large/odd order n={n} d={d} {dtype} b={b}")
-        codes, scales, kern = run_rq(torch, x, n, b, 0.9)
-        assert kern == "generic_lds"
-        st = parity.check_rotate_quantize(x, n, b, 0.9, codes, scales, f"n={n} d={d} b={b}")
-        say(f"  ok {st}")
+        for variant in (0, 1):
+            say(f"large/odd order n={n} d={d} {dtype} b={b} variant={variant}")
+            codes, scales, kern = run_rq(torch, x, n, b, 0.9, variant)
+            dense = variant == 0 and dtype == "bf16" and d % 8 == 0
+            assert kern == ("dense_block" if dense else "generic_lds")
+            st = parity.check_rotate_quantize(x, n, b, 0.9, codes, scales, f"n={n} d={d} b={b} [{kern}]")
+            say(f"  ok kernel={kern} {st}")
     h = handle(n)
     mse = binding.quant_error(h, parity.to_device(x), 3, [0.7, 1.0])
     torch.cuda.synchronize()
@@ -135,6 +137,23 @@ def test_large_blocks_and_byte_granular_rows(torch, n, d, dtype):
     torch.cuda.synchronize()
     want = oracle.rotate_back(oracle.dequantize(q, delta.astype(np.float32).astype(np.float64)), n, d)
     parity.check_float_rows(out.cpu().numpy(), want, what=f"n={n} inverse")
+
+
+@pytest.mark.parametrize("n,rows", [(32, 100), (64, 33), (96, 16), (104, 17), (1544, 333), (4080, 40), (4088, 5)])
+def test_dense_block_kernel_shapes(torch, n, rows):
+    # orders below 128 and whole-dimension blocks on the matrix cores; ragged last group of 16 rows
+    if oracle.factor_order(n) is None:
+        pytest.skip(f"{n} is not a constructible order")
+    rng = np.random.default_rng(n + rows)
+    xf = rng.standard_t(3.0, size=(rows, n)).astype(np.float32)
+    xf[rows // 2] = 0.0
+    x = wl.f32_to_bf16_bits(xf)
+    for b in (3, 4):
+        say(f"dense n={n} rows={rows} b={b}")
+        codes, scales, kern = run_rq(torch, x, n, b, 1.0)
+        assert kern == "dense_block"
+        st = parity.check_rotate_quantize(x, n, b, 1.0, codes, scales, f"dense n={n} b={b}")
+        say(f"  ok {st}")
 
 
 def test_leading_dimension_and_row_views(torch):
