@@ -93,13 +93,13 @@ MUTATIONS = {
 def test_planted_mistake_is_caught(name):
     broken = load_oracle(MUTATIONS[name])
     failed = []
-    for check in pins.ALL_CHECKS:
+    # cheap pins first; one failing pin is enough
+    for check in sorted(pins.ALL_CHECKS, key=lambda c: c.__name__ == "check_large_paley_blocks"):
         try:
             check(broken)
-        except AssertionError:
-            failed.append(check.__name__)
         except Exception:
             failed.append(check.__name__)
+            break
     assert failed, f"no pin notices the planted mistake {name!r}"
 
 
