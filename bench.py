@@ -8,7 +8,8 @@ over one batch of the Llama-shaped configuration: X bf16 [2048 x 4096], H_4096, 
 clip = 0.9.  Batches live in a ring of distinct HBM buffers larger than the last-level cache,
 so every step reads cold data; the K steps are replayed from one HIP graph so the timed region
 is kernel work, not Python launch overhead (the eager per-call rate is reported next to it).
-The last line printed is one JSON object (see the field notes in the design doc).
+The last line printed is one JSON object: metric / value / unit, the roofline of the dominant
+kernel, the sustained rate on a large launch, a per-configuration table and the CPU oracle's rate.
 """
 from __future__ import annotations
 

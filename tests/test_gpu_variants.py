@@ -126,3 +126,43 @@ def test_plain_quantize_views_and_zero_rows(torch):
     assert scales[7].item() == 0 and not codes[7].any().item()
     c0, s0 = binding.quantize(buf[:0, :96], 4, 0.8)
     assert c0.shape[0] == 0
+
+
+def test_graph_replay_and_side_stream(torch):
+    """The hot-path calls allocate nothing and run on the caller's stream: captured in a HIP graph on a
+    side stream and replayed several times with eager work in between, every replay must reproduce the
+    eager result (codes, scales, mse)."""
+    w = wl.WORKLOADS["llama_hidden"].with_rows(300)
+    x = parity.to_device(wl.generate(w))
+    wk = wl.WORKLOADS["kv_k"].with_rows(1000)
+    xk = parity.to_device(wl.generate(wk))
+    h, hk = handle(w.n), handle(wk.n)
+    clips = [0.6, 0.8, 1.0]
+    ref_c, ref_s = binding.rotate_quantize(h, x, 4, 0.9)
+    ref_kc, ref_ks, ref_km = binding.rotate_quantize_asym(hk, xk, 3, 0.9)
+    ref_m = binding.quant_error(h, x, 3, clips)
+    torch.cuda.synchronize()
+    codes, scales = torch.empty_like(ref_c), torch.empty_like(ref_s)
+    kc, ks, km = torch.empty_like(ref_kc), torch.empty_like(ref_ks), torch.empty_like(ref_km)
+    mse = torch.empty_like(ref_m)
+    ws = torch.empty(binding.quant_error_workspace(300, 3) // 8, dtype=torch.float64, device="cuda")
+    st = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(st):
+        # warm-up on the side stream, then capture
+        binding.rotate_quantize(h, x, 4, 0.9, codes=codes, scales=scales)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=st):
+            binding.rotate_quantize(h, x, 4, 0.9, codes=codes, scales=scales)
+            binding.rotate_quantize_asym(hk, xk, 3, 0.9, codes=kc, scales=ks, mins=km)
+            binding.quant_error(h, x, 3, clips, mse=mse, workspace=ws)
+    for rep in range(4):
+        for t in (codes, scales, kc, ks, km, mse):
+            t.zero_()                                   # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        say(f"graph replay {rep}")
+        assert torch.equal(codes, ref_c) and torch.equal(scales, ref_s)
+        assert torch.equal(kc, ref_kc) and torch.equal(ks, ref_ks) and torch.equal(km, ref_km)
+        assert torch.equal(mse, ref_m)
