@@ -84,20 +84,119 @@ def _nonzero_squares(p: int) -> frozenset:
     return frozenset((x * x) % p for x in range(1, p))
 
 
+# --- finite fields GF(p^k) for Paley orders from prime powers (the textbook generalisation: the
+# Legendre symbol becomes the quadratic character of GF(q); not used by the paper's examples).
+# An element is the tuple of its k coefficients, lowest degree first; element number i has the
+# base-p digits of i as coefficients; the modulus is the lexicographically smallest monic
+# irreducible polynomial of degree k (comparing coefficients from the highest degree down).
+
+def prime_power(q: int):
+    """(p, k) with q = p^k, p prime, k >= 1; None if q is not a prime power."""
+    if q < 2:
+        return None
+    for p in range(2, q + 1):
+        if q % p == 0:
+            if not is_prime(p):
+                return None
+            k, v = 0, q
+            while v % p == 0:
+                v //= p
+                k += 1
+            return (p, k) if v == 1 else None
+    return None
+
+
+def _poly_mod(a: list, f: list, p: int) -> list:
+    """Remainder of polynomial a modulo the monic polynomial f over GF(p) (coefficients low first)."""
+    a = [c % p for c in a]
+    k = len(f) - 1
+    for i in range(len(a) - 1, k - 1, -1):
+        c = a[i]
+        if c:
+            for j in range(k + 1):
+                a[i - k + j] = (a[i - k + j] - c * f[j]) % p
+    return (a + [0] * k)[:k]
+
+
+def _poly_irreducible(f: list, p: int) -> bool:
+    """Monic f of degree k is irreducible iff no monic polynomial of degree 1 .. k // 2 divides it."""
+    k = len(f) - 1
+    for deg in range(1, k // 2 + 1):
+        for idx in range(p ** deg):
+            g = [(idx // p ** j) % p for j in range(deg)] + [1]
+            r = list(f)
+            for i in range(k, deg - 1, -1):          # long division by the monic g
+                c = r[i] % p
+                if c:
+                    for j in range(deg + 1):
+                        r[i - deg + j] = (r[i - deg + j] - c * g[j]) % p
+            if not any(r[:deg]):
+                return False
+    return True
+
+
+@functools.lru_cache(maxsize=None)
+def field_modulus(p: int, k: int) -> tuple:
+    """Coefficients (low first, monic) of the modulus of GF(p^k): the lexicographically smallest
+    monic irreducible polynomial of degree k, coefficients compared from x^(k-1) down to x^0."""
+    for idx in range(p ** k):
+        low = [(idx // p ** (k - 1 - j)) % p for j in range(k)]     # c_{k-1}, ..., c_0
+        f = list(reversed(low)) + [1]
+        if _poly_irreducible(f, p):
+            return tuple(f)
+    raise AssertionError("an irreducible polynomial of every degree exists")
+
+
+def field_elements(q: int) -> list:
+    p, k = prime_power(q)
+    return [tuple((i // p ** j) % p for j in range(k)) for i in range(q)]
+
+
+def field_mul(a: tuple, b: tuple, p: int, f: tuple) -> tuple:
+    prod = [0] * (2 * len(a) - 1)
+    for i, x in enumerate(a):
+        for j, y in enumerate(b):
+            prod[i + j] += x * y
+    return tuple(_poly_mod(prod, list(f), p))
+
+
+@functools.lru_cache(maxsize=None)
+def _field_squares(q: int) -> frozenset:
+    p, k = prime_power(q)
+    f = field_modulus(p, k)
+    return frozenset(field_mul(x, x, p, f) for x in field_elements(q) if any(x))
+
+
+def quadratic_character(i: int, j: int, q: int) -> int:
+    """chi(a_i - a_j) in GF(q): 0 if the elements are equal, +1 if their difference is a non-zero
+    square, else -1.  For a prime q this is the Legendre symbol of i - j."""
+    p, k = prime_power(q)
+    if k == 1:
+        return legendre_symbol(i - j, q)
+    d = tuple(((i // p ** t) % p - (j // p ** t) % p) % p for t in range(k))
+    if not any(d):
+        return 0
+    return 1 if d in _field_squares(q) else -1
+
+
 def paley1(p: int) -> np.ndarray:
     """Order p+1 Hadamard matrix, p prime with p = 3 (mod 4); Algorithm 2 (Appendix B).
 
     All ones; first row and first column (except the corner) are -1; the diagonal below the
     corner is -1; every other entry [i, j] is the Legendre symbol of (i-1) - (j-1)."""
-    if not is_prime(p) or p % 4 != 3:
-        raise ValueError("Paley construction needs a prime p = 3 (mod 4)")
+    if prime_power(p) is None or p % 4 != 3:
+        raise ValueError("Paley construction needs a prime (power) p = 3 (mod 4)")
     n = p + 1
     h = np.ones((n, n), dtype=np.int64)
+    prime = is_prime(p)
     for i in range(1, n):
         h[i, 0] = -1
         h[0, i] = -1
         for j in range(1, n):
-            h[i, j] = -1 if i == j else legendre_symbol((i - 1) - (j - 1), p)
+            if i == j:
+                h[i, j] = -1
+            else:
+                h[i, j] = legendre_symbol((i - 1) - (j - 1), p) if prime else quadratic_character(i - 1, j - 1, p)
     return h
 
 
@@ -106,15 +205,16 @@ def paley2(q: int) -> np.ndarray:
 
     C is (q+1) x (q+1): C[0,0] = 0, C[0,j] = C[j,0] = 1, C[i,j] = legendre(i-j, q) otherwise.
     H[2i+u, 2j+v] = C[i,j] * A[u,v] + (i == j) * B[u,v], A = [[1,1],[1,-1]], B = [[1,-1],[-1,-1]]."""
-    if not is_prime(q) or q % 4 != 1:
-        raise ValueError("Paley II construction needs a prime q = 1 (mod 4)")
+    if prime_power(q) is None or q % 4 != 1:
+        raise ValueError("Paley II construction needs a prime (power) q = 1 (mod 4)")
     m = q + 1
     c = np.zeros((m, m), dtype=np.int64)
     c[0, 1:] = 1
     c[1:, 0] = 1
+    prime = is_prime(q)
     for i in range(1, m):
         for j in range(1, m):
-            c[i, j] = legendre_symbol(i - j, q)
+            c[i, j] = legendre_symbol(i - j, q) if prime else quadratic_character(i - 1, j - 1, q)
     a = np.array([[1, 1], [1, -1]], dtype=np.int64)
     b = np.array([[1, -1], [-1, -1]], dtype=np.int64)
     return np.kron(c, a) + np.kron(np.eye(m, dtype=np.int64), b)
@@ -122,10 +222,16 @@ def paley2(q: int) -> np.ndarray:
 
 def paley_kind(p: int):
     """(kind, q) for a block order p: (1, p-1) if Paley I applies, else (2, p/2-1) if Paley II
-    applies, else None.  Order rules: q+1 for q = 3 (mod 4), 2(q+1) for q = 1 (mod 4)."""
+    applies, else None.  Order rules: q+1 for q = 3 (mod 4), 2(q+1) for q = 1 (mod 4); q a prime,
+    or failing that a prime power."""
     if p >= 4 and is_prime(p - 1) and (p - 1) % 4 == 3:
         return 1, p - 1
     if p >= 4 and p % 2 == 0 and is_prime(p // 2 - 1) and (p // 2 - 1) % 4 == 1:
+        return 2, p // 2 - 1
+    # prime powers only where no prime serves the order (52 = 2 (25 + 1), 100 = 2 (49 + 1), 244 = 243 + 1)
+    if p >= 4 and prime_power(p - 1) is not None and (p - 1) % 4 == 3:
+        return 1, p - 1
+    if p >= 4 and p % 2 == 0 and prime_power(p // 2 - 1) is not None and (p // 2 - 1) % 4 == 1:
         return 2, p // 2 - 1
     return None
 

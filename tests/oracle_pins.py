@@ -155,14 +155,14 @@ def check_paley_orthogonal(o):
 
 
 def check_paley_guards(o):
-    for bad in (5, 13, 9, 15):                  # = 1 (mod 4), or not prime
+    for bad in (5, 13, 9, 15):                  # = 1 (mod 4), or not a prime power
         try:
             o.paley1(bad)
         except ValueError:
             pass
         else:
             raise AssertionError(f"paley1({bad}) must be refused")
-    for bad in (3, 7, 9, 25):
+    for bad in (3, 7, 27, 15, 21):            # = 3 (mod 4), or not a prime power
         try:
             o.paley2(bad)
         except ValueError:
@@ -429,6 +429,53 @@ def check_boundary_mask(o):
     assert m4.tolist() == [[True, True, False, True, True, True, True, False, False]]
 
 
+# ----------------------------------------------------------------------------- prime powers
+
+def check_prime_power_fields(o):
+    assert o.prime_power(27) == (3, 3) and o.prime_power(49) == (7, 2) and o.prime_power(13) == (13, 1)
+    assert o.prime_power(12) is None and o.prime_power(1) is None and o.prime_power(45) is None
+    # moduli worked by hand (smallest monic irreducible polynomial, coefficients low first):
+    # GF(9): x^2 + 1 (x^2 + 0 has a root); GF(27): x^3 + 2x + 1 (x^3+1, x^3+2, x^3+x+1, x^3+x+2 have roots 2, 1,
+    # 1, 2); GF(25): x^2 + 2 (x^2 + 1 has the root 2); GF(49): x^2 + 1 (-1 is no square mod 7)
+    assert o.field_modulus(3, 2) == (1, 0, 1) and o.field_modulus(3, 3) == (1, 2, 0, 1)
+    assert o.field_modulus(5, 2) == (2, 0, 1) and o.field_modulus(7, 2) == (1, 0, 1)
+    for q in (9, 25, 27, 49):
+        p, k = o.prime_power(q)
+        f = o.field_modulus(p, k)
+        els = o.field_elements(q)
+        assert len(set(els)) == q and els[0] == (0,) * k and els[1] == (1,) + (0,) * (k - 1)
+        # a field: every non-zero element has an inverse; exactly (q - 1) / 2 non-zero squares
+        one = els[1]
+        for a in els[1:]:
+            assert any(o.field_mul(a, b, p, f) == one for b in els[1:])
+        sq = {o.field_mul(a, a, p, f) for a in els[1:]}
+        assert len(sq) == (q - 1) // 2
+        # the character: antisymmetric for q = 3 (mod 4), symmetric for q = 1 (mod 4), rows sum to 0
+        for i in (0, 1, q // 2, q - 1):
+            row = [o.quadratic_character(i, j, q) for j in range(q)]
+            assert row[i] == 0 and sum(row) == 0
+            for j in (0, 2, q - 2):
+                if i != j:
+                    assert o.quadratic_character(j, i, q) == (row[j] if q % 4 == 1 else -row[j])
+    # GF(9) = GF(3)[x] / (x^2 + 1) by hand: the non-zero squares are 1, 2 = x^2, x = (x + 2)^2 and
+    # 2x = (x + 1)^2, i.e. the elements number 1, 2, 3, 6
+    assert [o.quadratic_character(i, 0, 9) for i in range(9)] == [0, 1, 1, 1, -1, -1, 1, -1, -1]
+    # for a prime the character is the Legendre symbol
+    for i in range(11):
+        for j in range(11):
+            assert o.quadratic_character(i, j, 11) == o.legendre_symbol(i - j, 11)
+    # the matrices, and the orders they add: 52, 100, 244 (20, 28, 164, 252 stay with their primes)
+    for fn, q, n in ((o.paley2, 9, 20), (o.paley2, 25, 52), (o.paley1, 27, 28), (o.paley2, 49, 100),
+                     (o.paley1, 243, 244)):
+        h = fn(q)
+        assert h.shape == (n, n) and set(np.unique(h)) == {-1, 1}
+        assert np.array_equal(h @ h.T, n * np.eye(n, dtype=np.int64))
+    assert o.paley_kind(52) == (2, 25) and o.paley_kind(100) == (2, 49) and o.paley_kind(244) == (1, 243)
+    assert o.paley_kind(20) == (1, 19) and o.paley_kind(28) == (2, 13) and o.paley_kind(164) == (1, 163)
+    assert o.factor_order(52 * 128) == (52, 2, 25, 7) and o.factor_order(100 * 32) == (100, 2, 49, 5)
+    assert o.paley_kind(116) is None and o.paley_kind(92) is None     # 115, 57 / 91, 45: nothing applies
+
+
 # ----------------------------------------------------------------------------- large blocks
 
 def check_large_paley_blocks(o):
@@ -442,7 +489,7 @@ def check_large_paley_blocks(o):
     h = o.hadamard_dense(1544).astype(np.float64)               # exact: integers far below 2^53
     assert np.array_equal(h @ h.T, 1544 * np.eye(1544))
     # the expansion helper keeps its cost rule (blocks of at most 256)
-    assert o.next_order(1537) == 1792 and o.next_order(1544) == 1792
+    assert o.next_order(1537) == 1664 and o.next_order(1544) == 1664      # 52 * 32, 52 = 2 (25 + 1)
     # rotation through the large block against explicit loops on a few outputs
     rng = np.random.default_rng(41)
     x = rng.standard_normal((2, 1544))

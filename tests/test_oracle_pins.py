@@ -39,10 +39,10 @@ def test_pin(oracle, check):
 MUTATIONS = {
     "sylvester_sign": ("np.block([[h, h], [h, -h]])", "np.block([[h, h], [-h, h]])"),
     "legendre_flipped": ("return 1 if a in _nonzero_squares(p) else -1", "return -1 if a in _nonzero_squares(p) else 1"),
-    "paley1_diag_plus": ("h[i, j] = -1 if i == j else", "h[i, j] = 1 if i == j else"),
+    "paley1_diag_plus": ("            if i == j:\n                h[i, j] = -1", "            if i == j:\n                h[i, j] = 1"),
     "paley1_transposed": ("legendre_symbol((i - 1) - (j - 1), p)", "legendre_symbol((j - 1) - (i - 1), p)"),
     "paley1_border": ("h[0, i] = -1", "h[0, i] = 1"),
-    "paley1_no_guard": ("if not is_prime(p) or p % 4 != 3:", "if not is_prime(p):"),
+    "paley1_no_guard": ("if prime_power(p) is None or p % 4 != 3:", "if prime_power(p) is None:"),
     "paley2_b_sign": ("b = np.array([[1, -1], [-1, -1]]", "b = np.array([[1, -1], [-1, 1]]"),
     "paley2_border": ("c[1:, 0] = 1", "c[1:, 0] = -1"),
     "paley2_kron_order": ("return np.kron(c, a) + np.kron(np.eye(m, dtype=np.int64), b)",
@@ -72,6 +72,10 @@ MUTATIONS = {
     "unpack_no_sign": ("field = np.where(field >= (1 << (b - 1)), field - (1 << b), field)", "field = field"),
     "boundary_tol": ("return (frac < tol)", "return (frac < 10 * tol)"),
     "large_block_smallest_k": ("    # (section 5.2.2: 1536 + 8 = 1544 = 1543 + 1 \"managed by the Paley algorithm\"), again with\n    # the largest 2^k\n    k = 0\n    while n % (1 << (k + 1)) == 0:\n        k += 1\n    while k >= 0:", "    kmax = 0\n    while n % (1 << (kmax + 1)) == 0:\n        kmax += 1\n    for k in range(0, kmax + 1):"),
+    "gf_modulus_order": ("low = [(idx // p ** (k - 1 - j)) % p for j in range(k)]", "low = [(idx // p ** j) % p for j in range(k)]"),
+    "gf_reduce_sign": ("a[i - k + j] = (a[i - k + j] - c * f[j]) % p", "a[i - k + j] = (a[i - k + j] + c * f[j]) % p"),
+    "gf_difference": ("d = tuple(((i // p ** t) % p - (j // p ** t) % p) % p for t in range(k))", "d = tuple(((i - j) // p ** t) % p for t in range(k))"),
+    "gf_character_flipped": ("return 1 if d in _field_squares(q) else -1", "return -1 if d in _field_squares(q) else 1"),
     "back_not_transposed": ('x = np.einsum("ba,rbc->rac", hp.astype(np.float64), x)', 'x = np.einsum("ab,rbc->rac", hp.astype(np.float64), x)'),
     "back_unnormalised": ("    x = x.reshape(rows, n) / math.sqrt(n)\n", "    x = x.reshape(rows, n) / n\n"),
     "fuse_wrong_side": ("    return rotate(w.T, n).T\n", "    return rotate_back(np.pad(w.T, ((0, 0), (0, n - w.shape[0]))), n).T\n"),
