@@ -1,6 +1,7 @@
 // Hadamard block construction on the host: Legendre symbols, the Paley construction of
-// Appendix B (Algorithm 2) for q = 3 (mod 4), Paley II for q = 1 (mod 4), and the order
-// factorisation n = p * 2^k (section 2.3.3).
+// Appendix B (Algorithm 2) for q = 3 (mod 4), Paley II for q = 1 (mod 4), both also for prime
+// powers q through the quadratic character of GF(q), and the order factorisation n = p * 2^k
+// (section 2.3.3).
 #include "hadamard.h"
 
 namespace rq {
@@ -30,14 +31,120 @@ int legendre(int64_t a, int q) {
     return pow_mod(r, (q - 1) / 2, q) == 1 ? 1 : -1;
 }
 
+bool prime_power(int q, int* p, int* k) {
+    if (q < 2) return false;
+    int f = 2;
+    while (q % f != 0) ++f;                 // smallest divisor: a prime
+    int v = q, e = 0;
+    while (v % f == 0) {
+        v /= f;
+        ++e;
+    }
+    if (v != 1) return false;
+    *p = f;
+    *k = e;
+    return true;
+}
+
+// GF(p^k) as polynomials over GF(p) modulo a monic irreducible polynomial of degree k; an element
+// is its coefficient vector (lowest degree first), element number i has the base-p digits of i.
+namespace {
+
+using Poly = std::vector<int>;
+
+// remainder of `a` modulo the monic polynomial `f` (degree k), coefficients low first
+Poly poly_rem(Poly a, const Poly& f, int p) {
+    const int k = (int)f.size() - 1;
+    for (int i = (int)a.size() - 1; i >= k; --i) {
+        const int c = a[i] % p;
+        if (c)
+            for (int j = 0; j <= k; ++j) a[i - k + j] = ((a[i - k + j] - c * f[j]) % p + p) % p;
+    }
+    a.resize(k, 0);
+    return a;
+}
+
+bool poly_irreducible(const Poly& f, int p) {
+    const int k = (int)f.size() - 1;
+    for (int deg = 1; deg <= k / 2; ++deg) {
+        int count = 1;
+        for (int j = 0; j < deg; ++j) count *= p;
+        for (int idx = 0; idx < count; ++idx) {
+            Poly g(deg + 1, 1);
+            for (int j = 0, v = idx; j < deg; ++j, v /= p) g[j] = v % p;
+            bool zero = true;
+            for (int c : poly_rem(f, g, p)) zero = zero && c == 0;
+            if (zero) return false;
+        }
+    }
+    return true;
+}
+
+// the smallest monic irreducible polynomial of degree k, coefficients compared from x^(k-1) down
+Poly field_modulus(int p, int k) {
+    int count = 1;
+    for (int j = 0; j < k; ++j) count *= p;
+    for (int idx = 0; idx < count; ++idx) {
+        Poly f(k + 1, 1);
+        for (int j = 0, v = idx; j < k; ++j, v /= p) f[j] = v % p;    // digit j of idx is c_j: idx orders by c_{k-1} first
+        if (poly_irreducible(f, p)) return f;
+    }
+    return Poly();
+}
+
+Poly field_mul(const Poly& a, const Poly& b, const Poly& f, int p) {
+    Poly prod(a.size() + b.size() - 1, 0);
+    for (size_t i = 0; i < a.size(); ++i)
+        for (size_t j = 0; j < b.size(); ++j) prod[i + j] = (prod[i + j] + a[i] * b[j]) % p;
+    return poly_rem(prod, f, p);
+}
+
+// table of the quadratic character by element number: a^((q-1)/2) is 1 for non-zero squares
+std::vector<int8_t> character_table(int q) {
+    int p = 0, k = 0;
+    prime_power(q, &p, &k);
+    const Poly f = field_modulus(p, k);
+    std::vector<int8_t> chi(q, 0);
+    for (int i = 1; i < q; ++i) {
+        Poly base(k), r(k, 0);
+        for (int j = 0, v = i; j < k; ++j, v /= p) base[j] = v % p;
+        r[0] = 1;
+        for (int e = (q - 1) / 2; e > 0; e >>= 1) {
+            if (e & 1) r = field_mul(r, base, f, p);
+            base = field_mul(base, base, f, p);
+        }
+        bool one = r[0] == 1;
+        for (int j = 1; j < k; ++j) one = one && r[j] == 0;
+        chi[i] = one ? 1 : -1;
+    }
+    return chi;
+}
+
+// number of the element a_i - a_j (digit-wise difference mod p)
+int element_diff(int i, int j, int p, int k) {
+    int out = 0, w = 1;
+    for (int t = 0; t < k; ++t, i /= p, j /= p, w *= p) out += (((i % p) - (j % p) + p) % p) * w;
+    return out;
+}
+
+}  // namespace
+
 void paley_kind(int p, int* kind, int* q) {
     *kind = 0;
     *q = 0;
     if (p < 4) return;
+    int pp, kk;
     if (is_prime(p - 1) && (p - 1) % 4 == 3) {
         *kind = 1;
         *q = p - 1;
     } else if (p % 2 == 0 && is_prime(p / 2 - 1) && (p / 2 - 1) % 4 == 1) {
+        *kind = 2;
+        *q = p / 2 - 1;
+    } else if (prime_power(p - 1, &pp, &kk) && (p - 1) % 4 == 3) {
+        // prime powers only where no prime serves the order (52, 100, 244 ...)
+        *kind = 1;
+        *q = p - 1;
+    } else if (p % 2 == 0 && prime_power(p / 2 - 1, &pp, &kk) && (p / 2 - 1) % 4 == 1) {
         *kind = 2;
         *q = p / 2 - 1;
     }
@@ -68,6 +175,18 @@ bool factor_order(int n, Factorisation* f) {
 std::vector<int8_t> build_block(const Factorisation& f) {
     const int p = f.p;
     std::vector<int8_t> h((size_t)p * p, 1);
+    // chi(a_i - a_j): the Legendre symbol of i - j for a prime q, the quadratic character of
+    // GF(q) for a prime power
+    int fp = 0, fk = 0;
+    std::vector<int8_t> chi;
+    if (f.kind != 0 && !is_prime(f.q)) {
+        prime_power(f.q, &fp, &fk);
+        chi = character_table(f.q);
+    }
+    auto character = [&](int i, int j) -> int {
+        if (chi.empty()) return legendre((int64_t)i - j, f.q);
+        return chi[element_diff(i, j, fp, fk)];
+    };
     if (f.kind == 1) {
         // order q+1: corner +1, rest of first row and column -1, diagonal -1, entry [i][j] the
         // Legendre symbol of i - j elsewhere
@@ -75,7 +194,7 @@ std::vector<int8_t> build_block(const Factorisation& f) {
             h[(size_t)i * p] = -1;
             h[i] = -1;
             for (int j = 1; j < p; ++j)
-                h[(size_t)i * p + j] = (i == j) ? -1 : (int8_t)legendre((int64_t)i - j, f.q);
+                h[(size_t)i * p + j] = (i == j) ? -1 : (int8_t)character(i - 1, j - 1);
         }
     } else if (f.kind == 2) {
         // order 2(q+1): 2x2 blocks; off-diagonal block (i,j) is c_ij * [[1,1],[1,-1]] with c the
@@ -87,7 +206,7 @@ std::vector<int8_t> build_block(const Factorisation& f) {
                 if (i == j) {
                     b[0] = 1; b[1] = -1; b[p] = -1; b[p + 1] = -1;
                 } else {
-                    int c = (i == 0 || j == 0) ? 1 : legendre((int64_t)i - j, f.q);
+                    int c = (i == 0 || j == 0) ? 1 : character(i - 1, j - 1);
                     b[0] = (int8_t)c; b[1] = (int8_t)c; b[p] = (int8_t)c; b[p + 1] = (int8_t)-c;
                 }
             }

@@ -9,7 +9,7 @@ struct Factorisation {
     int n = 0;       // order
     int p = 1;       // block order (1 = pure Sylvester)
     int kind = 0;    // 0 Sylvester, 1 Paley (Algorithm 2), 2 Paley II
-    int q = 0;       // prime of the Paley construction
+    int q = 0;       // prime (or prime power) of the Paley construction
     int log2m = 0;   // k: n = p * 2^k
 };
 
@@ -17,6 +17,8 @@ constexpr int kMaxPaleyOrder = 256;    // blocks the hot kernels and the expansi
 constexpr int kMaxLargeOrder = 4096;   // largest block at all (general kernel only)
 
 bool is_prime(int v);
+// q = p^k with p prime, k >= 1.
+bool prime_power(int q, int* p, int* k);
 // (a/q) for a prime q by Euler's criterion a^((q-1)/2) mod q; result in {-1, 0, 1}.
 int legendre(int64_t a, int q);
 // kind (1 or 2) and prime for a block order p, or kind 0 if p is not constructible.

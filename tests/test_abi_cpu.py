@@ -28,7 +28,7 @@ def test_exports_every_declared_symbol(L):
         assert hasattr(L, name), name
 
 
-@pytest.mark.parametrize("n", [32, 40, 56, 64, 96, 128, 224, 384, 448, 1184, 1536, 1544, 3008])
+@pytest.mark.parametrize("n", [32, 40, 56, 64, 96, 104, 128, 200, 224, 384, 416, 448, 488, 1184, 1536, 1544, 3008])
 def test_dense_matrix_equals_oracle(n):
     h = binding.hadamard_build(n)
     p, kind, q, k = oracle.factor_order(n)
@@ -40,7 +40,8 @@ def test_dense_matrix_equals_oracle(n):
 def test_orders_of_the_configurations():
     for n, want in ((4096, (1, 0, 0, 12)), (3584, (28, 2, 13, 7)), (18944, (148, 2, 73, 7)),
                     (3072, (12, 1, 11, 8)), (256, (1, 0, 0, 8)), (128, (1, 0, 0, 7)),
-                    (1544, (1544, 1, 1543, 0)), (3000, (1500, 1, 1499, 1))):
+                    (1544, (1544, 1, 1543, 0)), (3000, (1500, 1, 1499, 1)),
+                    (6656, (52, 2, 25, 7)), (3200, (100, 2, 49, 5)), (31232, (244, 1, 243, 7))):
         h = binding.hadamard_build(n)
         assert (h.p, h.kind, h.q, h.log2m) == want
         h.close()

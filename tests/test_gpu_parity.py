@@ -79,7 +79,10 @@ def test_small_cases(torch, name, rows, variant):
                                        (44 * 128, 44 * 128, "bf16"), (60 * 128, 7600, "bf16"),
                                        (84 * 128, 84 * 128, "bf16"), (108 * 128, 108 * 128, "bf16"),
                                        (168 * 128, 168 * 128, "bf16"), (200 * 128, 25000, "bf16"),
-                                       (252 * 128, 252 * 128, "bf16"), (38 * 256, 38 * 256, "bf16")])
+                                       (252 * 128, 252 * 128, "bf16"), (38 * 256, 38 * 256, "bf16"),
+                                       # prime-power Paley blocks: 52 = 2 (25 + 1), 100 = 2 (49 + 1), 244 = 243 + 1
+                                       (52 * 128, 52 * 128, "bf16"), (52 * 32, 1600, "bf16"), (100 * 64, 6400, "bf16"),
+                                       (100 * 128, 12000, "bf16"), (244 * 128, 244 * 128, "bf16")])
 @pytest.mark.parametrize("b", [3, 4])
 def test_other_orders_and_padding(torch, n, d, dtype, b):
     rng = np.random.default_rng(n * 7 + d + b)
