@@ -148,7 +148,8 @@ __global__ __launch_bounds__(64 * S) void k_wave_sylvester_split(WaveArgs a) {
 #pragma unroll
         for (int sp = 0; sp < S; ++sp) {
             const int e0 = ((sp * TS + t) * 64 + chunk) * 8;
-            const u32x4 raw = FULL ? load16(xr + e0) : load_chunk(xv, e0);
+            // plain (cached) loads: the S waves of the workgroup read the same lines
+            const u32x4 raw = FULL ? *reinterpret_cast<const u32x4*>(xr + e0) : load_chunk(xv, e0);
             const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
             acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, P0[sp]), bm, acc[t][0], 0, 0, 0);
             acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, P1[sp]), bm, acc[t][1], 0, 0, 0);
@@ -679,12 +680,13 @@ int launch_split(const WaveArgs& a, int bits, hipStream_t s) {
 
 template <int T>
 int launch_long(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
-    // fewer rows than half the SIMDs: a row split over 4 waves finishes sooner (measured on 4096-wide
-    // rows: 64 rows 3.1 -> 2.5 us, 512 rows 4.3 -> 4.0 us; from 1024 rows on one wave per row is faster)
+    // fewer rows than SIMDs: a row split over 4 (up to half the SIMDs) or 2 waves finishes sooner
+    // (measured on 4096-wide rows: 64 rows 3.1 -> 2.5 us, 512 rows 4.2 -> 3.7 us, 1024 rows 4.75 -> 4.5 us;
+    // from 2048 rows on one wave per row is faster)
     if constexpr (T >= 4) {
         const int64_t simds = (int64_t)h->num_cu * 4;
         if (h->split >= 0) {
-            const int want = h->split > 0 ? h->split : (a.rows * 2 <= simds ? 4 : 1);
+            const int want = h->split > 0 ? h->split : (a.rows * 2 <= simds ? 4 : a.rows <= simds ? 2 : 1);
             if (want == 4) return launch_split<T, 4>(a, bits, s);
             if (want == 2) return launch_split<T, 2>(a, bits, s);
         }
