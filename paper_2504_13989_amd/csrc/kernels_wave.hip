@@ -357,11 +357,64 @@ __device__ __forceinline__ void fused_group(float* v, const float (&sf)[4]) {
     }
 }
 
+// The rotation of one row for the block kernels: loads, block product on the matrix cores, the
+// 128-point transform along the columns.  y[column i][j]: register j = 4 h + ip holds block rows
+// 4 j .. 4 j + 3 (one per DPP row g); only the NV = ceil(pb / 4) registers that hold real block rows
+// are carried.  Values carry the lane's flip sign (see lane_stages_fused).  Returns the row's absmax.
+template <bool FULL, int NV>
+__device__ __forceinline__ float block_rotate_row(const WaveArgs& a, int64_t row, int e_base, const u32x4& A0,
+                                              const u32x4& A1, const float (&sf)[4], float (&y)[8][NV]) {
+    constexpr int NH1 = NV > 4 ? NV - 4 : 0;              // live registers of the second half
+    constexpr int NH0 = NV > 4 ? 4 : NV;
+    const uint16_t* xr = a.X + row * a.ld + e_base;
+    const RowView xv = row_view(a.X + row * a.ld, a.d);
+    u32x4 R[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+        R[t] = FULL ? load16(xr + t * 128) : load_chunk(xv, e_base + t * 128);
+#pragma unroll
+    for (int ic = 0; ic < 8; ++ic) {
+        u32x4 bm;
+        const uint32_t sel = (ic & 1) ? 0x07060302u : 0x05040100u;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            bm[w] = __builtin_amdgcn_perm(R[2 * w + 1][ic >> 1], R[2 * w][ic >> 1], sel);
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        const bf16x8 b8 = __builtin_bit_cast(bf16x8, bm);
+        const f32x4 d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), b8, z, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < NH0; ++j) y[ic][j] = d0[j];
+        if constexpr (NH1 > 0) {
+            const f32x4 d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), b8, z, 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < NH1; ++j) y[ic][4 + j] = d1[j];
+        }
+    }
+#pragma unroll
+    for (int s = 1; s < 8; s <<= 1)
+#pragma unroll
+        for (int ic = 0; ic < 8; ++ic)
+            if (!(ic & s))
+#pragma unroll
+                for (int j = 0; j < NV; ++j) {
+                    const float u = y[ic][j], v = y[ic | s][j];
+                    y[ic][j] = u + v;
+                    y[ic | s][j] = u - v;
+                }
+    float m = 0.0f;
+#pragma unroll
+    for (int ic = 0; ic < 8; ++ic) {
+        fused_group<NH0>(&y[ic][0], sf);
+        if constexpr (NH1 > 0) fused_group<NH1>(&y[ic][4], sf);
+#pragma unroll
+        for (int j = 0; j < NV; ++j) m = __builtin_fmaxf(m, __builtin_fabsf(y[ic][j]));
+    }
+    return wave_absmax<4>(m);
+}
+
 template <int BITS, bool FULL, int NV>
 __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
     constexpr int ROW_DWORDS_PER_A = 128 * BITS / 32;
-    constexpr int NH1 = NV > 4 ? NV - 4 : 0;              // live registers of the second half
-    constexpr int NH0 = NV > 4 ? 4 : NV;
     __shared__ __attribute__((aligned(16))) uint8_t stage[BITS == 3 ? 32 * 48 : 16];
     const int lane = threadIdx.x;
     const int g = lane >> 4, cphys = lane & 15;
@@ -378,53 +431,8 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
     const int base_g = 8 * g < pb - 8 ? 8 * g : pb - 8;
     const int e_base = base_g * 128 + c * 8;
     for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
-        const uint16_t* xr = a.X + row * a.ld + e_base;
-        const RowView xv = row_view(a.X + row * a.ld, a.d);
-        u32x4 R[8];
-#pragma unroll
-        for (int t = 0; t < 8; ++t)
-            R[t] = FULL ? load16(xr + t * 128) : load_chunk(xv, e_base + t * 128);
-        // y[column i][j]: register j = 4 h + ip holds block rows 4 j .. 4 j + 3 (one per DPP row g);
-        // only the NV = ceil(pb / 4) registers that hold real block rows are carried further
         float y[8][NV];
-#pragma unroll
-        for (int ic = 0; ic < 8; ++ic) {
-            u32x4 bm;
-            const uint32_t sel = (ic & 1) ? 0x07060302u : 0x05040100u;
-#pragma unroll
-            for (int w = 0; w < 4; ++w)
-                bm[w] = __builtin_amdgcn_perm(R[2 * w + 1][ic >> 1], R[2 * w][ic >> 1], sel);
-            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-            const bf16x8 b8 = __builtin_bit_cast(bf16x8, bm);
-            const f32x4 d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), b8, z, 0, 0, 0);
-#pragma unroll
-            for (int j = 0; j < NH0; ++j) y[ic][j] = d0[j];
-            if constexpr (NH1 > 0) {
-                const f32x4 d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), b8, z, 0, 0, 0);
-#pragma unroll
-                for (int j = 0; j < NH1; ++j) y[ic][4 + j] = d1[j];
-            }
-        }
-#pragma unroll
-        for (int s = 1; s < 8; s <<= 1)
-#pragma unroll
-            for (int ic = 0; ic < 8; ++ic)
-                if (!(ic & s))
-#pragma unroll
-                    for (int j = 0; j < NV; ++j) {
-                        const float u = y[ic][j], v = y[ic | s][j];
-                        y[ic][j] = u + v;
-                        y[ic | s][j] = u - v;
-                    }
-        float m = 0.0f;
-#pragma unroll
-        for (int ic = 0; ic < 8; ++ic) {
-            fused_group<NH0>(&y[ic][0], sf);
-            if constexpr (NH1 > 0) fused_group<NH1>(&y[ic][4], sf);
-#pragma unroll
-            for (int j = 0; j < NV; ++j) m = __builtin_fmaxf(m, __builtin_fabsf(y[ic][j]));
-        }
-        m = wave_absmax<4>(m);
+        float m = block_rotate_row<FULL, NV>(a, row, e_base, A0, A1, sf, y);
         const float s = m > 0.0f ? flip * (float)(a.c1 / (double)m) : 0.0f;
         const float scale = (float)(a.c2 * (double)m);
 
@@ -451,6 +459,61 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Squared quantization error of one rotated row for the clip ratios [k0, k1) (sections 2.1, 3.1):
+// t = y / Delta_k, r = clamp(round(t)), e = y - r Delta_k, sum e^2 - five vector-ALU operations per
+// value and candidate, four candidates at a time (independent chains, interleaved reductions).
+// v: the lane's NVAL values of the un-normalised rotated row, carrying the lane's sign `flip`;
+// m: the row's absmax.  The sum runs over the lanes that share the row: ROW_BITS lane bits inside a
+// DPP row plus the four DPP rows.  emit(k, sum) is called by every lane with the reduced sum.
+template <int NVAL, int BITS, int ROW_BITS, typename Emit>
+__device__ __forceinline__ void qe_candidates(const float (&v)[NVAL], float m, float flip, const ClipList& clips,
+                                              int k0, int k1, Emit emit) {
+    constexpr float kQmax = (float)((1 << (BITS - 1)) - 1), kQmin = -(float)(1 << (BITS - 1));
+    constexpr double lvl = (double)((1 << BITS) - 1);
+    const double inv_m = m > 0.0f ? 1.0 / (double)m : 0.0;
+    for (int kb = k0; kb < k1; kb += 4) {
+        float sk[4], ndk[4], e2[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k = kb + j < k1 ? kb + j : k1 - 1;
+            const double cl = (double)clips.v[k];
+            sk[j] = flip * (float)(lvl / cl * inv_m);          // lane sign folded in
+            ndk[j] = -flip * (float)(cl * (double)m / lvl);
+            e2[j] = 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < NVAL; ++i) {
+            const float y = v[i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float r = __builtin_amdgcn_fmed3f(__builtin_rintf(y * sk[j]), kQmin, kQmax);
+                const float e = fmaf(r, ndk[j], y);
+                e2[j] = fmaf(e, e, e2[j]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppXor1>(e2[j]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppXor2>(e2[j]);
+        if (ROW_BITS >= 3) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppHalfMirror>(e2[j]);
+        }
+        if (ROW_BITS >= 4) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppRor8>(e2[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 16, 64);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 32, 64);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (kb + j < k1) emit(kb + j, e2[j]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // quant_error for bf16 rows of Sylvester order n = 512 T (1024 .. 8192): the rotation of
 // k_wave_sylvester, then for each clip ratio of this wave's share [k0, k1) the row's squared
 // quantization error (sections 2.1, 3.1): t = y / Delta_k, r = clamp(round(t)),
@@ -470,8 +533,6 @@ __global__ __launch_bounds__(64) void k_wave_quant_error(WaveArgs a, ClipList cl
 #pragma unroll
     for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
     const float flip = (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;
-    constexpr float kQmax = (float)((1 << (BITS - 1)) - 1), kQmin = -(float)(1 << (BITS - 1));
-    const double lvl = (double)((1 << BITS) - 1);
 
     const int64_t n_items = a.rows * ksplit;
     for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
@@ -513,49 +574,92 @@ __global__ __launch_bounds__(64) void k_wave_quant_error(WaveArgs a, ClipList cl
             }
         m = wave_absmax(m);
 
-        // candidates four at a time: four independent chains per element, reductions interleaved
-        const double inv_m = m > 0.0f ? 1.0 / (double)m : 0.0;
-        for (int kb = k0; kb < k1; kb += 4) {
-            float sk[4], ndk[4], e2[4];
+        float v[T * 8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int k = kb + j < k1 ? kb + j : k1 - 1;
-                const double cl = (double)clips.v[k];
-                sk[j] = flip * (float)(lvl / cl * inv_m);          // lane sign folded in
-                ndk[j] = -flip * (float)(cl * (double)m / lvl);
-                e2[j] = 0.0f;
-            }
+        for (int t = 0; t < T; ++t)
 #pragma unroll
-            for (int t = 0; t < T; ++t)
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int h = 0; h < 2; ++h)
+                for (int i = 0; i < 4; ++i) v[(t * 2 + h) * 4 + i] = acc[t][h][i];
+        qe_candidates<T * 8, BITS, 4>(v, m, flip, clips, k0, k1, [&](int k, float e2) {
+            if (lane == 0) partial[row * n_clips + k] = (double)e2 / ((double)N * (double)N);
+        });
+    }
+}
+
+// The same for the block orders of k_wave_block (n = pb * 128, pb <= 32).
+template <int BITS, bool FULL, int NV>
+__global__ __launch_bounds__(64) void k_wave_block_qe(WaveArgs a, int pb, ClipList clips, int n_clips, int ksplit,
+                                                      double* partial) {
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, cphys = lane & 15;
+    const int c = (cphys & 4) ? (cphys ^ 3) : cphys;
+    const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
+    float sf[4];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float y = acc[t][h][i];
+    for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
+    const float flip = (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;
+    const int base_g = 8 * g < pb - 8 ? 8 * g : pb - 8;
+    const int e_base = base_g * 128 + c * 8;
+    const double nn = (double)pb * 128.0;
+    const int64_t n_items = a.rows * ksplit;
+    for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int64_t row = item / ksplit;
+        const int part = (int)(item - row * ksplit);
+        const int per = (n_clips + ksplit - 1) / ksplit;
+        const int k0 = part * per, k1 = (k0 + per < n_clips) ? k0 + per : n_clips;
+        float y[8][NV];
+        const float m = block_rotate_row<FULL, NV>(a, row, e_base, A0, A1, sf, y);
+        float v[8 * NV];
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const float r = __builtin_amdgcn_fmed3f(__builtin_rintf(y * sk[j]), kQmin, kQmax);
-                            const float e = fmaf(r, ndk[j], y);
-                            e2[j] = fmaf(e, e, e2[j]);
-                        }
-                    }
+        for (int ic = 0; ic < 8; ++ic)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppXor1>(e2[j]);
+            for (int j = 0; j < NV; ++j) v[ic * NV + j] = y[ic][j];
+        qe_candidates<8 * NV, BITS, 4>(v, m, flip, clips, k0, k1, [&](int k, float e2) {
+            if (lane == 0) partial[row * n_clips + k] = (double)e2 / (nn * nn);
+        });
+    }
+}
+
+// The same for short rows (n = 32 << CB: the KV head rows): 16 >> CB rows per wave pass, every
+// clip ratio for every row (there are always enough rows to fill the chip).
+template <int CB, int BITS>
+__global__ __launch_bounds__(64) void k_wave_short_qe(WaveArgs a, ClipList clips, int n_clips, double* partial) {
+    constexpr int RPW = 16 >> CB;
+    constexpr int N = 32 << CB;
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, nnl = lane & 15;
+    const int cphys = nnl & ((1 << CB) - 1);
+    const int rsub = nnl >> CB;
+    const int c = (CB >= 3 && (cphys & 4)) ? (cphys ^ 3) : cphys;
+    const int chunk = (g << CB) + c;
+    const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
+    float sf[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppXor2>(e2[j]);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppHalfMirror>(e2[j]);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppRor8>(e2[j]);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 16, 64);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 32, 64);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (lane == 0 && kb + j < k1)
-                    partial[row * n_clips + kb + j] = (double)e2[j] / ((double)N * (double)N);
-        }
+    for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
+    const uint32_t sg0 = (c & 1) ? 0x80000000u : 0u;
+    const float flip = (__builtin_popcount(c >> 1) & 1) ? -1.0f : 1.0f;   // stages 2.. are the fused ones
+    const int64_t n_pass = (a.rows + RPW - 1) / RPW;
+    for (int64_t pass = blockIdx.x; pass < n_pass; pass += gridDim.x) {
+        const int64_t row = pass * RPW + rsub;
+        const bool live = row < a.rows;
+        const bool in = live && chunk * 8 < a.d;
+        u32x4 raw = load16(a.X + (in ? row * a.ld + chunk * 8 : 0));
+        if (!in) raw = u32x4{0u, 0u, 0u, 0u};
+        const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        f32x4 v0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
+        f32x4 v1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), bm, z, 0, 0, 0);
+        lane_stage<kDppXor1>(v0, sg0);
+        lane_stage<kDppXor1>(v1, sg0);
+        lane_stages_tail<CB>(v0, sf);
+        lane_stages_tail<CB>(v1, sf);
+        float m = absmax4(absmax4(0.0f, v0), v1);
+        m = wave_absmax<CB>(m);
+        const float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+        qe_candidates<8, BITS, CB>(v, m, flip, clips, 0, n_clips, [&](int k, float e2) {
+            if (live && g == 0 && c == 0) partial[row * n_clips + k] = (double)e2 / ((double)N * (double)N);
+        });
     }
 }
 
@@ -808,20 +912,25 @@ bool wave_supports(const rq_hadamard* h, const RowArgs& a) {
 }
 
 bool wave_quant_error_supports(const rq_hadamard* h, const RowArgs& a) {
-    return wave_supports(h, a) && a.log2m >= 10;
+    return wave_supports(h, a) || wave_block_supports(h, a);
+}
+
+static int qe_ksplit(const rq_hadamard* h, int64_t rows, int n_clips) {
+    // Spread one row's candidates over several waves when there are few rows, aiming at about one
+    // wave per SIMD: every extra wave of a row repeats the rotation (about two candidates' worth
+    // of work), so splitting further than that costs more than it balances.
+    const int64_t target = (int64_t)h->num_cu * 4;
+    int ksplit = (int)((target + rows - 1) / rows);
+    if (ksplit < 1) ksplit = 1;
+    if (ksplit > n_clips) ksplit = n_clips;
+    if (ksplit > 8) ksplit = 8;
+    return ksplit;
 }
 
 template <int T>
 static int launch_qe(const rq_hadamard* h, const WaveArgs& w, const ClipList& clips, int n_clips,
                      int bits, double* partial, hipStream_t s) {
-    // Spread one row's candidates over several waves when there are few rows, aiming at about one
-    // wave per SIMD: every extra wave of a row repeats the rotation (about two candidates' worth
-    // of work), so splitting further than that costs more than it balances.
-    const int64_t target = (int64_t)h->num_cu * 4;
-    int ksplit = (int)((target + w.rows - 1) / w.rows);
-    if (ksplit < 1) ksplit = 1;
-    if (ksplit > n_clips) ksplit = n_clips;
-    if (ksplit > 8) ksplit = 8;
+    const int ksplit = qe_ksplit(h, w.rows, n_clips);
     const int64_t items = w.rows * ksplit;
     const int64_t cap = 1 << 24;
     const unsigned grid = (unsigned)(items < cap ? items : cap);
@@ -832,11 +941,56 @@ static int launch_qe(const rq_hadamard* h, const WaveArgs& w, const ClipList& cl
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 
+template <int NV>
+static int launch_block_qe(const rq_hadamard* h, const WaveArgs& w, int pb, const ClipList& clips, int n_clips,
+                           int bits, double* partial, hipStream_t s) {
+    const int ksplit = qe_ksplit(h, w.rows, n_clips);
+    const int64_t items = w.rows * ksplit;
+    const int64_t cap = 1 << 24;
+    const dim3 grid((unsigned)(items < cap ? items : cap)), block(64);
+    const bool full = w.d == pb * 128;
+    if (bits == 4) {
+        if (full) hipLaunchKernelGGL((k_wave_block_qe<4, true, NV>), grid, block, 0, s, w, pb, clips, n_clips, ksplit, partial);
+        else hipLaunchKernelGGL((k_wave_block_qe<4, false, NV>), grid, block, 0, s, w, pb, clips, n_clips, ksplit, partial);
+    } else {
+        if (full) hipLaunchKernelGGL((k_wave_block_qe<3, true, NV>), grid, block, 0, s, w, pb, clips, n_clips, ksplit, partial);
+        else hipLaunchKernelGGL((k_wave_block_qe<3, false, NV>), grid, block, 0, s, w, pb, clips, n_clips, ksplit, partial);
+    }
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+template <int CB>
+static int launch_short_qe(const WaveArgs& w, const ClipList& clips, int n_clips, int bits, double* partial,
+                           hipStream_t s) {
+    const int64_t passes = (w.rows + (16 >> CB) - 1) / (16 >> CB);
+    const int64_t cap = 1 << 24;
+    const dim3 grid((unsigned)(passes < cap ? passes : cap)), block(64);
+    if (bits == 4) hipLaunchKernelGGL((k_wave_short_qe<CB, 4>), grid, block, 0, s, w, clips, n_clips, partial);
+    else hipLaunchKernelGGL((k_wave_short_qe<CB, 3>), grid, block, 0, s, w, clips, n_clips, partial);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
 int wave_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
                      double* partial, hipStream_t s) {
     WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
                static_cast<const u32x4*>(h->d_tiles), nullptr, nullptr, 0.0, 0.0};
+    if (a.p > 1) {
+        const int pb = a.p << (a.log2m - 7);
+        switch ((pb + 3) / 4) {
+            case 2: return launch_block_qe<2>(h, w, pb, clips, n_clips, a.bits, partial, s);
+            case 3: return launch_block_qe<3>(h, w, pb, clips, n_clips, a.bits, partial, s);
+            case 4: return launch_block_qe<4>(h, w, pb, clips, n_clips, a.bits, partial, s);
+            case 5: return launch_block_qe<5>(h, w, pb, clips, n_clips, a.bits, partial, s);
+            case 6: return launch_block_qe<6>(h, w, pb, clips, n_clips, a.bits, partial, s);
+            case 7: return launch_block_qe<7>(h, w, pb, clips, n_clips, a.bits, partial, s);
+            case 8: return launch_block_qe<8>(h, w, pb, clips, n_clips, a.bits, partial, s);
+            default: return RQ_ERR_NO_ORDER;
+        }
+    }
     switch (a.log2m) {
+        case 7: return launch_short_qe<2>(w, clips, n_clips, a.bits, partial, s);
+        case 8: return launch_short_qe<3>(w, clips, n_clips, a.bits, partial, s);
+        case 9: return launch_short_qe<4>(w, clips, n_clips, a.bits, partial, s);
         case 10: return launch_qe<2>(h, w, clips, n_clips, a.bits, partial, s);
         case 11: return launch_qe<4>(h, w, clips, n_clips, a.bits, partial, s);
         case 12: return launch_qe<8>(h, w, clips, n_clips, a.bits, partial, s);

@@ -273,7 +273,8 @@ def test_full_size_kv_sampled(torch, name):
 @pytest.mark.parametrize("variant", [0, 1], ids=["auto", "general"])
 @pytest.mark.parametrize("name,rows,b", [("calib", 512, 3), ("calib", 77, 4), ("qwen_hidden", 50, 3),
                                          ("ffn_expand", 50, 3), ("tiny", 64, 3), ("kv_k", 300, 3),
-                                         ("ffn_down", 9, 3)])
+                                         ("ffn_down", 9, 3), ("qwen_hidden", 700, 4), ("kv_v", 1031, 4),
+                                         ("kv_k", 3, 3)])
 def test_quant_error(torch, name, rows, b, variant):
     w = wl.WORKLOADS[name].with_rows(rows)
     x = wl.generate(w)
@@ -286,6 +287,23 @@ def test_quant_error(torch, name, rows, b, variant):
     h.set_variant(0)
     rel = parity.check_quant_error(x, w.n, b, clips, mse.cpu().numpy(), what=f"{name} [{h.last_kernel}]")
     say(f"  ok kernel={h.last_kernel} max rel err {rel:.2e}")
+
+
+@pytest.mark.parametrize("n,d", [(256, 256), (512, 500 // 8 * 8), (1536, 1536), (2560, 2400), (1024, 1024)])
+def test_quant_error_other_orders(torch, n, d):
+    rng = np.random.default_rng(n + d)
+    xf = rng.standard_t(3.0, size=(45, d)).astype(np.float32)
+    xf[:, 1] *= 30.0
+    xf[7] = 0.0
+    x = wl.f32_to_bf16_bits(xf)
+    clips = [0.5, 0.77, 0.9, 1.0, 0.61]
+    h = handle(n)
+    for b in (3, 4):
+        say(f"quant_error order n={n} d={d} b={b}")
+        mse = binding.quant_error(h, parity.to_device(x), b, clips)
+        torch.cuda.synchronize()
+        assert h.last_kernel == "wave_quant_error"
+        parity.check_quant_error(x, n, b, clips, mse.cpu().numpy(), what=f"n={n} d={d} b={b}")
 
 
 def test_quant_error_consistent_with_rotate_quantize(torch):
