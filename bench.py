@@ -155,10 +155,23 @@ def time_all_configs(torch, binding, wl):
                          "note": "2 n^2 flops per row (dense +-1 matrix, bf16 operands); limited by the "
                                  "n^2/8 bytes of operand table each 16-row workgroup reads from L2"}}
         del x, codes, scales
+    # quant_error on the other projections a clip search visits (512 rows each; 65536 KV head rows)
+    clips = wl.clip_grid()
+    for name, rows in (("qwen_hidden", 512), ("ffn_expand", 512), ("ffn_down", 512), ("kv_k", 65536)):
+        w = wl.WORKLOADS[name].with_rows(rows)
+        x = torch.from_numpy(wl.generate(w).view(np.int16)).cuda().view(torch.bfloat16)
+        h = binding.hadamard_build(w.n)
+        mse = torch.empty(len(clips), dtype=torch.float32, device="cuda")
+        ws = torch.empty(binding.quant_error_workspace(rows, len(clips)) // 8, dtype=torch.float64, device="cuda")
+        ms = _min_ms(torch, lambda: binding.quant_error(h, x, 3, clips, mse=mse, workspace=ws), n=5, rounds=3)
+        ec = rows * w.n * len(clips)
+        res[f"quant_error_{name}_b3"] = {"rows": rows, "n": w.n, "clips": len(clips), "us": ms * 1e3,
+                                         "kernel": h.last_kernel, "element_candidates_per_s": ec / ms * 1e3,
+                                         "alu_frac": 5 * ec / ms / 1e9 / VALU_PEAK_TLANEOPS}
+        del x, mse, ws
     w = wl.WORKLOADS["calib"]
     x = torch.from_numpy(wl.generate(w).view(np.int16)).cuda().view(torch.bfloat16)
     h = binding.hadamard_build(w.n)
-    clips = wl.clip_grid()
     mse = torch.empty(len(clips), dtype=torch.float32, device="cuda")
     ws = torch.empty(binding.quant_error_workspace(w.rows, len(clips)) // 8, dtype=torch.float64, device="cuda")
     ms = _min_ms(torch, lambda: binding.quant_error(h, x, 3, clips, mse=mse, workspace=ws))

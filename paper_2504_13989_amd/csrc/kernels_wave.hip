@@ -459,61 +459,6 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Squared quantization error of one rotated row for the clip ratios [k0, k1) (sections 2.1, 3.1):
-// t = y / Delta_k, r = clamp(round(t)), e = y - r Delta_k, sum e^2 - five vector-ALU operations per
-// value and candidate, four candidates at a time (independent chains, interleaved reductions).
-// v: the lane's NVAL values of the un-normalised rotated row, carrying the lane's sign `flip`;
-// m: the row's absmax.  The sum runs over the lanes that share the row: ROW_BITS lane bits inside a
-// DPP row plus the four DPP rows.  emit(k, sum) is called by every lane with the reduced sum.
-template <int NVAL, int BITS, int ROW_BITS, typename Emit>
-__device__ __forceinline__ void qe_candidates(const float (&v)[NVAL], float m, float flip, const ClipList& clips,
-                                              int k0, int k1, Emit emit) {
-    constexpr float kQmax = (float)((1 << (BITS - 1)) - 1), kQmin = -(float)(1 << (BITS - 1));
-    constexpr double lvl = (double)((1 << BITS) - 1);
-    const double inv_m = m > 0.0f ? 1.0 / (double)m : 0.0;
-    for (int kb = k0; kb < k1; kb += 4) {
-        float sk[4], ndk[4], e2[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int k = kb + j < k1 ? kb + j : k1 - 1;
-            const double cl = (double)clips.v[k];
-            sk[j] = flip * (float)(lvl / cl * inv_m);          // lane sign folded in
-            ndk[j] = -flip * (float)(cl * (double)m / lvl);
-            e2[j] = 0.0f;
-        }
-#pragma unroll
-        for (int i = 0; i < NVAL; ++i) {
-            const float y = v[i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float r = __builtin_amdgcn_fmed3f(__builtin_rintf(y * sk[j]), kQmin, kQmax);
-                const float e = fmaf(r, ndk[j], y);
-                e2[j] = fmaf(e, e, e2[j]);
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppXor1>(e2[j]);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppXor2>(e2[j]);
-        if (ROW_BITS >= 3) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppHalfMirror>(e2[j]);
-        }
-        if (ROW_BITS >= 4) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppRor8>(e2[j]);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 16, 64);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 32, 64);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (kb + j < k1) emit(kb + j, e2[j]);
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
 // quant_error for bf16 rows of Sylvester order n = 512 T (1024 .. 8192): the rotation of
 // k_wave_sylvester, then for each clip ratio of this wave's share [k0, k1) the row's squared
 // quantization error (sections 2.1, 3.1): t = y / Delta_k, r = clamp(round(t)),

@@ -41,9 +41,18 @@ constexpr size_t wg_lds_bytes() { return (size_t)128 * wg_chunks<KK>() * 16 + (s
 // Waves of a workgroup are placed on the four SIMDs round robin from SIMD 0, so two resident
 // workgroups of 9 or 10 waves put 6 waves on a SIMD: each wave may then hold at most 80 VGPRs.
 // The register budget is requested accordingly (6 waves per SIMD up to pb = 160, 4 above).
-template <int KK, int BITS, bool FULL>
+// Extra arguments of the quant_error form of the kernel (QE): phases 1 - 3 are the same, phase 4
+// accumulates the squared quantization error per clip ratio instead of packing codes.
+struct QeArgs {
+    ClipList clips;
+    int n_clips;
+    double* partial;      // [rows][n_clips]
+};
+
+template <int KK, int BITS, bool FULL, bool QE>
 __global__ __launch_bounds__(128 * KK) __attribute__((amdgpu_waves_per_eu(KK <= 5 ? 6 : 4)))
-void k_wg_block(WaveArgs a, int pb) {
+void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
+    __shared__ float esum[QE ? 16 : 1][QE ? RQ_MAX_CLIPS : 1];
     constexpr int NCH = wg_chunks<KK>();
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     uint8_t* const ops = lds_raw;                        // [128 columns][NCH] x 16 bytes
@@ -148,6 +157,24 @@ void k_wg_block(WaveArgs a, int pb) {
         m = wmax[0];
         for (int w = 1; w < nw; ++w) m = fmaxf(m, wmax[w]);
         // ---- phase 4
+        if constexpr (QE) {
+            float v[32];
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+                for (int ip = 0; ip < 4; ++ip) v[nt * 4 + ip] = acc[nt][ip];
+            qe_candidates<32, BITS, 4>(v, m, flip, qe.clips, 0, qe.n_clips, [&](int k, float e2) {
+                if (lane == 0) esum[wave][k] = e2;
+            });
+            __syncthreads();   // the next row writes esum only after two more barriers
+            if ((int)threadIdx.x < qe.n_clips) {
+                float t = 0.0f;
+                for (int w = 0; w < nw; ++w) t += esum[w][threadIdx.x];
+                const double nn = (double)pb * 128.0;
+                qe.partial[row * qe.n_clips + threadIdx.x] = (double)t / (nn * nn);
+            }
+            continue;
+        }
         const float s = m > 0.0f ? flip * (float)(a.c1 / (double)m) : 0.0f;
         uint32_t* out = a.codes + row * (int64_t)(128 * BITS / 32) * pb;
 #pragma unroll
@@ -178,7 +205,7 @@ void k_wg_block(WaveArgs a, int pb) {
 }
 
 template <int KK>
-int launch_kk(const rq_hadamard* h, const WaveArgs& a, int bits, int pb, hipStream_t s) {
+int launch_kk(const rq_hadamard* h, const WaveArgs& a, int bits, int pb, hipStream_t s, const QeArgs* qe = nullptr) {
     const size_t lds = wg_lds_bytes<KK>();
     const int nw = (pb + 15) / 16;
     int per_cu = (int)((size_t)h->max_lds / (lds + 128));
@@ -188,12 +215,26 @@ int launch_kk(const rq_hadamard* h, const WaveArgs& a, int bits, int pb, hipStre
     const int64_t cap = (int64_t)h->num_cu * per_cu;
     const unsigned grid = (unsigned)(a.rows < cap ? a.rows : cap);
     const bool full = a.d == 128 * pb;
+    const dim3 g(grid), b(64 * nw);
+    if (qe) {
+        if (bits == 4) {
+            if (full) hipLaunchKernelGGL((k_wg_block<KK, 4, true, true>), g, b, lds, s, a, pb, *qe);
+            else hipLaunchKernelGGL((k_wg_block<KK, 4, false, true>), g, b, lds, s, a, pb, *qe);
+        } else {
+            if (full) hipLaunchKernelGGL((k_wg_block<KK, 3, true, true>), g, b, lds, s, a, pb, *qe);
+            else hipLaunchKernelGGL((k_wg_block<KK, 3, false, true>), g, b, lds, s, a, pb, *qe);
+        }
+        return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+    }
+    QeArgs none;
+    none.n_clips = 0;
+    none.partial = nullptr;
     if (bits == 4) {
-        if (full) hipLaunchKernelGGL((k_wg_block<KK, 4, true>), dim3(grid), dim3(64 * nw), lds, s, a, pb);
-        else hipLaunchKernelGGL((k_wg_block<KK, 4, false>), dim3(grid), dim3(64 * nw), lds, s, a, pb);
+        if (full) hipLaunchKernelGGL((k_wg_block<KK, 4, true, false>), g, b, lds, s, a, pb, none);
+        else hipLaunchKernelGGL((k_wg_block<KK, 4, false, false>), g, b, lds, s, a, pb, none);
     } else {
-        if (full) hipLaunchKernelGGL((k_wg_block<KK, 3, true>), dim3(grid), dim3(64 * nw), lds, s, a, pb);
-        else hipLaunchKernelGGL((k_wg_block<KK, 3, false>), dim3(grid), dim3(64 * nw), lds, s, a, pb);
+        if (full) hipLaunchKernelGGL((k_wg_block<KK, 3, true, false>), g, b, lds, s, a, pb, none);
+        else hipLaunchKernelGGL((k_wg_block<KK, 3, false, false>), g, b, lds, s, a, pb, none);
     }
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
@@ -208,8 +249,10 @@ template <int KK>
 bool prepare_kk() {
     const int lds = (int)wg_lds_bytes<KK>();
     if (lds <= 48 * 1024) return true;
-    return raise_lds(k_wg_block<KK, 4, true>, lds) && raise_lds(k_wg_block<KK, 4, false>, lds) &&
-           raise_lds(k_wg_block<KK, 3, true>, lds) && raise_lds(k_wg_block<KK, 3, false>, lds);
+    return raise_lds(k_wg_block<KK, 4, true, false>, lds) && raise_lds(k_wg_block<KK, 4, false, false>, lds) &&
+           raise_lds(k_wg_block<KK, 3, true, false>, lds) && raise_lds(k_wg_block<KK, 3, false, false>, lds) &&
+           raise_lds(k_wg_block<KK, 4, true, true>, lds) && raise_lds(k_wg_block<KK, 4, false, true>, lds) &&
+           raise_lds(k_wg_block<KK, 3, true, true>, lds) && raise_lds(k_wg_block<KK, 3, false, true>, lds);
 }
 
 }  // namespace
@@ -254,6 +297,27 @@ bool wg_block_supports(const rq_hadamard* h, const RowArgs& a) {
     if (pb <= 32 || pb > 256) return false;
     if ((reinterpret_cast<uintptr_t>(a.X) & 15) != 0 || (a.ld & 7) != 0 || (a.d & 7) != 0) return false;
     return true;
+}
+
+int wg_block_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
+                         double* partial, hipStream_t s) {
+    WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
+               static_cast<const u32x4*>(h->d_tiles), nullptr, nullptr, 0.0, 0.0};
+    QeArgs qe;
+    qe.clips = clips;
+    qe.n_clips = n_clips;
+    qe.partial = partial;
+    const int pb = a.p << (a.log2m - 7);
+    switch ((pb + 31) / 32) {
+        case 2: return launch_kk<2>(h, w, a.bits, pb, s, &qe);
+        case 3: return launch_kk<3>(h, w, a.bits, pb, s, &qe);
+        case 4: return launch_kk<4>(h, w, a.bits, pb, s, &qe);
+        case 5: return launch_kk<5>(h, w, a.bits, pb, s, &qe);
+        case 6: return launch_kk<6>(h, w, a.bits, pb, s, &qe);
+        case 7: return launch_kk<7>(h, w, a.bits, pb, s, &qe);
+        case 8: return launch_kk<8>(h, w, a.bits, pb, s, &qe);
+        default: return RQ_ERR_NO_ORDER;
+    }
 }
 
 int wg_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,

@@ -297,6 +297,12 @@ int rq_quant_error(const rq_hadamard_t* h, const void* X, int dtype, int64_t row
         if (rc != RQ_OK) return rc;
         return rq::reduce_partials(static_cast<double*>(workspace), rows, n_clips, mse, s);
     }
+    if (h->variant == 0 && rows > 0 && rq::wg_block_supports(h, a)) {
+        hm->last_kernel = "wg_block_quant_error";
+        rc = rq::wg_block_quant_error(h, a, cl, n_clips, static_cast<double*>(workspace), s);
+        if (rc != RQ_OK) return rc;
+        return rq::reduce_partials(static_cast<double*>(workspace), rows, n_clips, mse, s);
+    }
     if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
     hm->last_kernel = "generic_lds";
     return rq::generic_quant_error(h, a, cl, n_clips, mse, static_cast<double*>(workspace), s);

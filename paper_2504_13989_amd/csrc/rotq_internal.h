@@ -107,5 +107,7 @@ bool wg_block_prepare(int pb);
 bool wg_block_supports(const rq_hadamard* h, const RowArgs& a);
 int wg_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                              float* scales, hipStream_t s);
+int wg_block_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
+                         double* partial, hipStream_t s);
 
 }  // namespace rq
