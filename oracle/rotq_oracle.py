@@ -446,6 +446,18 @@ def dequantize_asym(codes: np.ndarray, delta: np.ndarray, lo: np.ndarray, group:
     return (cg * delta[:, :, None] + lo[:, :, None]).reshape(rows, n)
 
 
+def quant_error_asym(x: np.ndarray, n: int, b: int, clips, group: int = GROUP) -> np.ndarray:
+    """quant_error with the asymmetric group quantizer: mse[k] = mean over all rows * n rotated
+    elements of (dequantize_asym(quantize_asym(y; clips[k])) - y)^2 (the objective a clip search
+    sees for the KV cache, sections 4.1 and 5.1)."""
+    y = rotate(x, n)
+    out = np.empty(len(clips), dtype=np.float64)
+    for k, c in enumerate(clips):
+        codes, delta, lo, _ = quantize_asym(y, b, c, group)
+        out[k] = np.mean((dequantize_asym(codes, delta, lo, group) - y) ** 2)
+    return out
+
+
 def quantize_plain(x: np.ndarray, b: int, clip) -> tuple:
     """Per-token symmetric quantization of rows as they are (no rotation): the quantizer of
     section 2.1 applied to activations whose rotation was fused into the weights offline."""

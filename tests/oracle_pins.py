@@ -609,6 +609,33 @@ def check_asym_closed_forms(o):
     assert o.boundary_exempt_asym(tt, 4).tolist() == [[True, True, True, False, True, False]]
 
 
+def check_quant_error_asym(o):
+    # explicit loops on the rotated rows, formula written out per element
+    rng = np.random.default_rng(13)
+    x = rng.standard_normal((3, 128)) + 0.4
+    y = o.rotate(x, 128)
+    clips = [np.float32(0.6), np.float32(1.0)]
+    got = o.quant_error_asym(x, 128, 3, clips)
+    for k, c in enumerate(clips):
+        c = float(c)
+        tot = 0.0
+        for r in range(3):
+            lo, hi = c * min(y[r]), c * max(y[r])
+            delta = (hi - lo) / 7
+            for v in y[r]:
+                q = min(max(round((v - lo) / delta), 0), 7)      # Python rounds halves to even as well
+                tot += (q * delta + lo - v) ** 2
+        assert abs(got[k] - tot / (3 * 128)) <= 1e-12 * max(tot, 1e-30)
+    # values on the grid with clip 1 are reproduced: zero error; a constant group costs (1 - clip)^2 v^2
+    grid = (np.arange(128) % 8) * 0.5 - 1.0
+    h = o.hadamard_dense(128).astype(np.float64)
+    xg = (h.T @ grid / np.sqrt(128))[None, :]                  # rotates onto the grid
+    assert o.quant_error_asym(xg, 128, 3, [1.0])[0] < 1e-24
+    xc = np.zeros((1, 128)); xc[0, 0] = 4.0                    # rotated row is constant 4 / sqrt(128)
+    e = o.quant_error_asym(xc, 128, 4, [np.float32(0.75)])[0]
+    assert abs(e - (0.25 * 4.0 / np.sqrt(128)) ** 2) < 1e-15
+
+
 def check_quantize_plain(o):
     # no rotation: the section 2.1 quantizer on the row itself
     x = np.array([[0.0, 1.0, -2.0, 7.0, -7.0, 3.5, 0.4, -0.6]])

@@ -81,6 +81,7 @@ MUTATIONS = {
     "fuse_wrong_side": ("    return rotate(w.T, n).T\n", "    return rotate_back(np.pad(w.T, ((0, 0), (0, n - w.shape[0]))), n).T\n"),
     "limit_rounds_up": ("    return (n * (b - b_prime)) // b_prime", "    return -((-n * (b - b_prime)) // b_prime)"),
     "limit_wrong_divisor": ("    return (n * (b - b_prime)) // b_prime", "    return (n * (b - b_prime)) // b"),
+    "qe_asym_symmetric_codes": ("        codes, delta, lo, _ = quantize_asym(y, b, c, group)\n        out[k] = np.mean((dequantize_asym(codes, delta, lo, group) - y) ** 2)", "        codes, delta, _ = quantize(y, b, c)\n        out[k] = np.mean((dequantize(codes, delta) - y) ** 2)"),
     "asym_clip_one_side": ("    hi = clip64 * yg.max(axis=2)", "    hi = yg.max(axis=2)"),
     "asym_levels": ("    delta = (hi - lo) / lvl\n", "    delta = (hi - lo) / (lvl + 1)\n"),
     "asym_offset_dropped": ("return (cg * delta[:, :, None] + lo[:, :, None]).reshape(rows, n)", "return (cg * delta[:, :, None]).reshape(rows, n)"),
