@@ -218,6 +218,17 @@ int rq_quant_error(const rq_hadamard_t* h,
                    const float* clips, int n_clips,
                    float* mse, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * rq_quant_error with the asymmetric group quantizer of rq_rotate_quantize_asym (sections 4.1, 5.1:
+ * the objective of a clip search on the KV cache): mse[k] = (1 / (rows * n)) * sum of
+ * (code * Delta_g + lo_g - y)^2 at clip ratio clips[k].  The order n must be a multiple of RQ_GROUP.
+ * Arguments, workspace size (rq_quant_error_workspace) and errors as rq_quant_error.
+ */
+int rq_quant_error_asym(const rq_hadamard_t* h,
+                        const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits,
+                        const float* clips, int n_clips,
+                        float* mse, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of device workspace rq_gbs_search needs for `rows` rows; 0 on bad arguments. */
 size_t rq_gbs_workspace(int64_t rows);
 
@@ -245,6 +256,12 @@ int rq_gbs_search(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows
                   int bits, float eps, int max_evals, void* workspace, size_t workspace_bytes,
                   void* stream, float* clip_out, float* mse_out, float* trace_clips,
                   float* trace_mse, int* n_evals);
+
+/* rq_gbs_search with rq_quant_error_asym as the objective (n a multiple of RQ_GROUP). */
+int rq_gbs_search_asym(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d, int64_t ld,
+                       int bits, float eps, int max_evals, void* workspace, size_t workspace_bytes,
+                       void* stream, float* clip_out, float* mse_out, float* trace_clips,
+                       float* trace_mse, int* n_evals);
 
 /*
  * Select the kernel family for subsequent hot-path calls on this handle (testing /

@@ -53,10 +53,12 @@ def lib() -> C.CDLL:
     L.rq_quant_error_workspace.argtypes = [i64, i32]
     L.rq_quant_error_workspace.restype = C.c_size_t
     L.rq_quant_error.argtypes = [vp, vp, i32, i64, i32, i64, i32, f32p, i32, vp, vp, C.c_size_t, vp]
+    L.rq_quant_error_asym.argtypes = L.rq_quant_error.argtypes
     L.rq_gbs_workspace.argtypes = [i64]
     L.rq_gbs_workspace.restype = C.c_size_t
     L.rq_gbs_search.argtypes = [vp, vp, i32, i64, i32, i64, i32, C.c_float, i32, vp, C.c_size_t, vp,
                                 f32p, f32p, f32p, f32p, ip]
+    L.rq_gbs_search_asym.argtypes = L.rq_gbs_search.argtypes
     L.rq_hadamard_set_variant.argtypes = [vp, i32]
     L.rq_hadamard_last_kernel.argtypes = [vp]
     L.rq_hadamard_last_kernel.restype = C.c_char_p
@@ -269,8 +271,9 @@ def quant_error_workspace(rows: int, n_clips: int) -> int:
 
 
 def quant_error(h: Hadamard, x, bits: int, clips: Sequence[float], mse=None, workspace=None,
-                stream=None):
-    """rq_quant_error on a CUDA tensor x [..., d]; returns mse float32 [len(clips)] (device)."""
+                stream=None, asym: bool = False):
+    """rq_quant_error (rq_quant_error_asym with asym=True) on a CUDA tensor x [..., d]; returns mse
+    float32 [len(clips)] (device)."""
     import torch
     if not x.is_cuda:
         raise ValueError("x must be a device tensor")
@@ -283,16 +286,18 @@ def quant_error(h: Hadamard, x, bits: int, clips: Sequence[float], mse=None, wor
     if workspace is None:
         workspace = torch.empty((max(need, 8) + 7) // 8, dtype=torch.float64, device=x.device)
     ws_bytes = workspace.numel() * workspace.element_size()
-    rc = lib().rq_quant_error(h._h, C.c_void_p(x2.data_ptr()), _dtype_code(x2), rows, d, ld,
-                              int(bits), arr, k, C.c_void_p(mse.data_ptr()),
-                              C.c_void_p(workspace.data_ptr()), ws_bytes, _stream_ptr(stream))
-    _check(rc, "rq_quant_error")
+    fn = lib().rq_quant_error_asym if asym else lib().rq_quant_error
+    rc = fn(h._h, C.c_void_p(x2.data_ptr()), _dtype_code(x2), rows, d, ld, int(bits), arr, k,
+            C.c_void_p(mse.data_ptr()), C.c_void_p(workspace.data_ptr()), ws_bytes, _stream_ptr(stream))
+    _check(rc, "rq_quant_error_asym" if asym else "rq_quant_error")
     return mse
 
 
-def gbs_search(h: Hadamard, x, bits: int, eps: float, max_evals: int = 64, workspace=None, stream=None):
-    """rq_gbs_search on a CUDA tensor x [..., d]; returns (clip, mse, trace) with trace a list of
-    (probe, objective) pairs in evaluation order.  Synchronises the stream at every probe."""
+def gbs_search(h: Hadamard, x, bits: int, eps: float, max_evals: int = 64, workspace=None, stream=None,
+               asym: bool = False):
+    """rq_gbs_search (rq_gbs_search_asym with asym=True) on a CUDA tensor x [..., d]; returns
+    (clip, mse, trace) with trace a list of (probe, objective) pairs in evaluation order.
+    Synchronises the stream at every probe."""
     import torch
     if not x.is_cuda:
         raise ValueError("x must be a device tensor")
@@ -302,9 +307,10 @@ def gbs_search(h: Hadamard, x, bits: int, eps: float, max_evals: int = 64, works
         workspace = torch.empty((need + 7) // 8, dtype=torch.float64, device=x.device)
     clip, mse, n = C.c_float(), C.c_float(), C.c_int()
     tc, tm = (C.c_float * max_evals)(), (C.c_float * max_evals)()
-    rc = lib().rq_gbs_search(h._h, C.c_void_p(x2.data_ptr()), _dtype_code(x2), rows, d, ld, int(bits),
-                             C.c_float(eps), int(max_evals), C.c_void_p(workspace.data_ptr()),
-                             workspace.numel() * workspace.element_size(), _stream_ptr(stream),
-                             C.byref(clip), C.byref(mse), tc, tm, C.byref(n))
-    _check(rc, "rq_gbs_search")
+    fn = lib().rq_gbs_search_asym if asym else lib().rq_gbs_search
+    rc = fn(h._h, C.c_void_p(x2.data_ptr()), _dtype_code(x2), rows, d, ld, int(bits),
+            C.c_float(eps), int(max_evals), C.c_void_p(workspace.data_ptr()),
+            workspace.numel() * workspace.element_size(), _stream_ptr(stream),
+            C.byref(clip), C.byref(mse), tc, tm, C.byref(n))
+    _check(rc, "rq_gbs_search_asym" if asym else "rq_gbs_search")
     return clip.value, mse.value, [(tc[i], tm[i]) for i in range(n.value)]

@@ -325,6 +325,55 @@ __global__ __launch_bounds__(kThreads) void k_generic_quant_error(RowArgs a, Cli
     }
 }
 
+// quant_error with the asymmetric group-128 quantizer (sections 4.1, 5.1): per group lo = clip min,
+// Delta = clip (max - min) / (2^b - 1); e = y - (code Delta + lo).
+__global__ __launch_bounds__(kThreads) void k_generic_quant_error_asym(RowArgs a, ClipList clips,
+                                                                       int n_clips, double* partial) {
+    extern __shared__ float lds[];
+    __shared__ float red[4];
+    __shared__ double dred[4];
+    __shared__ float gmn[kMaxGroups], gmx[kMaxGroups];
+    const int64_t row = blockIdx.x;
+    float amax;
+    const float* y = rotate_row_lds(a, row, lds, lds + a.n, red, &amax);
+    const int n_groups = a.n / 128;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int gi = wave; gi < n_groups; gi += kThreads / 64) {
+        const float u = y[gi * 128 + lane], v = y[gi * 128 + 64 + lane];
+        float mn = fminf(u, v), mx = fmaxf(u, v);
+        for (int m = 32; m >= 1; m >>= 1) {
+            mn = fminf(mn, __shfl_xor(mn, m, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+        }
+        if (lane == 0) {
+            gmn[gi] = mn;
+            gmx[gi] = mx;
+        }
+    }
+    __syncthreads();
+    const double lvl = (double)((1 << a.bits) - 1);
+    for (int k = 0; k < n_clips; ++k) {
+        const double cl = (double)clips.v[k];
+        float acc = 0.0f;
+        for (int j = threadIdx.x; j < a.n; j += kThreads) {
+            const double mn = (double)gmn[j >> 7], r = (double)gmx[j >> 7] - mn;
+            const float lo = (float)(cl * mn), dk = (float)(cl * r / lvl);
+            const float ik = r > 0.0 ? (float)(lvl / (cl * r)) : 0.0f;
+            const float d = y[j] - lo;
+            const float q = fminf(fmaxf(rintf(d * ik), 0.0f), (float)lvl);
+            const float e = fmaf(-q, dk, d);
+            acc = fmaf(e, e, acc);
+        }
+        double tot = wave_sum((double)acc);
+        if ((threadIdx.x & 63) == 0) dred[threadIdx.x >> 6] = tot;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            partial[row * n_clips + k] =
+                (dred[0] + dred[1] + dred[2] + dred[3]) / ((double)a.n * (double)a.n);
+        __syncthreads();
+    }
+}
+
 // partial[row][k] is the row's mean squared error in the normalised domain (un-normalised sum
 // divided by n twice); mse[k] is its mean over rows, summed in a fixed order.
 __global__ __launch_bounds__(kThreads) void k_reduce_partials(const double* partial, int64_t rows,
@@ -369,6 +418,7 @@ bool generic_prepare(const rq_hadamard* h) {
         return false;
     if (prepare(k_generic_rotate, bytes) != RQ_OK || prepare(k_generic_dequant_rotate, bytes) != RQ_OK)
         return false;
+    if (h->f.n % 128 == 0 && prepare(k_generic_quant_error_asym, bytes) != RQ_OK) return false;
     return prepare(k_generic_rotate_quantize, bytes) == RQ_OK &&
            prepare(k_generic_quant_error, bytes) == RQ_OK;
 }
@@ -420,6 +470,18 @@ int reduce_partials(const double* partial, int64_t rows, int n_clips, float* mse
     hipLaunchKernelGGL(k_reduce_partials, dim3(n_clips), dim3(kThreads), 0, s, partial, rows, n_clips,
                        mse);
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+int generic_quant_error_asym(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
+                             float* mse, double* partial, hipStream_t s) {
+    const size_t bytes = lds_bytes(h);
+    if (a.rows > 0x7fffffffLL || a.n % 128 != 0) return RQ_ERR_ARG;
+    if (a.rows > 0) {
+        hipLaunchKernelGGL(k_generic_quant_error_asym, dim3((unsigned)a.rows), dim3(kThreads), bytes, s, a,
+                           clips, n_clips, partial);
+        if (hipGetLastError() != hipSuccess) return RQ_ERR_HIP;
+    }
+    return reduce_partials(partial, a.rows, n_clips, mse, s);
 }
 
 int generic_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,

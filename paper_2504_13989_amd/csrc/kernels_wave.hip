@@ -608,6 +608,81 @@ __global__ __launch_bounds__(64) void k_wave_short_qe(WaveArgs a, ClipList clips
     }
 }
 
+// quant_error of the asymmetric group-128 quantizer on rows of 128 (one group per row; sections 4.1,
+// 5.1): per clip ratio lo = clip min, Delta = clip (max - min) / (2^b - 1), e = (y - lo) - code Delta;
+// six vector-ALU operations per value and candidate, four candidates at a time.
+template <int BITS>
+__global__ __launch_bounds__(64) void k_wave_short_qe_asym(WaveArgs a, ClipList clips, int n_clips, double* partial) {
+    constexpr int CB = 2, RPW = 4, N = 128;
+    constexpr float kL = (float)((1 << BITS) - 1);
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, nnl = lane & 15;
+    const int c = nnl & 3, rsub = nnl >> 2;
+    const int chunk = (g << CB) + c;
+    const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
+    float sf[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
+    const uint32_t sg0 = (c & 1) ? 0x80000000u : 0u;
+    const float flip = (c & 2) ? -1.0f : 1.0f;            // the one fused stage (xor-2)
+    const int64_t n_pass = (a.rows + RPW - 1) / RPW;
+    for (int64_t pass = blockIdx.x; pass < n_pass; pass += gridDim.x) {
+        const int64_t row = pass * RPW + rsub;
+        const bool live = row < a.rows;
+        const bool in = live && chunk * 8 < a.d;
+        u32x4 raw = load16(a.X + (in ? row * a.ld + chunk * 8 : 0));
+        if (!in) raw = u32x4{0u, 0u, 0u, 0u};
+        const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        f32x4 v0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
+        f32x4 v1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), bm, z, 0, 0, 0);
+        lane_stage<kDppXor1>(v0, sg0);
+        lane_stage<kDppXor1>(v1, sg0);
+        lane_stages_tail<CB>(v0, sf);
+        lane_stages_tail<CB>(v1, sf);
+        const float yv[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+        const float lo8 = min8(yv), hi8 = max8(yv);
+        float mx = flip > 0.0f ? hi8 : -lo8;
+        float nm = flip > 0.0f ? -lo8 : hi8;
+        quad_rows_max_pair(mx, nm);
+        const double mn64 = -(double)nm, r64 = (double)mx + (double)nm;
+        for (int kb = 0; kb < n_clips; kb += 4) {
+            float los[4], sk[4], ndk[4], e2[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int k = kb + j < n_clips ? kb + j : n_clips - 1;
+                const double cl = (double)clips.v[k];
+                los[j] = flip * (float)(cl * mn64);                               // lane sign folded in
+                sk[j] = r64 > 0.0 ? flip * (float)((double)kL / (cl * r64)) : 0.0f;
+                ndk[j] = -flip * (float)(cl * r64 / (double)kL);
+                e2[j] = 0.0f;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float d = yv[i] - los[j];
+                    const float r = __builtin_amdgcn_fmed3f(__builtin_rintf(d * sk[j]), 0.0f, kL);
+                    const float e = fmaf(r, ndk[j], d);
+                    e2[j] = fmaf(e, e, e2[j]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppXor1>(e2[j]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppXor2>(e2[j]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 16, 64);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 32, 64);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (live && g == 0 && c == 0 && kb + j < n_clips)
+                    partial[row * n_clips + kb + j] = (double)e2[j] / ((double)N * (double)N);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Rotation-free quantizer (section 2.1 with the clip ratio of section 3.1 on the row itself): one
 // wave per bf16 row of d <= 512 T values, the row held in registers between the absmax pass and
@@ -912,6 +987,18 @@ static int launch_short_qe(const WaveArgs& w, const ClipList& clips, int n_clips
     const dim3 grid((unsigned)(passes < cap ? passes : cap)), block(64);
     if (bits == 4) hipLaunchKernelGGL((k_wave_short_qe<CB, 4>), grid, block, 0, s, w, clips, n_clips, partial);
     else hipLaunchKernelGGL((k_wave_short_qe<CB, 3>), grid, block, 0, s, w, clips, n_clips, partial);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+int wave_quant_error_asym(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
+                          double* partial, hipStream_t s) {
+    WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
+               static_cast<const u32x4*>(h->d_tiles), nullptr, nullptr, 0.0, 0.0};
+    const int64_t passes = (w.rows + 3) / 4;
+    const int64_t cap = 1 << 24;
+    const dim3 grid((unsigned)(passes < cap ? passes : cap)), block(64);
+    if (a.bits == 4) hipLaunchKernelGGL((k_wave_short_qe_asym<4>), grid, block, 0, s, w, clips, n_clips, partial);
+    else hipLaunchKernelGGL((k_wave_short_qe_asym<3>), grid, block, 0, s, w, clips, n_clips, partial);
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 

@@ -273,11 +273,12 @@ size_t rq_quant_error_workspace(int64_t rows, int n_clips) {
     return r * (size_t)n_clips * sizeof(double);
 }
 
-int rq_quant_error(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
-                   int64_t ld, int bits, const float* clips, int n_clips, float* mse,
-                   void* workspace, size_t workspace_bytes, void* stream) {
+static int quant_error_impl(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
+                            int64_t ld, int bits, const float* clips, int n_clips, float* mse,
+                            void* workspace, size_t workspace_bytes, void* stream, bool asym) {
     int rc = check_rows(h, X, dtype, rows, d, ld, bits);
     if (rc != RQ_OK) return rc;
+    if (asym && h->f.n % RQ_GROUP != 0) return RQ_ERR_ARG;
     if (!clips || n_clips < 1 || n_clips > RQ_MAX_CLIPS) return RQ_ERR_ARG;
     if (!mse || !aligned(mse, 4) || !workspace || !aligned(workspace, 8)) return RQ_ERR_ARG;
     if (workspace_bytes < rq_quant_error_workspace(rows, n_clips)) return RQ_ERR_ARG;
@@ -291,6 +292,17 @@ int rq_quant_error(const rq_hadamard_t* h, const void* X, int dtype, int64_t row
     rq_hadamard* hm = const_cast<rq_hadamard*>(h);
     const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, bits);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (asym) {
+        if (h->variant == 0 && rows > 0 && rq::wave_asym_supports(h, a)) {
+            hm->last_kernel = "wave_quant_error_asym";
+            rc = rq::wave_quant_error_asym(h, a, cl, n_clips, static_cast<double*>(workspace), s);
+            if (rc != RQ_OK) return rc;
+            return rq::reduce_partials(static_cast<double*>(workspace), rows, n_clips, mse, s);
+        }
+        if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
+        hm->last_kernel = "generic_lds_asym";
+        return rq::generic_quant_error_asym(h, a, cl, n_clips, mse, static_cast<double*>(workspace), s);
+    }
     if (h->variant == 0 && rows > 0 && rq::wave_quant_error_supports(h, a)) {
         hm->last_kernel = "wave_quant_error";
         rc = rq::wave_quant_error(h, a, cl, n_clips, static_cast<double*>(workspace), s);
@@ -308,17 +320,32 @@ int rq_quant_error(const rq_hadamard_t* h, const void* X, int dtype, int64_t row
     return rq::generic_quant_error(h, a, cl, n_clips, mse, static_cast<double*>(workspace), s);
 }
 
+int rq_quant_error(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
+                   int64_t ld, int bits, const float* clips, int n_clips, float* mse,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+    return quant_error_impl(h, X, dtype, rows, d, ld, bits, clips, n_clips, mse, workspace, workspace_bytes,
+                            stream, false);
+}
+
+int rq_quant_error_asym(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
+                        int64_t ld, int bits, const float* clips, int n_clips, float* mse,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    return quant_error_impl(h, X, dtype, rows, d, ld, bits, clips, n_clips, mse, workspace, workspace_bytes,
+                            stream, true);
+}
+
 size_t rq_gbs_workspace(int64_t rows) {
     const size_t q = rq_quant_error_workspace(rows, 1);
     return q ? q + 256 : 0;
 }
 
-int rq_gbs_search(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d, int64_t ld,
-                  int bits, float eps, int max_evals, void* workspace, size_t workspace_bytes,
-                  void* stream, float* clip_out, float* mse_out, float* trace_clips,
-                  float* trace_mse, int* n_evals) {
+static int gbs_impl(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d, int64_t ld,
+                    int bits, float eps, int max_evals, void* workspace, size_t workspace_bytes,
+                    void* stream, float* clip_out, float* mse_out, float* trace_clips,
+                    float* trace_mse, int* n_evals, bool asym) {
     int rc = check_rows(h, X, dtype, rows, d, ld, bits);
     if (rc != RQ_OK) return rc;
+    if (asym && h->f.n % RQ_GROUP != 0) return RQ_ERR_ARG;
     if (rows < 1 || !(eps > 0.0f) || max_evals < 1 || max_evals > 256) return RQ_ERR_ARG;
     if (!clip_out || !mse_out || !workspace || !aligned(workspace, 8)) return RQ_ERR_ARG;
     if (workspace_bytes < rq_gbs_workspace(rows)) return RQ_ERR_ARG;
@@ -331,7 +358,7 @@ int rq_gbs_search(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows
     int evals = 0;
     auto f = [&](double x, float* out) -> int {
         const float c = (float)x;
-        int r = rq_quant_error(h, X, dtype, rows, d, ld, bits, &c, 1, d_mse, qws, qws_bytes, stream);
+        int r = quant_error_impl(h, X, dtype, rows, d, ld, bits, &c, 1, d_mse, qws, qws_bytes, stream, asym);
         if (r != RQ_OK) return r;
         if (hipStreamSynchronize(s) != hipSuccess ||
             hipMemcpy(out, d_mse, sizeof(float), hipMemcpyDeviceToHost) != hipSuccess)
@@ -362,6 +389,22 @@ int rq_gbs_search(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows
     *mse_out = fm;
     if (n_evals) *n_evals = evals;
     return RQ_OK;
+}
+
+int rq_gbs_search(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d, int64_t ld,
+                  int bits, float eps, int max_evals, void* workspace, size_t workspace_bytes,
+                  void* stream, float* clip_out, float* mse_out, float* trace_clips,
+                  float* trace_mse, int* n_evals) {
+    return gbs_impl(h, X, dtype, rows, d, ld, bits, eps, max_evals, workspace, workspace_bytes, stream,
+                    clip_out, mse_out, trace_clips, trace_mse, n_evals, false);
+}
+
+int rq_gbs_search_asym(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d, int64_t ld,
+                       int bits, float eps, int max_evals, void* workspace, size_t workspace_bytes,
+                       void* stream, float* clip_out, float* mse_out, float* trace_clips,
+                       float* trace_mse, int* n_evals) {
+    return gbs_impl(h, X, dtype, rows, d, ld, bits, eps, max_evals, workspace, workspace_bytes, stream,
+                    clip_out, mse_out, trace_clips, trace_mse, n_evals, true);
 }
 
 const char* rq_strerror(int code) {

@@ -86,6 +86,10 @@ int wave_rotate_quantize_asym(const rq_hadamard* h, const RowArgs& a, float clip
 bool wave_quant_error_supports(const rq_hadamard* h, const RowArgs& a);
 int wave_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
                      double* partial, hipStream_t s);
+int wave_quant_error_asym(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
+                          double* partial, hipStream_t s);
+int generic_quant_error_asym(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
+                             float* mse, double* partial, hipStream_t s);
 int reduce_partials(const double* partial, int64_t rows, int n_clips, float* mse, hipStream_t s);
 // Block kernel: bf16 rows, n = pb * 128 with a +-1 block of order pb <= 32 (Paley (x) small
 // Sylvester) on the matrix cores.

@@ -136,8 +136,8 @@ def check_quantize_plain(x_np, b, clip, codes_gpu, scales_gpu, what=""):
     return {"elements": int(q.size), "mismatches": int(mism.sum())}
 
 
-def check_quant_error(x_np, n, b, clips, mse_gpu, rtol=REL_TOL, what=""):
-    want = oracle.quant_error(x_np, n, b, clips)
+def check_quant_error(x_np, n, b, clips, mse_gpu, rtol=REL_TOL, what="", asym=False):
+    want = (oracle.quant_error_asym if asym else oracle.quant_error)(x_np, n, b, clips)
     got = np.asarray(mse_gpu, dtype=np.float64)
     rel = np.abs(got - want) / np.maximum(want, 1e-300)
     assert np.all(rel <= rtol), f"{what}: mse rel err {rel.max():.3g} (got {got}, want {want})"

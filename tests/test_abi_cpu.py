@@ -230,6 +230,29 @@ def test_gbs_search_argument_errors(L):
     h.close()
 
 
+def test_asym_objective_argument_errors(L):
+    vp = C.c_void_p
+    E = binding.RQ_ERR_ARG
+    h = binding.hadamard_build(128)
+    h96 = binding.hadamard_build(96)
+    clips = (C.c_float * 2)(0.7, 1.0)
+
+    def qe(hh, d=128, n_clips=2, mse=0x3000, ws=0x4000, ws_bytes=1 << 20):
+        return L.rq_quant_error_asym(hh, vp(0x1000), 0, 4, d, d, 3, clips, n_clips, vp(mse), vp(ws), ws_bytes, None)
+
+    assert qe(None) == E and qe(h._h, n_clips=0) == E and qe(h._h, mse=0) == E and qe(h._h, ws_bytes=8) == E
+    assert qe(h96._h, d=96) == E                                   # groups of 128 need n % 128 == 0
+    out = (C.c_float * 2)()
+    rc = L.rq_gbs_search_asym(h96._h, vp(0x1000), 0, 4, 96, 96, 3, C.c_float(0.1), 8, vp(0x4000), 1 << 20, None,
+                              out, out, None, None, None)
+    assert rc == E
+    rc = L.rq_gbs_search_asym(h._h, vp(0x1000), 0, 4, 128, 128, 3, C.c_float(0.0), 8, vp(0x4000), 1 << 20, None,
+                              out, out, None, None, None)
+    assert rc == E
+    h.close()
+    h96.close()
+
+
 def test_info_and_variant_errors(L):
     assert L.rq_hadamard_info(None, None, None, None, None, None) == binding.RQ_ERR_ARG
     h = binding.hadamard_build(256)

@@ -128,6 +128,37 @@ def test_plain_quantize_views_and_zero_rows(torch):
     assert c0.shape[0] == 0
 
 
+@pytest.mark.parametrize("variant", [0, 1], ids=["auto", "general"])
+@pytest.mark.parametrize("name,rows,b", [("kv_k", 1029, 3), ("kv_v", 302, 4), ("kv_k", 3, 3), ("llama_hidden", 20, 3),
+                                         ("tiny", 64, 4)])
+def test_quant_error_asym(torch, name, rows, b, variant):
+    w = wl.WORKLOADS[name].with_rows(rows)
+    x = wl.generate(w)
+    clips = wl.clip_grid()
+    h = handle(w.n)
+    h.set_variant(variant)
+    say(f"quant_error_asym {name} rows={rows} n={w.n} b={b} variant={variant}")
+    mse = binding.quant_error(h, parity.to_device(x), b, clips, asym=True)
+    torch.cuda.synchronize()
+    h.set_variant(0)
+    rel = parity.check_quant_error(x, w.n, b, clips, mse.cpu().numpy(), what=f"{name} [{h.last_kernel}]", asym=True)
+    say(f"  ok kernel={h.last_kernel} max rel err {rel:.2e}")
+    if variant == 0 and w.n == 128:
+        assert h.last_kernel == "wave_quant_error_asym"
+
+
+def test_gbs_search_asym_follows_algorithm_1(torch):
+    import rotq_oracle as oracle
+    w = wl.WORKLOADS["kv_k"].with_rows(2000)
+    x = wl.generate(w)
+    h = handle(w.n)
+    clip, mse, trace = binding.gbs_search(h, parity.to_device(x), 3, 1.0 / 64, asym=True)
+    m, fm, otrace = oracle.gbs_search(lambda c: oracle.quant_error_asym(x, w.n, 3, [np.float32(c)])[0], 1.0 / 64)
+    say(f"gbs asym: clip {clip} after {len(trace)} probes (oracle {m})")
+    assert [p for p, _ in trace] == [np.float32(p) for p, _ in otrace]
+    assert clip == np.float32(m) and abs(mse - fm) <= 1e-5 * fm
+
+
 def test_graph_replay_and_side_stream(torch):
     """The hot-path calls allocate nothing and run on the caller's stream: captured in a HIP graph on a
     side stream and replayed several times with eager work in between, every replay must reproduce the
