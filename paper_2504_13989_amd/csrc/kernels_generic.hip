@@ -376,17 +376,45 @@ __global__ __launch_bounds__(kThreads) void k_generic_quant_error_asym(RowArgs a
 
 // partial[row][k] is the row's mean squared error in the normalised domain (un-normalised sum
 // divided by n twice); mse[k] is its mean over rows, summed in a fixed order.
-__global__ __launch_bounds__(kThreads) void k_reduce_partials(const double* partial, int64_t rows,
-                                                              int n_clips, float* mse) {
+__global__ __launch_bounds__(kThreads) void k_reduce_partials(const double* partial, int64_t count,
+                                                              int64_t stride, int64_t rows, int n_clips,
+                                                              float* mse) {
+    // sums partial[(i * stride)][k], i < count, in a fixed order; mse[k] = sum / rows
     __shared__ double dred[4];
     const int k = blockIdx.x;
     double acc = 0.0;
-    for (int64_t r = threadIdx.x; r < rows; r += kThreads) acc += partial[r * n_clips + k];
+    for (int64_t i = threadIdx.x; i < count; i += kThreads) acc += partial[i * stride * n_clips + k];
     acc = wave_sum(acc);
     if ((threadIdx.x & 63) == 0) dred[threadIdx.x >> 6] = acc;
     __syncthreads();
     if (threadIdx.x == 0)
         mse[k] = rows > 0 ? (float)((dred[0] + dred[1] + dred[2] + dred[3]) / (double)rows) : 0.0f;
+}
+
+// First level for many rows: one workgroup sums a chunk of kChunkRows rows for every clip ratio
+// (coalesced: consecutive threads read consecutive clip ratios of a row) and leaves the sums in the
+// chunk's own first row - read by no other workgroup - so no extra workspace is needed.
+constexpr int kChunkRows = 256;
+
+__global__ __launch_bounds__(kThreads) void k_reduce_chunks(double* partial, int64_t rows, int n_clips) {
+    __shared__ double part[kThreads];
+    int kp = 1;
+    while (kp < n_clips) kp <<= 1;                       // n_clips <= 64
+    const int lanes = kThreads / kp;                     // row lanes
+    const int k = threadIdx.x % kp, rl = threadIdx.x / kp;
+    const int64_t row0 = (int64_t)blockIdx.x * kChunkRows;
+    const int64_t left = rows - row0;
+    const int nrows = left < kChunkRows ? (int)left : kChunkRows;
+    double acc = 0.0;
+    if (k < n_clips)
+        for (int r = rl; r < nrows; r += lanes) acc += partial[(row0 + r) * n_clips + k];
+    part[threadIdx.x] = acc;
+    __syncthreads();                                     // every read of the chunk is done
+    if (rl == 0 && k < n_clips) {
+        double t = 0.0;
+        for (int i = 0; i < lanes; ++i) t += part[i * kp + k];
+        partial[row0 * n_clips + k] = t;
+    }
 }
 
 size_t lds_bytes(const rq_hadamard* h) {
@@ -466,9 +494,17 @@ int plain_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, in
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 
-int reduce_partials(const double* partial, int64_t rows, int n_clips, float* mse, hipStream_t s) {
-    hipLaunchKernelGGL(k_reduce_partials, dim3(n_clips), dim3(kThreads), 0, s, partial, rows, n_clips,
-                       mse);
+int reduce_partials(double* partial, int64_t rows, int n_clips, float* mse, hipStream_t s) {
+    if (rows > 16 * kChunkRows) {
+        const int64_t chunks = (rows + kChunkRows - 1) / kChunkRows;
+        if (chunks > 0x7fffffffLL) return RQ_ERR_ARG;
+        hipLaunchKernelGGL(k_reduce_chunks, dim3((unsigned)chunks), dim3(kThreads), 0, s, partial, rows, n_clips);
+        hipLaunchKernelGGL(k_reduce_partials, dim3(n_clips), dim3(kThreads), 0, s, partial, chunks,
+                           (int64_t)kChunkRows, rows, n_clips, mse);
+    } else {
+        hipLaunchKernelGGL(k_reduce_partials, dim3(n_clips), dim3(kThreads), 0, s, partial, rows, (int64_t)1,
+                           rows, n_clips, mse);
+    }
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 

@@ -90,7 +90,7 @@ int wave_quant_error_asym(const rq_hadamard* h, const RowArgs& a, const ClipList
                           double* partial, hipStream_t s);
 int generic_quant_error_asym(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
                              float* mse, double* partial, hipStream_t s);
-int reduce_partials(const double* partial, int64_t rows, int n_clips, float* mse, hipStream_t s);
+int reduce_partials(double* partial, int64_t rows, int n_clips, float* mse, hipStream_t s);
 // Block kernel: bf16 rows, n = pb * 128 with a +-1 block of order pb <= 32 (Paley (x) small
 // Sylvester) on the matrix cores.
 std::vector<uint32_t> wave_block_tiles(const std::vector<int8_t>& bm, int pb);

@@ -274,7 +274,7 @@ def test_full_size_kv_sampled(torch, name):
 @pytest.mark.parametrize("name,rows,b", [("calib", 512, 3), ("calib", 77, 4), ("qwen_hidden", 50, 3),
                                          ("ffn_expand", 50, 3), ("tiny", 64, 3), ("kv_k", 300, 3),
                                          ("ffn_down", 9, 3), ("qwen_hidden", 700, 4), ("kv_v", 1031, 4),
-                                         ("kv_k", 3, 3)])
+                                         ("kv_k", 3, 3), ("kv_k", 5003, 3), ("kv_v", 4096 + 256, 4)])
 def test_quant_error(torch, name, rows, b, variant):
     w = wl.WORKLOADS[name].with_rows(rows)
     x = wl.generate(w)

@@ -130,7 +130,7 @@ def test_plain_quantize_views_and_zero_rows(torch):
 
 @pytest.mark.parametrize("variant", [0, 1], ids=["auto", "general"])
 @pytest.mark.parametrize("name,rows,b", [("kv_k", 1029, 3), ("kv_v", 302, 4), ("kv_k", 3, 3), ("llama_hidden", 20, 3),
-                                         ("tiny", 64, 4)])
+                                         ("tiny", 64, 4), ("kv_k", 4999, 3)])
 def test_quant_error_asym(torch, name, rows, b, variant):
     w = wl.WORKLOADS[name].with_rows(rows)
     x = wl.generate(w)
