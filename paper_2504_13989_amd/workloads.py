@@ -99,7 +99,7 @@ def _structure(w: Workload):
         rows = np.sort(rng.choice(w.rows, min(w.n_massive_rows, w.rows), replace=False))
     if w.recipe == "kv_k":
         # outlier channels differ per (batch, head)
-        n_heads = max(1, w.rows // w.head_rows)
+        n_heads = max(1, -(-w.rows // w.head_rows))        # a last, partial head counts too
         ch = np.stack([np.sort(rng.choice(w.d, w.n_outlier_ch, replace=False))
                        for _ in range(n_heads)])
     return ch, rows

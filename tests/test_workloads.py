@@ -48,3 +48,12 @@ def test_kv_rows_and_clip_grid():
     g = wl.clip_grid()
     assert g.dtype == np.float32 and len(g) == 32 and g[0] == 0.5 and g[-1] == 1.0
     assert np.all(np.diff(g) > 0)
+
+
+def test_kv_rows_not_a_multiple_of_the_head_length():
+    # a row count that ends inside a head still has outlier channels for that head
+    w = wl.WORKLOADS["kv_k"].with_rows(8192 * 2 + 300)
+    x = wl.generate(w)
+    assert x.shape == (8192 * 2 + 300, 128)
+    full = wl.generate(wl.WORKLOADS["kv_k"].with_rows(8192 * 3))
+    assert np.array_equal(x[: 8192 * 2], full[: 8192 * 2])      # earlier heads do not depend on the row count
