@@ -153,7 +153,7 @@ def time_all_configs(torch, binding, wl):
             "roofline": {"bound": "mfma", "unit": "TFLOP/s", "achieved": flops / ms / 1e9, "peak": 2500.0,
                          "frac": flops / ms / 1e9 / 2500.0,
                          "note": "2 n^2 flops per row (dense +-1 matrix, bf16 operands); limited by the "
-                                 "n^2/8 bytes of operand table each 16-row workgroup reads from L2"}}
+                                 "n^2/8 bytes of operand table each workgroup (16 or 32 rows) reads"}}
         del x, codes, scales
     # quant_error on the other projections a clip search visits (512 rows each; 65536 KV head rows)
     clips = wl.clip_grid()
