@@ -48,6 +48,7 @@ extern "C" {
 
 #define RQ_BF16 0             /* X elements are bfloat16 (2 bytes) */
 #define RQ_F32  1             /* X elements are float (4 bytes) */
+#define RQ_F16  2             /* X elements are IEEE half precision (2 bytes); inputs only */
 
 #define RQ_KIND_SYLVESTER 0
 #define RQ_KIND_PALEY1    1

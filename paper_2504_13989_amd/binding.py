@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librotq.so")
 
 RQ_OK, RQ_ERR_ARG, RQ_ERR_NO_ORDER, RQ_ERR_HIP, RQ_ERR_NOMEM = 0, -1, -2, -3, -4
-RQ_BF16, RQ_F32 = 0, 1
+RQ_BF16, RQ_F32, RQ_F16 = 0, 1, 2
 RQ_MAX_CLIPS = 64
 
 _lib = None
@@ -128,6 +128,8 @@ def _dtype_code(x) -> int:
         return RQ_BF16
     if x.dtype == torch.float32:
         return RQ_F32
+    if x.dtype == torch.float16:
+        return RQ_F16
     raise TypeError(f"unsupported input dtype {x.dtype}")
 
 

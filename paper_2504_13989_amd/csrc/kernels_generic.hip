@@ -18,6 +18,7 @@ __device__ __forceinline__ float load_f32(const void* X, int dtype, int64_t idx)
         uint32_t b = static_cast<const uint16_t*>(X)[idx];
         return __uint_as_float(b << 16);
     }
+    if (dtype == RQ_F16) return (float)static_cast<const _Float16*>(X)[idx];      // exact
     return static_cast<const float*>(X)[idx];
 }
 

@@ -12,11 +12,11 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 int check_rows(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d, int64_t ld,
                int bits) {
     if (!h) return RQ_ERR_ARG;
-    if (dtype != RQ_BF16 && dtype != RQ_F32) return RQ_ERR_ARG;
+    if (dtype != RQ_BF16 && dtype != RQ_F32 && dtype != RQ_F16) return RQ_ERR_ARG;
     if (rows < 0 || d < 1 || d > h->f.n || ld < d) return RQ_ERR_ARG;
     if (bits != 3 && bits != 4) return RQ_ERR_ARG;
     // with no rows nothing is read or written through X / codes / scales: they may be NULL
-    if (rows > 0 && (!X || !aligned(X, dtype == RQ_BF16 ? 2 : 4))) return RQ_ERR_ARG;
+    if (rows > 0 && (!X || !aligned(X, dtype == RQ_F32 ? 4 : 2))) return RQ_ERR_ARG;
     return RQ_OK;
 }
 
@@ -209,12 +209,12 @@ int rq_rotate_quantize_asym(const rq_hadamard_t* h, const void* X, int dtype, in
 
 int rq_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
                 void* codes, float* scales, void* stream) {
-    if (dtype != RQ_BF16 && dtype != RQ_F32) return RQ_ERR_ARG;
+    if (dtype != RQ_BF16 && dtype != RQ_F32 && dtype != RQ_F16) return RQ_ERR_ARG;
     if (rows < 0 || d < 32 || d % 32 != 0 || ld < d) return RQ_ERR_ARG;
     if (bits != 3 && bits != 4) return RQ_ERR_ARG;
     if (!clip_ok(clip)) return RQ_ERR_ARG;
     if (rows == 0) return RQ_OK;
-    if (!X || !aligned(X, dtype == RQ_BF16 ? 2 : 4)) return RQ_ERR_ARG;
+    if (!X || !aligned(X, dtype == RQ_F32 ? 4 : 2)) return RQ_ERR_ARG;
     if (!codes || !scales || !aligned(codes, 4) || !aligned(scales, 4)) return RQ_ERR_ARG;
     if (rq::plain_wave_supports(X, dtype, d, ld))
         return rq::plain_wave_quantize(X, rows, d, ld, bits, clip, static_cast<uint32_t*>(codes), scales,

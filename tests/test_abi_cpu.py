@@ -86,6 +86,7 @@ def test_rotate_quantize_argument_errors(L):
     assert _call_rq(L, h._h, codes=0) == E
     assert _call_rq(L, h._h, scales=0) == E
     assert _call_rq(L, h._h, dtype=7) == E
+    assert _call_rq(L, h._h, dtype=2, X=0x1001) == E        # fp16 needs 2-byte alignment
     assert _call_rq(L, h._h, rows=-1) == E
     assert _call_rq(L, h._h, d=0) == E
     assert _call_rq(L, h._h, d=129, ld=129) == E
@@ -130,7 +131,7 @@ def test_asym_and_plain_argument_errors(L):
 
     assert plain(X=0) == E and plain(codes=0) == E and plain(scales=0) == E
     assert plain(d=100, ld=100) == E and plain(d=0) == E and plain(ld=64) == E
-    assert plain(dtype=2) == E and plain(bits=5) == E and plain(clip=float("nan")) == E
+    assert plain(dtype=3) == E and plain(bits=5) == E and plain(clip=float("nan")) == E
     assert plain(X=0x1001) == E and plain(rows=-1) == E
     assert plain(rows=0, X=0, codes=0, scales=0) == binding.RQ_OK
 

@@ -159,6 +159,42 @@ def test_gbs_search_asym_follows_algorithm_1(torch):
     assert clip == np.float32(m) and abs(mse - fm) <= 1e-5 * fm
 
 
+@pytest.mark.parametrize("n,d", [(128, 128), (256, 200), (4096, 4096), (3584, 3584), (3072, 3000), (1544, 1544),
+                                 (148 * 128, 148 * 128), (96, 96)])
+def test_half_precision_input(torch, n, d):
+    # IEEE fp16 rows (the paper's models run in FP16): every entry point that reads X
+    rng = np.random.default_rng(n + d)
+    x = (rng.standard_t(3.0, size=(37, d)) * 0.7).astype(np.float32)
+    x[:, 2] *= 20.0
+    x = x.astype(np.float16)
+    h = handle(n)
+    xt = parity.to_device(x)
+    assert xt.dtype == torch.float16
+    for b in (3, 4):
+        say(f"fp16 n={n} d={d} b={b}")
+        codes, scales = binding.rotate_quantize(h, xt, b, 0.9)
+        torch.cuda.synchronize()
+        st = parity.check_rotate_quantize(x, n, b, 0.9, codes.cpu().numpy(), scales.cpu().numpy(),
+                                          f"fp16 n={n} b={b} [{h.last_kernel}]")
+        say(f"  ok kernel={h.last_kernel} {st}")
+    clips = [0.6, 0.85, 1.0]
+    mse = binding.quant_error(h, xt, 3, clips)
+    torch.cuda.synchronize()
+    parity.check_quant_error(x, n, 3, clips, mse.cpu().numpy(), what=f"fp16 n={n}")
+    y = binding.rotate(h, xt)
+    torch.cuda.synchronize()
+    parity.check_float_rows(y.cpu().numpy(), __import__("rotq_oracle").rotate(x, n), what=f"fp16 rotate n={n}")
+    if n % 128 == 0:
+        codes, scales, mins = binding.rotate_quantize_asym(h, xt, 3, 1.0)
+        torch.cuda.synchronize()
+        parity.check_rotate_quantize_asym(x, n, 3, 1.0, codes.cpu().numpy(), scales.cpu().numpy(),
+                                          mins.cpu().numpy(), f"fp16 asym n={n}")
+    if d % 32 == 0:
+        codes, scales = binding.quantize(xt, 4, 0.9)
+        torch.cuda.synchronize()
+        parity.check_quantize_plain(x, 4, 0.9, codes.cpu().numpy(), scales.cpu().numpy(), f"fp16 plain d={d}")
+
+
 def test_graph_replay_and_side_stream(torch):
     """The hot-path calls allocate nothing and run on the caller's stream: captured in a HIP graph on a
     side stream and replayed several times with eager work in between, every replay must reproduce the
