@@ -25,7 +25,7 @@ namespace rq {
 namespace {
 
 // Long rows: n = 512 T (T = 2 .. 16), one wave per row.  FULL: d == n (no zero padding).
-template <int T, int BITS, bool FULL>
+template <int T, int BITS, bool FULL, bool F16 = false>
 __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
     constexpr int ROW_DWORDS = 512 * T * BITS / 32;
     __shared__ __attribute__((aligned(16))) uint8_t stage[BITS == 3 ? ROW_DWORDS * 4 : 16];
@@ -48,10 +48,9 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
         for (int t = 0; t < T; ++t) {
             const int e0 = (t * 64 + chunk) * 8;
             const u32x4 raw = FULL ? load16(xr + e0) : load_chunk(xv, e0);
-            const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
-            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), bm, z, 0, 0, 0);
+            acc[t][0] = mfma_pm1<F16>(A0, raw, z);
+            acc[t][1] = mfma_pm1<F16>(A1, raw, z);
         }
         // register stages over the t bits
 #pragma unroll
@@ -217,7 +216,7 @@ __global__ __launch_bounds__(64 * S) void k_wave_sylvester_split(WaveArgs a) {
 // Lane (g, r, c): DPP row g holds contraction slots, r selects the row of the pass, c the
 // column chunk; the matrix cores transform the (g, i) bits, CB DPP stages the c bits.
 // GUARD: the super-group may be ragged (rows missing at the end) or d < n.
-template <int CB, int BITS, int U, bool GUARD, bool ASYM>
+template <int CB, int BITS, int U, bool GUARD, bool ASYM, bool F16>
 __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_t* base, uint32_t* obase,
                                                 float* sbase, int64_t row0, int rem, const u32x4& A0, const u32x4& A1,
                                                 uint32_t sg0, const float (&sf)[4], float flip, int g, int c, int rsub,
@@ -242,10 +241,9 @@ __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_
     for (int u = 0; u < U; ++u) {
         const int rr = u * RPW + rsub;
         const bool live = !GUARD || rr < rem;
-        const bf16x8 bm = __builtin_bit_cast(bf16x8, raw[u]);
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        f32x4 v0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
-        f32x4 v1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), bm, z, 0, 0, 0);
+        f32x4 v0 = mfma_pm1<F16>(A0, raw[u], z);
+        f32x4 v1 = mfma_pm1<F16>(A1, raw[u], z);
         lane_stage<kDppXor1>(v0, sg0);
         lane_stage<kDppXor1>(v1, sg0);
         lane_stages_tail<CB>(v0, sf);
@@ -292,7 +290,7 @@ __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_
     }
 }
 
-template <int CB, int BITS, int U, bool ASYM = false>
+template <int CB, int BITS, int U, bool ASYM = false, bool F16 = false>
 __global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
     static_assert(CB >= 2 && CB <= 4, "unsupported shape");
     constexpr int RPW = 16 >> CB;
@@ -324,10 +322,10 @@ __global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
         uint32_t* obase = a.codes + row0 * ROW_DWORDS;
         float* sbase = a.scales + row0;
         if (rem == SUPER && full_d)
-            short_rows_pass<CB, BITS, U, false, ASYM>(a, base, obase, sbase, row0, rem, A0, A1, sg0, sf, flip, g, c, rsub, chunk,
+            short_rows_pass<CB, BITS, U, false, ASYM, F16>(a, base, obase, sbase, row0, rem, A0, A1, sg0, sf, flip, g, c, rsub, chunk,
                                                 c1h, c1l, c2h, c2l);
         else
-            short_rows_pass<CB, BITS, U, true, ASYM>(a, base, obase, sbase, row0, rem, A0, A1, sg0, sf, flip, g, c, rsub, chunk,
+            short_rows_pass<CB, BITS, U, true, ASYM, F16>(a, base, obase, sbase, row0, rem, A0, A1, sg0, sf, flip, g, c, rsub, chunk,
                                                c1h, c1l, c2h, c2l);
     }
 }
@@ -361,7 +359,7 @@ __device__ __forceinline__ void fused_group(float* v, const float (&sf)[4]) {
 // 128-point transform along the columns.  y[column i][j]: register j = 4 h + ip holds block rows
 // 4 j .. 4 j + 3 (one per DPP row g); only the NV = ceil(pb / 4) registers that hold real block rows
 // are carried.  Values carry the lane's flip sign (see lane_stages_fused).  Returns the row's absmax.
-template <bool FULL, int NV>
+template <bool FULL, int NV, bool F16 = false>
 __device__ __forceinline__ float block_rotate_row(const WaveArgs& a, int64_t row, int e_base, const u32x4& A0,
                                               const u32x4& A1, const float (&sf)[4], float (&y)[8][NV]) {
     constexpr int NH1 = NV > 4 ? NV - 4 : 0;              // live registers of the second half
@@ -380,12 +378,11 @@ __device__ __forceinline__ float block_rotate_row(const WaveArgs& a, int64_t row
         for (int w = 0; w < 4; ++w)
             bm[w] = __builtin_amdgcn_perm(R[2 * w + 1][ic >> 1], R[2 * w][ic >> 1], sel);
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        const bf16x8 b8 = __builtin_bit_cast(bf16x8, bm);
-        const f32x4 d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), b8, z, 0, 0, 0);
+        const f32x4 d0 = mfma_pm1<F16>(A0, bm, z);
 #pragma unroll
         for (int j = 0; j < NH0; ++j) y[ic][j] = d0[j];
         if constexpr (NH1 > 0) {
-            const f32x4 d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), b8, z, 0, 0, 0);
+            const f32x4 d1 = mfma_pm1<F16>(A1, bm, z);
 #pragma unroll
             for (int j = 0; j < NH1; ++j) y[ic][4 + j] = d1[j];
         }
@@ -412,7 +409,7 @@ __device__ __forceinline__ float block_rotate_row(const WaveArgs& a, int64_t row
     return wave_absmax<4>(m);
 }
 
-template <int BITS, bool FULL, int NV>
+template <int BITS, bool FULL, int NV, bool F16 = false>
 __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
     constexpr int ROW_DWORDS_PER_A = 128 * BITS / 32;
     __shared__ __attribute__((aligned(16))) uint8_t stage[BITS == 3 ? 32 * 48 : 16];
@@ -432,7 +429,7 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
     const int e_base = base_g * 128 + c * 8;
     for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
         float y[8][NV];
-        float m = block_rotate_row<FULL, NV>(a, row, e_base, A0, A1, sf, y);
+        float m = block_rotate_row<FULL, NV, F16>(a, row, e_base, A0, A1, sf, y);
         const float s = m > 0.0f ? flip * (float)(a.c1 / (double)m) : 0.0f;
         const float scale = (float)(a.c2 * (double)m);
 
@@ -689,6 +686,18 @@ __global__ __launch_bounds__(64) void k_wave_short_qe_asym(WaveArgs a, ClipList 
 // the quantization pass.  Un-rotated bf16 values sit on a coarse grid, so x / Delta lands on or
 // next to a rounding tie far more often than rotated values do; every code whose fp32 residual
 // is within 0.001 of a tie is therefore retaken with the exact fp64 quotient.
+// The two 16-bit values of a dword as floats (exact): bf16, or IEEE fp16 when F16.
+template <bool F16>
+__device__ __forceinline__ float half_lo(uint32_t w) {
+    if constexpr (F16) return (float)__builtin_bit_cast(_Float16, (uint16_t)w);
+    else return __uint_as_float(w << 16);
+}
+template <bool F16>
+__device__ __forceinline__ float half_hi(uint32_t w) {
+    if constexpr (F16) return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16));
+    else return __uint_as_float(w & 0xffff0000u);
+}
+
 struct PlainArgs {
     const uint16_t* X;
     int64_t rows;
@@ -697,9 +706,10 @@ struct PlainArgs {
     uint32_t* codes;
     float* scales;
     double clip;
+    bool f16;
 };
 
-template <int T, int BITS>
+template <int T, int BITS, bool F16 = false>
 __global__ __launch_bounds__(64) void k_plain_wave(PlainArgs a) {
     const int lane = threadIdx.x;
     const int nchunks = a.d >> 3;
@@ -719,8 +729,8 @@ __global__ __launch_bounds__(64) void k_plain_wave(PlainArgs a) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const uint32_t w = raw[t][k];
-                m = __builtin_fmaxf(m, __builtin_fabsf(__uint_as_float(w << 16)));
-                m = __builtin_fmaxf(m, __builtin_fabsf(__uint_as_float(w & 0xffff0000u)));
+                m = __builtin_fmaxf(m, __builtin_fabsf(half_lo<F16>(w)));
+                m = __builtin_fmaxf(m, __builtin_fabsf(half_hi<F16>(w)));
             }
         m = wave_absmax<4>(m);
         const double delta = a.clip * (double)m / kLvl;
@@ -732,8 +742,8 @@ __global__ __launch_bounds__(64) void k_plain_wave(PlainArgs a) {
             float x[8];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                x[2 * k] = __uint_as_float(raw[t][k] << 16);
-                x[2 * k + 1] = __uint_as_float(raw[t][k] & 0xffff0000u);
+                x[2 * k] = half_lo<F16>(raw[t][k]);
+                x[2 * k + 1] = half_hi<F16>(raw[t][k]);
             }
             uint32_t w = 0;
             bool near = false;
@@ -770,7 +780,10 @@ template <int T>
 int launch_plain(const PlainArgs& a, int bits, hipStream_t s) {
     const int64_t cap = 1 << 24;
     const unsigned grid = (unsigned)(a.rows < cap ? a.rows : cap);
-    if (bits == 4) hipLaunchKernelGGL((k_plain_wave<T, 4>), dim3(grid), dim3(64), 0, s, a);
+    if (a.f16) {
+        if (bits == 4) hipLaunchKernelGGL((k_plain_wave<T, 4, true>), dim3(grid), dim3(64), 0, s, a);
+        else hipLaunchKernelGGL((k_plain_wave<T, 3, true>), dim3(grid), dim3(64), 0, s, a);
+    } else if (bits == 4) hipLaunchKernelGGL((k_plain_wave<T, 4>), dim3(grid), dim3(64), 0, s, a);
     else hipLaunchKernelGGL((k_plain_wave<T, 3>), dim3(grid), dim3(64), 0, s, a);
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
@@ -809,13 +822,20 @@ int launch_long(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s
     // from 2048 rows on one wave per row is faster)
     if constexpr (T >= 4) {
         const int64_t simds = (int64_t)h->num_cu * 4;
-        if (h->split >= 0) {
+        if (h->split >= 0 && !a.f16) {
             const int want = h->split > 0 ? h->split : (a.rows * 2 <= simds ? 4 : a.rows <= simds ? 2 : 1);
             if (want == 4) return launch_split<T, 4>(a, bits, s);
             if (want == 2) return launch_split<T, 2>(a, bits, s);
         }
     }
     const bool full = a.d == 512 * T;
+    if (a.f16) {
+        if (bits == 4)
+            return full ? launch_wave(k_wave_sylvester<T, 4, true, true>, h, a, a.rows, 4, s)
+                        : launch_wave(k_wave_sylvester<T, 4, false, true>, h, a, a.rows, 4, s);
+        return full ? launch_wave(k_wave_sylvester<T, 3, true, true>, h, a, a.rows, 4, s)
+                    : launch_wave(k_wave_sylvester<T, 3, false, true>, h, a, a.rows, 4, s);
+    }
     if (bits == 4)
         return full ? launch_wave(k_wave_sylvester<T, 4, true>, h, a, a.rows, 4, s)
                     : launch_wave(k_wave_sylvester<T, 4, false>, h, a, a.rows, 4, s);
@@ -828,6 +848,9 @@ int launch_short(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t 
     constexpr int U = 4;
     constexpr int SUPER = (16 >> CB) * U;
     const int64_t items = (a.rows + SUPER - 1) / SUPER;
+    if (a.f16)
+        return bits == 4 ? launch_wave(k_wave_short<CB, 4, U, false, true>, h, a, items, 8, s)
+                         : launch_wave(k_wave_short<CB, 3, U, false, true>, h, a, items, 8, s);
     return bits == 4 ? launch_wave(k_wave_short<CB, 4, U>, h, a, items, 8, s)
                      : launch_wave(k_wave_short<CB, 3, U>, h, a, items, 8, s);
 }
@@ -836,6 +859,9 @@ int launch_short_asym(const rq_hadamard* h, const WaveArgs& a, int bits, hipStre
     constexpr int U = 4;
     constexpr int SUPER = 4 * U;
     const int64_t items = (a.rows + SUPER - 1) / SUPER;
+    if (a.f16)
+        return bits == 4 ? launch_wave(k_wave_short<2, 4, U, true, true>, h, a, items, 8, s)
+                         : launch_wave(k_wave_short<2, 3, U, true, true>, h, a, items, 8, s);
     return bits == 4 ? launch_wave(k_wave_short<2, 4, U, true>, h, a, items, 8, s)
                      : launch_wave(k_wave_short<2, 3, U, true>, h, a, items, 8, s);
 }
@@ -861,8 +887,32 @@ std::vector<uint32_t> wave_sylvester_tiles() {
     return t;
 }
 
+std::vector<uint32_t> tiles_to_f16(const std::vector<uint32_t>& t) {
+    std::vector<uint32_t> o(t.size());
+    for (size_t i = 0; i < t.size(); ++i) {
+        uint32_t w = 0;
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t v = (t[i] >> (16 * h)) & 0xffffu;     // 0, bf16 +1 or bf16 -1
+            const uint32_t f = v == 0x3F80u ? 0x3C00u : v == 0xBF80u ? 0xBC00u : 0u;
+            w |= f << (16 * h);
+        }
+        o[i] = w;
+    }
+    return o;
+}
+
 template <int NV>
 static void launch_block_nv(int bits, bool full, unsigned grid, hipStream_t s, const WaveArgs& w, int pb) {
+    if (w.f16) {
+        if (bits == 4) {
+            if (full) hipLaunchKernelGGL((k_wave_block<4, true, NV, true>), dim3(grid), dim3(64), 0, s, w, pb);
+            else hipLaunchKernelGGL((k_wave_block<4, false, NV, true>), dim3(grid), dim3(64), 0, s, w, pb);
+        } else {
+            if (full) hipLaunchKernelGGL((k_wave_block<3, true, NV, true>), dim3(grid), dim3(64), 0, s, w, pb);
+            else hipLaunchKernelGGL((k_wave_block<3, false, NV, true>), dim3(grid), dim3(64), 0, s, w, pb);
+        }
+        return;
+    }
     if (bits == 4) {
         if (full) hipLaunchKernelGGL((k_wave_block<4, true, NV>), dim3(grid), dim3(64), 0, s, w, pb);
         else hipLaunchKernelGGL((k_wave_block<4, false, NV>), dim3(grid), dim3(64), 0, s, w, pb);
@@ -894,8 +944,12 @@ std::vector<uint32_t> wave_block_tiles(const std::vector<int8_t>& bm, int pb) {
     return t;
 }
 
+static bool wave_dtype_ok(const rq_hadamard* h, const RowArgs& a) {
+    return a.dtype == RQ_BF16 || (a.dtype == RQ_F16 && h->d_tiles_f16);
+}
+
 bool wave_block_supports(const rq_hadamard* h, const RowArgs& a) {
-    if (h->device < 0 || !h->d_tiles || a.dtype != RQ_BF16 || a.p == 1) return false;
+    if (h->device < 0 || !h->d_tiles || !wave_dtype_ok(h, a) || a.p == 1) return false;
     if (a.log2m < 7 || (a.p << (a.log2m - 7)) > 32 || (a.p << (a.log2m - 7)) < 8) return false;
     if ((reinterpret_cast<uintptr_t>(a.X) & 15) != 0 || (a.ld & 7) != 0 || (a.d & 7) != 0) return false;
     return true;
@@ -907,6 +961,10 @@ int wave_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float cli
     WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
                static_cast<const u32x4*>(h->d_tiles), codes, scales,
                lvl / (double)clip, (double)clip / (std::sqrt((double)a.n) * lvl)};
+    if (a.dtype == RQ_F16) {
+        w.f16 = true;
+        w.tiles = static_cast<const u32x4*>(h->d_tiles_f16);
+    }
     const int pb = a.p << (a.log2m - 7);
     const int64_t cap = 1 << 24;
     const unsigned grid = (unsigned)(a.rows < cap ? a.rows : cap);
@@ -925,14 +983,14 @@ int wave_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float cli
 }
 
 bool wave_supports(const rq_hadamard* h, const RowArgs& a) {
-    if (h->device < 0 || !h->d_tiles || a.dtype != RQ_BF16 || a.p != 1) return false;
+    if (h->device < 0 || !h->d_tiles || !wave_dtype_ok(h, a) || a.p != 1) return false;
     if (a.log2m < 7 || a.log2m > 13) return false;
     if ((reinterpret_cast<uintptr_t>(a.X) & 15) != 0 || (a.ld & 7) != 0 || (a.d & 7) != 0) return false;
     return true;
 }
 
 bool wave_quant_error_supports(const rq_hadamard* h, const RowArgs& a) {
-    return wave_supports(h, a) || wave_block_supports(h, a);
+    return a.dtype == RQ_BF16 && (wave_supports(h, a) || wave_block_supports(h, a));
 }
 
 static int qe_ksplit(const rq_hadamard* h, int64_t rows, int n_clips) {
@@ -1037,6 +1095,10 @@ int wave_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uin
     WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
                static_cast<const u32x4*>(h->d_tiles), codes, scales,
                lvl / (double)clip, (double)clip / (std::sqrt((double)a.n) * lvl)};
+    if (a.dtype == RQ_F16) {
+        w.f16 = true;
+        w.tiles = static_cast<const u32x4*>(h->d_tiles_f16);
+    }
     switch (a.log2m) {
         case 7: return launch_short<2>(h, w, a.bits, s);
         case 8: return launch_short<3>(h, w, a.bits, s);
@@ -1050,13 +1112,13 @@ int wave_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uin
 }
 
 bool plain_wave_supports(const void* X, int dtype, int d, int64_t ld) {
-    return dtype == RQ_BF16 && d % 32 == 0 && d <= 512 * 40 && ld % 8 == 0 &&
+    return (dtype == RQ_BF16 || dtype == RQ_F16) && d % 32 == 0 && d <= 512 * 40 && ld % 8 == 0 &&
            (reinterpret_cast<uintptr_t>(X) % 16) == 0;
 }
 
-int plain_wave_quantize(const void* X, int64_t rows, int d, int64_t ld, int bits, float clip,
+int plain_wave_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
                         uint32_t* codes, float* scales, hipStream_t s) {
-    const PlainArgs a{static_cast<const uint16_t*>(X), rows, d, ld, codes, scales, (double)clip};
+    const PlainArgs a{static_cast<const uint16_t*>(X), rows, d, ld, codes, scales, (double)clip, dtype == RQ_F16};
     const int t = (d + 511) / 512;
     if (t <= 1) return launch_plain<1>(a, bits, s);
     if (t <= 2) return launch_plain<2>(a, bits, s);
@@ -1078,6 +1140,10 @@ int wave_rotate_quantize_asym(const rq_hadamard* h, const RowArgs& a, float clip
     WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
                static_cast<const u32x4*>(h->d_tiles), codes, scales,
                lvl / (double)clip, (double)clip / (rn * lvl), mins, (double)clip, (double)clip / rn};
+    if (a.dtype == RQ_F16) {
+        w.f16 = true;
+        w.tiles = static_cast<const u32x4*>(h->d_tiles_f16);
+    }
     return launch_short_asym(h, w, a.bits, s);
 }
 

@@ -98,6 +98,14 @@ int rq_hadamard_build(int n, rq_hadamard_t** out) {
             rq_hadamard_free(h);
             return RQ_ERR_HIP;
         }
+        if (sylv || (blk && (f.p << (f.log2m - 7)) <= 32)) {
+            const std::vector<uint32_t> t16 = rq::tiles_to_f16(tiles);
+            if (hipMalloc(&h->d_tiles_f16, tb) != hipSuccess ||
+                hipMemcpy(h->d_tiles_f16, t16.data(), tb, hipMemcpyHostToDevice) != hipSuccess) {
+                rq_hadamard_free(h);
+                return RQ_ERR_HIP;
+            }
+        }
     }
     h->device = dev;
     h->generic_ok = rq::generic_prepare(h);
@@ -109,6 +117,7 @@ void rq_hadamard_free(rq_hadamard_t* h) {
     if (!h) return;
     if (h->d_block) (void)hipFree(h->d_block);
     if (h->d_tiles) (void)hipFree(h->d_tiles);
+    if (h->d_tiles_f16) (void)hipFree(h->d_tiles_f16);
     delete h;
 }
 
@@ -217,7 +226,7 @@ int rq_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int b
     if (!X || !aligned(X, dtype == RQ_F32 ? 4 : 2)) return RQ_ERR_ARG;
     if (!codes || !scales || !aligned(codes, 4) || !aligned(scales, 4)) return RQ_ERR_ARG;
     if (rq::plain_wave_supports(X, dtype, d, ld))
-        return rq::plain_wave_quantize(X, rows, d, ld, bits, clip, static_cast<uint32_t*>(codes), scales,
+        return rq::plain_wave_quantize(X, dtype, rows, d, ld, bits, clip, static_cast<uint32_t*>(codes), scales,
                                        static_cast<hipStream_t>(stream));
     return rq::plain_quantize(X, dtype, rows, d, ld, bits, clip, static_cast<uint32_t*>(codes), scales,
                               static_cast<hipStream_t>(stream));
@@ -293,7 +302,7 @@ static int quant_error_impl(const rq_hadamard_t* h, const void* X, int dtype, in
     const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, bits);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (asym) {
-        if (h->variant == 0 && rows > 0 && rq::wave_asym_supports(h, a)) {
+        if (h->variant == 0 && rows > 0 && dtype == RQ_BF16 && rq::wave_asym_supports(h, a)) {
             hm->last_kernel = "wave_quant_error_asym";
             rc = rq::wave_quant_error_asym(h, a, cl, n_clips, static_cast<double*>(workspace), s);
             if (rc != RQ_OK) return rc;

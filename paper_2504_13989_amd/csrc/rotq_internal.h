@@ -14,6 +14,7 @@ struct rq_hadamard {
     int device = -1;                 // device the tables live on; -1 = host-only handle
     int8_t* d_block = nullptr;       // device copy of `block`
     void* d_tiles = nullptr;         // device MFMA operand tiles of the block stage (bf16)
+    void* d_tiles_f16 = nullptr;     // the same tiles encoded in fp16 (wave kernels only)
     int max_lds = 0;                 // bytes of LDS one workgroup may use on `device`
     int num_cu = 0;
     bool wg_ok = false;              // the workgroup block kernel is usable for this order
@@ -67,13 +68,15 @@ int plain_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, in
                    uint32_t* codes, float* scales, hipStream_t s);
 // The same on the wave path: bf16 rows up to 20480 wide, 16-byte aligned.
 bool plain_wave_supports(const void* X, int dtype, int d, int64_t ld);
-int plain_wave_quantize(const void* X, int64_t rows, int d, int64_t ld, int bits, float clip,
+int plain_wave_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
                         uint32_t* codes, float* scales, hipStream_t s);
 bool generic_supports(const rq_hadamard* h);
 bool generic_prepare(const rq_hadamard* h);
 
 // Wave-per-row kernels (bf16 rows, Sylvester orders 128 .. 8192, 16-byte aligned rows).
 std::vector<uint32_t> wave_sylvester_tiles();
+// The +-1 entries of a bf16 operand table re-encoded as IEEE fp16.
+std::vector<uint32_t> tiles_to_f16(const std::vector<uint32_t>& bf16_tiles);
 bool wave_supports(const rq_hadamard* h, const RowArgs& a);
 int wave_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                          float* scales, hipStream_t s);

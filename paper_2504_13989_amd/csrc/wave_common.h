@@ -9,6 +9,19 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// One matrix-core step D = A * B + C with 16-bit operands held as four dwords: bf16, or IEEE fp16
+// when F16 (the +-1 operand tile is then encoded in fp16 as well).  Products with +-1 are exact
+// in both formats; accumulation is fp32.
+template <bool F16>
+__device__ __forceinline__ float __attribute__((ext_vector_type(4)))
+mfma_pm1(const u32x4& a, const u32x4& b, const float __attribute__((ext_vector_type(4))) & c) {
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
 
 constexpr int kDppXor1 = 0xB1;         // quad_perm:[1,0,3,2]
 constexpr int kDppXor2 = 0x4E;         // quad_perm:[2,3,0,1]
@@ -210,6 +223,7 @@ struct WaveArgs {
     float* mins = nullptr;
     double clip = 0.0;
     double c3 = 0.0;      // clip / sqrt(n)
+    bool f16 = false;     // X holds IEEE fp16 instead of bf16 (tiles must be the fp16 table then)
 };
 
 

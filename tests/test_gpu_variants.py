@@ -177,6 +177,10 @@ def test_half_precision_input(torch, n, d):
         st = parity.check_rotate_quantize(x, n, b, 0.9, codes.cpu().numpy(), scales.cpu().numpy(),
                                           f"fp16 n={n} b={b} [{h.last_kernel}]")
         say(f"  ok kernel={h.last_kernel} {st}")
+        # the wave kernels take fp16 directly (fp16 matrix-core instruction, fp16 operand tiles)
+        want = {128: "wave_sylvester", 4096: "wave_sylvester", 3584: "wave_block", 3072: "wave_block"}.get(n)
+        if want and d % 8 == 0:
+            assert h.last_kernel == want
     clips = [0.6, 0.85, 1.0]
     mse = binding.quant_error(h, xt, 3, clips)
     torch.cuda.synchronize()
