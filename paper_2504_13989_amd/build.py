@@ -4,6 +4,8 @@ from __future__ import annotations
 import os
 import shutil
 import subprocess
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -28,10 +30,7 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found; the rotq library cannot be built")
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    tmp = LIB_PATH + ".tmp"
-    cmd = [hipcc_path(), *FLAGS, *extra_flags, "-x", "hip", *srcs, "-o", tmp]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -40,6 +39,20 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
     if verbose and res.stderr.strip():
         print(res.stderr)
+
+
+def build_library(verbose: bool = False, extra_flags=()) -> str:
+    """Compile every source to an object (a few at a time), then link the shared library."""
+    hipcc = hipcc_path()
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+    with tempfile.TemporaryDirectory(prefix="rotq_build_") as tmpdir:
+        objs = [os.path.join(tmpdir, os.path.splitext(s)[0] + ".o") for s in SOURCES]
+        jobs = [[hipcc, *compile_flags, *extra_flags, "-c", "-x", "hip", os.path.join(CSRC, s), "-o", o]
+                for s, o in zip(SOURCES, objs)]
+        with ThreadPoolExecutor(max_workers=min(len(jobs), 6)) as pool:
+            list(pool.map(lambda c: _run(c, verbose), jobs))
+        tmp = LIB_PATH + ".tmp"
+        _run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", tmp], verbose)
     os.replace(tmp, LIB_PATH)
     return LIB_PATH
 

@@ -20,6 +20,13 @@
 // Column tile nt holds columns {8 c + nt}, so a lane ends up with 8 consecutive columns of 4
 // block rows.  One wave per 16 block rows keeps a wave near 100 VGPRs, so two workgroups share a
 // CU.  A workgroup loops over rows; barriers order the LDS reuse.
+//
+// Short Sylvester factors (CB < 4): n = p * 2^k with k = CB + 3 = 5 or 6 has block rows of only 32
+// or 64 columns, so RPW = 128 / 2^k consecutive rows of X are laid side by side and taken in one
+// pass: column group c = (row of the pass, 8-column chunk of that row).  The block product treats
+// the 128 columns alike; the column transform then runs over CB lane bits only, and absmax, scale
+// and the output rows are per row of the pass.  Here the block is H_p itself, of any order
+// 4 <= p <= 256.
 #include "wave_common.h"
 
 namespace rq {
@@ -49,15 +56,18 @@ struct QeArgs {
     double* partial;      // [rows][n_clips]
 };
 
-template <int KK, int BITS, bool FULL, bool QE>
+template <int KK, int BITS, bool FULL, bool QE, int CB = 4, bool F16 = false>
 __global__ __launch_bounds__(128 * KK) __attribute__((amdgpu_waves_per_eu(KK <= 5 ? 6 : 4)))
 void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
+    static_assert(CB >= 2 && CB <= 4 && (CB == 4 || (!FULL && !QE)), "unsupported shape");
+    constexpr int RPW = 16 >> CB;                        // rows of X per pass
+    constexpr int SEG = 8 << CB;                         // columns of one block row (2^k)
     __shared__ float esum[QE ? 16 : 1][QE ? RQ_MAX_CLIPS : 1];
     constexpr int NCH = wg_chunks<KK>();
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     uint8_t* const ops = lds_raw;                        // [128 columns][NCH] x 16 bytes
     uint8_t* const stage = lds_raw + 128 * NCH * 16;     // packed codes of the row (b = 3)
-    __shared__ float wmax[16];
+    __shared__ float wmax[16 * RPW];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nw = blockDim.x >> 6;                      // ceil(pb / 16)
@@ -67,6 +77,8 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
     // DPP row then touch 16 neighbouring columns, whose 16-byte units - start halves alternating
     // with c & 1, unit index xor-ed with c >> 1 - are 16 different ones of a 256-byte bank window.
     const int swz = (c >> 1) & 7;
+    const int rsub = CB == 4 ? 0 : c >> CB;              // row of the pass
+    const int cl = CB == 4 ? c : c & ((1 << CB) - 1);    // 8-column chunk inside that row
 
     u32x4 A[KK];
 #pragma unroll
@@ -74,7 +86,9 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
     float sf[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
-    const float flip = (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;
+    // CB < 4: the first lane stage is the plain one, the fused ones start at the second bit
+    const float flip = (__builtin_popcount(CB == 4 ? c : cl >> 1) & 1) ? -1.0f : 1.0f;
+    const uint32_t sg0 = (c & 1) ? 0x80000000u : 0u;
 
     // phase-1 geometry: lane (g, c) loads block rows 16 wave + 4 g + t, t = 0..3 (rows at or beyond pb
     // meet zero columns of B: any in-bounds data will do, the last real row is reused)
@@ -82,7 +96,7 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int r = 16 * wave + 4 * g + t;
-        eoff[t] = (r < pb ? r : pb - 1) * 128 + c * 8;
+        eoff[t] = (r < pb ? r : pb - 1) * SEG + cl * 8;
     }
     // 8-byte half of the 16-byte unit that holds block rows 8 q .. 8 q + 7, q = 2 wave + g / 2
     const int wr_unit = ((2 * wave + (g >> 1)) ^ swz) * 16 + (g & 1) * 8;
@@ -102,12 +116,24 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
     u32x4 R[4];
     auto load_row = [&](int64_t row) {
         const uint16_t* xr = a.X + row * a.ld;
-        const RowView xv = row_view(xr, a.d);
+        if constexpr (CB == 4) {
+            const RowView xv = row_view(xr, a.d);
 #pragma unroll
-        for (int t = 0; t < 4; ++t) R[t] = FULL ? load16(xr + eoff[t]) : load_chunk(xv, eoff[t]);
+            for (int t = 0; t < 4; ++t) R[t] = FULL ? load16(xr + eoff[t]) : load_chunk(xv, eoff[t]);
+        } else {
+            // the lanes of a wave read different rows: per-lane addresses, whole chunks (d % 8 == 0)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                R[t] = eoff[t] < a.d ? load16(xr + eoff[t]) : u32x4{0u, 0u, 0u, 0u};
+        }
     };
-    for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
-        load_row(row);
+    const int64_t n_pass = (a.rows + RPW - 1) / RPW;
+    for (int64_t pass = blockIdx.x; pass < n_pass; pass += gridDim.x) {
+        // CB == 4: one row per pass, uniform over the workgroup; otherwise the lane's own row, the
+        // last row standing in (loads only) for rows beyond the end
+        const int64_t row = pass * RPW + rsub;
+        const bool live = CB == 4 || row < a.rows;
+        load_row(live ? row : a.rows - 1);
         // ---- phase 1
 #pragma unroll
         for (int ic = 0; ic < 8; ++ic) {
@@ -129,8 +155,7 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
                 // two per-lane bases (kk even / odd) plus a compile-time offset
                 const u32x4 raw = *reinterpret_cast<const u32x4*>(((kk & 1) ? rd1 : rd0) +
                                                                   nt * 16 * (NCH * 16) + (kk >> 1) * 128);
-                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[kk]),
-                                                                   __builtin_bit_cast(bf16x8, raw), acc[nt], 0, 0, 0);
+                acc[nt] = mfma_pm1<F16>(A[kk], raw, acc[nt]);
             }
         }
         // ---- phase 3
@@ -147,15 +172,20 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) {
             f32x4 v = acc[nt];
-            lane_stages_fused(v, sf[0], sf[1], sf[2], sf[3]);
+            if constexpr (CB == 4) {
+                lane_stages_fused(v, sf[0], sf[1], sf[2], sf[3]);
+            } else {
+                lane_stage<kDppXor1>(v, sg0);
+                lane_stages_tail<CB>(v, sf);
+            }
             acc[nt] = v;
             m = absmax4(m, v);
         }
-        m = wave_absmax<4>(m);
-        if (lane == 0) wmax[wave] = m;
+        m = wave_absmax<CB>(m);                          // over the lanes that share the row
+        if (g == 0 && cl == 0) wmax[wave * RPW + rsub] = m;
         __syncthreads();    // also: every wave is done reading this row's operands from LDS
-        m = wmax[0];
-        for (int w = 1; w < nw; ++w) m = fmaxf(m, wmax[w]);
+        m = wmax[rsub];
+        for (int w = 1; w < nw; ++w) m = fmaxf(m, wmax[w * RPW + rsub]);
         // ---- phase 4
         if constexpr (QE) {
             float v[32];
@@ -176,20 +206,43 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
             continue;
         }
         const float s = m > 0.0f ? flip * (float)(a.c1 / (double)m) : 0.0f;
-        uint32_t* out = a.codes + row * (int64_t)(128 * BITS / 32) * pb;
+        uint32_t* out = a.codes + row * (int64_t)(SEG * BITS / 32) * pb;   // used by live lanes only
 #pragma unroll
         for (int ip = 0; ip < 4; ++ip) {
             const int ao = 16 * wave + 4 * ip + g;      // output block row of this register
             const uint32_t w = Quant<BITS>::pack8(acc[0][ip], acc[1][ip], acc[2][ip], acc[3][ip],
                                                   acc[4][ip], acc[5][ip], acc[6][ip], acc[7][ip], s);
-            const int word = ao * 16 + c;
-            if (BITS == 4) {
-                if (ao < pb) store_codes(out + word, w);
-            } else {
-                stage24(stage, word, w);                // block rows >= pb land beyond the copied part
+            if constexpr (CB == 4) {
+                const int word = ao * 16 + c;
+                if (BITS == 4) {
+                    if (ao < pb) store_codes(out + word, w);
+                } else {
+                    stage24(stage, word, w);            // block rows >= pb land beyond the copied part
+                }
+            } else if (ao < pb) {
+                // the pass's rows are staged one after the other, each pb * 2^CB groups of 8 codes
+                if (BITS == 4) {
+                    if (live) store_codes(out + (ao << CB) + cl, w);
+                } else {
+                    stage24(stage, ((rsub * pb + ao) << CB) + cl, w);
+                }
             }
         }
-        if (BITS == 3) {
+        if (BITS == 3 && CB < 4) {
+            // as below; a wave's 16 block rows are 3 * 2^CB 16-byte units in each row of the pass
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            constexpr int UPR = 3 << CB;
+            const int rs = lane / UPR;
+            const int unit = UPR * wave + lane % UPR;   // the row has pb * UPR / 16 units
+            const int64_t orow = pass * RPW + rs;
+            if (lane < 48 && unit * 16 < pb * UPR && orow < a.rows)
+                __builtin_nontemporal_store(
+                    *reinterpret_cast<const u32x4*>(stage + (size_t)rs * pb * UPR + unit * 16),
+                    reinterpret_cast<u32x4*>(a.codes + orow * (int64_t)(SEG * 3 / 32) * pb) + unit);
+        }
+        if (BITS == 3 && CB == 4) {
             // a wave's 16 block rows are 768 contiguous bytes of the packed row, written and read
             // back by the same wave: no workgroup barrier, only the wave's own LDS ordering
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -200,12 +253,58 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
                 __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(stage + unit * 16),
                                             reinterpret_cast<u32x4*>(out) + unit);
         }
-        if (threadIdx.x == 0) a.scales[row] = (float)(a.c2 * (double)m);
+        if (wave == 0 && g == 0 && cl == 0 && live) a.scales[row] = (float)(a.c2 * (double)m);
     }
 }
 
+using WgKernel = void (*)(WaveArgs, int, QeArgs);
+
+template <int KK, int BITS, int CB, bool F16>
+WgKernel pick_rq(bool full) {
+    if constexpr (CB == 4) {
+        return full ? static_cast<WgKernel>(k_wg_block<KK, BITS, true, false, 4, F16>)
+                    : static_cast<WgKernel>(k_wg_block<KK, BITS, false, false, 4, F16>);
+    } else {
+        return static_cast<WgKernel>(k_wg_block<KK, BITS, false, false, CB, F16>);
+    }
+}
+
+// The kernel instance for a launch, or nullptr when the combination is not built: cb = 4 needs
+// KK >= 2 (smaller blocks have the one-wave kernel), quant_error is bf16 with cb = 4 only.
 template <int KK>
-int launch_kk(const rq_hadamard* h, const WaveArgs& a, int bits, int pb, hipStream_t s, const QeArgs* qe = nullptr) {
+WgKernel pick_kernel(int bits, bool full, bool qe, int cb, bool f16) {
+    if (bits != 3 && bits != 4) return nullptr;
+    if (qe) {
+        if constexpr (KK >= 2) {
+            if (cb != 4 || f16) return nullptr;
+            if (bits == 4) return full ? static_cast<WgKernel>(k_wg_block<KK, 4, true, true>)
+                                       : static_cast<WgKernel>(k_wg_block<KK, 4, false, true>);
+            return full ? static_cast<WgKernel>(k_wg_block<KK, 3, true, true>)
+                        : static_cast<WgKernel>(k_wg_block<KK, 3, false, true>);
+        }
+        return nullptr;
+    }
+    if (cb == 4) {
+        if constexpr (KK >= 2) {
+            if (bits == 4) return f16 ? pick_rq<KK, 4, 4, true>(full) : pick_rq<KK, 4, 4, false>(full);
+            return f16 ? pick_rq<KK, 3, 4, true>(full) : pick_rq<KK, 3, 4, false>(full);
+        }
+        return nullptr;
+    }
+    if (cb == 3) {
+        if (bits == 4) return f16 ? pick_rq<KK, 4, 3, true>(false) : pick_rq<KK, 4, 3, false>(false);
+        return f16 ? pick_rq<KK, 3, 3, true>(false) : pick_rq<KK, 3, 3, false>(false);
+    }
+    if (cb == 2) {
+        if (bits == 4) return f16 ? pick_rq<KK, 4, 2, true>(false) : pick_rq<KK, 4, 2, false>(false);
+        return f16 ? pick_rq<KK, 3, 2, true>(false) : pick_rq<KK, 3, 2, false>(false);
+    }
+    return nullptr;
+}
+
+template <int KK>
+int launch_kk(const rq_hadamard* h, const WaveArgs& a, int bits, int pb, int cb, hipStream_t s,
+              const QeArgs* qe = nullptr) {
     const size_t lds = wg_lds_bytes<KK>();
     const int nw = (pb + 15) / 16;
     int per_cu = (int)((size_t)h->max_lds / (lds + 128));
@@ -213,46 +312,39 @@ int launch_kk(const rq_hadamard* h, const WaveArgs& a, int bits, int pb, hipStre
     if (per_cu > by_waves) per_cu = by_waves;
     if (per_cu < 1) per_cu = 1;
     const int64_t cap = (int64_t)h->num_cu * per_cu;
-    const unsigned grid = (unsigned)(a.rows < cap ? a.rows : cap);
-    const bool full = a.d == 128 * pb;
-    const dim3 g(grid), b(64 * nw);
+    const int rpw = 16 >> cb;
+    const int64_t passes = (a.rows + rpw - 1) / rpw;
+    const unsigned grid = (unsigned)(passes < cap ? passes : cap);
+    const bool full = cb == 4 && a.d == 128 * pb;
+    WgKernel fn = pick_kernel<KK>(bits, full, qe != nullptr, cb, a.f16);
+    if (!fn) return RQ_ERR_NO_ORDER;
+    QeArgs q;
     if (qe) {
-        if (bits == 4) {
-            if (full) hipLaunchKernelGGL((k_wg_block<KK, 4, true, true>), g, b, lds, s, a, pb, *qe);
-            else hipLaunchKernelGGL((k_wg_block<KK, 4, false, true>), g, b, lds, s, a, pb, *qe);
-        } else {
-            if (full) hipLaunchKernelGGL((k_wg_block<KK, 3, true, true>), g, b, lds, s, a, pb, *qe);
-            else hipLaunchKernelGGL((k_wg_block<KK, 3, false, true>), g, b, lds, s, a, pb, *qe);
-        }
-        return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
-    }
-    QeArgs none;
-    none.n_clips = 0;
-    none.partial = nullptr;
-    if (bits == 4) {
-        if (full) hipLaunchKernelGGL((k_wg_block<KK, 4, true, false>), g, b, lds, s, a, pb, none);
-        else hipLaunchKernelGGL((k_wg_block<KK, 4, false, false>), g, b, lds, s, a, pb, none);
+        q = *qe;
     } else {
-        if (full) hipLaunchKernelGGL((k_wg_block<KK, 3, true, false>), g, b, lds, s, a, pb, none);
-        else hipLaunchKernelGGL((k_wg_block<KK, 3, false, false>), g, b, lds, s, a, pb, none);
+        q.n_clips = 0;
+        q.partial = nullptr;
     }
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(64 * nw), lds, s, a, pb, q);
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
-}
-
-template <typename K>
-bool raise_lds(K kernel, int lds) {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, lds) == hipSuccess;
 }
 
 template <int KK>
 bool prepare_kk() {
     const int lds = (int)wg_lds_bytes<KK>();
     if (lds <= 48 * 1024) return true;
-    return raise_lds(k_wg_block<KK, 4, true, false>, lds) && raise_lds(k_wg_block<KK, 4, false, false>, lds) &&
-           raise_lds(k_wg_block<KK, 3, true, false>, lds) && raise_lds(k_wg_block<KK, 3, false, false>, lds) &&
-           raise_lds(k_wg_block<KK, 4, true, true>, lds) && raise_lds(k_wg_block<KK, 4, false, true>, lds) &&
-           raise_lds(k_wg_block<KK, 3, true, true>, lds) && raise_lds(k_wg_block<KK, 3, false, true>, lds);
+    for (int bits = 3; bits <= 4; ++bits)
+        for (int full = 0; full < 2; ++full)
+            for (int qe = 0; qe < 2; ++qe)
+                for (int cb = 2; cb <= 4; ++cb)
+                    for (int f16 = 0; f16 < 2; ++f16) {
+                        WgKernel fn = pick_kernel<KK>(bits, full != 0, qe != 0, cb, f16 != 0);
+                        if (fn && hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                                      hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                      lds) != hipSuccess)
+                            return false;
+                    }
+    return true;
 }
 
 }  // namespace
@@ -280,6 +372,7 @@ std::vector<uint32_t> wg_block_tiles(const std::vector<int8_t>& bm, int pb) {
 
 bool wg_block_prepare(int pb) {
     switch ((pb + 31) / 32) {
+        case 1: return prepare_kk<1>();
         case 2: return prepare_kk<2>();
         case 3: return prepare_kk<3>();
         case 4: return prepare_kk<4>();
@@ -291,52 +384,71 @@ bool wg_block_prepare(int pb) {
     }
 }
 
-bool wg_block_supports(const rq_hadamard* h, const RowArgs& a) {
-    if (h->device < 0 || !h->d_tiles || !h->wg_ok || a.dtype != RQ_BF16 || a.p == 1) return false;
-    const int pb = a.log2m >= 7 ? (a.p << (a.log2m - 7)) : 0;
-    if (pb <= 32 || pb > 256) return false;
+// Shape of a launch: block order and lane bits of the column transform (4: block rows of 128
+// columns; 3, 2: block rows of 64 / 32 columns, several rows of X per pass).  False when the order
+// is not served by this kernel.
+static bool wg_shape(const RowArgs& a, int* pb, int* cb) {
+    if (a.p == 1) return false;
+    if (a.log2m >= 7) {
+        *pb = a.p << (a.log2m - 7);
+        *cb = 4;
+        return *pb > 32 && *pb <= 256;
+    }
+    *pb = a.p;
+    *cb = a.log2m - 3;
+    return a.log2m >= 5 && a.p >= 4 && a.p <= 256;
+}
+
+bool wg_block_supports(const rq_hadamard* h, const RowArgs& a, bool quant_error) {
+    int pb, cb;
+    if (h->device < 0 || !h->d_tiles || !h->wg_ok || !wg_shape(a, &pb, &cb)) return false;
+    if (quant_error ? (a.dtype != RQ_BF16 || cb != 4)
+                    : (a.dtype != RQ_BF16 && !(a.dtype == RQ_F16 && h->d_tiles_f16)))
+        return false;
     if ((reinterpret_cast<uintptr_t>(a.X) & 15) != 0 || (a.ld & 7) != 0 || (a.d & 7) != 0) return false;
     return true;
 }
 
+template <typename... Extra>
+static int launch_by_kk(const rq_hadamard* h, const WaveArgs& w, int bits, int pb, int cb, hipStream_t s,
+                        Extra... extra) {
+    switch ((pb + 31) / 32) {
+        case 1: return launch_kk<1>(h, w, bits, pb, cb, s, extra...);
+        case 2: return launch_kk<2>(h, w, bits, pb, cb, s, extra...);
+        case 3: return launch_kk<3>(h, w, bits, pb, cb, s, extra...);
+        case 4: return launch_kk<4>(h, w, bits, pb, cb, s, extra...);
+        case 5: return launch_kk<5>(h, w, bits, pb, cb, s, extra...);
+        case 6: return launch_kk<6>(h, w, bits, pb, cb, s, extra...);
+        case 7: return launch_kk<7>(h, w, bits, pb, cb, s, extra...);
+        case 8: return launch_kk<8>(h, w, bits, pb, cb, s, extra...);
+        default: return RQ_ERR_NO_ORDER;
+    }
+}
+
 int wg_block_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
                          double* partial, hipStream_t s) {
+    int pb, cb;
+    if (!wg_shape(a, &pb, &cb)) return RQ_ERR_NO_ORDER;
     WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
                static_cast<const u32x4*>(h->d_tiles), nullptr, nullptr, 0.0, 0.0};
     QeArgs qe;
     qe.clips = clips;
     qe.n_clips = n_clips;
     qe.partial = partial;
-    const int pb = a.p << (a.log2m - 7);
-    switch ((pb + 31) / 32) {
-        case 2: return launch_kk<2>(h, w, a.bits, pb, s, &qe);
-        case 3: return launch_kk<3>(h, w, a.bits, pb, s, &qe);
-        case 4: return launch_kk<4>(h, w, a.bits, pb, s, &qe);
-        case 5: return launch_kk<5>(h, w, a.bits, pb, s, &qe);
-        case 6: return launch_kk<6>(h, w, a.bits, pb, s, &qe);
-        case 7: return launch_kk<7>(h, w, a.bits, pb, s, &qe);
-        case 8: return launch_kk<8>(h, w, a.bits, pb, s, &qe);
-        default: return RQ_ERR_NO_ORDER;
-    }
+    return launch_by_kk(h, w, a.bits, pb, cb, s, &qe);
 }
 
 int wg_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                              float* scales, hipStream_t s) {
+    int pb, cb;
+    if (!wg_shape(a, &pb, &cb)) return RQ_ERR_NO_ORDER;
+    const bool f16 = a.dtype == RQ_F16;
     const double lvl = (double)((1 << a.bits) - 1);
     WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
-               static_cast<const u32x4*>(h->d_tiles), codes, scales,
+               static_cast<const u32x4*>(f16 ? h->d_tiles_f16 : h->d_tiles), codes, scales,
                lvl / (double)clip, (double)clip / (std::sqrt((double)a.n) * lvl)};
-    const int pb = a.p << (a.log2m - 7);
-    switch ((pb + 31) / 32) {
-        case 2: return launch_kk<2>(h, w, a.bits, pb, s);
-        case 3: return launch_kk<3>(h, w, a.bits, pb, s);
-        case 4: return launch_kk<4>(h, w, a.bits, pb, s);
-        case 5: return launch_kk<5>(h, w, a.bits, pb, s);
-        case 6: return launch_kk<6>(h, w, a.bits, pb, s);
-        case 7: return launch_kk<7>(h, w, a.bits, pb, s);
-        case 8: return launch_kk<8>(h, w, a.bits, pb, s);
-        default: return RQ_ERR_NO_ORDER;
-    }
+    w.f16 = f16;
+    return launch_by_kk(h, w, a.bits, pb, cb, s);
 }
 
 }  // namespace rq

@@ -68,9 +68,11 @@ int rq_hadamard_build(int n, rq_hadamard_t** out) {
     }
     const bool sylv = f.p == 1 && f.log2m >= 7 && f.log2m <= 13;
     const bool blk = f.p > 1 && f.log2m >= 7 && (f.p << (f.log2m - 7)) <= 256;
-    const bool dense = !sylv && !blk && n <= 4096;
-    if (sylv || blk || dense) {
+    const bool blk_short = f.p > 1 && (f.log2m == 5 || f.log2m == 6) && f.p <= 256;   // block rows of 32 / 64
+    const bool dense = !sylv && !blk && !blk_short && n <= 4096;
+    if (sylv || blk || blk_short || dense) {
         std::vector<uint32_t> tiles;
+        bool f16_table = sylv;
         if (sylv) {
             tiles = rq::wave_sylvester_tiles();
         } else if (dense) {
@@ -81,6 +83,10 @@ int rq_hadamard_build(int n, rq_hadamard_t** out) {
             }
             tiles = rq::dense_block_tiles(hm, n);
             h->dense_ok = true;
+        } else if (blk_short) {
+            tiles = rq::wg_block_tiles(h->block, f.p);
+            h->wg_ok = rq::wg_block_prepare(f.p);
+            f16_table = true;
         } else {
             // block of the strided axis: H_p (x) H_{2^(k-7)}, index a * 2^(k-7) + (high bits of c)
             const int e = 1 << (f.log2m - 7), pb = f.p * e;
@@ -91,6 +97,7 @@ int rq_hadamard_build(int n, rq_hadamard_t** out) {
                                                       rq::sylvester_entry(i % e, j % e));
             tiles = pb <= 32 ? rq::wave_block_tiles(bm, pb) : rq::wg_block_tiles(bm, pb);
             if (pb > 32) h->wg_ok = rq::wg_block_prepare(pb);
+            f16_table = true;
         }
         const size_t tb = tiles.size() * sizeof(uint32_t);
         if (hipMalloc(&h->d_tiles, tb) != hipSuccess ||
@@ -98,7 +105,7 @@ int rq_hadamard_build(int n, rq_hadamard_t** out) {
             rq_hadamard_free(h);
             return RQ_ERR_HIP;
         }
-        if (sylv || (blk && (f.p << (f.log2m - 7)) <= 32)) {
+        if (f16_table) {
             const std::vector<uint32_t> t16 = rq::tiles_to_f16(tiles);
             if (hipMalloc(&h->d_tiles_f16, tb) != hipSuccess ||
                 hipMemcpy(h->d_tiles_f16, t16.data(), tb, hipMemcpyHostToDevice) != hipSuccess) {
@@ -318,7 +325,7 @@ static int quant_error_impl(const rq_hadamard_t* h, const void* X, int dtype, in
         if (rc != RQ_OK) return rc;
         return rq::reduce_partials(static_cast<double*>(workspace), rows, n_clips, mse, s);
     }
-    if (h->variant == 0 && rows > 0 && rq::wg_block_supports(h, a)) {
+    if (h->variant == 0 && rows > 0 && rq::wg_block_supports(h, a, true)) {
         hm->last_kernel = "wg_block_quant_error";
         rc = rq::wg_block_quant_error(h, a, cl, n_clips, static_cast<double*>(workspace), s);
         if (rc != RQ_OK) return rc;

@@ -108,10 +108,11 @@ bool dense_block_supports(const rq_hadamard* h, const RowArgs& a);
 int dense_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                                 float* scales, hipStream_t s);
 
-// Workgroup block kernel: bf16 rows, n = pb * 128 with 32 < pb <= 256 (e.g. 18944 = 148 * 128).
+// Workgroup block kernel: bf16 or fp16 rows, n = pb * 128 with 32 < pb <= 256 (e.g. 18944 = 148 * 128),
+// or n = p * 64 / p * 32 with 4 <= p <= 256 (several rows per pass); quant_error: the former, bf16.
 std::vector<uint32_t> wg_block_tiles(const std::vector<int8_t>& bm, int pb);
 bool wg_block_prepare(int pb);
-bool wg_block_supports(const rq_hadamard* h, const RowArgs& a);
+bool wg_block_supports(const rq_hadamard* h, const RowArgs& a, bool quant_error = false);
 int wg_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                              float* scales, hipStream_t s);
 int wg_block_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,

@@ -95,6 +95,32 @@ def test_other_orders_and_padding(torch, n, d, dtype, b):
     parity.check_rotate_quantize(x, n, b, 0.85, codes, scales, f"n={n} d={d} {dtype} b={b} [{kern}]")
 
 
+@pytest.mark.parametrize("n,d,rows", [(28 * 32, 28 * 32, 67), (28 * 32, 800, 5), (12 * 32, 12 * 32, 1), (12 * 64, 12 * 64, 3),
+                                      (20 * 64, 1200, 130), (76 * 64, 76 * 64, 67), (76 * 64, 4800, 2),
+                                      (140 * 64, 140 * 64, 33), (44 * 32, 44 * 32, 10), (252 * 64, 16000, 9),
+                                      (196 * 32, 6200, 6), (28 * 32, 28 * 32, 2101)])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_short_sylvester_factor_blocks(torch, n, d, rows, dtype):
+    # n = p 2^k with k = 5, 6: the block kernel lays 4 / 2 rows side by side; row counts that do not
+    # fill the last pass, padded widths, a leading dimension beyond d
+    rng = np.random.default_rng(n + 3 * d + rows)
+    ld = d + 24
+    full = rng.standard_t(3.0, size=(rows, ld)).astype(np.float32)
+    full[:, rng.choice(d, 3, replace=False)] *= 40
+    full = wl.f32_to_bf16_bits(full) if dtype == "bf16" else full.astype(np.float16)
+    x = full[:, :d]
+    h = handle(n)
+    xt = parity.to_device(full)[:, :d]
+    for b in (3, 4):
+        say(f"short factor n={n} d={d} rows={rows} {dtype} b={b}")
+        codes, scales = binding.rotate_quantize(h, xt, b, 0.85)
+        torch.cuda.synchronize()
+        assert h.last_kernel == "wg_block"
+        st = parity.check_rotate_quantize(np.ascontiguousarray(x), n, b, 0.85, codes.cpu().numpy(),
+                                          scales.cpu().numpy(), f"n={n} d={d} {dtype} b={b} [wg_block]")
+        say(f"  ok {st}")
+
+
 @pytest.mark.parametrize("variant", [2, 3, 4], ids=["one_wave", "split2", "split4"])
 @pytest.mark.parametrize("n,d", [(2048, 2048), (4096, 4096), (4096, 4000), (8192, 8192), (8192, 6000)])
 def test_long_rows_split_over_waves(torch, n, d, variant):
