@@ -32,12 +32,17 @@
 namespace rq {
 namespace {
 
-// 16-byte units per LDS column: at least 4 KK (32 block rows per contraction step), a multiple of 8
-// (the swizzle permutes units inside aligned groups of 8) and = 8 (mod 16), so that a column
-// is an odd multiple of 128 bytes: neighbouring columns then start in opposite halves of the
-// 256-byte bank window.
+// 16-byte units per LDS column, at least 4 KK (32 block rows per contraction step).  The 16 lanes
+// of a DPP row read one unit each from 16 neighbouring columns, and all 16 must fall into different
+// 16-byte slots of the 256-byte bank window:
+//   KK odd   exactly 4 KK units: a column is an odd multiple of 64 bytes, so four neighbouring
+//            columns start in the four quarters of the window; the unit index is xor-ed with c >> 2
+//            (two bits), which separates the four columns that share a quarter;
+//   KK even  a multiple of 8 that is = 8 (mod 16): columns start in alternating halves and the
+//            unit index is xor-ed with c >> 1 (three bits).
 template <int KK>
 constexpr int wg_chunks() {
+    if (KK % 2 == 1) return 4 * KK;
     int n = ((4 * KK + 7) / 8) * 8;
     return (n % 16 == 8) ? n : n + 8;
 }
@@ -45,9 +50,19 @@ constexpr int wg_chunks() {
 template <int KK>
 constexpr size_t wg_lds_bytes() { return (size_t)128 * wg_chunks<KK>() * 16 + (size_t)KK * 32 * 48; }
 
-// Waves of a workgroup are placed on the four SIMDs round robin from SIMD 0, so two resident
-// workgroups of 9 or 10 waves put 6 waves on a SIMD: each wave may then hold at most 80 VGPRs.
-// The register budget is requested accordingly (6 waves per SIMD up to pb = 160, 4 above).
+// Register budget, as waves per SIMD (512 VGPRs per SIMD lane).  The hardware deals the waves of
+// successive workgroups round robin over the four SIMDs, so a CU holds 4 x this many waves:
+//   KK <= 3, KK == 5  6 (80 VGPRs): several small workgroups per CU, or two of 9 - 10 waves (3 of
+//            which may land on one SIMD, so 96 registers would often leave room for one only);
+//   KK == 4, KK >= 6   4 (128): two workgroups of up to 8 waves, or one of up to 16.
+// At 128 registers there is room for the next pass's 16 load registers, so its loads are issued one
+// pass ahead (right after the barrier that ends phase 1) and their latency is covered by phases
+// 2 - 4.  At 80 registers the same prefetch spills, and spill reloads wait on the same counter as the
+// loads: measured slower.  (Touching one byte per 128 of the next row a pass ahead, to bring it into
+// the L2 cache, measured no better than the plain loads either.)
+template <int KK>
+constexpr int wg_waves_per_simd() { return (KK <= 3 || KK == 5) ? 6 : 4; }
+
 // Extra arguments of the quant_error form of the kernel (QE): phases 1 - 3 are the same, phase 4
 // accumulates the squared quantization error per clip ratio instead of packing codes.
 struct QeArgs {
@@ -57,11 +72,12 @@ struct QeArgs {
 };
 
 template <int KK, int BITS, bool FULL, bool QE, int CB = 4, bool F16 = false>
-__global__ __launch_bounds__(128 * KK) __attribute__((amdgpu_waves_per_eu(KK <= 5 ? 6 : 4)))
+__global__ __launch_bounds__(128 * KK) __attribute__((amdgpu_waves_per_eu(wg_waves_per_simd<KK>())))
 void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
     static_assert(CB >= 2 && CB <= 4 && (CB == 4 || (!FULL && !QE)), "unsupported shape");
     constexpr int RPW = 16 >> CB;                        // rows of X per pass
     constexpr int SEG = 8 << CB;                         // columns of one block row (2^k)
+    constexpr bool PF = wg_waves_per_simd<KK>() == 4;    // loads run one pass ahead
     __shared__ float esum[QE ? 16 : 1][QE ? RQ_MAX_CLIPS : 1];
     constexpr int NCH = wg_chunks<KK>();
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
@@ -74,30 +90,25 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
     const int g = lane >> 4, cphys = lane & 15;
     const int c = (cphys & 4) ? (cphys ^ 3) : cphys;    // logical column group (8 columns)
     // LDS column of (column group c, position ic inside the group) is ic * 16 + c: the 16 lanes of a
-    // DPP row then touch 16 neighbouring columns, whose 16-byte units - start halves alternating
-    // with c & 1, unit index xor-ed with c >> 1 - are 16 different ones of a 256-byte bank window.
-    const int swz = (c >> 1) & 7;
+    // DPP row then touch 16 neighbouring columns, whose 16-byte units are 16 different ones of a
+    // 256-byte bank window (see wg_chunks).
+    constexpr bool Q4 = NCH % 8 == 4;                    // quarter-window layout (KK odd)
+    const int swz = Q4 ? (c >> 2) & 3 : (c >> 1) & 7;
     const int rsub = CB == 4 ? 0 : c >> CB;              // row of the pass
     const int cl = CB == 4 ? c : c & ((1 << CB) - 1);    // 8-column chunk inside that row
 
     u32x4 A[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) A[kk] = a.tiles[(wave * KK + kk) * 64 + lane];
-    float sf[4];
-#pragma unroll
-    for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
     // CB < 4: the first lane stage is the plain one, the fused ones start at the second bit
     const float flip = (__builtin_popcount(CB == 4 ? c : cl >> 1) & 1) ? -1.0f : 1.0f;
     const uint32_t sg0 = (c & 1) ? 0x80000000u : 0u;
 
-    // phase-1 geometry: lane (g, c) loads block rows 16 wave + 4 g + t, t = 0..3 (rows at or beyond pb
-    // meet zero columns of B: any in-bounds data will do, the last real row is reused)
-    int eoff[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int r = 16 * wave + 4 * g + t;
-        eoff[t] = (r < pb ? r : pb - 1) * SEG + cl * 8;
-    }
+    // phase-1 geometry: lane (g, c) loads block rows 16 wave + 4 g + t, t = 0..3, at constant
+    // strides from one offset.  A group of four at or beyond pb (a multiple of 4) meets zero columns
+    // of B: any in-bounds data will do, and it reads the last four real rows.
+    const int r0 = 16 * wave + 4 * g;
+    const int eoff0 = (r0 < pb ? r0 : pb - 4) * SEG + cl * 8;
     // 8-byte half of the 16-byte unit that holds block rows 8 q .. 8 q + 7, q = 2 wave + g / 2
     const int wr_unit = ((2 * wave + (g >> 1)) ^ swz) * 16 + (g & 1) * 8;
 
@@ -111,29 +122,33 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
         reinterpret_cast<u32x4*>(ops)[i] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
 
-    // (Issuing a row's loads one iteration ahead costs 16 more live registers; at the 80-register
-    // budget that means spills whose reloads wait on the same counter as the loads: measured slower.)
     u32x4 R[4];
     auto load_row = [&](int64_t row) {
         const uint16_t* xr = a.X + row * a.ld;
         if constexpr (CB == 4) {
             const RowView xv = row_view(xr, a.d);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) R[t] = FULL ? load16(xr + eoff[t]) : load_chunk(xv, eoff[t]);
+            for (int t = 0; t < 4; ++t)
+                R[t] = FULL ? load16(xr + eoff0 + t * SEG) : load_chunk(xv, eoff0 + t * SEG);
         } else {
             // the lanes of a wave read different rows: per-lane addresses, whole chunks (d % 8 == 0)
 #pragma unroll
             for (int t = 0; t < 4; ++t)
-                R[t] = eoff[t] < a.d ? load16(xr + eoff[t]) : u32x4{0u, 0u, 0u, 0u};
+                R[t] = eoff0 + t * SEG < a.d ? load16(xr + eoff0 + t * SEG) : u32x4{0u, 0u, 0u, 0u};
         }
     };
     const int64_t n_pass = (a.rows + RPW - 1) / RPW;
+    // CB == 4: one row per pass, uniform over the workgroup; otherwise the lane's own row, the
+    // last row standing in (loads only) for rows beyond the end
+    auto load_pass = [&](int64_t ps) {
+        const int64_t r = ps * RPW + rsub;
+        load_row(CB == 4 || r < a.rows ? r : a.rows - 1);
+    };
+    if (PF && (int64_t)blockIdx.x < n_pass) load_pass(blockIdx.x);
     for (int64_t pass = blockIdx.x; pass < n_pass; pass += gridDim.x) {
-        // CB == 4: one row per pass, uniform over the workgroup; otherwise the lane's own row, the
-        // last row standing in (loads only) for rows beyond the end
         const int64_t row = pass * RPW + rsub;
         const bool live = CB == 4 || row < a.rows;
-        load_row(live ? row : a.rows - 1);
+        if (!PF) load_pass(pass);
         // ---- phase 1
 #pragma unroll
         for (int ic = 0; ic < 8; ++ic) {
@@ -144,6 +159,7 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
             *reinterpret_cast<uint2*>(wr0 + ic * 16 * (NCH * 16)) = v;
         }
         __syncthreads();
+        if (PF && pass + gridDim.x < n_pass) load_pass(pass + gridDim.x);
         // ---- phase 2
         f32x4 acc[8];
 #pragma unroll
@@ -151,10 +167,11 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
             acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                // unit (4 kk + g) ^ swz: the xor touches the low three bits only, so the address is one of
-                // two per-lane bases (kk even / odd) plus a compile-time offset
-                const u32x4 raw = *reinterpret_cast<const u32x4*>(((kk & 1) ? rd1 : rd0) +
-                                                                  nt * 16 * (NCH * 16) + (kk >> 1) * 128);
+                // unit (4 kk + g) ^ swz: a two-bit xor leaves one per-lane base plus a compile-time offset,
+                // a three-bit xor two bases (kk even / odd)
+                const u32x4 raw = *reinterpret_cast<const u32x4*>(
+                    Q4 ? rd0 + nt * 16 * (NCH * 16) + kk * 64
+                       : ((kk & 1) ? rd1 : rd0) + nt * 16 * (NCH * 16) + (kk >> 1) * 128);
                 acc[nt] = mfma_pm1<F16>(A[kk], raw, acc[nt]);
             }
         }
@@ -169,6 +186,13 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
                     acc[nt | s] = u - v;
                 }
         float m = 0.0f;
+        // the stage signs are rebuilt from the column group every pass (two instructions each) rather
+        // than held in registers across phases 1 and 2
+        int cs = c;
+        asm volatile("" : "+v"(cs));
+        float sf[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) sf[b] = __uint_as_float(0x3F800000u | ((uint32_t)(cs >> b) << 31));
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) {
             f32x4 v = acc[nt];
@@ -308,7 +332,7 @@ int launch_kk(const rq_hadamard* h, const WaveArgs& a, int bits, int pb, int cb,
     const size_t lds = wg_lds_bytes<KK>();
     const int nw = (pb + 15) / 16;
     int per_cu = (int)((size_t)h->max_lds / (lds + 128));
-    const int by_waves = nw <= 10 ? 2 : 1;               // see the register budget note at the kernel
+    const int by_waves = 4 * wg_waves_per_simd<KK>() / nw;   // see the register budget note at the kernel
     if (per_cu > by_waves) per_cu = by_waves;
     if (per_cu < 1) per_cu = 1;
     const int64_t cap = (int64_t)h->num_cu * per_cu;
