@@ -462,7 +462,7 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
 // e = y - r Delta_k, sum e^2.  The grid is rows x ksplit: with few rows the candidates of one
 // row are spread over several waves (each repeats the rotation) so the chip is filled.
 // partial[row][k] receives sum e^2 / n^2, the row's mean squared error in the normalised domain.
-template <int T, int BITS>
+template <int T, int BITS, bool F16 = false>
 __global__ __launch_bounds__(64) void k_wave_quant_error(WaveArgs a, ClipList clips, int n_clips,
                                                          int ksplit, double* partial) {
     constexpr int N = 512 * T;
@@ -488,10 +488,9 @@ __global__ __launch_bounds__(64) void k_wave_quant_error(WaveArgs a, ClipList cl
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             const u32x4 raw = load_chunk(xv, (t * 64 + chunk) * 8);
-            const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
-            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), bm, z, 0, 0, 0);
+            acc[t][0] = mfma_pm1<F16>(A0, raw, z);
+            acc[t][1] = mfma_pm1<F16>(A1, raw, z);
         }
 #pragma unroll
         for (int s = 1; s < T; s <<= 1)
@@ -530,7 +529,7 @@ __global__ __launch_bounds__(64) void k_wave_quant_error(WaveArgs a, ClipList cl
 }
 
 // The same for the block orders of k_wave_block (n = pb * 128, pb <= 32).
-template <int BITS, bool FULL, int NV>
+template <int BITS, bool FULL, int NV, bool F16 = false>
 __global__ __launch_bounds__(64) void k_wave_block_qe(WaveArgs a, int pb, ClipList clips, int n_clips, int ksplit,
                                                       double* partial) {
     const int lane = threadIdx.x;
@@ -551,7 +550,7 @@ __global__ __launch_bounds__(64) void k_wave_block_qe(WaveArgs a, int pb, ClipLi
         const int per = (n_clips + ksplit - 1) / ksplit;
         const int k0 = part * per, k1 = (k0 + per < n_clips) ? k0 + per : n_clips;
         float y[8][NV];
-        const float m = block_rotate_row<FULL, NV>(a, row, e_base, A0, A1, sf, y);
+        const float m = block_rotate_row<FULL, NV, F16>(a, row, e_base, A0, A1, sf, y);
         float v[8 * NV];
 #pragma unroll
         for (int ic = 0; ic < 8; ++ic)
@@ -565,7 +564,7 @@ __global__ __launch_bounds__(64) void k_wave_block_qe(WaveArgs a, int pb, ClipLi
 
 // The same for short rows (n = 32 << CB: the KV head rows): 16 >> CB rows per wave pass, every
 // clip ratio for every row (there are always enough rows to fill the chip).
-template <int CB, int BITS>
+template <int CB, int BITS, bool F16 = false>
 __global__ __launch_bounds__(64) void k_wave_short_qe(WaveArgs a, ClipList clips, int n_clips, double* partial) {
     constexpr int RPW = 16 >> CB;
     constexpr int N = 32 << CB;
@@ -588,10 +587,9 @@ __global__ __launch_bounds__(64) void k_wave_short_qe(WaveArgs a, ClipList clips
         const bool in = live && chunk * 8 < a.d;
         u32x4 raw = load16(a.X + (in ? row * a.ld + chunk * 8 : 0));
         if (!in) raw = u32x4{0u, 0u, 0u, 0u};
-        const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        f32x4 v0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
-        f32x4 v1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), bm, z, 0, 0, 0);
+        f32x4 v0 = mfma_pm1<F16>(A0, raw, z);
+        f32x4 v1 = mfma_pm1<F16>(A1, raw, z);
         lane_stage<kDppXor1>(v0, sg0);
         lane_stage<kDppXor1>(v1, sg0);
         lane_stages_tail<CB>(v0, sf);
@@ -608,7 +606,7 @@ __global__ __launch_bounds__(64) void k_wave_short_qe(WaveArgs a, ClipList clips
 // quant_error of the asymmetric group-128 quantizer on rows of 128 (one group per row; sections 4.1,
 // 5.1): per clip ratio lo = clip min, Delta = clip (max - min) / (2^b - 1), e = (y - lo) - code Delta;
 // six vector-ALU operations per value and candidate, four candidates at a time.
-template <int BITS>
+template <int BITS, bool F16 = false>
 __global__ __launch_bounds__(64) void k_wave_short_qe_asym(WaveArgs a, ClipList clips, int n_clips, double* partial) {
     constexpr int CB = 2, RPW = 4, N = 128;
     constexpr float kL = (float)((1 << BITS) - 1);
@@ -629,10 +627,9 @@ __global__ __launch_bounds__(64) void k_wave_short_qe_asym(WaveArgs a, ClipList 
         const bool in = live && chunk * 8 < a.d;
         u32x4 raw = load16(a.X + (in ? row * a.ld + chunk * 8 : 0));
         if (!in) raw = u32x4{0u, 0u, 0u, 0u};
-        const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        f32x4 v0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A0), bm, z, 0, 0, 0);
-        f32x4 v1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A1), bm, z, 0, 0, 0);
+        f32x4 v0 = mfma_pm1<F16>(A0, raw, z);
+        f32x4 v1 = mfma_pm1<F16>(A1, raw, z);
         lane_stage<kDppXor1>(v0, sg0);
         lane_stage<kDppXor1>(v1, sg0);
         lane_stages_tail<CB>(v0, sf);
@@ -990,7 +987,7 @@ bool wave_supports(const rq_hadamard* h, const RowArgs& a) {
 }
 
 bool wave_quant_error_supports(const rq_hadamard* h, const RowArgs& a) {
-    return a.dtype == RQ_BF16 && (wave_supports(h, a) || wave_block_supports(h, a));
+    return wave_supports(h, a) || wave_block_supports(h, a);
 }
 
 static int qe_ksplit(const rq_hadamard* h, int64_t rows, int n_clips) {
@@ -1012,10 +1009,12 @@ static int launch_qe(const rq_hadamard* h, const WaveArgs& w, const ClipList& cl
     const int64_t items = w.rows * ksplit;
     const int64_t cap = 1 << 24;
     const unsigned grid = (unsigned)(items < cap ? items : cap);
-    if (bits == 4)
-        hipLaunchKernelGGL((k_wave_quant_error<T, 4>), dim3(grid), dim3(64), 0, s, w, clips, n_clips, ksplit, partial);
-    else
-        hipLaunchKernelGGL((k_wave_quant_error<T, 3>), dim3(grid), dim3(64), 0, s, w, clips, n_clips, ksplit, partial);
+    auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, dim3(grid), dim3(64), 0, s, w, clips, n_clips, ksplit, partial); };
+    if (w.f16) {
+        if (bits == 4) go(k_wave_quant_error<T, 4, true>); else go(k_wave_quant_error<T, 3, true>);
+    } else {
+        if (bits == 4) go(k_wave_quant_error<T, 4, false>); else go(k_wave_quant_error<T, 3, false>);
+    }
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 
@@ -1027,12 +1026,13 @@ static int launch_block_qe(const rq_hadamard* h, const WaveArgs& w, int pb, cons
     const int64_t cap = 1 << 24;
     const dim3 grid((unsigned)(items < cap ? items : cap)), block(64);
     const bool full = w.d == pb * 128;
-    if (bits == 4) {
-        if (full) hipLaunchKernelGGL((k_wave_block_qe<4, true, NV>), grid, block, 0, s, w, pb, clips, n_clips, ksplit, partial);
-        else hipLaunchKernelGGL((k_wave_block_qe<4, false, NV>), grid, block, 0, s, w, pb, clips, n_clips, ksplit, partial);
+    auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, 0, s, w, pb, clips, n_clips, ksplit, partial); };
+    if (w.f16) {
+        if (bits == 4) { if (full) go(k_wave_block_qe<4, true, NV, true>); else go(k_wave_block_qe<4, false, NV, true>); }
+        else { if (full) go(k_wave_block_qe<3, true, NV, true>); else go(k_wave_block_qe<3, false, NV, true>); }
     } else {
-        if (full) hipLaunchKernelGGL((k_wave_block_qe<3, true, NV>), grid, block, 0, s, w, pb, clips, n_clips, ksplit, partial);
-        else hipLaunchKernelGGL((k_wave_block_qe<3, false, NV>), grid, block, 0, s, w, pb, clips, n_clips, ksplit, partial);
+        if (bits == 4) { if (full) go(k_wave_block_qe<4, true, NV, false>); else go(k_wave_block_qe<4, false, NV, false>); }
+        else { if (full) go(k_wave_block_qe<3, true, NV, false>); else go(k_wave_block_qe<3, false, NV, false>); }
     }
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
@@ -1043,27 +1043,39 @@ static int launch_short_qe(const WaveArgs& w, const ClipList& clips, int n_clips
     const int64_t passes = (w.rows + (16 >> CB) - 1) / (16 >> CB);
     const int64_t cap = 1 << 24;
     const dim3 grid((unsigned)(passes < cap ? passes : cap)), block(64);
-    if (bits == 4) hipLaunchKernelGGL((k_wave_short_qe<CB, 4>), grid, block, 0, s, w, clips, n_clips, partial);
-    else hipLaunchKernelGGL((k_wave_short_qe<CB, 3>), grid, block, 0, s, w, clips, n_clips, partial);
+    auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, 0, s, w, clips, n_clips, partial); };
+    if (w.f16) {
+        if (bits == 4) go(k_wave_short_qe<CB, 4, true>); else go(k_wave_short_qe<CB, 3, true>);
+    } else {
+        if (bits == 4) go(k_wave_short_qe<CB, 4, false>); else go(k_wave_short_qe<CB, 3, false>);
+    }
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 
 int wave_quant_error_asym(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
                           double* partial, hipStream_t s) {
+    const bool f16 = a.dtype == RQ_F16;
     WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
-               static_cast<const u32x4*>(h->d_tiles), nullptr, nullptr, 0.0, 0.0};
+               static_cast<const u32x4*>(f16 ? h->d_tiles_f16 : h->d_tiles), nullptr, nullptr, 0.0, 0.0};
+    w.f16 = f16;
     const int64_t passes = (w.rows + 3) / 4;
     const int64_t cap = 1 << 24;
     const dim3 grid((unsigned)(passes < cap ? passes : cap)), block(64);
-    if (a.bits == 4) hipLaunchKernelGGL((k_wave_short_qe_asym<4>), grid, block, 0, s, w, clips, n_clips, partial);
-    else hipLaunchKernelGGL((k_wave_short_qe_asym<3>), grid, block, 0, s, w, clips, n_clips, partial);
+    auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, 0, s, w, clips, n_clips, partial); };
+    if (f16) {
+        if (a.bits == 4) go(k_wave_short_qe_asym<4, true>); else go(k_wave_short_qe_asym<3, true>);
+    } else {
+        if (a.bits == 4) go(k_wave_short_qe_asym<4, false>); else go(k_wave_short_qe_asym<3, false>);
+    }
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 
 int wave_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
                      double* partial, hipStream_t s) {
+    const bool f16 = a.dtype == RQ_F16;
     WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
-               static_cast<const u32x4*>(h->d_tiles), nullptr, nullptr, 0.0, 0.0};
+               static_cast<const u32x4*>(f16 ? h->d_tiles_f16 : h->d_tiles), nullptr, nullptr, 0.0, 0.0};
+    w.f16 = f16;
     if (a.p > 1) {
         const int pb = a.p << (a.log2m - 7);
         switch ((pb + 3) / 4) {

@@ -294,13 +294,19 @@ WgKernel pick_rq(bool full) {
 }
 
 // The kernel instance for a launch, or nullptr when the combination is not built: cb = 4 needs
-// KK >= 2 (smaller blocks have the one-wave kernel), quant_error is bf16 with cb = 4 only.
+// KK >= 2 (smaller blocks have the one-wave kernel), quant_error cb = 4.
 template <int KK>
 WgKernel pick_kernel(int bits, bool full, bool qe, int cb, bool f16) {
     if (bits != 3 && bits != 4) return nullptr;
     if (qe) {
         if constexpr (KK >= 2) {
-            if (cb != 4 || f16) return nullptr;
+            if (cb != 4) return nullptr;
+            if (f16) {
+                if (bits == 4) return full ? static_cast<WgKernel>(k_wg_block<KK, 4, true, true, 4, true>)
+                                           : static_cast<WgKernel>(k_wg_block<KK, 4, false, true, 4, true>);
+                return full ? static_cast<WgKernel>(k_wg_block<KK, 3, true, true, 4, true>)
+                            : static_cast<WgKernel>(k_wg_block<KK, 3, false, true, 4, true>);
+            }
             if (bits == 4) return full ? static_cast<WgKernel>(k_wg_block<KK, 4, true, true>)
                                        : static_cast<WgKernel>(k_wg_block<KK, 4, false, true>);
             return full ? static_cast<WgKernel>(k_wg_block<KK, 3, true, true>)
@@ -426,9 +432,8 @@ static bool wg_shape(const RowArgs& a, int* pb, int* cb) {
 bool wg_block_supports(const rq_hadamard* h, const RowArgs& a, bool quant_error) {
     int pb, cb;
     if (h->device < 0 || !h->d_tiles || !h->wg_ok || !wg_shape(a, &pb, &cb)) return false;
-    if (quant_error ? (a.dtype != RQ_BF16 || cb != 4)
-                    : (a.dtype != RQ_BF16 && !(a.dtype == RQ_F16 && h->d_tiles_f16)))
-        return false;
+    if (a.dtype != RQ_BF16 && !(a.dtype == RQ_F16 && h->d_tiles_f16)) return false;
+    if (quant_error && cb != 4) return false;
     if ((reinterpret_cast<uintptr_t>(a.X) & 15) != 0 || (a.ld & 7) != 0 || (a.d & 7) != 0) return false;
     return true;
 }
@@ -453,8 +458,10 @@ int wg_block_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList&
                          double* partial, hipStream_t s) {
     int pb, cb;
     if (!wg_shape(a, &pb, &cb)) return RQ_ERR_NO_ORDER;
+    const bool f16 = a.dtype == RQ_F16;
     WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld,
-               static_cast<const u32x4*>(h->d_tiles), nullptr, nullptr, 0.0, 0.0};
+               static_cast<const u32x4*>(f16 ? h->d_tiles_f16 : h->d_tiles), nullptr, nullptr, 0.0, 0.0};
+    w.f16 = f16;
     QeArgs qe;
     qe.clips = clips;
     qe.n_clips = n_clips;

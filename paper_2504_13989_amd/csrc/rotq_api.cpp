@@ -309,7 +309,7 @@ static int quant_error_impl(const rq_hadamard_t* h, const void* X, int dtype, in
     const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, bits);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (asym) {
-        if (h->variant == 0 && rows > 0 && dtype == RQ_BF16 && rq::wave_asym_supports(h, a)) {
+        if (h->variant == 0 && rows > 0 && rq::wave_asym_supports(h, a)) {
             hm->last_kernel = "wave_quant_error_asym";
             rc = rq::wave_quant_error_asym(h, a, cl, n_clips, static_cast<double*>(workspace), s);
             if (rc != RQ_OK) return rc;

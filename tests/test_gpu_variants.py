@@ -186,6 +186,15 @@ def test_half_precision_input(torch, n, d):
     mse = binding.quant_error(h, xt, 3, clips)
     torch.cuda.synchronize()
     parity.check_quant_error(x, n, 3, clips, mse.cpu().numpy(), what=f"fp16 n={n}")
+    want = {128: "wave_quant_error", 4096: "wave_quant_error", 3584: "wave_quant_error", 3072: "wave_quant_error",
+            148 * 128: "wg_block_quant_error", 5120: "wg_block_quant_error"}.get(n)
+    if want and d % 8 == 0:
+        assert h.last_kernel == want
+    if n == 128:
+        mse = binding.quant_error(h, xt, 3, clips, asym=True)
+        torch.cuda.synchronize()
+        assert h.last_kernel == "wave_quant_error_asym"
+        parity.check_quant_error(x, n, 3, clips, mse.cpu().numpy(), what=f"fp16 asym n={n}", asym=True)
     y = binding.rotate(h, xt)
     torch.cuda.synchronize()
     parity.check_float_rows(y.cpu().numpy(), __import__("rotq_oracle").rotate(x, n), what=f"fp16 rotate n={n}")
