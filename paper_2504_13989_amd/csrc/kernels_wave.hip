@@ -106,7 +106,7 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
 // tile where H_S has -1.  Every wave therefore loads the whole row (S times the L1 traffic, the
 // same HBM traffic) but carries only T / S accumulator sets through the vector-ALU stages; the
 // waves exchange nothing but their absmax.
-template <int T, int BITS, bool FULL, int S>
+template <int T, int BITS, bool FULL, int S, bool F16 = false>
 __global__ __launch_bounds__(64 * S) void k_wave_sylvester_split(WaveArgs a) {
     static_assert(T % S == 0 && (S == 2 || S == 4), "unsupported split");
     constexpr int TS = T / S;
@@ -121,7 +121,8 @@ __global__ __launch_bounds__(64 * S) void k_wave_sylvester_split(WaveArgs a) {
     const int chunk = (g << 4) + c;
 
     const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
-    // operand tiles per input segment: negated where H_S[seg][sp] = -1 (Sylvester sign)
+    // operand tiles per input segment: negated where H_S[seg][sp] = -1 (Sylvester sign; bit 15 is the
+    // sign of a bf16 and of an fp16 alike)
     u32x4 P0[S], P1[S];
 #pragma unroll
     for (int sp = 0; sp < S; ++sp) {
@@ -149,9 +150,8 @@ __global__ __launch_bounds__(64 * S) void k_wave_sylvester_split(WaveArgs a) {
             const int e0 = ((sp * TS + t) * 64 + chunk) * 8;
             // plain (cached) loads: the S waves of the workgroup read the same lines
             const u32x4 raw = FULL ? *reinterpret_cast<const u32x4*>(xr + e0) : load_chunk(xv, e0);
-            const bf16x8 bm = __builtin_bit_cast(bf16x8, raw);
-            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, P0[sp]), bm, acc[t][0], 0, 0, 0);
-            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, P1[sp]), bm, acc[t][1], 0, 0, 0);
+            acc[t][0] = mfma_pm1<F16>(P0[sp], raw, acc[t][0]);
+            acc[t][1] = mfma_pm1<F16>(P1[sp], raw, acc[t][1]);
         }
     }
 #pragma unroll
@@ -802,12 +802,13 @@ template <int T, int S>
 int launch_split(const WaveArgs& a, int bits, hipStream_t s) {
     const bool full = a.d == 512 * T;
     const dim3 grid((unsigned)a.rows), block(64 * S);
-    if (bits == 4) {
-        if (full) hipLaunchKernelGGL((k_wave_sylvester_split<T, 4, true, S>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_wave_sylvester_split<T, 4, false, S>), grid, block, 0, s, a);
+    auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, 0, s, a); };
+    if (a.f16) {
+        if (bits == 4) { if (full) go(k_wave_sylvester_split<T, 4, true, S, true>); else go(k_wave_sylvester_split<T, 4, false, S, true>); }
+        else { if (full) go(k_wave_sylvester_split<T, 3, true, S, true>); else go(k_wave_sylvester_split<T, 3, false, S, true>); }
     } else {
-        if (full) hipLaunchKernelGGL((k_wave_sylvester_split<T, 3, true, S>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_wave_sylvester_split<T, 3, false, S>), grid, block, 0, s, a);
+        if (bits == 4) { if (full) go(k_wave_sylvester_split<T, 4, true, S, false>); else go(k_wave_sylvester_split<T, 4, false, S, false>); }
+        else { if (full) go(k_wave_sylvester_split<T, 3, true, S, false>); else go(k_wave_sylvester_split<T, 3, false, S, false>); }
     }
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
@@ -819,7 +820,7 @@ int launch_long(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s
     // from 2048 rows on one wave per row is faster)
     if constexpr (T >= 4) {
         const int64_t simds = (int64_t)h->num_cu * 4;
-        if (h->split >= 0 && !a.f16) {
+        if (h->split >= 0) {
             const int want = h->split > 0 ? h->split : (a.rows * 2 <= simds ? 4 : a.rows <= simds ? 2 : 1);
             if (want == 4) return launch_split<T, 4>(a, bits, s);
             if (want == 2) return launch_split<T, 2>(a, bits, s);

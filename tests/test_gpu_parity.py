@@ -123,14 +123,15 @@ def test_short_sylvester_factor_blocks(torch, n, d, rows, dtype):
 
 @pytest.mark.parametrize("variant", [2, 3, 4], ids=["one_wave", "split2", "split4"])
 @pytest.mark.parametrize("n,d", [(2048, 2048), (4096, 4096), (4096, 4000), (8192, 8192), (8192, 6000)])
-def test_long_rows_split_over_waves(torch, n, d, variant):
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_long_rows_split_over_waves(torch, n, d, variant, dtype):
     # the same rows through one wave per row and through 2 / 4 waves per row
     rng = np.random.default_rng(n + d)
     xf = rng.standard_t(3.0, size=(77, d)).astype(np.float32)
     xf[:, 5] *= 40.0
-    x = wl.f32_to_bf16_bits(xf)
+    x = wl.f32_to_bf16_bits(xf) if dtype == "bf16" else xf.astype(np.float16)
     for b in (3, 4):
-        say(f"split n={n} d={d} b={b} variant={variant}")
+        say(f"split n={n} d={d} b={b} variant={variant} {dtype}")
         codes, scales, kern = run_rq(torch, x, n, b, 0.9, variant)
         assert kern == "wave_sylvester"
         st = parity.check_rotate_quantize(x, n, b, 0.9, codes, scales, f"n={n} d={d} b={b} variant={variant}")
