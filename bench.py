@@ -67,7 +67,7 @@ def time_steady_state(torch, binding, h, base, bits, clip, rows_total):
 VALU_PEAK_TLANEOPS = 39.3       # 256 CUs x 64 lanes x 2.4 GHz, packed fp32 excluded (T lane-ops/s)
 
 
-def _min_ms(torch, fn, n=10, rounds=4):
+def _min_ms(torch, fn, n=6, rounds=8):
     for _ in range(2):
         fn()
     torch.cuda.synchronize()
@@ -86,7 +86,7 @@ def _min_ms(torch, fn, n=10, rounds=4):
 def time_all_configs(torch, binding, wl):
     """Every configuration's rotate_quantize at its own row count and at a steady-state row count
     (input >= 1 GiB, rows tiled from a 2048-row seeded sample), plus quant_error on the
-    calibration tensor.  Best of 4 rounds of 10 launches, HIP events, inputs resident and reused
+    calibration tensor.  Best of 8 rounds of 6 launches, HIP events, inputs resident and reused
     (warm caches for the small shapes): context next to the cold-ring headline figure."""
     res = {}
     for name in ("llama_hidden", "qwen_hidden", "ffn_expand", "ffn_down", "kv_k"):
@@ -182,6 +182,26 @@ def time_all_configs(torch, binding, wl):
         "roofline": {"bound": "alu", "unit": "T lane-ops/s", "achieved": 5 * ec / ms / 1e9,
                      "peak": VALU_PEAK_TLANEOPS, "frac": 5 * ec / ms / 1e9 / VALU_PEAK_TLANEOPS,
                      "note": "5 VALU lane-ops per element-candidate; two launches (row sums, reduction)"}}
+    # hidden and FFN widths of the model families the paper evaluates (section 5), b = 4, bf16 and
+    # fp16 rows, N(0, 1/4) entries, 512 MiB of input per launch; a width without a Hadamard order is
+    # zero-padded to the next one (section 4.2)
+    widths = {}
+    for d in (896, 1536, 2048, 3584, 4096, 5120, 8192, 4864, 8960, 11008, 13824, 14336, 18944, 28672):
+        n = binding.next_order(d)
+        h = binding.hadamard_build(n)
+        rows = max(256, (1 << 29) // (2 * d) // 256 * 256)
+        entry = {"n": n, "p": h.p, "rows": rows}
+        for dt, key in ((torch.bfloat16, "bf16"), (torch.float16, "f16")):
+            x = (torch.randn(rows, d, device="cuda") * 0.5).to(dt)
+            codes = torch.empty((rows, n * 4 // 8), dtype=torch.uint8, device="cuda")
+            scales = torch.empty((rows,), dtype=torch.float32, device="cuda")
+            ms = _min_ms(torch, lambda: binding.rotate_quantize(h, x, 4, 0.9, codes=codes, scales=scales), n=4, rounds=6)
+            entry[key] = {"us": ms * 1e3, "frac_hbm_peak": rows * algorithmic_bytes_per_row(d, n, 4) / ms / 1e6 / HBM_PEAK_GBPS,
+                          "kernel": h.last_kernel}
+            del x, codes, scales
+        widths[str(d)] = entry
+    res["model_widths_b4"] = widths
+    torch.cuda.empty_cache()
     return res
 
 
