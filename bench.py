@@ -245,6 +245,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-steady-state", action="store_true")
+    ap.add_argument("--no-stream-reference", action="store_true",
+                    help="skip the traffic-only reference kernel (practical floor of the launch)")
     ap.add_argument("--no-configs", action="store_true", help="skip the per-configuration table")
     ap.add_argument("--variant", type=int, default=0,
                     help="rq_hadamard_set_variant value for the timed step (0 = automatic kernel choice)")
@@ -346,6 +348,39 @@ def main():
                      "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(kernel_name), "kernel": kernel_name,
                      "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": batch_bytes},
     }
+    if not args.no_stream_reference:
+        # the same ring and graph with the traffic-only kernel: the practical floor of this launch shape
+        def ref_step(i):
+            sl = i % ring
+            binding.stream_reference(xs[sl], bits, codes=codes[sl], scales=scales[sl])
+        with torch.cuda.stream(side):
+            ref_step(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        ref_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(ref_graph):
+            for i in range(args.steps):
+                ref_step(i)
+        ref_graph.replay()
+        torch.cuda.synchronize()
+        r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        r0.record()
+        ref_graph.replay()
+        r1.record()
+        torch.cuda.synchronize()
+        ref_ms = r0.elapsed_time(r1) / args.steps
+        xl = base.repeat(131072 // base.shape[0], 1)
+        cl = torch.empty((xl.shape[0], w.n * bits // 8), dtype=torch.uint8, device="cuda")
+        sl_ = torch.empty((xl.shape[0],), dtype=torch.float32, device="cuda")
+        ref_long = _min_ms(torch, lambda: binding.stream_reference(xl, bits, codes=cl, scales=sl_))
+        out["stream_reference"] = {
+            "what": "kernel with the same loads and stores and no arithmetic (rq_stream_reference), same ring and graph",
+            "kernel_ms": ref_ms, "GBps": batch_bytes / ref_ms / 1e6,
+            "frac_hbm_peak": batch_bytes / ref_ms / 1e6 / HBM_PEAK_GBPS,
+            "rotate_quantize_over_reference": kernel_ms / ref_ms,
+            "steady_rows": int(xl.shape[0]), "steady_ms": ref_long,
+            "steady_frac_hbm_peak": xl.shape[0] * row_bytes / ref_long / 1e6 / HBM_PEAK_GBPS}
+        del xl, cl, sl_
     if args.pmc_calibrate:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(7)
         dst = torch.empty_like(src)

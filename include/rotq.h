@@ -145,6 +145,21 @@ int rq_rotate_quantize_asym(const rq_hadamard_t* h,
                             void* codes, float* scales, float* mins, void* stream);
 
 /*
+ * Measurement aid (no operation of the paper): a kernel with the memory traffic of
+ * rq_rotate_quantize on 16-bit rows of width n and no arithmetic - it reads every row with the same
+ * loads and writes n * bits / 8 bytes of codes and one float per row (an xor fold of the input, not
+ * a quantization).  Its duration is the practical floor for a rotate_quantize launch of that shape
+ * on this chip; bench.py reports it next to the real kernel.
+ *   X       [in]  DEVICE, rows x n 16-bit elements, leading dimension ld >= n (a multiple of 8),
+ *                 16-byte aligned
+ *   n       [in]  a multiple of 512, at most 8192
+ *   codes   [out] DEVICE, rows * n * bits / 8 bytes, 4-byte aligned;  scales [out] DEVICE, rows floats
+ * Errors: RQ_ERR_ARG, RQ_ERR_HIP.
+ */
+int rq_stream_reference(const void* X, int64_t rows, int n, int64_t ld, int bits, void* codes,
+                        float* scales, void* stream);
+
+/*
  * The per-token symmetric quantizer of section 2.1 (with the clip ratio of section 3.1) on the
  * rows as they are, without a rotation: for activations whose rotation has been fused into the
  * neighbouring weights offline (section 2.2), so that only the quantizer remains online.

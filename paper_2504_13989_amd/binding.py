@@ -48,6 +48,7 @@ def lib() -> C.CDLL:
     L.rq_rotate_quantize_asym.argtypes = [vp, vp, i32, i64, i32, i64, i32, C.c_float, vp, vp, vp, vp]
     L.rq_quantize.argtypes = [vp, i32, i64, i32, i64, i32, C.c_float, vp, vp, vp]
     L.rq_rotate.argtypes = [vp, vp, i32, i64, i32, i64, i32, vp, i32, i32, i64, vp]
+    L.rq_stream_reference.argtypes = [vp, i64, i32, i64, i32, vp, vp, vp]
     L.rq_dequantize_rotate.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, i32, i32, i64, vp]
     L.rq_expand_limit.argtypes = [i32, i32, i32, C.POINTER(C.c_int64)]
     L.rq_quant_error_workspace.argtypes = [i64, i32]
@@ -211,6 +212,24 @@ def quantize(x, bits: int, clip: float, codes=None, scales=None, stream=None):
                            C.c_float(clip), C.c_void_p(codes.data_ptr()),
                            C.c_void_p(scales.data_ptr()), _stream_ptr(stream))
     _check(rc, "rq_quantize")
+    return codes, scales
+
+
+def stream_reference(x, bits: int, codes=None, scales=None, stream=None):
+    """rq_stream_reference: the traffic of rotate_quantize on 16-bit rows [rows, n] without the
+    arithmetic (measurement aid; the outputs are not a quantization)."""
+    import torch
+    if not x.is_cuda:
+        raise ValueError("x must be a device tensor")
+    x2, rows, n, ld = _rows_view(x)
+    if codes is None:
+        codes = torch.empty((rows, n * bits // 8), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty((rows,), dtype=torch.float32, device=x.device)
+    rc = lib().rq_stream_reference(C.c_void_p(x2.data_ptr()), rows, n, ld, int(bits),
+                                   C.c_void_p(codes.data_ptr()), C.c_void_p(scales.data_ptr()),
+                                   _stream_ptr(stream))
+    _check(rc, "rq_stream_reference")
     return codes, scales
 
 

@@ -223,6 +223,16 @@ int rq_rotate_quantize_asym(const rq_hadamard_t* h, const void* X, int dtype, in
     return rq::generic_rotate_quantize_asym(h, a, clip, static_cast<uint32_t*>(codes), scales, mins, s);
 }
 
+int rq_stream_reference(const void* X, int64_t rows, int n, int64_t ld, int bits, void* codes,
+                        float* scales, void* stream) {
+    if (rows < 0 || n < 512 || n > 8192 || n % 512 != 0 || ld < n || ld % 8 != 0 || (bits != 3 && bits != 4))
+        return RQ_ERR_ARG;
+    if (rows == 0) return RQ_OK;
+    if (!X || !codes || !scales || !aligned(X, 16) || !aligned(codes, 4) || !aligned(scales, 4)) return RQ_ERR_ARG;
+    return rq::stream_reference(X, rows, n, ld, bits, static_cast<uint32_t*>(codes), scales,
+                                static_cast<hipStream_t>(stream));
+}
+
 int rq_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
                 void* codes, float* scales, void* stream) {
     if (dtype != RQ_BF16 && dtype != RQ_F32 && dtype != RQ_F16) return RQ_ERR_ARG;

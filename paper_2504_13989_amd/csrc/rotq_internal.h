@@ -118,4 +118,8 @@ int wg_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip,
 int wg_block_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
                          double* partial, hipStream_t s);
 
+// Traffic-only reference kernel (measurement aid): rows of n = 512 T 16-bit values.
+int stream_reference(const void* X, int64_t rows, int n, int64_t ld, int bits, uint32_t* codes, float* scales,
+                     hipStream_t s);
+
 }  // namespace rq

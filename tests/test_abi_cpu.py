@@ -269,3 +269,17 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "librotq.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         binding.lib()
+
+
+def test_stream_reference_argument_errors(L):
+    E = binding.RQ_ERR_ARG
+    vp = C.c_void_p
+
+    def call(X=4096, rows=4, n=4096, ld=4096, bits=4, codes=4096, scales=4096):
+        return L.rq_stream_reference(vp(X), rows, n, ld, bits, vp(codes), vp(scales), None)
+    assert call(rows=0) == binding.RQ_OK
+    assert call(rows=-1) == E
+    assert call(n=500) == E and call(n=256) == E and call(n=16384) == E
+    assert call(ld=4000) == E and call(ld=4100) == E
+    assert call(bits=5) == E
+    assert call(X=0) == E and call(X=4104) == E and call(codes=0) == E and call(codes=4098) == E and call(scales=0) == E

@@ -247,3 +247,24 @@ def test_graph_replay_and_side_stream(torch):
         assert torch.equal(codes, ref_c) and torch.equal(scales, ref_s)
         assert torch.equal(kc, ref_kc) and torch.equal(ks, ref_ks) and torch.equal(km, ref_km)
         assert torch.equal(mse, ref_m)
+
+
+@pytest.mark.parametrize("n,rows,b", [(4096, 77, 4), (4096, 5, 3), (1024, 300, 3), (8192, 9, 4)])
+def test_stream_reference_moves_the_stated_bytes(torch, n, rows, b):
+    # the measurement aid writes an xor fold of every 16-byte chunk where rotate_quantize writes that
+    # chunk's codes: same loads, same stores, checkable bit for bit
+    rng = np.random.default_rng(n + rows)
+    bits16 = rng.integers(0, 1 << 16, size=(rows, n + 8), dtype=np.uint16)
+    xt = parity.to_device(bits16)[:, :n]
+    guard = 0xA5
+    codes = torch.full((rows + 1, n * b // 8), guard, dtype=torch.uint8, device="cuda")
+    scales = torch.zeros((rows,), dtype=torch.float32, device="cuda")
+    binding.stream_reference(xt, b, codes=codes[:rows], scales=scales)
+    torch.cuda.synchronize()
+    got = codes.cpu().numpy()
+    assert (got[rows] == guard).all()
+    words = np.ascontiguousarray(bits16[:, :n]).view(np.uint32).reshape(rows, n // 8, 4)
+    fold = words[:, :, 0] ^ words[:, :, 1] ^ words[:, :, 2] ^ words[:, :, 3]
+    if b == 3:
+        fold = fold.reshape(rows, n // 32, 4)[:, :, :3].reshape(rows, -1)
+    assert np.array_equal(got[:rows].view(np.uint32).reshape(rows, -1), fold)
