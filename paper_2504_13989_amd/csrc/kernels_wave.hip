@@ -640,15 +640,16 @@ __global__ __launch_bounds__(64) void k_wave_short_qe_asym(WaveArgs a, ClipList 
         float nm = flip > 0.0f ? -lo8 : hi8;
         quad_rows_max_pair(mx, nm);
         const double mn64 = -(double)nm, r64 = (double)mx + (double)nm;
+        const double inv_r = r64 > 0.0 ? 1.0 / r64 : 0.0;
         for (int kb = 0; kb < n_clips; kb += 4) {
             float los[4], sk[4], ndk[4], e2[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int k = kb + j < n_clips ? kb + j : n_clips - 1;
-                const double cl = (double)clips.v[k];
-                los[j] = flip * (float)(cl * mn64);                               // lane sign folded in
-                sk[j] = r64 > 0.0 ? flip * (float)((double)kL / (cl * r64)) : 0.0f;
-                ndk[j] = -flip * (float)(cl * r64 / (double)kL);
+                // the row-independent factors (levels / clip, clip / levels) come with the clip list
+                los[j] = flip * (float)((double)clips.v[k] * mn64);               // lane sign folded in
+                sk[j] = flip * (float)(clips.lvl_over_clip[k] * inv_r);
+                ndk[j] = -flip * (float)(clips.clip_over_lvl[k] * r64);
                 e2[j] = 0.0f;
             }
 #pragma unroll
@@ -666,9 +667,7 @@ __global__ __launch_bounds__(64) void k_wave_short_qe_asym(WaveArgs a, ClipList 
 #pragma unroll
             for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppXor2>(e2[j]);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 16, 64);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 32, 64);
+            for (int j = 0; j < 4; ++j) e2[j] = rows_sum(e2[j]);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 if (live && g == 0 && c == 0 && kb + j < n_clips)

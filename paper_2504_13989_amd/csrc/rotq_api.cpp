@@ -313,6 +313,9 @@ static int quant_error_impl(const rq_hadamard_t* h, const void* X, int dtype, in
     for (int k = 0; k < n_clips; ++k) {
         if (!clip_ok(clips[k])) return RQ_ERR_ARG;
         cl.v[k] = clips[k];
+        const double lvl = (double)((1 << bits) - 1);
+        cl.lvl_over_clip[k] = lvl / (double)clips[k];
+        cl.clip_over_lvl[k] = (double)clips[k] / lvl;
     }
     if (h->device < 0) return RQ_ERR_HIP;
     rq_hadamard* hm = const_cast<rq_hadamard*>(h);

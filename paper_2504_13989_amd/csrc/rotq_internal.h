@@ -47,6 +47,10 @@ struct OutArgs {
 
 struct ClipList {
     float v[RQ_MAX_CLIPS];
+    // row-independent factors of the candidate scales, formed once on the host in fp64:
+    // levels / clip and clip / levels, levels = 2^b - 1
+    double lvl_over_clip[RQ_MAX_CLIPS];
+    double clip_over_lvl[RQ_MAX_CLIPS];
 };
 
 // General LDS kernels: one workgroup per row, any supported order that fits in LDS.

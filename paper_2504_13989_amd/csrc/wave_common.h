@@ -324,6 +324,14 @@ __device__ __forceinline__ uint32_t rows_max_u32(uint32_t m) {
     return max((uint32_t)b[0], (uint32_t)b[1]);
 }
 
+// Sum over the four DPP rows of a wave with the same two row swaps: every lane ends with the total.
+__device__ __forceinline__ float rows_sum(float v) {
+    const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float((uint32_t)a[0]) + __uint_as_float((uint32_t)a[1]);
+    const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float((uint32_t)b[0]) + __uint_as_float((uint32_t)b[1]);
+}
+
 // Max of a non-negative float over lanes: non-negative floats order like their bit patterns,
 // so the reduction runs on unsigned integers (one DPP-fused v_max_u32 per step).  ROW_BITS of
 // the four DPP row patterns are used (lanes that share a row differ in those bits), then the two
@@ -420,16 +428,16 @@ template <int NVAL, int BITS, int ROW_BITS, typename Emit>
 __device__ __forceinline__ void qe_candidates(const float (&v)[NVAL], float m, float flip, const ClipList& clips,
                                               int k0, int k1, Emit emit) {
     constexpr float kQmax = (float)((1 << (BITS - 1)) - 1), kQmin = -(float)(1 << (BITS - 1));
-    constexpr double lvl = (double)((1 << BITS) - 1);
     const double inv_m = m > 0.0f ? 1.0 / (double)m : 0.0;
     for (int kb = k0; kb < k1; kb += 4) {
         float sk[4], ndk[4], e2[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int k = kb + j < k1 ? kb + j : k1 - 1;
-            const double cl = (double)clips.v[k];
-            sk[j] = flip * (float)(lvl / cl * inv_m);          // lane sign folded in
-            ndk[j] = -flip * (float)(cl * (double)m / lvl);
+            // 1 / Delta_k = (levels / clip_k) / amax and Delta_k = (clip_k / levels) amax: the
+            // row-independent factors come with the clip list, so a candidate costs two fp64 products
+            sk[j] = flip * (float)(clips.lvl_over_clip[k] * inv_m);          // lane sign folded in
+            ndk[j] = -flip * (float)(clips.clip_over_lvl[k] * (double)m);
             e2[j] = 0.0f;
         }
 #pragma unroll
@@ -455,9 +463,7 @@ __device__ __forceinline__ void qe_candidates(const float (&v)[NVAL], float m, f
             for (int j = 0; j < 4; ++j) e2[j] += dpp_f<kDppRor8>(e2[j]);
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 16, 64);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) e2[j] += __shfl_xor(e2[j], 32, 64);
+        for (int j = 0; j < 4; ++j) e2[j] = rows_sum(e2[j]);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if (kb + j < k1) emit(kb + j, e2[j]);
