@@ -182,6 +182,13 @@ def time_all_configs(torch, binding, wl):
         "roofline": {"bound": "alu", "unit": "T lane-ops/s", "achieved": 5 * ec / ms / 1e9,
                      "peak": VALU_PEAK_TLANEOPS, "frac": 5 * ec / ms / 1e9 / VALU_PEAK_TLANEOPS,
                      "note": "5 VALU lane-ops per element-candidate; two launches (row sums, reduction)"}}
+    # Algorithm 1 on the calibration tensor with quant_error as the objective (host loop, batched probes)
+    t0 = time.perf_counter()
+    n_search = 20
+    for _ in range(n_search):
+        clip_found, _, trace = binding.gbs_search(h, x, 3, 1.0 / 256)
+    res["gbs_search_calib_b3"] = {"rows": w.rows, "n": w.n, "eps": 1.0 / 256, "probes": len(trace), "clip": clip_found,
+                                  "ms_per_search": (time.perf_counter() - t0) * 1e3 / n_search}
     # hidden and FFN widths of the model families the paper evaluates (section 5), b = 4, bf16 and
     # fp16 rows, N(0, 1/4) entries, 512 MiB of input per launch; a width without a Hadamard order is
     # zero-padded to the next one (section 4.2)

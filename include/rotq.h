@@ -255,8 +255,10 @@ size_t rq_gbs_workspace(int64_t rows);
  * a = 0, b = 1, m = 1/2; iterations alternate the probes (a + m)/2 and (b + m)/2; a probe with
  * f(x) < f(m) becomes the new middle and the far bracket end moves to the old middle, otherwise
  * the bracket end on the probe's side moves to the probe; stops when b - a <= eps or after
- * max_evals evaluations of f.  Every evaluation enqueues rq_quant_error on `stream`,
- * synchronises the stream and reads one float back: a calibration call, not a hot-path call.
+ * max_evals evaluations of f.  The probes and their values are those of that loop taken one at a
+ * time; they are evaluated ahead in batches (one rq_quant_error launch covers every probe the next
+ * few steps can ask for, whatever the comparisons give), each batch followed by a synchronisation of
+ * `stream` and a read-back: a calibration call, not a hot-path call.
  *   eps          [in]  bracket width to stop at, > 0
  *   max_evals    [in]  1 .. 256
  *   workspace    [in]  DEVICE, >= rq_gbs_workspace(rows) bytes, 8-byte aligned, scratch

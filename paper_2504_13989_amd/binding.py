@@ -317,8 +317,8 @@ def quant_error(h: Hadamard, x, bits: int, clips: Sequence[float], mse=None, wor
 def gbs_search(h: Hadamard, x, bits: int, eps: float, max_evals: int = 64, workspace=None, stream=None,
                asym: bool = False):
     """rq_gbs_search (rq_gbs_search_asym with asym=True) on a CUDA tensor x [..., d]; returns
-    (clip, mse, trace) with trace a list of (probe, objective) pairs in evaluation order.
-    Synchronises the stream at every probe."""
+    (clip, mse, trace) with trace a list of (probe, objective) pairs in the algorithm's order.
+    Synchronises the stream once per batch of probes."""
     import torch
     if not x.is_cuda:
         raise ValueError("x must be a device tensor")

@@ -364,9 +364,43 @@ int rq_quant_error_asym(const rq_hadamard_t* h, const void* X, int dtype, int64_
 }
 
 size_t rq_gbs_workspace(int64_t rows) {
-    const size_t q = rq_quant_error_workspace(rows, 1);
+    const size_t q = rq_quant_error_workspace(rows, RQ_MAX_CLIPS);
     return q ? q + 256 : 0;
 }
+
+namespace {
+
+// State of Algorithm 1's inner loop (section 4.1): bracket [a, b], best point m, iteration parity.
+struct GbsState {
+    double a, b, m;
+    int it;
+    double probe() const { return (it % 2 == 0) ? (a + m) / 2 : (b + m) / 2; }
+    // the update of the listing after probing x: `better` = the probe beat the best point
+    GbsState next(double x, bool better) const {
+        GbsState n = *this;
+        if (better) {
+            if (x < m) n.b = m; else n.a = m;
+            n.m = x;
+        } else {
+            if (x < m) n.a = x; else n.b = x;
+        }
+        n.it = it + 1;
+        return n;
+    }
+};
+
+// Probes of the next `depth` steps for every outcome of the comparisons on the way, in heap order
+// (node i: children 2 i for "better", 2 i + 1 for "not better"); the positions do not depend on the
+// objective values, only on the outcomes.  x[i] < 0 marks a node the search cannot reach.
+void gbs_tree(const GbsState& st, double eps, int depth, int idx, double* x) {
+    if (depth == 0 || st.b - st.a <= eps) return;
+    const double p = st.probe();
+    x[idx] = p;
+    gbs_tree(st.next(p, true), eps, depth - 1, 2 * idx, x);
+    gbs_tree(st.next(p, false), eps, depth - 1, 2 * idx + 1, x);
+}
+
+}  // namespace
 
 static int gbs_impl(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d, int64_t ld,
                     int bits, float eps, int max_evals, void* workspace, size_t workspace_bytes,
@@ -379,42 +413,70 @@ static int gbs_impl(const rq_hadamard_t* h, const void* X, int dtype, int64_t ro
     if (!clip_out || !mse_out || !workspace || !aligned(workspace, 8)) return RQ_ERR_ARG;
     if (workspace_bytes < rq_gbs_workspace(rows)) return RQ_ERR_ARG;
     if (h->device < 0) return RQ_ERR_HIP;
-    // layout of the workspace: [0, 256) one float for the objective, then the quant_error scratch
+    // layout of the workspace: [0, 256) the objective values of one batch, then the quant_error scratch
     float* d_mse = static_cast<float*>(workspace);
     void* qws = static_cast<char*>(workspace) + 256;
     const size_t qws_bytes = workspace_bytes - 256;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    int evals = 0;
-    auto f = [&](double x, float* out) -> int {
-        const float c = (float)x;
-        int r = quant_error_impl(h, X, dtype, rows, d, ld, bits, &c, 1, d_mse, qws, qws_bytes, stream, asym);
+    // The probes of Algorithm 1 are taken in the listing's order, but evaluated ahead of time in
+    // batches: one quant_error launch covers every probe the next `depth` steps can ask for (a binary
+    // tree over the comparison outcomes), then the host walks the tree with the values.  The values
+    // and the sequence of probes are those of the one-at-a-time loop; what changes is the number of
+    // launches and stream synchronisations (each costs more than a candidate on a small tensor).
+    // Small tensors look 5 steps ahead (31 candidates), large ones 3 (7 candidates: about the work
+    // of the 3 rotations it saves).
+    const int depth = (double)rows * (double)h->f.n <= (double)(1 << 22) ? 5 : 3;
+    float vals[RQ_MAX_CLIPS];
+    float clips[RQ_MAX_CLIPS];
+    auto evaluate = [&](int count) -> int {
+        int r = quant_error_impl(h, X, dtype, rows, d, ld, bits, clips, count, d_mse, qws, qws_bytes, stream, asym);
         if (r != RQ_OK) return r;
         if (hipStreamSynchronize(s) != hipSuccess ||
-            hipMemcpy(out, d_mse, sizeof(float), hipMemcpyDeviceToHost) != hipSuccess)
+            hipMemcpy(vals, d_mse, sizeof(float) * count, hipMemcpyDeviceToHost) != hipSuccess)
             return RQ_ERR_HIP;
-        if (trace_clips) trace_clips[evals] = c;
-        if (trace_mse) trace_mse[evals] = *out;
-        ++evals;
         return RQ_OK;
     };
-    double a = 0.0, b = 1.0, m = 0.5;
+    int evals = 0;
+    auto record = [&](float c, float v) {
+        if (trace_clips) trace_clips[evals] = c;
+        if (trace_mse) trace_mse[evals] = v;
+        ++evals;
+    };
+    GbsState st{0.0, 1.0, 0.5, 0};
     float fm = 0.0f;
-    rc = f(m, &fm);
-    if (rc != RQ_OK) return rc;
-    for (int it = 0; b - a > (double)eps && evals < max_evals; ++it) {
-        const double x = (it % 2 == 0) ? (a + m) / 2 : (b + m) / 2;
-        float fx = 0.0f;
-        rc = f(x, &fx);
+    bool first = true;
+    while (first || (st.b - st.a > (double)eps && evals < max_evals)) {
+        double x[64];
+        int slot[64];
+        for (int i = 0; i < 64; ++i) x[i] = -1.0;
+        gbs_tree(st, (double)eps, depth, 1, x);
+        int count = 0;
+        if (first) clips[count++] = (float)st.m;          // the starting point rides along with the first batch
+        for (int i = 1; i < (1 << depth); ++i)
+            if (x[i] >= 0.0) {
+                slot[i] = count;
+                clips[count++] = (float)x[i];
+            }
+        if (count == 0) break;
+        rc = evaluate(count);
         if (rc != RQ_OK) return rc;
-        if (fx < fm) {
-            if (x < m) b = m; else a = m;
-            m = x;
-            fm = fx;
-        } else {
-            if (x < m) a = x; else b = x;
+        if (first) {
+            fm = vals[0];
+            record(clips[0], fm);
+            first = false;
+        }
+        int idx = 1;
+        for (int lvl = 0; lvl < depth && st.b - st.a > (double)eps && evals < max_evals; ++lvl) {
+            const double p = x[idx];
+            const float fx = vals[slot[idx]];
+            record((float)p, fx);
+            const bool better = fx < fm;
+            if (better) fm = fx;
+            st = st.next(p, better);
+            idx = 2 * idx + (better ? 0 : 1);
         }
     }
-    *clip_out = (float)m;
+    *clip_out = (float)st.m;
     *mse_out = fm;
     if (n_evals) *n_evals = evals;
     return RQ_OK;
