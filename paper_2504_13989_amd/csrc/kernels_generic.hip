@@ -1,6 +1,10 @@
-// General rotate-and-quantize kernels: one 256-thread workgroup per row, the row held in LDS
-// as fp32.  They cover every supported order p * 2^k that fits in LDS and both input types,
-// and serve as the fallback for shapes the specialised wave kernels do not handle.
+// General rotate-and-quantize kernels: one 256-thread workgroup per row, the row held in LDS.
+// They cover every supported order p * 2^k that fits in LDS and all input types, and serve as
+// the fallback for shapes the specialised wave kernels do not handle.
+// The quantizing kernels hold the row as fp32 for 16-bit inputs and as fp64 for fp32 inputs: sums of
+// 16-bit values lose next to nothing in fp32, but log2(n) fp32 butterfly stages on 24-bit inputs move a
+// rotated value by up to ~2e-7 of its size, enough to push one in a million across a rounding
+// boundary that the exact value misses by more than the 1e-6 the codes are allowed.
 //
 // Per row: load + zero-pad (section 4.2, Eq. 2) -> butterflies along the 2^k axis
 // (section 2.3.2, Eq. 1) -> dense +-1 block product along the p axis (section 2.3.3) ->
@@ -26,6 +30,10 @@ __device__ __forceinline__ float wave_max(float v) {
     for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
     return v;
 }
+__device__ __forceinline__ double wave_max(double v) {
+    for (int m = 32; m >= 1; m >>= 1) v = fmax(v, __shfl_xor(v, m, 64));
+    return v;
+}
 
 __device__ __forceinline__ double wave_sum(double v) {
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
@@ -35,14 +43,15 @@ __device__ __forceinline__ double wave_sum(double v) {
 // Transforms the row held in buf0 (n floats, already visible to the whole workgroup) in place
 // and returns the buffer that holds the un-normalised result H_n v, or H_n^T v when `transpose`
 // is set ((H_p (x) H_m)^T = H_p^T (x) H_m: only the +-1 block changes).
-__device__ float* transform_row_lds(const RowArgs& a, float* buf0, float* buf1, bool transpose) {
+template <typename T>
+__device__ T* transform_row_lds(const RowArgs& a, T* buf0, T* buf1, bool transpose) {
     const int tid = threadIdx.x;
     const int n = a.n;
     for (int s = 0; s < a.log2m; ++s) {
         const int h = 1 << s;
         for (int idx = tid; idx < n / 2; idx += kThreads) {
             const int i = ((idx >> s) << (s + 1)) | (idx & (h - 1));
-            const float u = buf0[i], v = buf0[i + h];
+            const T u = buf0[i], v = buf0[i + h];
             buf0[i] = u + v;
             buf0[i + h] = u - v;
         }
@@ -56,38 +65,48 @@ __device__ float* transform_row_lds(const RowArgs& a, float* buf0, float* buf1, 
         const int hstep = transpose ? a.p : 1;
         double acc = 0.0;
         for (int ai = 0; ai < a.p; ++ai) {
-            const float v = buf0[ai * m + c];
+            const T v = buf0[ai * m + c];
             acc += (hrow[(size_t)ai * hstep] > 0) ? (double)v : -(double)v;
         }
-        buf1[o] = (float)acc;
+        buf1[o] = (T)acc;
     }
     __syncthreads();
     return buf1;
 }
 
-__device__ void load_row_lds(const RowArgs& a, int64_t row, float* buf0) {
+template <typename T>
+__device__ void load_row_lds(const RowArgs& a, int64_t row, T* buf0) {
     const int64_t base = row * a.ld;
     for (int j = threadIdx.x; j < a.n; j += kThreads)
-        buf0[j] = (j < a.d) ? load_f32(a.X, a.dtype, base + j) : 0.0f;
+        buf0[j] = (j < a.d) ? (T)load_f32(a.X, a.dtype, base + j) : (T)0;
     __syncthreads();
 }
 
 // Rotates one row into LDS (un-normalised: y_u = H_n pad(x)) and returns the buffer that holds
 // it; also returns the row's max |y_u| in *amax (same value in every thread).
-__device__ float* rotate_row_lds(const RowArgs& a, int64_t row, float* buf0, float* buf1,
-                                 float* red, float* amax) {
+template <typename T>
+__device__ T* rotate_row_lds(const RowArgs& a, int64_t row, T* buf0, T* buf1, T* red, T* amax) {
     const int tid = threadIdx.x;
     const int n = a.n;
     load_row_lds(a, row, buf0);
-    float* y = transform_row_lds(a, buf0, buf1, false);
-    float mx = 0.0f;
-    for (int j = tid; j < n; j += kThreads) mx = fmaxf(mx, fabsf(y[j]));
+    T* y = transform_row_lds(a, buf0, buf1, false);
+    T mx = 0;
+    for (int j = tid; j < n; j += kThreads) {
+        const T v = y[j];
+        const T av = v < 0 ? -v : v;
+        mx = av > mx ? av : mx;
+    }
     mx = wave_max(mx);
     if ((tid & 63) == 0) red[tid >> 6] = mx;
     __syncthreads();
-    *amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    T r = red[0];
+    for (int w = 1; w < 4; ++w) r = red[w] > r ? red[w] : r;
+    *amax = r;
     return y;
 }
+
+__device__ __forceinline__ float round_clamp(float t, float lo, float hi) { return fminf(fmaxf(rintf(t), lo), hi); }
+__device__ __forceinline__ double round_clamp(double t, double lo, double hi) { return fmin(fmax(rint(t), lo), hi); }
 
 // Store of one result value as fp32 or bf16 (round to nearest even).
 __device__ __forceinline__ void store_out(const OutArgs& o, int64_t idx, float v) {
@@ -144,18 +163,21 @@ __global__ __launch_bounds__(kThreads) void k_generic_dequant_rotate(RowArgs a, 
         store_out(o, row * o.ld_out + j, (float)((double)y[j] * k));
 }
 
+template <typename T>
 __global__ __launch_bounds__(kThreads) void k_generic_rotate_quantize(RowArgs a, float clip,
                                                                       uint32_t* codes,
                                                                       float* scales) {
-    extern __shared__ float lds[];
-    __shared__ float red[4];
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_bytes_[];
+    T* const lds = reinterpret_cast<T*>(lds_bytes_);
+    __shared__ T red[4];
     const int64_t row = blockIdx.x;
-    float amax;
-    const float* y = rotate_row_lds(a, row, lds, lds + a.n, red, &amax);
+    T amax;
+    const T* y = rotate_row_lds<T>(a, row, lds, lds + a.n, red, &amax);
     const int bits = a.bits;
     const double lvl = (double)((1 << bits) - 1);
-    const float qmax = (float)((1 << (bits - 1)) - 1), qmin = -(float)(1 << (bits - 1));
-    const float s = amax > 0.0f ? (float)(lvl / ((double)clip * (double)amax)) : 0.0f;
+    const T qmax = (T)((1 << (bits - 1)) - 1), qmin = -(T)(1 << (bits - 1));
+    // fp32 rows: one rounding of lvl / (clip amax); fp64 rows: the quotient itself
+    const T s = amax > 0 ? (T)(lvl / ((double)clip * (double)amax)) : (T)0;
     if (threadIdx.x == 0)
         scales[row] = (float)((double)clip * (double)amax / (sqrt((double)a.n) * lvl));
     const uint32_t mask = (1u << bits) - 1u;
@@ -166,8 +188,8 @@ __global__ __launch_bounds__(kThreads) void k_generic_rotate_quantize(RowArgs a,
         for (int g = threadIdx.x; g < a.n / 8; g += kThreads) {
             uint32_t acc = 0;
             for (int e = 0; e < 8; ++e) {
-                const float t = y[g * 8 + e] * s;
-                const int q = (int)fminf(fmaxf(rintf(t), qmin), qmax);
+                const T t = y[g * 8 + e] * s;
+                const int q = (int)round_clamp(t, qmin, qmax);
                 acc |= ((uint32_t)q & mask) << (e * bits);
             }
             for (int k = 0; k < bits; ++k) outb[g * bits + k] = (uint8_t)(acc >> (8 * k));
@@ -179,8 +201,8 @@ __global__ __launch_bounds__(kThreads) void k_generic_rotate_quantize(RowArgs a,
         uint64_t acc = 0;
         int nb = 0, w = 0;
         for (int e = 0; e < 32; ++e) {
-            const float t = y[g * 32 + e] * s;
-            const int q = (int)fminf(fmaxf(rintf(t), qmin), qmax);
+            const T t = y[g * 32 + e] * s;
+            const int q = (int)round_clamp(t, qmin, qmax);
             acc |= (uint64_t)((uint32_t)q & mask) << nb;
             nb += bits;
             if (nb >= 32) {
@@ -195,24 +217,27 @@ __global__ __launch_bounds__(kThreads) void k_generic_rotate_quantize(RowArgs a,
 // Asymmetric quantization in groups of 128 rotated values (section 5.1, KV cache): per group
 // lo = clip * min, delta = clip * (max - min) / (2^b - 1), code = clamp(rne((y - lo) / delta), 0,
 // 2^b - 1).  The decision is taken in fp64 here; this kernel is the general fallback.
+template <typename T>
 __global__ __launch_bounds__(kThreads) void k_generic_rotate_quantize_asym(RowArgs a, float clip,
                                                                            uint32_t* codes,
                                                                            float* scales, float* mins) {
-    extern __shared__ float lds[];
-    __shared__ float red[4];
-    __shared__ float gmn[kMaxGroups], gmx[kMaxGroups];
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_bytes_[];
+    T* const lds = reinterpret_cast<T*>(lds_bytes_);
+    __shared__ T red[4];
+    __shared__ T gmn[kMaxGroups], gmx[kMaxGroups];
     const int64_t row = blockIdx.x;
-    float amax;
-    const float* y = rotate_row_lds(a, row, lds, lds + a.n, red, &amax);
+    T amax;
+    const T* y = rotate_row_lds<T>(a, row, lds, lds + a.n, red, &amax);
     const int bits = a.bits;
     const int n_groups = a.n / 128;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (int gi = wave; gi < n_groups; gi += kThreads / 64) {
-        const float u = y[gi * 128 + lane], v = y[gi * 128 + 64 + lane];
-        float mn = fminf(u, v), mx = fmaxf(u, v);
+        const T u = y[gi * 128 + lane], v = y[gi * 128 + 64 + lane];
+        T mn = u < v ? u : v, mx = u < v ? v : u;
         for (int m = 32; m >= 1; m >>= 1) {
-            mn = fminf(mn, __shfl_xor(mn, m, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+            const T on = __shfl_xor(mn, m, 64), ox = __shfl_xor(mx, m, 64);
+            mn = on < mn ? on : mn;
+            mx = ox > mx ? ox : mx;
         }
         if (lane == 0) {
             gmn[gi] = mn;
@@ -439,25 +464,37 @@ bool generic_supports(const rq_hadamard* h) { return h->device >= 0 && h->generi
 
 // Called once when the handle is built (never on the hot path): checks that the row fits in
 // LDS and raises the kernels' dynamic-LDS limit where the default does not cover it.
-bool generic_prepare(const rq_hadamard* h) {
+bool generic_prepare(rq_hadamard* h) {
     const size_t bytes = lds_bytes(h);
+    h->generic_f64_ok = false;
     if (bytes + 256 > (size_t)h->max_lds) return false;
     if (h->f.n % 128 == 0 && (h->f.n / 128 > kMaxGroups ||
-                              prepare(k_generic_rotate_quantize_asym, bytes) != RQ_OK))
+                              prepare(k_generic_rotate_quantize_asym<float>, bytes) != RQ_OK))
         return false;
     if (prepare(k_generic_rotate, bytes) != RQ_OK || prepare(k_generic_dequant_rotate, bytes) != RQ_OK)
         return false;
     if (h->f.n % 128 == 0 && prepare(k_generic_quant_error_asym, bytes) != RQ_OK) return false;
-    return prepare(k_generic_rotate_quantize, bytes) == RQ_OK &&
-           prepare(k_generic_quant_error, bytes) == RQ_OK;
+    if (prepare(k_generic_rotate_quantize<float>, bytes) != RQ_OK || prepare(k_generic_quant_error, bytes) != RQ_OK)
+        return false;
+    // fp32 rows are quantized from an fp64 copy of the row: twice the LDS (plus the fp64 group extremes)
+    h->generic_f64_ok = 2 * bytes + 8 * 1024 <= (size_t)h->max_lds &&
+                        prepare(k_generic_rotate_quantize<double>, 2 * bytes) == RQ_OK &&
+                        (h->f.n % 128 != 0 || prepare(k_generic_rotate_quantize_asym<double>, 2 * bytes) == RQ_OK);
+    return true;
 }
 
 int generic_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                             float* scales, hipStream_t s) {
     const size_t bytes = lds_bytes(h);
     if (a.rows > 0x7fffffffLL) return RQ_ERR_ARG;
-    hipLaunchKernelGGL(k_generic_rotate_quantize, dim3((unsigned)a.rows), dim3(kThreads), bytes, s, a,
-                       clip, codes, scales);
+    if (a.dtype == RQ_F32) {
+        if (!h->generic_f64_ok) return RQ_ERR_NO_ORDER;
+        hipLaunchKernelGGL(k_generic_rotate_quantize<double>, dim3((unsigned)a.rows), dim3(kThreads), 2 * bytes,
+                           s, a, clip, codes, scales);
+    } else {
+        hipLaunchKernelGGL(k_generic_rotate_quantize<float>, dim3((unsigned)a.rows), dim3(kThreads), bytes, s, a,
+                           clip, codes, scales);
+    }
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 
@@ -465,8 +502,14 @@ int generic_rotate_quantize_asym(const rq_hadamard* h, const RowArgs& a, float c
                                  float* scales, float* mins, hipStream_t s) {
     const size_t bytes = lds_bytes(h);
     if (a.rows > 0x7fffffffLL || a.n % 128 != 0) return RQ_ERR_ARG;
-    hipLaunchKernelGGL(k_generic_rotate_quantize_asym, dim3((unsigned)a.rows), dim3(kThreads), bytes, s,
-                       a, clip, codes, scales, mins);
+    if (a.dtype == RQ_F32) {
+        if (!h->generic_f64_ok) return RQ_ERR_NO_ORDER;
+        hipLaunchKernelGGL(k_generic_rotate_quantize_asym<double>, dim3((unsigned)a.rows), dim3(kThreads),
+                           2 * bytes, s, a, clip, codes, scales, mins);
+    } else {
+        hipLaunchKernelGGL(k_generic_rotate_quantize_asym<float>, dim3((unsigned)a.rows), dim3(kThreads), bytes,
+                           s, a, clip, codes, scales, mins);
+    }
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 

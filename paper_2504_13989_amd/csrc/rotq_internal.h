@@ -20,6 +20,7 @@ struct rq_hadamard {
     bool wg_ok = false;              // the workgroup block kernel is usable for this order
     bool dense_ok = false;           // d_tiles holds the whole matrix for the dense-block kernel
     bool generic_ok = false;         // the general LDS kernel can hold a row of this order
+    bool generic_f64_ok = false;     // ... and an fp64 copy of it (how fp32 rows are quantized)
     int variant = 0;                 // 0 auto, 1 general LDS kernel
     int split = 0;                   // long Sylvester rows: 0 auto, 2 / 4 waves per row, -1 never split
     const char* last_kernel = "";
@@ -75,7 +76,7 @@ bool plain_wave_supports(const void* X, int dtype, int d, int64_t ld);
 int plain_wave_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
                         uint32_t* codes, float* scales, hipStream_t s);
 bool generic_supports(const rq_hadamard* h);
-bool generic_prepare(const rq_hadamard* h);
+bool generic_prepare(rq_hadamard* h);
 
 // Wave-per-row kernels (bf16 rows, Sylvester orders 128 .. 8192, 16-byte aligned rows).
 std::vector<uint32_t> wave_sylvester_tiles();
