@@ -268,3 +268,23 @@ def test_stream_reference_moves_the_stated_bytes(torch, n, rows, b):
     if b == 3:
         fold = fold.reshape(rows, n // 32, 4)[:, :, :3].reshape(rows, -1)
     assert np.array_equal(got[:rows].view(np.uint32).reshape(rows, -1), fold)
+
+
+@pytest.mark.parametrize("name", ["llama_hidden", "qwen_hidden"])
+def test_full_size_fp16(torch, name):
+    # the configuration's rows on the fp16 grid with all 11 mantissa bits in use (the bf16 values
+    # jittered by 0.2 %), every row compared: 8 and 15 million codes
+    w = wl.WORKLOADS[name]
+    xb = wl.generate(w)
+    xf = (xb.astype(np.uint32) << 16).view(np.float32)
+    rng = np.random.default_rng(5)
+    x = np.clip(xf * (1 + rng.uniform(-2e-3, 2e-3, size=xf.shape).astype(np.float32)), -6e4, 6e4).astype(np.float16)
+    h = handle(w.n)
+    xt = parity.to_device(x)
+    b = w.bits[0]
+    say(f"full fp16 {name} [{w.rows} x {w.d}] b={b}")
+    codes, scales = binding.rotate_quantize(h, xt, b, w.clip)
+    torch.cuda.synchronize()
+    st = parity.check_rotate_quantize(x, w.n, b, w.clip, codes.cpu().numpy(), scales.cpu().numpy(),
+                                      f"{name} fp16 full [{h.last_kernel}]")
+    say(f"  ok kernel={h.last_kernel} {st}")
