@@ -1,6 +1,7 @@
 // Workgroup block kernel: bf16 rows of order n = pb * 128 with a +-1 block of order
 // 32 < pb <= 256 along the strided axis (H_n = B (x) H_128, B = H_p (x) H_{2^(k-7)}; sections
-// 2.3.2, 2.3.3) - e.g. 18944 = 148 * 128 with the order-148 Paley II block.
+// 2.3.2, 2.3.3) - e.g. 18944 = 148 * 128 with the order-148 Paley II block; also the Sylvester
+// orders 2^14 and 2^15, which are too long for one wave (B = H_128, H_256).
 //
 // The dense block product Y1[pb x 128] = B * X[pb x 128] is a real contraction (pb adds per
 // output), so it runs on the matrix cores.  NW = ceil(pb / 16) waves share a row, wave w owning
@@ -418,7 +419,13 @@ bool wg_block_prepare(int pb) {
 // columns; 3, 2: block rows of 64 / 32 columns, several rows of X per pass).  False when the order
 // is not served by this kernel.
 static bool wg_shape(const RowArgs& a, int* pb, int* cb) {
-    if (a.p == 1) return false;
+    if (a.p == 1) {
+        // Sylvester orders beyond the one-wave kernel (2^14, 2^15): the block is H_128 / H_256 itself
+        if (a.log2m < 14 || a.log2m > 15) return false;
+        *pb = 1 << (a.log2m - 7);
+        *cb = 4;
+        return true;
+    }
     if (a.log2m >= 7) {
         *pb = a.p << (a.log2m - 7);
         *cb = 4;

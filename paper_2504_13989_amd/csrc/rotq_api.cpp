@@ -67,7 +67,9 @@ int rq_hadamard_build(int n, rq_hadamard_t** out) {
         return RQ_ERR_HIP;
     }
     const bool sylv = f.p == 1 && f.log2m >= 7 && f.log2m <= 13;
-    const bool blk = f.p > 1 && f.log2m >= 7 && (f.p << (f.log2m - 7)) <= 256;
+    // block orders of the block kernels; the Sylvester orders 2^14, 2^15 ride along with p = 1
+    const bool blk = (f.p > 1 && f.log2m >= 7 && (f.p << (f.log2m - 7)) <= 256) ||
+                     (f.p == 1 && (f.log2m == 14 || f.log2m == 15));
     const bool blk_short = f.p > 1 && (f.log2m == 5 || f.log2m == 6) && f.p <= 256;   // block rows of 32 / 64
     const bool dense = !sylv && !blk && !blk_short && n <= 4096;
     if (sylv || blk || blk_short || dense) {

@@ -27,9 +27,15 @@ def to_device(x_np, device="cuda"):
     return torch.from_numpy(x_np).to(device)
 
 
-def check_rotate_quantize(x_np, n, b, clip, codes_gpu, scales_gpu, what=""):
-    """x_np: the rows given to the GPU; codes_gpu uint8 [rows, n*b/8]; scales_gpu float32 [rows]."""
-    q, delta, t, y = oracle.rotate_quantize(x_np, n, b, clip)
+def check_rotate_quantize(x_np, n, b, clip, codes_gpu, scales_gpu, what="", rotated=None):
+    """x_np: the rows given to the GPU; codes_gpu uint8 [rows, n*b/8]; scales_gpu float32 [rows].
+    rotated: the oracle's rotated rows when the caller has formed them another way (orders whose
+    dense matrix is too large to build in one piece)."""
+    if rotated is None:
+        q, delta, t, y = oracle.rotate_quantize(x_np, n, b, clip)
+    else:
+        y = rotated
+        q, delta, t = oracle.quantize(y, b, clip)
     rows = q.shape[0]
     codes_gpu = np.asarray(codes_gpu).reshape(rows, n * b // 8)
     scales_gpu = np.asarray(scales_gpu, dtype=np.float64).reshape(rows)

@@ -121,6 +121,42 @@ def test_short_sylvester_factor_blocks(torch, n, d, rows, dtype):
         say(f"  ok {st}")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_sylvester_orders_beyond_one_wave(torch, dtype):
+    # n = 2^14 and 2^15 run on the block kernel with B = H_128 / H_256.  The oracle for 2^14 is the
+    # dense product as always; for 2^15 the dense matrix (8 GiB as int64) is not built: Sylvester's
+    # recursion (section 2.3.2, Eq. 1) H_2n = [[H_n, H_n], [H_n, -H_n]] is written out on the two
+    # halves of the row with the oracle's own H_{2^14}.
+    hs = oracle.sylvester(14).astype(np.float64)
+    for n, d, rows in ((1 << 14, 1 << 14, 19), (1 << 14, 16000, 3), (1 << 15, 1 << 15, 11), (1 << 15, 30000, 4)):
+        rng = np.random.default_rng(n + d)
+        xf = rng.standard_t(3.0, size=(rows, d)).astype(np.float32)
+        xf[:, rng.choice(d, 3, replace=False)] *= 40
+        x = wl.f32_to_bf16_bits(xf) if dtype == "bf16" else xf.astype(np.float16)
+        xp = np.zeros((rows, n))
+        xp[:, :d] = oracle.as_f64(x)
+        if n == 1 << 14:
+            y = xp @ hs.T / np.sqrt(n)
+        else:
+            a, bb = xp[:, : n // 2] @ hs.T, xp[:, n // 2:] @ hs.T
+            y = np.concatenate([a + bb, a - bb], axis=1) / np.sqrt(n)
+        for b in (3, 4):
+            say(f"long sylvester n={n} d={d} {dtype} b={b}")
+            codes, scales, kern = run_rq(torch, x, n, b, 0.9)
+            assert kern == "wg_block"
+            st = parity.check_rotate_quantize(x, n, b, 0.9, codes, scales, f"n={n} d={d} {dtype} b={b}", rotated=y)
+            say(f"  ok {st}")
+    h = handle(1 << 14)
+    clips = [0.6, 0.9, 1.0]
+    xq = wl.f32_to_bf16_bits(np.random.default_rng(3).standard_normal((9, 1 << 14)).astype(np.float32))
+    mse = binding.quant_error(h, parity.to_device(xq), 3, clips)
+    torch.cuda.synchronize()
+    assert h.last_kernel == "wg_block_quant_error"
+    yq = oracle.as_f64(xq) @ hs.T / np.sqrt(1 << 14)
+    want = [np.mean((oracle.dequantize(*oracle.quantize(yq, 3, c)[:2]) - yq) ** 2) for c in clips]
+    assert np.allclose(mse.cpu().numpy(), want, rtol=1e-5, atol=0)
+
+
 @pytest.mark.parametrize("variant", [2, 3, 4], ids=["one_wave", "split2", "split4"])
 @pytest.mark.parametrize("n,d", [(2048, 2048), (4096, 4096), (4096, 4000), (8192, 8192), (8192, 6000)])
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
