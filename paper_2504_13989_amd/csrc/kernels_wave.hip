@@ -339,22 +339,6 @@ __global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
 // loads into one operand (a 16-bit transpose inside the lane, v_perm_b32).  Outputs come back
 // with 8 block rows x 8 consecutive columns per lane; butterflies over i (registers) and c
 // (DPP), quantization and packing then work exactly as in the Sylvester kernel.
-// The four fused cross-lane stages on N (1..4) consecutive values.
-template <int N>
-__device__ __forceinline__ void fused_group(float* v, const float (&sf)[4]) {
-    if constexpr (N == 4) {
-        f32x4 q = {v[0], v[1], v[2], v[3]};
-        lane_stages_fused(q, sf[0], sf[1], sf[2], sf[3]);
-        v[0] = q[0]; v[1] = q[1]; v[2] = q[2]; v[3] = q[3];
-    } else if constexpr (N == 3) {
-        lane_stages_fused3(v[0], v[1], v[2], sf[0], sf[1], sf[2], sf[3]);
-    } else if constexpr (N == 2) {
-        lane_stages_fused2(v[0], v[1], sf[0], sf[1], sf[2], sf[3]);
-    } else {
-        lane_stages_fused1(v[0], sf[0], sf[1], sf[2], sf[3]);
-    }
-}
-
 // The rotation of one row for the block kernels: loads, block product on the matrix cores, the
 // 128-point transform along the columns.  y[column i][j]: register j = 4 h + ip holds block rows
 // 4 j .. 4 j + 3 (one per DPP row g); only the NV = ceil(pb / 4) registers that hold real block rows

@@ -100,6 +100,17 @@ int rq_hadamard_build(int n, rq_hadamard_t** out) {
             tiles = pb <= 32 ? rq::wave_block_tiles(bm, pb) : rq::wg_block_tiles(bm, pb);
             if (pb > 32) h->wg_ok = rq::wg_block_prepare(pb);
             f16_table = true;
+            if (pb > 32 && pb <= 64) {
+                // these blocks also have a one-wave kernel (rotate_quantize), with operand tiles of its own
+                const std::vector<uint32_t> t2 = rq::wave_block2_tiles(bm, pb), t2h = rq::tiles_to_f16(t2);
+                const size_t b2 = t2.size() * sizeof(uint32_t);
+                if (hipMalloc(&h->d_tiles2, b2) != hipSuccess || hipMalloc(&h->d_tiles2_f16, b2) != hipSuccess ||
+                    hipMemcpy(h->d_tiles2, t2.data(), b2, hipMemcpyHostToDevice) != hipSuccess ||
+                    hipMemcpy(h->d_tiles2_f16, t2h.data(), b2, hipMemcpyHostToDevice) != hipSuccess) {
+                    rq_hadamard_free(h);
+                    return RQ_ERR_HIP;
+                }
+            }
         }
         const size_t tb = tiles.size() * sizeof(uint32_t);
         if (hipMalloc(&h->d_tiles, tb) != hipSuccess ||
@@ -127,6 +138,8 @@ void rq_hadamard_free(rq_hadamard_t* h) {
     if (h->d_block) (void)hipFree(h->d_block);
     if (h->d_tiles) (void)hipFree(h->d_tiles);
     if (h->d_tiles_f16) (void)hipFree(h->d_tiles_f16);
+    if (h->d_tiles2) (void)hipFree(h->d_tiles2);
+    if (h->d_tiles2_f16) (void)hipFree(h->d_tiles2_f16);
     delete h;
 }
 
@@ -189,6 +202,10 @@ int rq_rotate_quantize(const rq_hadamard_t* h, const void* X, int dtype, int64_t
     if (h->variant == 0 && rq::wave_block_supports(h, a)) {
         hm->last_kernel = "wave_block";
         return rq::wave_block_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
+    }
+    if (h->variant == 0 && rq::wave_block2_supports(h, a)) {
+        hm->last_kernel = "wave_block";
+        return rq::wave_block2_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
     }
     if (h->variant == 0 && rq::wg_block_supports(h, a)) {
         hm->last_kernel = "wg_block";

@@ -314,6 +314,22 @@ __device__ __forceinline__ void copy_out16(const uint8_t* stage, uint32_t* out, 
 // Packed codes are written once and not read back by this kernel: non-temporal store.
 __device__ __forceinline__ void store_codes(uint32_t* p, uint32_t v) { __builtin_nontemporal_store(v, p); }
 
+// The four fused cross-lane stages on N (1..4) consecutive values.
+template <int N>
+__device__ __forceinline__ void fused_group(float* v, const float (&sf)[4]) {
+    if constexpr (N == 4) {
+        f32x4 q = {v[0], v[1], v[2], v[3]};
+        lane_stages_fused(q, sf[0], sf[1], sf[2], sf[3]);
+        v[0] = q[0]; v[1] = q[1]; v[2] = q[2]; v[3] = q[3];
+    } else if constexpr (N == 3) {
+        lane_stages_fused3(v[0], v[1], v[2], sf[0], sf[1], sf[2], sf[3]);
+    } else if constexpr (N == 2) {
+        lane_stages_fused2(v[0], v[1], sf[0], sf[1], sf[2], sf[3]);
+    } else {
+        lane_stages_fused1(v[0], sf[0], sf[1], sf[2], sf[3]);
+    }
+}
+
 // Max over the four DPP rows of a wave (lanes l, l ^ 16, l ^ 32, l ^ 48) with the row-swap
 // instructions: v_permlane16_swap(a, b) returns rows [a0 b0 a2 b2] and [a1 b1 a3 b3],
 // v_permlane32_swap(a, b) returns [a0 a1 b0 b1] and [a2 a3 b2 b3]; no LDS traffic.

@@ -179,7 +179,7 @@ def test_half_precision_input(torch, n, d):
         say(f"  ok kernel={h.last_kernel} {st}")
         # the wave kernels take fp16 directly (fp16 matrix-core instruction, fp16 operand tiles)
         want = {128: "wave_sylvester", 4096: "wave_sylvester", 3584: "wave_block", 3072: "wave_block",
-                148 * 128: "wg_block", 5120: "wg_block", 44 * 256: "wg_block"}.get(n)
+                148 * 128: "wg_block", 5120: "wave_block", 44 * 256: "wg_block"}.get(n)
         if want and d % 8 == 0:
             assert h.last_kernel == want
     clips = [0.6, 0.85, 1.0]
