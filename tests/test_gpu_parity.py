@@ -75,6 +75,9 @@ def test_small_cases(torch, name, rows, variant):
                                        (2048, 2048, "bf16"), (8192, 8192, "bf16"), (512, 512, "bf16"),
                                        (640, 640, "bf16"), (64, 64, "bf16"), (32, 20, "f32"),
                                        (2560, 2560, "bf16"), (2560, 2400, "bf16"), (5120, 5120, "bf16"),
+                                       # blocks of 33 .. 64 on one wave: 36, 40, 48, 56
+                                       (36 * 128, 36 * 128, "bf16"), (36 * 128, 4000, "bf16"), (5120, 5000, "bf16"),
+                                       (48 * 128, 48 * 128, "bf16"), (56 * 128, 7000, "bf16"),
                                        # blocks above 32: 44 (q=43), 60 (II, q=29), 84, 108, 168, 200, 252
                                        (44 * 128, 44 * 128, "bf16"), (60 * 128, 7600, "bf16"),
                                        (84 * 128, 84 * 128, "bf16"), (108 * 128, 108 * 128, "bf16"),

@@ -160,7 +160,8 @@ def test_gbs_search_asym_follows_algorithm_1(torch):
 
 
 @pytest.mark.parametrize("n,d", [(128, 128), (256, 200), (4096, 4096), (3584, 3584), (3072, 3000), (1544, 1544),
-                                 (148 * 128, 148 * 128), (96, 96), (5120, 5120), (44 * 256, 11008)])
+                                 (148 * 128, 148 * 128), (96, 96), (5120, 5120), (44 * 256, 11008),
+                                 (36 * 128, 4600), (60 * 128, 60 * 128)])
 def test_half_precision_input(torch, n, d):
     # IEEE fp16 rows (the paper's models run in FP16): every entry point that reads X
     rng = np.random.default_rng(n + d)
@@ -179,7 +180,8 @@ def test_half_precision_input(torch, n, d):
         say(f"  ok kernel={h.last_kernel} {st}")
         # the wave kernels take fp16 directly (fp16 matrix-core instruction, fp16 operand tiles)
         want = {128: "wave_sylvester", 4096: "wave_sylvester", 3584: "wave_block", 3072: "wave_block",
-                148 * 128: "wg_block", 5120: "wave_block", 44 * 256: "wg_block"}.get(n)
+                148 * 128: "wg_block", 5120: "wave_block", 44 * 256: "wg_block", 36 * 128: "wave_block",
+                60 * 128: "wave_block"}.get(n)
         if want and d % 8 == 0:
             assert h.last_kernel == want
     clips = [0.6, 0.85, 1.0]
