@@ -101,6 +101,7 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
     u32x4 A[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) A[kk] = a.tiles[(wave * KK + kk) * 64 + lane];
+    const float c1h = (float)a.c1, c1l = (float)(a.c1 - (double)c1h);
     // CB < 4: the first lane stage is the plain one, the fused ones start at the second bit
     const float flip = (__builtin_popcount(CB == 4 ? c : cl >> 1) & 1) ? -1.0f : 1.0f;
     const uint32_t sg0 = (c & 1) ? 0x80000000u : 0u;
@@ -230,7 +231,8 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
             }
             continue;
         }
-        const float s = m > 0.0f ? flip * (float)(a.c1 / (double)m) : 0.0f;
+        // (2^b - 1) / (clip m) from a float pair of the constant: reciprocal, Newton step, correction
+        const float s = m > 0.0f ? flip * div_pair(c1h, c1l, m) : 0.0f;
         uint32_t* out = a.codes + row * (int64_t)(SEG * BITS / 32) * pb;   // used by live lanes only
 #pragma unroll
         for (int ip = 0; ip < 4; ++ip) {
