@@ -126,6 +126,17 @@ def time_all_configs(torch, binding, wl):
     res[f"kv_k_asym_b{b}"] = {"n": w.n, "d": w.d, "bits": b, "rows": int(x.shape[0]), "us": ms * 1e3,
                               "GBps": gbps, "frac_hbm_peak": gbps / HBM_PEAK_GBPS, "kernel": h.last_kernel}
     del x, codes, scales, mins
+    # rotation alone (the query heads carry the same per-head H_128 as the keys): bf16 in, bf16 out
+    w = wl.WORKLOADS["kv_k"]
+    x = torch.from_numpy(wl.generate(w.with_rows(2048)).view(np.int16)).cuda().view(torch.bfloat16)
+    x = x.repeat(w.rows // 2048, 1)
+    h = binding.hadamard_build(w.n)
+    y = torch.empty_like(x)
+    ms = _min_ms(torch, lambda: binding.rotate(h, x, out=y))
+    gbps = x.shape[0] * 4 * w.d / ms / 1e6
+    res["rotate_heads_bf16"] = {"n": w.n, "rows": int(x.shape[0]), "us": ms * 1e3, "GBps": gbps,
+                                "frac_hbm_peak": gbps / HBM_PEAK_GBPS, "kernel": h.last_kernel}
+    del x, y
     w = wl.WORKLOADS["llama_hidden"]
     x = torch.from_numpy(wl.generate(w).view(np.int16)).cuda().view(torch.bfloat16).repeat(64, 1)
     codes = torch.empty((x.shape[0], w.d * 4 // 8), dtype=torch.uint8, device="cuda")

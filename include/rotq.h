@@ -48,7 +48,7 @@ extern "C" {
 
 #define RQ_BF16 0             /* X elements are bfloat16 (2 bytes) */
 #define RQ_F32  1             /* X elements are float (4 bytes) */
-#define RQ_F16  2             /* X elements are IEEE half precision (2 bytes); inputs only */
+#define RQ_F16  2             /* IEEE half precision (2 bytes): rows of X, and results of rq_rotate / rq_dequantize_rotate */
 
 #define RQ_KIND_SYLVESTER 0
 #define RQ_KIND_PALEY1    1
@@ -175,14 +175,17 @@ int rq_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld,
 
 /*
  * Rotation alone with a floating-point result: Y = (H_n pad(x) / sqrt(n))[:d_out] for every row,
- * or with H_n^T when transpose = 1.  Two uses:
+ * or with H_n^T when transpose = 1.  Three uses:
+ *   - the online rotation of a tensor that is not quantized afterwards (section 2.2: the part of
+ *     the rotations that "needs to be done at inference"), e.g. the query heads, which must carry
+ *     the same per-head rotation as the keys that go into the quantized cache;
  *   - offline weight fusion (section 4.2, Eq. 2): W' = H_n pad(W) / sqrt(n) is this call on the
  *     rows of W^T (input side) or of W (output side), so that rotate(x) W' = x W;
  *   - the inverse rotation x = H_n^T y / sqrt(n) (H_n^T H_n = n I, section 2.3) with
  *     transpose = 1 and d_out = the un-padded width.
  *   X        [in]  DEVICE, rows x d, leading dimension ld, `dtype` (as rq_rotate_quantize)
- *   Y        [out] DEVICE, rows x d_out elements of out_dtype (RQ_F32, or RQ_BF16 rounded to
- *                  nearest even), leading dimension ld_out >= d_out; 1 <= d_out <= n
+ *   Y        [out] DEVICE, rows x d_out elements of out_dtype (RQ_F32, or RQ_BF16 / RQ_F16 rounded
+ *                  to nearest even), leading dimension ld_out >= d_out; 1 <= d_out <= n
  * rows == 0 is a successful no-op.
  * Errors: RQ_ERR_ARG, RQ_ERR_NO_ORDER (the row does not fit the kernel's LDS), RQ_ERR_HIP.
  */

@@ -238,7 +238,9 @@ def _out_code(torch, dtype):
         return RQ_F32
     if dtype == torch.bfloat16:
         return RQ_BF16
-    raise ValueError("output dtype must be float32 or bfloat16")
+    if dtype == torch.float16:
+        return RQ_F16
+    raise ValueError("output dtype must be float32, bfloat16 or float16")
 
 
 def rotate(h: Hadamard, x, transpose: bool = False, d_out: Optional[int] = None, out_dtype=None,

@@ -113,6 +113,8 @@ __device__ __forceinline__ void store_out(const OutArgs& o, int64_t idx, float v
     if (o.dtype == RQ_BF16) {
         const uint32_t u = __float_as_uint(v);
         static_cast<uint16_t*>(o.Y)[idx] = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+    } else if (o.dtype == RQ_F16) {
+        static_cast<_Float16*>(o.Y)[idx] = (_Float16)v;
     } else {
         static_cast<float*>(o.Y)[idx] = v;
     }

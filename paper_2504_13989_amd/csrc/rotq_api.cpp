@@ -272,15 +272,19 @@ int rq_rotate(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, in
               int transpose, void* Y, int out_dtype, int d_out, int64_t ld_out, void* stream) {
     int rc = check_rows(h, X, dtype, rows, d, ld, 4);
     if (rc != RQ_OK) return rc;
-    if (out_dtype != RQ_BF16 && out_dtype != RQ_F32) return RQ_ERR_ARG;
+    if (out_dtype != RQ_BF16 && out_dtype != RQ_F32 && out_dtype != RQ_F16) return RQ_ERR_ARG;
     if (d_out < 1 || d_out > h->f.n || ld_out < d_out || (transpose != 0 && transpose != 1))
         return RQ_ERR_ARG;
     if (rows == 0) return RQ_OK;
-    if (!Y || !aligned(Y, out_dtype == RQ_BF16 ? 2 : 4)) return RQ_ERR_ARG;
+    if (!Y || !aligned(Y, out_dtype == RQ_F32 ? 4 : 2)) return RQ_ERR_ARG;
     if (h->device < 0) return RQ_ERR_HIP;
-    if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
     const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, 4);
     const rq::OutArgs o{Y, out_dtype, d_out, ld_out};
+    if (h->variant == 0 && rq::wave_rotate_supports(h, a, o)) {      // Sylvester orders: H is symmetric
+        const_cast<rq_hadamard*>(h)->last_kernel = "wave_rotate";
+        return rq::wave_rotate(h, a, o, static_cast<hipStream_t>(stream));
+    }
+    if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
     const_cast<rq_hadamard*>(h)->last_kernel = "generic_rotate";
     return rq::generic_rotate(h, a, transpose, o, static_cast<hipStream_t>(stream));
 }
@@ -289,13 +293,13 @@ int rq_dequantize_rotate(const rq_hadamard_t* h, const void* codes, const float*
                          const float* mins, int64_t rows, int bits, int transpose, void* Y,
                          int out_dtype, int d_out, int64_t ld_out, void* stream) {
     if (!h || rows < 0 || (bits != 3 && bits != 4)) return RQ_ERR_ARG;
-    if (out_dtype != RQ_BF16 && out_dtype != RQ_F32) return RQ_ERR_ARG;
+    if (out_dtype != RQ_BF16 && out_dtype != RQ_F32 && out_dtype != RQ_F16) return RQ_ERR_ARG;
     if (d_out < 1 || d_out > h->f.n || ld_out < d_out || (transpose != 0 && transpose != 1))
         return RQ_ERR_ARG;
     if (mins && h->f.n % RQ_GROUP != 0) return RQ_ERR_ARG;
     if (rows == 0) return RQ_OK;
     if (!codes || !scales || !Y || !aligned(codes, 4) || !aligned(scales, 4) || !aligned(mins, 4) ||
-        !aligned(Y, out_dtype == RQ_BF16 ? 2 : 4))
+        !aligned(Y, out_dtype == RQ_F32 ? 4 : 2))
         return RQ_ERR_ARG;
     if (h->device < 0) return RQ_ERR_HIP;
     if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;

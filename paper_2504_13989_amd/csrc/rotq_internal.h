@@ -114,6 +114,10 @@ bool wave_block2_supports(const rq_hadamard* h, const RowArgs& a);
 int wave_block2_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                                 float* scales, hipStream_t s);
 
+// Rotation alone on the wave path: 16-bit rows of Sylvester order 128 .. 8192, 16-byte aligned rows in and out.
+bool wave_rotate_supports(const rq_hadamard* h, const RowArgs& a, const OutArgs& o);
+int wave_rotate(const rq_hadamard* h, const RowArgs& a, const OutArgs& o, hipStream_t s);
+
 // Dense-block kernel: bf16 rows, any order n <= 4096 that the wave kernels do not serve (the whole
 // matrix on the matrix cores), e.g. 1544 as one Paley block.
 std::vector<uint32_t> dense_block_tiles(const std::vector<int8_t>& hm, int n);

@@ -126,3 +126,45 @@ def test_dequantize_rotate_asym(torch, name, rows, b):
     torch.cuda.synchronize()
     want = oracle.rotate_back(oracle.dequantize_asym(q, d32.astype(np.float64), l32.astype(np.float64)), w.n, w.d)
     parity.check_float_rows(out.cpu().numpy(), want, what=f"{name} asym inverse")
+
+
+@pytest.mark.parametrize("n,d,rows", [(128, 128, 1029), (128, 96, 7), (256, 256, 333), (512, 400, 65), (1024, 1024, 40),
+                                      (2048, 2000, 9), (4096, 4096, 77), (8192, 8192, 5)])
+@pytest.mark.parametrize("in_dtype", ["bf16", "f16"])
+def test_rotate_on_the_wave_path(torch, n, d, rows, in_dtype):
+    # Sylvester orders, 16-bit rows: the online rotation without a quantizer (e.g. the query heads),
+    # every output type, a narrower output, a leading dimension beyond the width
+    rng = np.random.default_rng(n + d + rows)
+    xf = rng.standard_t(4.0, size=(rows, d + 8)).astype(np.float32)
+    xf[:, 3] *= 30
+    full = wl.f32_to_bf16_bits(xf) if in_dtype == "bf16" else xf.astype(np.float16)
+    x = np.ascontiguousarray(full[:, :d])
+    h = handle(n)
+    xt = parity.to_device(full)[:, :d]
+    want = oracle.rotate(x, n)
+    for out_dtype, tol_bits in ((torch.float32, None), (torch.bfloat16, 8), (torch.float16, 11)):
+        say(f"wave rotate n={n} d={d} rows={rows} {in_dtype} -> {out_dtype}")
+        y = binding.rotate(h, xt, out_dtype=out_dtype)
+        torch.cuda.synchronize()
+        assert h.last_kernel == "wave_rotate"
+        got = y.double().cpu().numpy()
+        amax = np.abs(want).max(axis=1, keepdims=True)
+        if tol_bits is None:
+            parity.check_float_rows(y.cpu().numpy(), want, what=f"n={n} f32")
+        else:
+            # one rounding to the output format on top of the fp32 result
+            err = np.abs(got - want)
+            assert np.all(err <= np.abs(want) * 2.0 ** -tol_bits + 1e-5 * amax + (6.2e-5 if tol_bits == 11 else 0.0)), \
+                f"n={n} {out_dtype}: {err.max()}"
+    # narrower output and a padded output row
+    d_out = max(8, (d // 2) // 8 * 8)
+    buf = torch.full((rows, d_out + 16), 7.0, dtype=torch.float32, device="cuda")
+    binding.rotate(h, xt, d_out=d_out, out=buf[:, :d_out])
+    torch.cuda.synchronize()
+    assert h.last_kernel == "wave_rotate"
+    parity.check_float_rows(buf[:, :d_out].cpu().numpy(), want[:, :d_out], what=f"n={n} d_out={d_out}")
+    assert bool((buf[:, d_out:] == 7.0).all())
+    # H is symmetric for these orders: the transposed product is the same
+    yt = binding.rotate(h, xt, transpose=True)
+    torch.cuda.synchronize()
+    parity.check_float_rows(yt.cpu().numpy(), want, what=f"n={n} transposed")
