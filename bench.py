@@ -126,6 +126,19 @@ def time_all_configs(torch, binding, wl):
     res[f"kv_k_asym_b{b}"] = {"n": w.n, "d": w.d, "bits": b, "rows": int(x.shape[0]), "us": ms * 1e3,
                               "GBps": gbps, "frac_hbm_peak": gbps / HBM_PEAK_GBPS, "kernel": h.last_kernel}
     del x, codes, scales, mins
+    # asymmetric group-128 quantizer without a rotation (the value cache: its rotation is fused upstream)
+    w = wl.WORKLOADS["kv_v"]
+    x = torch.from_numpy(wl.generate(w.with_rows(2048)).view(np.int16)).cuda().view(torch.bfloat16)
+    x = x.repeat(w.rows // 2048, 1)
+    b = w.bits[0]
+    codes = torch.empty((x.shape[0], w.d * b // 8), dtype=torch.uint8, device="cuda")
+    scales = torch.empty((x.shape[0], 1), dtype=torch.float32, device="cuda")
+    mins = torch.empty((x.shape[0], 1), dtype=torch.float32, device="cuda")
+    ms = _min_ms(torch, lambda: binding.quantize_asym(x, b, w.clip, codes=codes, scales=scales, mins=mins))
+    gbps = x.shape[0] * (2 * w.d + w.d * b / 8 + 8) / ms / 1e6
+    res[f"kv_v_plain_asym_b{b}"] = {"d": w.d, "bits": b, "rows": int(x.shape[0]), "us": ms * 1e3, "GBps": gbps,
+                                    "frac_hbm_peak": gbps / HBM_PEAK_GBPS, "kernel": "plain_quantize_asym"}
+    del x, codes, scales, mins
     # rotation alone (the query heads carry the same per-head H_128 as the keys): bf16 in, bf16 out
     w = wl.WORKLOADS["kv_k"]
     x = torch.from_numpy(wl.generate(w.with_rows(2048)).view(np.int16)).cuda().view(torch.bfloat16)

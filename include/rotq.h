@@ -174,6 +174,22 @@ int rq_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld,
                 int bits, float clip, void* codes, float* scales, void* stream);
 
 /*
+ * The asymmetric group quantizer of rq_rotate_quantize_asym on the rows as they are, without a
+ * rotation (section 5.1 for a tensor whose rotation is fused into the producing weights, e.g. the
+ * value cache): per group of RQ_GROUP consecutive values lo = clip * min, hi = clip * max,
+ * Delta = (hi - lo) / (2^b - 1), code = clamp(round((x - lo) / Delta), 0, 2^b - 1).
+ *   X       [in]  DEVICE, rows x d elements of `dtype`, leading dimension ld >= d
+ *   d       [in]  row width, a multiple of RQ_GROUP
+ *   codes   [out] DEVICE, rows * d * bits / 8 bytes, 4-byte aligned (unsigned fields, same bit stream)
+ *   scales  [out] DEVICE, rows * d / RQ_GROUP floats: Delta of each group
+ *   mins    [out] DEVICE, rows * d / RQ_GROUP floats: lo of each group
+ * Runs on the current device.  rows == 0 is a successful no-op.
+ * Errors: RQ_ERR_ARG, RQ_ERR_HIP.
+ */
+int rq_quantize_asym(const void* X, int dtype, int64_t rows, int d, int64_t ld,
+                     int bits, float clip, void* codes, float* scales, float* mins, void* stream);
+
+/*
  * Rotation alone with a floating-point result: Y = (H_n pad(x) / sqrt(n))[:d_out] for every row,
  * or with H_n^T when transpose = 1.  Three uses:
  *   - the online rotation of a tensor that is not quantized afterwards (section 2.2: the part of

@@ -47,6 +47,7 @@ def lib() -> C.CDLL:
     L.rq_rotate_quantize.argtypes = [vp, vp, i32, i64, i32, i64, i32, C.c_float, vp, vp, vp]
     L.rq_rotate_quantize_asym.argtypes = [vp, vp, i32, i64, i32, i64, i32, C.c_float, vp, vp, vp, vp]
     L.rq_quantize.argtypes = [vp, i32, i64, i32, i64, i32, C.c_float, vp, vp, vp]
+    L.rq_quantize_asym.argtypes = [vp, i32, i64, i32, i64, i32, C.c_float, vp, vp, vp, vp]
     L.rq_rotate.argtypes = [vp, vp, i32, i64, i32, i64, i32, vp, i32, i32, i64, vp]
     L.rq_stream_reference.argtypes = [vp, i64, i32, i64, i32, vp, vp, vp]
     L.rq_dequantize_rotate.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, i32, i32, i64, vp]
@@ -213,6 +214,28 @@ def quantize(x, bits: int, clip: float, codes=None, scales=None, stream=None):
                            C.c_void_p(scales.data_ptr()), _stream_ptr(stream))
     _check(rc, "rq_quantize")
     return codes, scales
+
+
+def quantize_asym(x, bits: int, clip: float, codes=None, scales=None, mins=None, stream=None):
+    """rq_quantize_asym (no rotation, asymmetric groups of 128) on a CUDA tensor x [..., d]; returns
+    (codes uint8 [rows, d*bits/8], scales float32 [rows, d/128], mins float32 [rows, d/128])."""
+    import torch
+    if not x.is_cuda:
+        raise ValueError("x must be a device tensor")
+    x2, rows, d, ld = _rows_view(x)
+    groups = max(d // GROUP, 1)
+    if codes is None:
+        codes = torch.empty((rows, d * bits // 8), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty((rows, groups), dtype=torch.float32, device=x.device)
+    if mins is None:
+        mins = torch.empty((rows, groups), dtype=torch.float32, device=x.device)
+    rc = lib().rq_quantize_asym(C.c_void_p(x2.data_ptr()), _dtype_code(x2), rows, d, ld, int(bits),
+                                C.c_float(clip), C.c_void_p(codes.data_ptr()),
+                                C.c_void_p(scales.data_ptr()), C.c_void_p(mins.data_ptr()),
+                                _stream_ptr(stream))
+    _check(rc, "rq_quantize_asym")
+    return codes, scales, mins
 
 
 def stream_reference(x, bits: int, codes=None, scales=None, stream=None):

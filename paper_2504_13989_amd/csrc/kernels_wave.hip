@@ -665,7 +665,7 @@ __global__ __launch_bounds__(64) void k_wave_short_qe_asym(WaveArgs a, ClipList 
 // wave per bf16 row of d <= 512 T values, the row held in registers between the absmax pass and
 // the quantization pass.  Un-rotated bf16 values sit on a coarse grid, so x / Delta lands on or
 // next to a rounding tie far more often than rotated values do; every code whose fp32 residual
-// is within 0.001 of a tie is therefore retaken with the exact fp64 quotient.
+// is within 2e-5 of a tie is therefore retaken with the exact fp64 quotient.
 // The two 16-bit values of a dword as floats (exact): bf16, or IEEE fp16 when F16.
 template <bool F16>
 __device__ __forceinline__ float half_lo(uint32_t w) {
@@ -726,24 +726,18 @@ __global__ __launch_bounds__(64) void k_plain_wave(PlainArgs a) {
                 x[2 * k + 1] = half_hi<F16>(raw[t][k]);
             }
             uint32_t w = 0;
-            bool near = false;
 #pragma unroll
             for (int r = 7; r >= 0; --r) {
                 float u = fmaf(x[r], s, Quant<BITS>::kBias);
                 const float e = fmaf(x[r], s, Quant<BITS>::kBias - u);     // t - round(t)
-                near |= __builtin_fabsf(e) > 0.499f;
                 u = __builtin_amdgcn_fmed3f(u, Quant<BITS>::kLo, Quant<BITS>::kHi);
+                // within 2e-5 of a rounding tie (the fp32 quotient is good to about 2e-6): the exact fp64
+                // quotient decides, for this value only
+                if (__builtin_fabsf(e) > 0.49998f && m > 0.0f)
+                    u = Quant<BITS>::kBias + fminf(fmaxf((float)rint((double)x[r] / delta), kQmin), kQmax);
                 w = (w << BITS) + __float_as_uint(u);
             }
             w = (w - Quant<BITS>::csum()) ^ Quant<BITS>::msb();
-            if (near) {
-                w = 0;
-#pragma unroll
-                for (int r = 7; r >= 0; --r) {
-                    const float q = fminf(fmaxf((float)rint((double)x[r] / delta), kQmin), kQmax);
-                    w = (w << BITS) | ((uint32_t)(int)q & ((1u << BITS) - 1u));
-                }
-            }
             if (BITS == 4) {
                 if (idx < nchunks) store_codes(out + idx, w);
             } else {

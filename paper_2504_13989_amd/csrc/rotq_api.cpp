@@ -268,6 +268,19 @@ int rq_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int b
                               static_cast<hipStream_t>(stream));
 }
 
+int rq_quantize_asym(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
+                     void* codes, float* scales, float* mins, void* stream) {
+    if (dtype != RQ_BF16 && dtype != RQ_F32 && dtype != RQ_F16) return RQ_ERR_ARG;
+    if (rows < 0 || d < RQ_GROUP || d % RQ_GROUP != 0 || ld < d) return RQ_ERR_ARG;
+    if (bits != 3 && bits != 4) return RQ_ERR_ARG;
+    if (!clip_ok(clip)) return RQ_ERR_ARG;
+    if (rows == 0) return RQ_OK;
+    if (!X || !aligned(X, dtype == RQ_F32 ? 4 : 2)) return RQ_ERR_ARG;
+    if (!codes || !scales || !mins || !aligned(codes, 4) || !aligned(scales, 4) || !aligned(mins, 4)) return RQ_ERR_ARG;
+    return rq::plain_quantize_asym(X, dtype, rows, d, ld, bits, clip, static_cast<uint32_t*>(codes), scales, mins,
+                                   static_cast<hipStream_t>(stream));
+}
+
 int rq_rotate(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d, int64_t ld,
               int transpose, void* Y, int out_dtype, int d_out, int64_t ld_out, void* stream) {
     int rc = check_rows(h, X, dtype, rows, d, ld, 4);

@@ -114,6 +114,10 @@ bool wave_block2_supports(const rq_hadamard* h, const RowArgs& a);
 int wave_block2_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                                 float* scales, hipStream_t s);
 
+// Rotation-free asymmetric group-128 quantizer: any input type; 16-byte loads when the rows allow.
+int plain_quantize_asym(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
+                        uint32_t* codes, float* scales, float* mins, hipStream_t s);
+
 // Rotation alone on the wave path: 16-bit rows of Sylvester order 128 .. 8192, 16-byte aligned rows in and out.
 bool wave_rotate_supports(const rq_hadamard* h, const RowArgs& a, const OutArgs& o);
 int wave_rotate(const rq_hadamard* h, const RowArgs& a, const OutArgs& o, hipStream_t s);

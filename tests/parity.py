@@ -77,10 +77,11 @@ def check_rotate_quantize(x_np, n, b, clip, codes_gpu, scales_gpu, what="", rota
             "max_scale_rel": float(rel.max()) if rel.size else 0.0}
 
 
-def check_rotate_quantize_asym(x_np, n, b, clip, codes_gpu, scales_gpu, mins_gpu, what=""):
+def check_rotate_quantize_asym(x_np, n, b, clip, codes_gpu, scales_gpu, mins_gpu, what="", rotate=True):
     """Asymmetric group-128 variant: codes exact away from rounding boundaries, Delta within 1e-5
-    relative, lo within 1e-5 of the group's range, dequantized values within 1e-5 of the range."""
-    y = oracle.rotate(x_np, n)
+    relative, lo within 1e-5 of the group's range, dequantized values within 1e-5 of the range.
+    rotate=False: the rotation-free quantizer (the rows themselves are quantized, n = their width)."""
+    y = oracle.rotate(x_np, n) if rotate else oracle.as_f64(x_np)
     q, delta, lo, t = oracle.quantize_asym(y, b, clip)
     rows = q.shape[0]
     groups = n // oracle.GROUP

@@ -283,3 +283,16 @@ def test_stream_reference_argument_errors(L):
     assert call(ld=4000) == E and call(ld=4100) == E
     assert call(bits=5) == E
     assert call(X=0) == E and call(X=4104) == E and call(codes=0) == E and call(codes=4098) == E and call(scales=0) == E
+
+
+def test_quantize_asym_argument_errors(L):
+    E = binding.RQ_ERR_ARG
+    vp = C.c_void_p
+
+    def call(X=4096, dtype=0, rows=4, d=256, ld=256, bits=4, clip=0.9, codes=4096, scales=4096, mins=4096):
+        return L.rq_quantize_asym(vp(X), dtype, rows, d, ld, bits, C.c_float(clip), vp(codes), vp(scales), vp(mins), None)
+    assert call(rows=0) == binding.RQ_OK
+    assert call(dtype=3) == E and call(rows=-1) == E
+    assert call(d=64) == E and call(d=200) == E and call(ld=128) == E
+    assert call(bits=2) == E and call(clip=0.0) == E and call(clip=1.5) == E
+    assert call(X=0) == E and call(X=4097) == E and call(codes=0) == E and call(scales=4098) == E and call(mins=0) == E

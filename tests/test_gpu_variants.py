@@ -290,3 +290,50 @@ def test_full_size_fp16(torch, name):
     st = parity.check_rotate_quantize(x, w.n, b, w.clip, codes.cpu().numpy(), scales.cpu().numpy(),
                                       f"{name} fp16 full [{h.last_kernel}]")
     say(f"  ok kernel={h.last_kernel} {st}")
+
+
+@pytest.mark.parametrize("name,rows", [("kv_v", 1029), ("kv_k", 515), ("llama_hidden", 77), ("ffn_down", 9), ("tiny", 64)])
+@pytest.mark.parametrize("b", [3, 4])
+def test_plain_quantize_asym(torch, name, rows, b):
+    # the asymmetric group-128 quantizer on rows as they are (value cache): bf16, fp16 and fp32 rows,
+    # un-rotated values on their coarse grid (rounding ties are common), a view with a leading
+    # dimension beyond the width and a misaligned view
+    w = wl.WORKLOADS[name].with_rows(rows)
+    x = wl.generate(w)
+    d = w.d // 128 * 128
+    x = np.ascontiguousarray(x[:, :d])
+    variants = [("as generated", x)]
+    if x.dtype == np.uint16:
+        xf = (x.astype(np.uint32) << 16).view(np.float32)
+        variants += [("fp16", np.clip(xf, -6e4, 6e4).astype(np.float16)), ("fp32", xf * np.float32(1.0009765625))]
+    for label, xv in variants:
+        say(f"plain asym {name} rows={rows} d={d} b={b} {label}")
+        codes, scales, mins = binding.quantize_asym(parity.to_device(xv), b, 0.9)
+        torch.cuda.synchronize()
+        st = parity.check_rotate_quantize_asym(xv, d, b, 0.9, codes.cpu().numpy(), scales.cpu().numpy(),
+                                               mins.cpu().numpy(), f"plain asym {name} {label} b={b}", rotate=False)
+        say(f"  ok {st}")
+    # leading dimension beyond d, and a row start that is not 16-byte aligned
+    pad = np.zeros((rows, d + 9), dtype=x.dtype)
+    pad[:, 1:d + 1] = x
+    xt = parity.to_device(pad)[:, 1:d + 1]
+    codes, scales, mins = binding.quantize_asym(xt, b, 1.0)
+    torch.cuda.synchronize()
+    parity.check_rotate_quantize_asym(x, d, b, 1.0, codes.cpu().numpy(), scales.cpu().numpy(), mins.cpu().numpy(),
+                                      f"plain asym {name} view b={b}", rotate=False)
+
+
+def test_plain_quantize_asym_flat_groups_and_round_trip(torch):
+    rng = np.random.default_rng(11)
+    xf = rng.standard_normal((33, 256)).astype(np.float32)
+    xf[3, :128] = 2.5                      # a constant group: Delta = 0, codes 0, lo = clip * value
+    xf[4] = 0.0
+    x = wl.f32_to_bf16_bits(xf)
+    codes, scales, mins = binding.quantize_asym(parity.to_device(x), 4, 1.0)
+    torch.cuda.synchronize()
+    parity.check_rotate_quantize_asym(x, 256, 4, 1.0, codes.cpu().numpy(), scales.cpu().numpy(), mins.cpu().numpy(),
+                                      "plain asym flat", rotate=False)
+    s, m = scales.cpu().numpy(), mins.cpu().numpy()
+    assert s[3, 0] == 0 and m[3, 0] == 2.5 and s[4, 0] == 0 and m[4, 1] == 0
+    # zero rows: nothing written
+    binding.quantize_asym(parity.to_device(x)[:0], 4, 1.0)
