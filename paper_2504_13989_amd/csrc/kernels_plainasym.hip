@@ -5,7 +5,8 @@
 // per pass.  The extremes cross the 16 lanes with four DPP steps; the codes are taken in fp32 as
 // in the rotating kernels (centred on the value that maps to the middle code), and - since
 // un-rotated inputs can sit exactly on rounding ties - every value whose fp32 quotient is within 2e-5
-// of a tie is retaken with the exact fp64 quotient.
+// of a tie (wider for a group that lies far from zero, where fp32 places the centre less well) is
+// retaken with the exact fp64 quotient.
 #include "wave_common.h"
 
 namespace rq {
@@ -52,63 +53,109 @@ __device__ __forceinline__ void load8(const void* X, int64_t idx, float (&x)[8])
     }
 }
 
+// Minimum of mn and maximum of mx over the 16 lanes of a DPP row, every lane ending with both: four
+// butterfly steps, each one instruction with a DPP operand (assembly: the compiler does not fold a DPP
+// operand into a float min / max, and first passes each operand through a canonicalizing max).  The
+// s_nop keep two wait states between a vector write of a register and a DPP read of it.
+__device__ __forceinline__ void row_min_max(float& mn, float& mx) {
+    asm("s_nop 1\n\t"
+        "v_min_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_min_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1"
+        : "+v"(mn), "+v"(mx));
+}
+
 template <int BITS, int DT, bool ALIGNED, int U>
-__global__ __launch_bounds__(64) void k_plain_asym(const void* X, int64_t n_groups, int gpr, int64_t ld, double clip,
+__global__ __launch_bounds__(64) void k_plain_asym(const void* X, int64_t n_groups, int gpr, int gpr_shift, uint32_t gpr_magic, int64_t ld, double clip,
                                                    uint32_t* codes, float* scales, float* mins) {
     constexpr double kL = (double)((1 << BITS) - 1);
-    constexpr double kMid = (double)(1 << (BITS - 1)) / kL;
+    constexpr double kMid = (double)(1 << (BITS - 1)) / kL;     // centre of the code range
     const int lane = threadIdx.x;
     const int g = lane >> 4, c = lane & 15;
-    const double c1 = kL / clip;
-    const float c1h = (float)c1, c1l = (float)(c1 - (double)c1h);
+    constexpr float kMidF = (float)kMid;
+    const float c1f = (float)(kL / clip), clipf = (float)clip;
     // a wave takes U passes of four groups per iteration, all loads issued before the first is used
     for (int64_t g0 = (int64_t)blockIdx.x * (4 * U); g0 < n_groups; g0 += (int64_t)gridDim.x * (4 * U)) {
         float x[U][8];
+        // uniform over the wave, so scalar work - but a 64-bit scalar division is a hundred instructions:
+        // a shift where gpr is a power of two (the usual widths), else a 32-bit division if that will do
+        int64_t row0;
+        if (gpr_shift >= 0) row0 = g0 >> gpr_shift;
+        else if (n_groups <= 0xffffffffll) row0 = (uint32_t)g0 / (uint32_t)gpr;
+        else row0 = g0 / gpr;
+        const uint32_t rem0 = (uint32_t)(g0 - row0 * gpr);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t gi = g0 + u * 4 + g;
             const int64_t gl = gi < n_groups ? gi : n_groups - 1;
-            const int64_t row = gpr == 1 ? gl : gl / gpr;
-            const int64_t gc = gl - row * gpr;
-            load8<DT, ALIGNED>(X, row * ld + gc * 128 + c * 8, x[u]);
+            // (row, group of the row) from the iteration's uniform split plus a small offset, whose
+            // quotient by gpr is a multiply-high with ceil(2^32 / gpr): exact while offset * gpr < 2^32
+            const uint32_t off = rem0 + (uint32_t)(gl - g0);
+            const uint32_t k = gpr == 1 ? off : __umulhi(off, gpr_magic);
+            const int64_t row = row0 + k;
+            const uint32_t gc = off - k * (uint32_t)gpr;
+            load8<DT, ALIGNED>(X, row * ld + (int64_t)gc * 128 + c * 8, x[u]);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t gi = g0 + u * 4 + g;
             const bool live = gi < n_groups;
             float mn = min8(x[u]), mx = max8(x[u]);
-            mn = fminf(mn, dpp_f<kDppXor1>(mn));
-            mx = fmaxf(mx, dpp_f<kDppXor1>(mx));
-            mn = fminf(mn, dpp_f<kDppXor2>(mn));
-            mx = fmaxf(mx, dpp_f<kDppXor2>(mx));
-            mn = fminf(mn, dpp_f<kDppHalfMirror>(mn));
-            mx = fmaxf(mx, dpp_f<kDppHalfMirror>(mx));
-            mn = fminf(mn, dpp_f<kDppRor8>(mn));
-            mx = fmaxf(mx, dpp_f<kDppRor8>(mx));
-            const double lo64 = clip * (double)mn, hi64 = clip * (double)mx;
-            // the reported Delta takes a product (one fp64 ulp is far inside its tolerance); the tie
-            // decisions below take the quotient itself, since an exact tie turns on the last bit
-            const double delta64 = (hi64 - lo64) * (1.0 / kL);
-            const double r64 = (double)mx - (double)mn;           // exact
-            const float rh = (float)r64, rl = (float)(r64 - (double)rh);
-            const bool flat = !(delta64 > 0.0);
-            const float s = flat ? 0.0f : div_pair2(c1h, c1l, rh, rl);
-            const float cen = (float)(clip * fma(r64, kMid, (double)mn));
+            row_min_max(mn, mx);
+            // Group parameters in fp32.  What they cost the pre-round value t in accuracy: the range r
+            // and the multiplier s (reciprocal plus one Newton step) about 3e-7 relative, |t - mid| <= 8;
+            // the centre about 2.5 ulp, which in units of t is 3e-7 |cen| s - small for a group that
+            // straddles zero, unbounded for a narrow group far from it.  Both go into the tie window, so
+            // a group whose offset swamps its range is simply taken in fp64 throughout.
+            const float r = mx - mn;
+            const bool flat = !(r > 0.0f);
+            float q = __builtin_amdgcn_rcpf(r);
+            q = fmaf(fmaf(-r, q, 1.0f), q, q);
+            const float s = flat ? 0.0f : c1f * q;
+            const float cen = clipf * fmaf(r, kMidF, mn);
+            // (a range whose reciprocal is subnormal - the reciprocal instruction returns zero for it -
+            // or so small that s overflows leaves no window at all)
+            const float thr = (r < 4e37f && s < 1e30f) ? fmaf(-3e-7f * __builtin_fabsf(cen), s, 0.49998f) : -1.0f;
             const float bias = flat ? Quant<BITS>::kMagic : Quant<BITS>::kBias;
+            float v[8], e[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const float dx = x[u][k] - cen;
+                v[k] = fmaf(dx, s, bias);
+                e[k] = fmaf(dx, s, bias - v[k]);                   // t - round(t)
+            }
+            // near a rounding tie: the definition itself, in fp64 and with its two divisions (an exact tie
+            // turns on their last bit), for that value only; one test per lane and pass guards the lot
+            float emax;
+            asm("v_max3_f32 %0, |%1|, |%2|, |%3|\n\t"
+                "v_max3_f32 %0, %0, |%4|, |%5|\n\t"
+                "v_max3_f32 %0, %0, |%6|, |%7|\n\t"
+                "v_max_f32 %0, %0, |%8|"
+                : "=&v"(emax)
+                : "v"(e[0]), "v"(e[1]), "v"(e[2]), "v"(e[3]), "v"(e[4]), "v"(e[5]), "v"(e[6]), "v"(e[7]));
+            if (!(emax <= thr) && !flat) {
+                float mn_here = mn;
+                asm volatile("" : "+v"(mn_here));                  // keeps the fp64 work inside the branch
+                const double lo64 = clip * (double)mn_here, hi64 = clip * (double)mx;
+                const double delta64 = (hi64 - lo64) / kL;
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (!(__builtin_fabsf(e[k]) <= thr))
+                        v[k] = Quant<BITS>::kMagic + (float)fmin(fmax(rint(((double)x[u][k] - lo64) / delta64), 0.0), kL);
+            }
             uint32_t w = 0;
 #pragma unroll
-            for (int r = 7; r >= 0; --r) {
-                const float dx = x[u][r] - cen;
-                float v = fmaf(dx, s, bias);
-                const float e = fmaf(dx, s, bias - v);             // t - round(t)
-                v = __builtin_amdgcn_fmed3f(v, Quant<BITS>::kLo, Quant<BITS>::kHi);
-                // within 2e-5 of a rounding tie (five times the worst fp32 error of t, 4e-6; four values in
-                // a hundred thousand): the exact fp64 quotient decides, for this value only
-                if (__builtin_fabsf(e) > 0.49998f && !flat)
-                    v = Quant<BITS>::kMagic +
-                        (float)fmin(fmax(rint(((double)x[u][r] - lo64) / ((hi64 - lo64) / kL)), 0.0), kL);
-                w = (w << BITS) + __float_as_uint(v);
-            }
+            for (int k = 7; k >= 0; --k)
+                w = (w << BITS) + __float_as_uint(__builtin_amdgcn_fmed3f(v[k], Quant<BITS>::kLo, Quant<BITS>::kHi));
             w -= Quant<BITS>::csum();
             if (BITS == 4) {
                 if (live) store_codes(codes + gi * 16 + c, w);
@@ -118,8 +165,14 @@ __global__ __launch_bounds__(64) void k_plain_asym(const void* X, int64_t n_grou
                 if (live && qpos < 3) store_codes(codes + gi * 12 + (c >> 2) * 3 + qpos, dw);
             }
             if (live && c == 0) {
-                scales[gi] = (float)delta64;
-                mins[gi] = (float)lo64;
+                float delta = clipf * r * (float)(1.0 / kL);        // each factor good to 6e-8
+                if (!(r < 3e38f)) {                                 // max - min beyond fp32
+                    float mx_here = mx;
+                    asm volatile("" : "+v"(mx_here));
+                    delta = (float)((clip * (double)mx_here - clip * (double)mn) * (1.0 / kL));
+                }
+                scales[gi] = delta;
+                mins[gi] = clipf * mn;
             }
         }
     }
@@ -128,7 +181,9 @@ __global__ __launch_bounds__(64) void k_plain_asym(const void* X, int64_t n_grou
 template <int DT>
 void launch_dt(bool aligned, int bits, unsigned grid, hipStream_t s, const void* X, int64_t n_groups, int gpr,
                int64_t ld, double clip, uint32_t* codes, float* scales, float* mins) {
-    auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, dim3(grid), dim3(64), 0, s, X, n_groups, gpr, ld, clip, codes, scales, mins); };
+    const int gpr_shift = (gpr & (gpr - 1)) == 0 ? __builtin_ctz((unsigned)gpr) : -1;
+    const uint32_t gpr_magic = (uint32_t)((((uint64_t)1 << 32) + gpr - 1) / gpr);   // gpr >= 2 where it is used
+    auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, dim3(grid), dim3(64), 0, s, X, n_groups, gpr, gpr_shift, gpr_magic, ld, clip, codes, scales, mins); };
     if (aligned) {
         if (bits == 4) go(k_plain_asym<4, DT, true, 4>); else go(k_plain_asym<3, DT, true, 4>);
     } else {

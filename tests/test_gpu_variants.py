@@ -323,6 +323,31 @@ def test_plain_quantize_asym(torch, name, rows, b):
                                       f"plain asym {name} view b={b}", rotate=False)
 
 
+@pytest.mark.parametrize("b", [3, 4])
+def test_plain_quantize_asym_groups_far_from_zero(torch, b):
+    # groups whose offset is large against their range: fp32 cannot place the centre of such a group
+    # to within the tie window, so these have to reach the exact quotient; also values at the edge of
+    # the formats' ranges
+    rng = np.random.default_rng(5 + b)
+    base = rng.standard_normal((257, 384)).astype(np.float32)
+    off = np.repeat(rng.choice([-1.0, 1.0], size=(257, 3)) * 10.0 ** rng.uniform(0, 4, size=(257, 3)), 128, axis=1)
+    spread = np.repeat(10.0 ** rng.uniform(-3, 0, size=(257, 3)), 128, axis=1)
+    xf = (off + off * spread * base * 0.1).astype(np.float32)
+    cases = [("fp32", xf), ("bf16", wl.f32_to_bf16_bits(xf)), ("fp16", np.clip(xf, -6e4, 6e4).astype(np.float16))]
+    big = (base * np.float32(6e37)).astype(np.float32)          # max - min beyond fp32 in some groups
+    assert np.isfinite(big).all() and (big.max(axis=1) - big.min(axis=1) == np.inf).any()
+    cases += [("fp32 huge", big), ("bf16 huge", wl.f32_to_bf16_bits(big)),
+              ("fp32 small", (base * np.float32(1e-30)).astype(np.float32))]
+    for label, xv in cases:
+        for clip in (1.0, 0.85):
+            say(f"plain asym offset groups {label} b={b} clip={clip}")
+            codes, scales, mins = binding.quantize_asym(parity.to_device(xv), b, clip)
+            torch.cuda.synchronize()
+            st = parity.check_rotate_quantize_asym(xv, 384, b, clip, codes.cpu().numpy(), scales.cpu().numpy(),
+                                                   mins.cpu().numpy(), f"plain asym offset {label} b={b}", rotate=False)
+            say(f"  ok {st}")
+
+
 def test_plain_quantize_asym_flat_groups_and_round_trip(torch):
     rng = np.random.default_rng(11)
     xf = rng.standard_normal((33, 256)).astype(np.float32)
