@@ -1,4 +1,5 @@
-// Rotation-free asymmetric quantizer in groups of 128 values (section 5.1, the KV-cache setting, for
+// Rotation-free quantizers for short groups of values (head rows).
+// First the asymmetric quantizer in groups of 128 values (section 5.1, the KV-cache setting, for
 // a tensor whose rotation is fused into the producing weights - the value cache): per group
 // lo = clip * min, hi = clip * max, Delta = (hi - lo) / (2^b - 1), code = clamp(rne((x - lo) / Delta),
 // 0, 2^b - 1).  A group is the 16 lanes of a DPP row, 8 values per lane; a wave takes four groups
@@ -74,6 +75,18 @@ __device__ __forceinline__ void row_min_max(float& mn, float& mx) {
         : "+v"(mn), "+v"(mx));
 }
 
+// max |y_k| of eight floats as three-operand instructions with magnitude operands
+__device__ __forceinline__ float absmax8(const float (&y)[8]) {
+    float m;
+    asm("v_max3_f32 %0, |%1|, |%2|, |%3|\n\t"
+        "v_max3_f32 %0, %0, |%4|, |%5|\n\t"
+        "v_max3_f32 %0, %0, |%6|, |%7|\n\t"
+        "v_max_f32 %0, %0, |%8|"
+        : "=&v"(m)
+        : "v"(y[0]), "v"(y[1]), "v"(y[2]), "v"(y[3]), "v"(y[4]), "v"(y[5]), "v"(y[6]), "v"(y[7]));
+    return m;
+}
+
 template <int BITS, int DT, bool ALIGNED, int U>
 __global__ __launch_bounds__(64) void k_plain_asym(const void* X, int64_t n_groups, int gpr, int gpr_shift, uint32_t gpr_magic, int64_t ld, double clip,
                                                    uint32_t* codes, float* scales, float* mins) {
@@ -135,13 +148,7 @@ __global__ __launch_bounds__(64) void k_plain_asym(const void* X, int64_t n_grou
             }
             // near a rounding tie: the definition itself, in fp64 and with its two divisions (an exact tie
             // turns on their last bit), for that value only; one test per lane and pass guards the lot
-            float emax;
-            asm("v_max3_f32 %0, |%1|, |%2|, |%3|\n\t"
-                "v_max3_f32 %0, %0, |%4|, |%5|\n\t"
-                "v_max3_f32 %0, %0, |%6|, |%7|\n\t"
-                "v_max_f32 %0, %0, |%8|"
-                : "=&v"(emax)
-                : "v"(e[0]), "v"(e[1]), "v"(e[2]), "v"(e[3]), "v"(e[4]), "v"(e[5]), "v"(e[6]), "v"(e[7]));
+            const float emax = absmax8(e);
             if (!(emax <= thr) && !flat) {
                 float mn_here = mn;
                 asm volatile("" : "+v"(mn_here));                  // keeps the fp64 work inside the branch
@@ -178,6 +185,111 @@ __global__ __launch_bounds__(64) void k_plain_asym(const void* X, int64_t n_grou
     }
 }
 
+// Per-token symmetric quantizer (section 2.1) for short rows, d <= 8 LPR <= 512 - head rows that arrive
+// already rotated: LPR = 16, 32 or 64 lanes hold a row, 8 values each, so a wave takes 4, 2 or 1 rows
+// per pass and U passes per iteration.  Same scheme as above without the offset: absmax over the row's
+// lanes (bit patterns of non-negative floats order like unsigned integers), s = (2^b - 1) / (clip amax)
+// in fp32, codes by one fused multiply-add, values within 2e-5 of a tie retaken from the exact fp64
+// quotient x / Delta.
+template <int BITS, int DT, int LPR, int U>
+__global__ __launch_bounds__(64) void k_plain_short(const void* X, int64_t rows, int d, int64_t ld, double clip,
+                                                    uint32_t* codes, float* scales) {
+    constexpr double kL = (double)((1 << BITS) - 1);
+    constexpr int RPP = 64 / LPR;                                 // rows per pass
+    constexpr float kQmin = -(float)(1 << (BITS - 1)), kQmax = (float)((1 << (BITS - 1)) - 1);
+    const int lane = threadIdx.x;
+    const int sr = lane / LPR, c = lane % LPR;
+    const bool has = c * 8 < d;                                   // d is a multiple of 32: whole quads of lanes
+    const int row_dwords = d * BITS / 32;
+    const float c1f = (float)(kL / clip), clipf = (float)clip;
+    for (int64_t r0 = (int64_t)blockIdx.x * (RPP * U); r0 < rows; r0 += (int64_t)gridDim.x * (RPP * U)) {
+        float x[U][8];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t row = r0 + u * RPP + sr;
+            const int64_t rl = row < rows ? row : rows - 1;
+            if (has) load8<DT, true>(X, rl * ld + c * 8, x[u]);
+            else
+#pragma unroll
+                for (int k = 0; k < 8; ++k) x[u][k] = 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t row = r0 + u * RPP + sr;
+            const bool live = row < rows && has;
+            uint32_t mi = __float_as_uint(absmax8(x[u]));
+            mi = max(mi, dpp_u<kDppXor1>(mi));
+            mi = max(mi, dpp_u<kDppXor2>(mi));
+            mi = max(mi, dpp_u<kDppHalfMirror>(mi));
+            mi = max(mi, dpp_u<kDppRor8>(mi));
+            if constexpr (LPR >= 32) {                            // DPP rows 0 | 1 and 2 | 3
+                const auto a = __builtin_amdgcn_permlane16_swap(mi, mi, false, false);
+                mi = max((uint32_t)a[0], (uint32_t)a[1]);
+            }
+            if constexpr (LPR == 64) {
+                const auto b = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);
+                mi = max((uint32_t)b[0], (uint32_t)b[1]);
+            }
+            const float m = __uint_as_float(mi);
+            const bool flat = !(m > 0.0f);
+            float q = __builtin_amdgcn_rcpf(m);
+            q = fmaf(fmaf(-m, q, 1.0f), q, q);
+            const float s = flat ? 0.0f : c1f * q;
+            // (no window where the reciprocal of amax is subnormal or s overflows: fp64 throughout)
+            const float thr = (m < 4e37f && s < 1e30f) ? 0.49998f : -1.0f;
+            float v[8], e[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                v[k] = fmaf(x[u][k], s, Quant<BITS>::kBias);
+                e[k] = fmaf(x[u][k], s, Quant<BITS>::kBias - v[k]);     // t - round(t)
+            }
+            const float emax = absmax8(e);
+            if (!(emax <= thr) && !flat) {
+                float m_here = m;
+                asm volatile("" : "+v"(m_here));                  // keeps the fp64 work inside the branch
+                const double delta64 = clip * (double)m_here / kL;
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (!(__builtin_fabsf(e[k]) <= thr))
+                        v[k] = Quant<BITS>::kBias + fminf(fmaxf((float)rint((double)x[u][k] / delta64), kQmin), kQmax);
+            }
+            uint32_t w = 0;
+#pragma unroll
+            for (int k = 7; k >= 0; --k)
+                w = (w << BITS) + __float_as_uint(__builtin_amdgcn_fmed3f(v[k], Quant<BITS>::kLo, Quant<BITS>::kHi));
+            w = (w - Quant<BITS>::csum()) ^ Quant<BITS>::msb();
+            uint32_t* out = codes + row * (int64_t)row_dwords;
+            if (BITS == 4) {
+                if (live) store_codes(out + c, w);
+            } else {
+                const int qpos = c & 3;
+                const uint32_t dw = merge24<false>(w, qpos);
+                if (live && qpos < 3) store_codes(out + (c >> 2) * 3 + qpos, dw);
+            }
+            if (live && c == 0) scales[row] = clipf * m * (float)(1.0 / kL);
+        }
+    }
+}
+
+template <int DT, int LPR>
+void launch_short(int bits, hipStream_t s, const void* X, int64_t rows, int d, int64_t ld, double clip,
+                  uint32_t* codes, float* scales) {
+    constexpr int U = 4;
+    const int64_t iters = (rows + (64 / LPR) * U - 1) / ((64 / LPR) * U);
+    const int64_t cap = 1 << 24;
+    const unsigned grid = (unsigned)(iters < cap ? iters : cap);
+    if (bits == 4) hipLaunchKernelGGL((k_plain_short<4, DT, LPR, U>), dim3(grid), dim3(64), 0, s, X, rows, d, ld, clip, codes, scales);
+    else hipLaunchKernelGGL((k_plain_short<3, DT, LPR, U>), dim3(grid), dim3(64), 0, s, X, rows, d, ld, clip, codes, scales);
+}
+
+template <int DT>
+void launch_short_dt(int bits, hipStream_t s, const void* X, int64_t rows, int d, int64_t ld, double clip,
+                     uint32_t* codes, float* scales) {
+    if (d <= 128) launch_short<DT, 16>(bits, s, X, rows, d, ld, clip, codes, scales);
+    else if (d <= 256) launch_short<DT, 32>(bits, s, X, rows, d, ld, clip, codes, scales);
+    else launch_short<DT, 64>(bits, s, X, rows, d, ld, clip, codes, scales);
+}
+
 template <int DT>
 void launch_dt(bool aligned, int bits, unsigned grid, hipStream_t s, const void* X, int64_t n_groups, int gpr,
                int64_t ld, double clip, uint32_t* codes, float* scales, float* mins) {
@@ -205,6 +317,19 @@ int plain_quantize_asym(const void* X, int dtype, int64_t rows, int d, int64_t l
     if (dtype == RQ_BF16) launch_dt<0>(aligned, bits, grid, s, X, n_groups, gpr, ld, (double)clip, codes, scales, mins);
     else if (dtype == RQ_F32) launch_dt<1>(aligned, bits, grid, s, X, n_groups, gpr, ld, (double)clip, codes, scales, mins);
     else launch_dt<2>(aligned, bits, grid, s, X, n_groups, gpr, ld, (double)clip, codes, scales, mins);
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+bool plain_short_supports(const void* X, int dtype, int d, int64_t ld) {
+    const int esz = dtype == RQ_F32 ? 4 : 2;
+    return d <= 512 && d % 32 == 0 && (reinterpret_cast<uintptr_t>(X) & 15) == 0 && (ld * esz) % 16 == 0;
+}
+
+int plain_short_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
+                         uint32_t* codes, float* scales, hipStream_t s) {
+    if (dtype == RQ_BF16) launch_short_dt<0>(bits, s, X, rows, d, ld, (double)clip, codes, scales);
+    else if (dtype == RQ_F32) launch_short_dt<1>(bits, s, X, rows, d, ld, (double)clip, codes, scales);
+    else launch_short_dt<2>(bits, s, X, rows, d, ld, (double)clip, codes, scales);
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
 }
 

@@ -115,6 +115,9 @@ int wave_block2_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float cl
                                 float* scales, hipStream_t s);
 
 // Rotation-free asymmetric group-128 quantizer: any input type; 16-byte loads when the rows allow.
+bool plain_short_supports(const void* X, int dtype, int d, int64_t ld);
+int plain_short_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
+                         uint32_t* codes, float* scales, hipStream_t s);
 int plain_quantize_asym(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
                         uint32_t* codes, float* scales, float* mins, hipStream_t s);
 

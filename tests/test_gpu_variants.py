@@ -114,6 +114,35 @@ def test_plain_quantize(torch, name, rows, b):
     say(f"  ok {st}")
 
 
+@pytest.mark.parametrize("d", [32, 64, 96, 128, 160, 256, 288, 512])
+@pytest.mark.parametrize("b", [3, 4])
+def test_plain_quantize_short_rows(torch, d, b):
+    # head rows that arrive rotated: several rows per wave.  Row counts that leave the last pass and
+    # the last iteration ragged; bf16 / fp16 values on their coarse grid (rounding ties are common),
+    # fp32; an all-zero row; magnitudes at both ends of fp32; a view with a longer leading dimension
+    rng = np.random.default_rng(100 * d + b)
+    for rows in (1, 5, 67, 1030):
+        xf = (rng.standard_t(3, size=(rows, d)) * rng.choice([1e-3, 1.0, 30.0], size=(rows, 1))).astype(np.float32)
+        if rows > 4:
+            xf[3] = 0.0
+            xf[4, : d // 2] = 0.0
+        cases = [("bf16", wl.f32_to_bf16_bits(xf)), ("fp16", np.clip(xf, -6e4, 6e4).astype(np.float16)), ("fp32", xf),
+                 ("fp32 huge", np.clip(xf, -30, 30) * np.float32(1e37)), ("fp32 small", xf * np.float32(1e-30))]
+        for label, xv in cases:
+            for clip in (1.0, 0.9):
+                say(f"plain short d={d} rows={rows} b={b} {label} clip={clip}")
+                codes, scales = binding.quantize(parity.to_device(xv), b, clip)
+                torch.cuda.synchronize()
+                parity.check_quantize_plain(xv, b, clip, codes.cpu().numpy(), scales.cpu().numpy(),
+                                            f"plain short d={d} rows={rows} {label} b={b}")
+    xv = wl.f32_to_bf16_bits(rng.standard_normal((77, d)).astype(np.float32))
+    buf = torch.zeros((77, d + 40), dtype=torch.bfloat16, device="cuda")
+    buf[:, 8:d + 8] = parity.to_device(xv)
+    codes, scales = binding.quantize(buf[:, 8:d + 8], b, 0.95)
+    torch.cuda.synchronize()
+    parity.check_quantize_plain(xv, b, 0.95, codes.cpu().numpy(), scales.cpu().numpy(), f"plain short view d={d}")
+
+
 def test_plain_quantize_views_and_zero_rows(torch):
     rng = np.random.default_rng(6)
     xf = rng.standard_normal((50, 96)).astype(np.float32)
