@@ -219,7 +219,7 @@ __global__ __launch_bounds__(64 * S) void k_wave_sylvester_split(WaveArgs a) {
 template <int CB, int BITS, int U, bool GUARD, bool ASYM, bool F16>
 __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_t* base, uint32_t* obase,
                                                 float* sbase, int64_t row0, int rem, const u32x4& A0, const u32x4& A1,
-                                                uint32_t sg0, const float (&sf)[4], float flip, int g, int c, int rsub,
+                                                const float (&sf)[4], float flip, int g, int c, int rsub,
                                                 int chunk,
                                                 float c1h, float c1l, float c2h, float c2l) {
     constexpr int RPW = 16 >> CB;
@@ -244,10 +244,8 @@ __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
         f32x4 v0 = mfma_pm1<F16>(A0, raw[u], z);
         f32x4 v1 = mfma_pm1<F16>(A1, raw[u], z);
-        lane_stage<kDppXor1>(v0, sg0);
-        lane_stage<kDppXor1>(v1, sg0);
-        lane_stages_tail<CB>(v0, sf);
-        lane_stages_tail<CB>(v1, sf);
+        lane_stages_mfma<CB>(v0, sf);
+        lane_stages_mfma<CB>(v1, sf);
         uint32_t w;
         float m = 0.0f;
         if constexpr (ASYM) {
@@ -307,8 +305,7 @@ __global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
     float sf[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
-    const uint32_t sg0 = (c & 1) ? 0x80000000u : 0u;
-    const float flip = (__builtin_popcount(c >> 1) & 1) ? -1.0f : 1.0f;   // stages 2.. are the fused ones
+    const float flip = (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;        // all stages are the fused ones
     const float c1h = (float)a.c1, c1l = (float)(a.c1 - (double)c1h);
     const float c2h = (float)a.c2, c2l = (float)(a.c2 - (double)c2h);
     const bool full_d = a.d == N;
@@ -322,10 +319,10 @@ __global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
         uint32_t* obase = a.codes + row0 * ROW_DWORDS;
         float* sbase = a.scales + row0;
         if (rem == SUPER && full_d)
-            short_rows_pass<CB, BITS, U, false, ASYM, F16>(a, base, obase, sbase, row0, rem, A0, A1, sg0, sf, flip, g, c, rsub, chunk,
+            short_rows_pass<CB, BITS, U, false, ASYM, F16>(a, base, obase, sbase, row0, rem, A0, A1, sf, flip, g, c, rsub, chunk,
                                                 c1h, c1l, c2h, c2l);
         else
-            short_rows_pass<CB, BITS, U, true, ASYM, F16>(a, base, obase, sbase, row0, rem, A0, A1, sg0, sf, flip, g, c, rsub, chunk,
+            short_rows_pass<CB, BITS, U, true, ASYM, F16>(a, base, obase, sbase, row0, rem, A0, A1, sf, flip, g, c, rsub, chunk,
                                                c1h, c1l, c2h, c2l);
     }
 }

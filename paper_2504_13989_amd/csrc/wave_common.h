@@ -141,6 +141,44 @@ __device__ __forceinline__ void lane_stages_tail(f32x4& v, const float (&sf)[4])
     else lane_stages_tail_3(v, sf[1], sf[2], sf[3]);
 }
 
+// All CB stages for the four results of one matrix-core instruction, in the fused convention
+// throughout (so the lane sign is the parity of all CB bits).  Only the first element's first
+// stage is code the compiler sees: it puts the wait states a matrix-core write needs in front
+// of that read, all four result registers are written by then, and the assembly block - which
+// takes that element as an operand and so cannot move ahead of it - may read the other three.
+template <int CB>
+__device__ __forceinline__ void lane_stages_mfma(f32x4& v, const float (&sf)[4]) {
+    float x0 = v[0], x1 = v[1], x2 = v[2], x3 = v[3];
+    x0 = fmaf(dpp_f<kDppXor1>(x0), sf[0], x0);
+#define RQ_ST1(r) "v_fmac_f32_dpp " r ", " r ", %4 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+#define RQ_ST2(r) "v_fmac_f32_dpp " r ", " r ", %5 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+#define RQ_ST3(r) "v_fmac_f32_dpp " r ", " r ", %6 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+#define RQ_ST4(r) "v_fmac_f32_dpp " r ", " r ", %7 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+    if constexpr (CB == 2)
+        asm("s_nop 1\n\t" RQ_ST1("%1") RQ_ST1("%2") RQ_ST1("%3")
+            RQ_ST2("%0") RQ_ST2("%1") RQ_ST2("%2") RQ_ST2("%3")
+            : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3)
+            : "v"(sf[0]), "v"(sf[1]), "v"(sf[2]), "v"(sf[3]));
+    else if constexpr (CB == 3)
+        asm("s_nop 1\n\t" RQ_ST1("%1") RQ_ST1("%2") RQ_ST1("%3")
+            RQ_ST2("%0") RQ_ST2("%1") RQ_ST2("%2") RQ_ST2("%3")
+            RQ_ST3("%0") RQ_ST3("%1") RQ_ST3("%2") RQ_ST3("%3")
+            : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3)
+            : "v"(sf[0]), "v"(sf[1]), "v"(sf[2]), "v"(sf[3]));
+    else
+        asm("s_nop 1\n\t" RQ_ST1("%1") RQ_ST1("%2") RQ_ST1("%3")
+            RQ_ST2("%0") RQ_ST2("%1") RQ_ST2("%2") RQ_ST2("%3")
+            RQ_ST3("%0") RQ_ST3("%1") RQ_ST3("%2") RQ_ST3("%3")
+            RQ_ST4("%0") RQ_ST4("%1") RQ_ST4("%2") RQ_ST4("%3")
+            : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3)
+            : "v"(sf[0]), "v"(sf[1]), "v"(sf[2]), "v"(sf[3]));
+#undef RQ_ST1
+#undef RQ_ST2
+#undef RQ_ST3
+#undef RQ_ST4
+    v[0] = x0; v[1] = x1; v[2] = x2; v[3] = x3;
+}
+
 // The same on one, two or three values; with fewer than three values in flight an s_nop keeps
 // two wait states between a value's consecutive stages.
 __device__ __forceinline__ void lane_stages_fused1(float& x0, float s0, float s1, float s2, float s3) {
