@@ -44,13 +44,20 @@ __global__ __launch_bounds__(64) void k_wave_sylvester(WaveArgs a) {
         const uint16_t* xr = a.X + row * a.ld;
         const RowView xv = row_view(xr, a.d);
         f32x4 acc[T][2];
+        // every load of the row is issued before anything waits for one (left to itself the compiler
+        // holds half of them back until the first has returned: a second memory round trip per row)
+        u32x4 raw[T];
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             const int e0 = (t * 64 + chunk) * 8;
-            const u32x4 raw = FULL ? load16(xr + e0) : load_chunk(xv, e0);
+            raw[t] = FULL ? load16(xr + e0) : load_chunk(xv, e0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-            acc[t][0] = mfma_pm1<F16>(A0, raw, z);
-            acc[t][1] = mfma_pm1<F16>(A1, raw, z);
+            acc[t][0] = mfma_pm1<F16>(A0, raw[t], z);
+            acc[t][1] = mfma_pm1<F16>(A1, raw[t], z);
         }
         // register stages over the t bits
 #pragma unroll
@@ -141,17 +148,25 @@ __global__ __launch_bounds__(64 * S) void k_wave_sylvester_split(WaveArgs a) {
     const uint16_t* xr = a.X + row * a.ld;
     const RowView xv = row_view(xr, a.d);
     f32x4 acc[TS][2];
+    // all T loads of the row first (see k_wave_sylvester); plain (cached) loads: the S waves of the
+    // workgroup read the same lines
+    u32x4 raw[TS][S];
+#pragma unroll
+    for (int t = 0; t < TS; ++t)
+#pragma unroll
+        for (int sp = 0; sp < S; ++sp) {
+            const int e0 = ((sp * TS + t) * 64 + chunk) * 8;
+            raw[t][sp] = FULL ? *reinterpret_cast<const u32x4*>(xr + e0) : load_chunk(xv, e0);
+        }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int t = 0; t < TS; ++t) {
         acc[t][0] = f32x4{0.f, 0.f, 0.f, 0.f};
         acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int sp = 0; sp < S; ++sp) {
-            const int e0 = ((sp * TS + t) * 64 + chunk) * 8;
-            // plain (cached) loads: the S waves of the workgroup read the same lines
-            const u32x4 raw = FULL ? *reinterpret_cast<const u32x4*>(xr + e0) : load_chunk(xv, e0);
-            acc[t][0] = mfma_pm1<F16>(P0[sp], raw, acc[t][0]);
-            acc[t][1] = mfma_pm1<F16>(P1[sp], raw, acc[t][1]);
+            acc[t][0] = mfma_pm1<F16>(P0[sp], raw[t][sp], acc[t][0]);
+            acc[t][1] = mfma_pm1<F16>(P1[sp], raw[t][sp], acc[t][1]);
         }
     }
 #pragma unroll
