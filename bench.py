@@ -138,6 +138,12 @@ def time_all_configs(torch, binding, wl):
     gbps = x.shape[0] * (2 * w.d + w.d * b / 8 + 8) / ms / 1e6
     res[f"kv_v_plain_asym_b{b}"] = {"d": w.d, "bits": b, "rows": int(x.shape[0]), "us": ms * 1e3, "GBps": gbps,
                                     "frac_hbm_peak": gbps / HBM_PEAK_GBPS, "kernel": "plain_quantize_asym"}
+    # the same rows through the per-token symmetric quantizer without a rotation (several rows per wave)
+    codes = torch.empty((x.shape[0], w.d * b // 8), dtype=torch.uint8, device="cuda")
+    ms = _min_ms(torch, lambda: binding.quantize(x, b, w.clip, codes=codes, scales=scales))
+    gbps = x.shape[0] * (2 * w.d + w.d * b / 8 + 4) / ms / 1e6
+    res[f"kv_v_plain_sym_b{b}"] = {"d": w.d, "bits": b, "rows": int(x.shape[0]), "us": ms * 1e3, "GBps": gbps,
+                                   "frac_hbm_peak": gbps / HBM_PEAK_GBPS, "kernel": "plain_quantize_short"}
     del x, codes, scales, mins
     # rotation alone (the query heads carry the same per-head H_128 as the keys): bf16 in, bf16 out
     w = wl.WORKLOADS["kv_k"]
