@@ -67,12 +67,15 @@ __global__ __launch_bounds__(64) void k_wave_rotate(RotArgs a) {
     for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
         const RowView xv = row_view(a.X + row * a.ld, a.d);
         f32x4 acc[T][2];
+        u32x4 raw[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) raw[t] = load_chunk(xv, (t * 64 + chunk) * 8);
+        __builtin_amdgcn_sched_barrier(0);              // every load is issued before the first wait
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            const u32x4 raw = load_chunk(xv, (t * 64 + chunk) * 8);
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-            acc[t][0] = mfma_pm1<F16>(A0, raw, z);
-            acc[t][1] = mfma_pm1<F16>(A1, raw, z);
+            acc[t][0] = mfma_pm1<F16>(A0, raw[t], z);
+            acc[t][1] = mfma_pm1<F16>(A1, raw[t], z);
         }
 #pragma unroll
         for (int s = 1; s < T; s <<= 1)
@@ -129,11 +132,12 @@ __global__ __launch_bounds__(64) void k_wave_rotate_short(RotArgs a) {
             const int64_t row = row0 + u * RPW + rsub;
             const bool in = row < a.rows && chunk * 8 < a.d;
             raw[u] = load16(a.X + (in ? row * a.ld + chunk * 8 : 0));
-            if (!in) raw[u] = u32x4{0u, 0u, 0u, 0u};
         }
+        __builtin_amdgcn_sched_barrier(0);              // every load is issued before the first wait
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t row = row0 + u * RPW + rsub;
+            if (!(row < a.rows && chunk * 8 < a.d)) raw[u] = u32x4{0u, 0u, 0u, 0u};
             const f32x4 z = {0.f, 0.f, 0.f, 0.f};
             f32x4 v0 = mfma_pm1<F16>(A0, raw[u], z);
             f32x4 v1 = mfma_pm1<F16>(A1, raw[u], z);

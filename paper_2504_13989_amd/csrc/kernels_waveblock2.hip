@@ -44,6 +44,7 @@ __global__ __launch_bounds__(64) void k_wave_block2(WaveArgs a, int pb) {
         for (int t = 0; t < 8; ++t) R0[t] = FULL ? load16(xr + e0 + t * 128) : load_chunk(xv, e0 + t * 128);
 #pragma unroll
         for (int t = 0; t < 8; ++t) R1[t] = FULL ? load16(xr + e1 + t * 128) : load_chunk(xv, e1 + t * 128);
+        __builtin_amdgcn_sched_barrier(0);              // every load is issued before the first wait
         float y[8][NV];
 #pragma unroll
         for (int ic = 0; ic < 8; ++ic) {
