@@ -143,6 +143,32 @@ def test_plain_quantize_short_rows(torch, d, b):
     parity.check_quantize_plain(xv, b, 0.95, codes.cpu().numpy(), scales.cpu().numpy(), f"plain short view d={d}")
 
 
+@pytest.mark.parametrize("b", [3, 4])
+def test_plain_quantize_general_kernel(torch, b):
+    # what neither the short-row nor the wave kernel takes: fp32 rows wider than 512, rows that do not
+    # start on 16 bytes, a leading dimension that is not a multiple of 8, rows wider than 20480
+    rng = np.random.default_rng(40 + b)
+    xf = (rng.standard_t(3, size=(37, 1024)) * 3).astype(np.float32)
+    xf[5] = 0.0
+    cases = [("fp32 1024", xf, None), ("fp32 4096", np.tile(xf, (1, 4))[:9], None)]
+    xb = wl.f32_to_bf16_bits(xf)
+    cases += [("bf16 misaligned", xb[:, :992], (1, 1037)), ("fp16 odd ld", xf[:, :640].astype(np.float16), (0, 645))]
+    wide = wl.f32_to_bf16_bits(rng.standard_normal((5, 28672)).astype(np.float32))
+    cases += [("bf16 28672", wide, None)]
+    for label, xv, view in cases:
+        say(f"plain general {label} b={b}")
+        if view is None:
+            xt = parity.to_device(xv)
+        else:
+            off, ld = view
+            buf = parity.to_device(np.zeros((xv.shape[0], ld), dtype=xv.dtype))
+            buf[:, off:off + xv.shape[1]] = parity.to_device(xv)
+            xt = buf[:, off:off + xv.shape[1]]
+        codes, scales = binding.quantize(xt, b, 0.9)
+        torch.cuda.synchronize()
+        parity.check_quantize_plain(xv, b, 0.9, codes.cpu().numpy(), scales.cpu().numpy(), f"plain general {label} b={b}")
+
+
 def test_plain_quantize_views_and_zero_rows(torch):
     rng = np.random.default_rng(6)
     xf = rng.standard_normal((50, 96)).astype(np.float32)
