@@ -155,6 +155,8 @@ def test_plain_quantize_general_kernel(torch, b):
     cases += [("bf16 misaligned", xb[:, :992], (1, 1037)), ("fp16 odd ld", xf[:, :640].astype(np.float16), (0, 645))]
     wide = wl.f32_to_bf16_bits(rng.standard_normal((5, 28672)).astype(np.float32))
     cases += [("bf16 28672", wide, None)]
+    cases += [("fp32 huge", np.clip(xf, -30, 30) * np.float32(1e37), None), ("fp32 small", xf * np.float32(1e-30), None),
+              ("bf16 huge 4096", wl.f32_to_bf16_bits(np.tile(np.clip(xf, -30, 30) * np.float32(1e37), (1, 4))[:9]), None)]
     for label, xv, view in cases:
         say(f"plain general {label} b={b}")
         if view is None:
