@@ -160,6 +160,29 @@ def test_sylvester_orders_beyond_one_wave(torch, dtype):
     assert np.allclose(mse.cpu().numpy(), want, rtol=1e-5, atol=0)
 
 
+@pytest.mark.parametrize("n", [128, 512, 1536, 3584, 4096, 5120, 8960, 18944])
+@pytest.mark.parametrize("scale", [1e-30, 1e30])
+def test_rows_of_very_small_and_very_large_magnitude(torch, n, scale):
+    # the scales' reciprocals, the fp32 butterflies and the reported Delta at both ends of the exponent
+    # range (the rotated row stays finite: n * 30 * 1e30 < 3.4e38), through every kernel family
+    rng = np.random.default_rng(n)
+    xf = (np.clip(rng.standard_t(3.0, size=(19, n)), -30, 30) * scale).astype(np.float32)
+    for dtype, x in (("bf16", wl.f32_to_bf16_bits(xf)), ("f32", xf)):
+        if dtype == "f32" and n > 8960:
+            continue                       # fp32 rows of this length do not fit the general kernel's LDS copy
+        for b in (3, 4):
+            say(f"magnitude n={n} scale={scale} {dtype} b={b}")
+            codes, scales, kern = run_rq(torch, x, n, b, 0.9)
+            st = parity.check_rotate_quantize(x, n, b, 0.9, codes, scales, f"n={n} scale={scale} {dtype} b={b} [{kern}]")
+            say(f"  ok kernel={kern} {st}")
+        if n % 128 == 0:
+            h = handle(n)
+            ca, sa, ma = binding.rotate_quantize_asym(h, parity.to_device(x), 3, 0.9)
+            torch.cuda.synchronize()
+            parity.check_rotate_quantize_asym(x, n, 3, 0.9, ca.cpu().numpy(), sa.cpu().numpy(), ma.cpu().numpy(),
+                                              f"asym n={n} scale={scale} {dtype} [{h.last_kernel}]")
+
+
 @pytest.mark.parametrize("variant", [2, 3, 4], ids=["one_wave", "split2", "split4"])
 @pytest.mark.parametrize("n,d", [(2048, 2048), (4096, 4096), (4096, 4000), (8192, 8192), (8192, 6000)])
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
