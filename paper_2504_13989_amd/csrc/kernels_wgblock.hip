@@ -163,19 +163,50 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
         __syncthreads();
         if (PF && pass + gridDim.x < n_pass) load_pass(pass + gridDim.x);
         // ---- phase 2
+        // Long contractions (KK >= 6, one workgroup of 12 - 16 waves per CU): the 8 KK operand reads are kept
+        // DEPTH ahead of the matrix-core instructions that use them, in a ring of DEPTH register quads
+        // (left to itself the compiler issues each read right before its use and waits for it: one LDS
+        // round trip per instruction; 28672- and 32768-wide rows gain 4 %).  Items run over pairs of column
+        // tiles, so that consecutive instructions alternate between two accumulators.
         f32x4 acc[8];
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt) {
-            acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int nt = 0; nt < 8; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (KK < 6) {
+            // each read right before its use: with 80 registers a ring of reads in flight spills (11008-wide
+            // rows 0.585 -> 0.50 of peak), and for KK = 4 it measured no gain (13824 + 1.5 %, 16384 - 3 %):
+            // the other resident waves cover the LDS latency
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                // unit (4 kk + g) ^ swz: a two-bit xor leaves one per-lane base plus a compile-time offset,
-                // a three-bit xor two bases (kk even / odd)
-                const u32x4 raw = *reinterpret_cast<const u32x4*>(
+            for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) {
+                    const u32x4 raw = *reinterpret_cast<const u32x4*>(
+                        Q4 ? rd0 + nt * 16 * (NCH * 16) + kk * 64
+                           : ((kk & 1) ? rd1 : rd0) + nt * 16 * (NCH * 16) + (kk >> 1) * 128);
+                    acc[nt] = mfma_pm1<F16>(A[kk], raw, acc[nt]);
+                }
+        } else {
+            constexpr int DEPTH = 4, ITEMS = 8 * KK;
+            // item i -> (column tile, contraction step)
+            auto item_nt = [](int i) { return 2 * (i / (2 * KK)) + (i & 1); };
+            auto item_kk = [](int i) { return (i % (2 * KK)) >> 1; };
+            // unit (4 kk + g) ^ swz: a two-bit xor leaves one per-lane base plus a compile-time offset,
+            // a three-bit xor two bases (kk even / odd)
+            auto read_item = [&](int i) {
+                const int nt = item_nt(i), kk = item_kk(i);
+                return *reinterpret_cast<const u32x4*>(
                     Q4 ? rd0 + nt * 16 * (NCH * 16) + kk * 64
                        : ((kk & 1) ? rd1 : rd0) + nt * 16 * (NCH * 16) + (kk >> 1) * 128);
-                acc[nt] = mfma_pm1<F16>(A[kk], raw, acc[nt]);
+            };
+            u32x4 ring[DEPTH];
+#pragma unroll
+            for (int i = 0; i < DEPTH; ++i) ring[i] = read_item(i);
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i) {
+                __builtin_amdgcn_sched_barrier(0);
+                acc[item_nt(i)] = mfma_pm1<F16>(A[item_kk(i)], ring[i % DEPTH], acc[item_nt(i)]);
+                if (i + DEPTH < ITEMS) ring[i % DEPTH] = read_item(i + DEPTH);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
         // ---- phase 3
 #pragma unroll
