@@ -75,11 +75,11 @@ struct QeArgs {
 template <int KK, int BITS, bool FULL, bool QE, int CB = 4, bool F16 = false>
 __global__ __launch_bounds__(128 * KK) __attribute__((amdgpu_waves_per_eu(wg_waves_per_simd<KK>())))
 void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
-    static_assert(CB >= 2 && CB <= 4 && (CB == 4 || (!FULL && !QE)), "unsupported shape");
+    static_assert(CB >= 2 && CB <= 4 && (CB == 4 || !FULL), "unsupported shape");
     constexpr int RPW = 16 >> CB;                        // rows of X per pass
     constexpr int SEG = 8 << CB;                         // columns of one block row (2^k)
     constexpr bool PF = wg_waves_per_simd<KK>() == 4;    // loads run one pass ahead
-    __shared__ float esum[QE ? 16 : 1][QE ? RQ_MAX_CLIPS : 1];
+    __shared__ float esum[QE ? 16 : 1][QE ? RPW : 1][QE ? RQ_MAX_CLIPS : 1];   // [wave][row of the pass][clip]
     constexpr int NCH = wg_chunks<KK>();
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     uint8_t* const ops = lds_raw;                        // [128 columns][NCH] x 16 bytes
@@ -250,15 +250,20 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
             for (int nt = 0; nt < 8; ++nt)
 #pragma unroll
                 for (int ip = 0; ip < 4; ++ip) v[nt * 4 + ip] = acc[nt][ip];
-            qe_candidates<32, BITS, 4>(v, m, flip, qe.clips, 0, qe.n_clips, [&](int k, float e2) {
-                if (lane == 0) esum[wave][k] = e2;
+            // the sums run over the lanes that share a row of the pass: CB lane bits and the four DPP rows
+            qe_candidates<32, BITS, CB>(v, m, flip, qe.clips, 0, qe.n_clips, [&](int k, float e2) {
+                if (g == 0 && cl == 0) esum[wave][rsub][k] = e2;
             });
             __syncthreads();   // the next row writes esum only after two more barriers
-            if ((int)threadIdx.x < qe.n_clips) {
-                float t = 0.0f;
-                for (int w = 0; w < nw; ++w) t += esum[w][threadIdx.x];
-                const double nn = (double)pb * 128.0;
-                qe.partial[row * qe.n_clips + threadIdx.x] = (double)t / (nn * nn);
+            for (int i = threadIdx.x; i < RPW * qe.n_clips; i += blockDim.x) {
+                const int rs = i / qe.n_clips, k = i - rs * qe.n_clips;
+                const int64_t orow = pass * RPW + rs;
+                if (orow < a.rows) {
+                    float t = 0.0f;
+                    for (int w = 0; w < nw; ++w) t += esum[w][rs][k];
+                    const double nn = (double)pb * (double)SEG;
+                    qe.partial[orow * qe.n_clips + k] = (double)t / (nn * nn);
+                }
             }
             continue;
         }
@@ -328,13 +333,27 @@ WgKernel pick_rq(bool full) {
 }
 
 // The kernel instance for a launch, or nullptr when the combination is not built: cb = 4 needs
-// KK >= 2 (smaller blocks have the one-wave kernel), quant_error cb = 4.
+// KK >= 2 (smaller blocks have the one-wave kernel).
 template <int KK>
 WgKernel pick_kernel(int bits, bool full, bool qe, int cb, bool f16) {
     if (bits != 3 && bits != 4) return nullptr;
+    if (qe && cb != 4) {
+        if (cb == 3) {
+            if (bits == 4) return f16 ? static_cast<WgKernel>(k_wg_block<KK, 4, false, true, 3, true>)
+                                      : static_cast<WgKernel>(k_wg_block<KK, 4, false, true, 3, false>);
+            return f16 ? static_cast<WgKernel>(k_wg_block<KK, 3, false, true, 3, true>)
+                       : static_cast<WgKernel>(k_wg_block<KK, 3, false, true, 3, false>);
+        }
+        if (cb == 2) {
+            if (bits == 4) return f16 ? static_cast<WgKernel>(k_wg_block<KK, 4, false, true, 2, true>)
+                                      : static_cast<WgKernel>(k_wg_block<KK, 4, false, true, 2, false>);
+            return f16 ? static_cast<WgKernel>(k_wg_block<KK, 3, false, true, 2, true>)
+                       : static_cast<WgKernel>(k_wg_block<KK, 3, false, true, 2, false>);
+        }
+        return nullptr;
+    }
     if (qe) {
         if constexpr (KK >= 2) {
-            if (cb != 4) return nullptr;
             if (f16) {
                 if (bits == 4) return full ? static_cast<WgKernel>(k_wg_block<KK, 4, true, true, 4, true>)
                                            : static_cast<WgKernel>(k_wg_block<KK, 4, false, true, 4, true>);
@@ -470,10 +489,10 @@ static bool wg_shape(const RowArgs& a, int* pb, int* cb) {
 }
 
 bool wg_block_supports(const rq_hadamard* h, const RowArgs& a, bool quant_error) {
+    (void)quant_error;                                  // both forms cover the same shapes
     int pb, cb;
     if (h->device < 0 || !h->d_tiles || !h->wg_ok || !wg_shape(a, &pb, &cb)) return false;
     if (a.dtype != RQ_BF16 && !(a.dtype == RQ_F16 && h->d_tiles_f16)) return false;
-    if (quant_error && cb != 4) return false;
     if ((reinterpret_cast<uintptr_t>(a.X) & 15) != 0 || (a.ld & 7) != 0 || (a.d & 7) != 0) return false;
     return true;
 }

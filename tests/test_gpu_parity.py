@@ -397,6 +397,28 @@ def test_quant_error_other_orders(torch, n, d):
         parity.check_quant_error(x, n, b, clips, mse.cpu().numpy(), what=f"n={n} d={d} b={b}")
 
 
+@pytest.mark.parametrize("n,d", [(896, 896), (4864, 4864), (8960, 8960), (8960, 8000), (1792, 1792), (640, 640),
+                                 (2432, 2400)])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_quant_error_orders_with_short_sylvester_factor(torch, n, d, dtype):
+    # n = p * 64 or p * 32: several rows per pass of the workgroup kernel, sums per row of the pass;
+    # row counts that leave the last pass ragged, 1 .. 32 clip ratios
+    h = handle(n)
+    rng = np.random.default_rng(n * 3 + d)
+    for rows, k in ((1, 1), (7, 5), (66, 32), (301, 3)):
+        xf = (rng.standard_t(3.0, size=(rows, d)) * rng.choice([0.1, 1.0, 20.0], size=(rows, 1))).astype(np.float32)
+        if rows > 3:
+            xf[2] = 0.0
+        x = wl.f32_to_bf16_bits(xf) if dtype == "bf16" else np.clip(xf, -6e4, 6e4).astype(np.float16)
+        clips = [float(np.float32(c)) for c in np.linspace(0.5, 1.0, k)]
+        for b in (3, 4):
+            say(f"quant_error short-factor order n={n} d={d} rows={rows} clips={k} {dtype} b={b}")
+            mse = binding.quant_error(h, parity.to_device(x), b, clips)
+            torch.cuda.synchronize()
+            assert h.last_kernel == "wg_block_quant_error"
+            parity.check_quant_error(x, n, b, clips, mse.cpu().numpy(), what=f"n={n} d={d} rows={rows} b={b} {dtype}")
+
+
 def test_quant_error_consistent_with_rotate_quantize(torch):
     # the two entry points agree: mse[k] equals the error of dequantized rotate_quantize output
     w = wl.WORKLOADS["calib"].with_rows(64)
