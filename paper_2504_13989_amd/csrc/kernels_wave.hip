@@ -830,9 +830,13 @@ int launch_long(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s
                 : launch_wave(k_wave_sylvester<T, 3, false>, h, a, a.rows, 4, s);
 }
 
-template <int CB>
-int launch_short(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
-    constexpr int U = 4;
+// Passes in flight per wave: four, or eight on inputs of 2^27 elements and more, where the deeper queue of
+// loads is worth 3 - 4 % (KV head rows: 4 194 304 x 128, b = 3, 230 -> 223 us, asymmetric 258 -> 248 us) and
+// the longer wave no longer costs anything at the ends of the launch (65 536 rows: 5.6 -> 6.0 us).
+inline bool short_deep(const WaveArgs& a, int n) { return a.rows * (int64_t)n >= ((int64_t)1 << 27); }
+
+template <int CB, int U>
+int launch_short_u(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
     constexpr int SUPER = (16 >> CB) * U;
     const int64_t items = (a.rows + SUPER - 1) / SUPER;
     if (a.f16)
@@ -842,8 +846,13 @@ int launch_short(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t 
                      : launch_wave(k_wave_short<CB, 3, U>, h, a, items, 8, s);
 }
 
-int launch_short_asym(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
-    constexpr int U = 4;
+template <int CB>
+int launch_short(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
+    return short_deep(a, 32 << CB) ? launch_short_u<CB, 8>(h, a, bits, s) : launch_short_u<CB, 4>(h, a, bits, s);
+}
+
+template <int U>
+int launch_short_asym_u(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
     constexpr int SUPER = 4 * U;
     const int64_t items = (a.rows + SUPER - 1) / SUPER;
     if (a.f16)
@@ -851,6 +860,10 @@ int launch_short_asym(const rq_hadamard* h, const WaveArgs& a, int bits, hipStre
                          : launch_wave(k_wave_short<2, 3, U, true, true>, h, a, items, 8, s);
     return bits == 4 ? launch_wave(k_wave_short<2, 4, U, true>, h, a, items, 8, s)
                      : launch_wave(k_wave_short<2, 3, U, true>, h, a, items, 8, s);
+}
+
+int launch_short_asym(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s) {
+    return short_deep(a, 128) ? launch_short_asym_u<8>(h, a, bits, s) : launch_short_asym_u<4>(h, a, bits, s);
 }
 
 }  // namespace

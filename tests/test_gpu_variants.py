@@ -143,6 +143,33 @@ def test_plain_quantize_short_rows(torch, d, b):
     parity.check_quantize_plain(xv, b, 0.95, codes.cpu().numpy(), scales.cpu().numpy(), f"plain short view d={d}")
 
 
+@pytest.mark.parametrize("n,rows", [(128, (1 << 20) + 37), (256, (1 << 19) + 11), (512, (1 << 18) + 3)])
+def test_short_rows_large_inputs_ragged_end(torch, n, rows):
+    # inputs of 2^27 elements and more take eight passes per wave: the first and the last rows (a ragged last
+    # wave) against the oracle, symmetric and - for rows of 128 - asymmetric
+    rng = np.random.default_rng(n)
+    base = wl.f32_to_bf16_bits(rng.standard_t(3.0, size=(4096, n)).astype(np.float32))
+    reps = (rows + 4095) // 4096
+    x = np.tile(base, (reps, 1))[:rows]
+    x[-300:] = wl.f32_to_bf16_bits((rng.standard_normal((300, n)) * 3).astype(np.float32))
+    xt = parity.to_device(x)
+    h = handle(n)
+    pick = np.r_[0:64, rows - 300:rows]
+    idx = torch.from_numpy(pick).to("cuda")
+    for b in (3, 4):
+        say(f"short rows, large input n={n} rows={rows} b={b}")
+        codes, scales = binding.rotate_quantize(h, xt, b, 0.9)
+        torch.cuda.synchronize()
+        assert h.last_kernel == "wave_sylvester"
+        parity.check_rotate_quantize(x[pick], n, b, 0.9, codes[idx].cpu().numpy(), scales[idx].cpu().numpy(),
+                                     f"large short n={n} b={b}")
+        if n == 128:
+            ca, sa, ma = binding.rotate_quantize_asym(h, xt, b, 0.9)
+            torch.cuda.synchronize()
+            parity.check_rotate_quantize_asym(x[pick], n, b, 0.9, ca[idx].cpu().numpy(), sa[idx].cpu().numpy(),
+                                              ma[idx].cpu().numpy(), f"large short asym b={b}")
+
+
 @pytest.mark.parametrize("b", [3, 4])
 def test_plain_quantize_general_kernel(torch, b):
     # what neither the short-row nor the wave kernel takes: fp32 rows wider than 512, rows that do not
