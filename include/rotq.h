@@ -13,7 +13,14 @@
  *     Paley order <= 256: p = q+1 with q prime, q = 3 (mod 4) (Algorithm 2), or
  *     p = 2(q+1) with q prime, q = 1 (mod 4) (Paley II; not in the paper, standard
  *     construction H = C (x) [[1,1],[1,-1]] + I (x) [[1,-1],[-1,-1]]).  Where both
- *     exist for one p the first is used.  n must be a multiple of 32.
+ *     exist for one p the first is used.  n must be a multiple of 8 and at least 32 (packed rows are
+ *     whole bytes); where no block of at most 256 exists a Paley block of up to 4096 is taken.  The
+ *     fast kernels serve 16-bit rows of the orders rq_next_order returns (2^k >= 32, block <= 256);
+ *     every other case (fp32 rows, unaligned rows, other orders) runs on a general kernel that
+ *     keeps the row in the 160 KB of LDS, which bounds n: 2^15 for Sylvester orders and 20448 for
+ *     block orders; fp32 rows are quantized from an fp64 copy of the row and stop at n = 2^14
+ *     (Sylvester) and 9728 (block orders).  A row call on an order beyond what its kernels can hold
+ *     returns RQ_ERR_NO_ORDER.
  *   - H_n = H_p (x) H_{2^k}: flat index j = a * 2^k + c (a < p, c < 2^k),
  *     H_n[i, j] = H_p[i / 2^k, j / 2^k] * (-1)^popcount((i % 2^k) & (j % 2^k)).
  *   - Rotated row: y = H_n pad(x) / sqrt(n), pad() appends n - d zeros.
@@ -42,7 +49,7 @@ extern "C" {
 
 #define RQ_OK             0
 #define RQ_ERR_ARG       -1   /* bad pointer, size, stride, bit-width, clip, alignment, workspace */
-#define RQ_ERR_NO_ORDER  -2   /* n has no supported factorisation p * 2^k, or n % 32 != 0 */
+#define RQ_ERR_NO_ORDER  -2   /* n has no supported factorisation p * 2^k, n % 8 != 0, or no kernel can hold a row of n */
 #define RQ_ERR_HIP       -3   /* HIP allocation / launch failure, or the handle has no device table */
 #define RQ_ERR_NOMEM     -4   /* host allocation failure */
 
@@ -57,7 +64,12 @@ extern "C" {
 #define RQ_MAX_CLIPS 64
 #define RQ_GROUP 128
 
-typedef struct rq_hadamard rq_hadamard_t;   /* opaque; immutable after build */
+/* Opaque.  The factorisation and the device tables do not change after rq_hadamard_build, and the
+ * row calls take the handle as const: one handle may serve any number of host threads and streams at
+ * once.  Two fields are written later, both atomically: the kernel selector of
+ * rq_hadamard_set_variant (a test hook; calls already running keep the kernel they chose) and the
+ * diagnostic name read by rq_hadamard_last_kernel (the most recent call on any thread). */
+typedef struct rq_hadamard rq_hadamard_t;
 
 /*
  * Build the rotation of order n (sections 2.3.2, 2.3.3, Appendix B Algorithm 2): factor
@@ -71,7 +83,8 @@ typedef struct rq_hadamard rq_hadamard_t;   /* opaque; immutable after build */
  *   n    [in]  rotation order, multiple of 8 (packed rows are whole bytes)
  *   out  [out] host pointer receiving the handle; owned by the caller, released with
  *              rq_hadamard_free.  Untouched on error.
- * Errors: RQ_ERR_ARG (out NULL, n < 32), RQ_ERR_NO_ORDER, RQ_ERR_NOMEM, RQ_ERR_HIP.
+ * Errors: RQ_ERR_ARG (out NULL, n < 32), RQ_ERR_NO_ORDER (n not a multiple of 8, or no
+ * factorisation), RQ_ERR_NOMEM, RQ_ERR_HIP.
  */
 int rq_hadamard_build(int n, rq_hadamard_t** out);
 
@@ -115,7 +128,8 @@ int rq_next_order(int d, int* n_out);
  *   stream  [in]  hipStream_t (NULL = the null stream)
  * rows == 0 is a successful no-op (X, codes and scales may then be NULL).
  * Errors: RQ_ERR_ARG (NULL pointer, rows < 0, d < 1, d > n, ld < d, bits not 3/4, clip not in
- * (0,1] or NaN, misaligned pointer, unknown dtype), RQ_ERR_HIP.
+ * (0,1] or NaN, misaligned pointer, unknown dtype), RQ_ERR_NO_ORDER (no kernel can hold a row of
+ * this order and type, see Conventions), RQ_ERR_HIP.
  */
 int rq_rotate_quantize(const rq_hadamard_t* h,
                        const void* X, int dtype, int64_t rows, int d, int64_t ld,
@@ -222,6 +236,28 @@ int rq_dequantize_rotate(const rq_hadamard_t* h, const void* codes, const float*
                          void* Y, int out_dtype, int d_out, int64_t ld_out, void* stream);
 
 /*
+ * Dequantize in the rotated, normalised domain (section 2.1: X^ = round(X / Delta) * Delta), no
+ * rotation: Y[r, j] = code_j * scales[r] for the signed codes rq_rotate_quantize / rq_quantize write.
+ *   h       [in]  handle of the order n the codes were written with (n codes per row)
+ *   codes   [in]  DEVICE, rows * n * bits / 8 bytes, 4-byte aligned
+ *   scales  [in]  DEVICE, rows floats
+ *   Y       [out] DEVICE, rows x n floats, row-major, leading dimension n, 4-byte aligned, caller-owned
+ * The product is a single fp32 multiplication.  rows == 0 is a successful no-op.
+ * Errors: RQ_ERR_ARG (NULL or misaligned pointer, rows < 0, bits not 3/4), RQ_ERR_HIP.
+ */
+int rq_dequantize(const rq_hadamard_t* h, const void* codes, const float* scales, int64_t rows, int bits,
+                  float* Y, void* stream);
+
+/*
+ * The same for the unsigned group codes of rq_rotate_quantize_asym / rq_quantize_asym (section 5.1):
+ * Y[r, j] = code_j * scales[r, g] + mins[r, g], g = j / RQ_GROUP, one fused multiply-add.
+ *   scales, mins [in] DEVICE, rows * (n / RQ_GROUP) floats each
+ * Errors: RQ_ERR_ARG (as rq_dequantize, or n not a multiple of RQ_GROUP), RQ_ERR_HIP.
+ */
+int rq_dequantize_asym(const rq_hadamard_t* h, const void* codes, const float* scales, const float* mins,
+                       int64_t rows, int bits, float* Y, void* stream);
+
+/*
  * Lemma "Expanding limit" (section 4.2): the largest number of added dimensions d for which a
  * product over n + d dimensions at bits_reduced bits costs no more bit operations than the
  * product over n dimensions at `bits` bits: (n + d) * bits_reduced <= n * bits, i.e.
@@ -246,7 +282,7 @@ size_t rq_quant_error_workspace(int64_t rows, int n_clips);
  * Other arguments as in rq_rotate_quantize.  rows == 0 writes zeros to mse (X may then be NULL).
  * The result is deterministic (fixed reduction order).
  * Errors: RQ_ERR_ARG (as above, n_clips out of range, a clip not in (0,1], workspace too small
- * or misaligned), RQ_ERR_HIP.
+ * or misaligned), RQ_ERR_NO_ORDER (as rq_rotate_quantize), RQ_ERR_HIP.
  */
 int rq_quant_error(const rq_hadamard_t* h,
                    const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits,

@@ -56,6 +56,8 @@ def lib() -> C.CDLL:
     L.rq_quant_error_workspace.restype = C.c_size_t
     L.rq_quant_error.argtypes = [vp, vp, i32, i64, i32, i64, i32, f32p, i32, vp, vp, C.c_size_t, vp]
     L.rq_quant_error_asym.argtypes = L.rq_quant_error.argtypes
+    L.rq_dequantize.argtypes = [vp, vp, vp, i64, i32, vp, vp]
+    L.rq_dequantize_asym.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp]
     L.rq_gbs_workspace.argtypes = [i64]
     L.rq_gbs_workspace.restype = C.c_size_t
     L.rq_gbs_search.argtypes = [vp, vp, i32, i64, i32, i64, i32, C.c_float, i32, vp, C.c_size_t, vp,
@@ -302,6 +304,25 @@ def dequantize_rotate(h: Hadamard, codes, scales, bits: int, mins=None, transpos
                                     out.stride(0) if rows > 1 else max(d_out, out.stride(0)),
                                     _stream_ptr(stream))
     _check(rc, "rq_dequantize_rotate")
+    return out
+
+
+def dequantize(h: Hadamard, codes, scales, bits: int, mins=None, out=None, stream=None):
+    """rq_dequantize (rq_dequantize_asym when mins is given): packed codes and scales to float32
+    values [rows, n] in the rotated domain."""
+    import torch
+    rows = codes.shape[0]
+    if out is None:
+        out = torch.empty((rows, h.n), dtype=torch.float32, device=codes.device)
+    if mins is None:
+        rc = lib().rq_dequantize(h._h, C.c_void_p(codes.data_ptr()), C.c_void_p(scales.data_ptr()), rows,
+                                 int(bits), C.c_void_p(out.data_ptr()), _stream_ptr(stream))
+        _check(rc, "rq_dequantize")
+    else:
+        rc = lib().rq_dequantize_asym(h._h, C.c_void_p(codes.data_ptr()), C.c_void_p(scales.data_ptr()),
+                                      C.c_void_p(mins.data_ptr()), rows, int(bits),
+                                      C.c_void_p(out.data_ptr()), _stream_ptr(stream))
+        _check(rc, "rq_dequantize_asym")
     return out
 
 

@@ -809,8 +809,9 @@ int launch_long(const rq_hadamard* h, const WaveArgs& a, int bits, hipStream_t s
     // from 2048 rows on one wave per row is faster)
     if constexpr (T >= 4) {
         const int64_t simds = (int64_t)h->num_cu * 4;
-        if (h->split >= 0) {
-            const int want = h->split > 0 ? h->split : (a.rows * 2 <= simds ? 4 : a.rows <= simds ? 2 : 1);
+        const int split = h->split.load(std::memory_order_relaxed);
+        if (split >= 0) {
+            const int want = split > 0 ? split : (a.rows * 2 <= simds ? 4 : a.rows <= simds ? 2 : 1);
             if (want == 4) return launch_split<T, 4>(a, bits, s);
             if (want == 2) return launch_split<T, 2>(a, bits, s);
         }

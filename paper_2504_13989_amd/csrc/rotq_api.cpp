@@ -22,6 +22,9 @@ int check_rows(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, i
 
 bool clip_ok(float c) { return c > 0.0f && c <= 1.0f; }   // false for NaN
 
+// records which kernel family a call chose (diagnostic; the handle's only field written after build)
+void note(const rq_hadamard_t* h, const char* name) { h->last_kernel.store(name, std::memory_order_relaxed); }
+
 rq::RowArgs row_args(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
                      int64_t ld, int bits) {
     return rq::RowArgs{X, dtype, rows, d, ld, h->f.n, h->f.p, h->f.log2m, h->d_block, bits};
@@ -182,7 +185,9 @@ int rq_hadamard_set_variant(rq_hadamard_t* h, int variant) {
     return RQ_OK;
 }
 
-const char* rq_hadamard_last_kernel(const rq_hadamard_t* h) { return h ? h->last_kernel : ""; }
+const char* rq_hadamard_last_kernel(const rq_hadamard_t* h) {
+    return h ? h->last_kernel.load(std::memory_order_relaxed) : "";
+}
 
 int rq_rotate_quantize(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
                        int64_t ld, int bits, float clip, void* codes, float* scales, void* stream) {
@@ -192,31 +197,30 @@ int rq_rotate_quantize(const rq_hadamard_t* h, const void* X, int dtype, int64_t
     if (rows == 0) return RQ_OK;
     if (!codes || !scales || !aligned(codes, 4) || !aligned(scales, 4)) return RQ_ERR_ARG;
     if (h->device < 0) return RQ_ERR_HIP;
-    rq_hadamard* hm = const_cast<rq_hadamard*>(h);
     const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, bits);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (h->variant == 0 && rq::wave_supports(h, a)) {
-        hm->last_kernel = "wave_sylvester";
+        note(h, "wave_sylvester");
         return rq::wave_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
     }
     if (h->variant == 0 && rq::wave_block_supports(h, a)) {
-        hm->last_kernel = "wave_block";
+        note(h, "wave_block");
         return rq::wave_block_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
     }
     if (h->variant == 0 && rq::wave_block2_supports(h, a)) {
-        hm->last_kernel = "wave_block";
+        note(h, "wave_block");
         return rq::wave_block2_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
     }
     if (h->variant == 0 && rq::wg_block_supports(h, a)) {
-        hm->last_kernel = "wg_block";
+        note(h, "wg_block");
         return rq::wg_block_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
     }
     if (h->variant == 0 && rq::dense_block_supports(h, a)) {
-        hm->last_kernel = "dense_block";
+        note(h, "dense_block");
         return rq::dense_block_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
     }
     if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
-    hm->last_kernel = "generic_lds";
+    note(h, "generic_lds");
     return rq::generic_rotate_quantize(h, a, clip, static_cast<uint32_t*>(codes), scales, s);
 }
 
@@ -230,15 +234,14 @@ int rq_rotate_quantize_asym(const rq_hadamard_t* h, const void* X, int dtype, in
     if (!codes || !scales || !mins || !aligned(codes, 4) || !aligned(scales, 4) || !aligned(mins, 4))
         return RQ_ERR_ARG;
     if (h->device < 0) return RQ_ERR_HIP;
-    rq_hadamard* hm = const_cast<rq_hadamard*>(h);
     const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, bits);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (h->variant == 0 && rq::wave_asym_supports(h, a)) {
-        hm->last_kernel = "wave_short_asym";
+        note(h, "wave_short_asym");
         return rq::wave_rotate_quantize_asym(h, a, clip, static_cast<uint32_t*>(codes), scales, mins, s);
     }
     if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
-    hm->last_kernel = "generic_lds_asym";
+    note(h, "generic_lds_asym");
     return rq::generic_rotate_quantize_asym(h, a, clip, static_cast<uint32_t*>(codes), scales, mins, s);
 }
 
@@ -297,11 +300,11 @@ int rq_rotate(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, in
     const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, 4);
     const rq::OutArgs o{Y, out_dtype, d_out, ld_out};
     if (h->variant == 0 && rq::wave_rotate_supports(h, a, o)) {      // Sylvester orders: H is symmetric
-        const_cast<rq_hadamard*>(h)->last_kernel = "wave_rotate";
+        note(h, "wave_rotate");
         return rq::wave_rotate(h, a, o, static_cast<hipStream_t>(stream));
     }
     if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
-    const_cast<rq_hadamard*>(h)->last_kernel = "generic_rotate";
+    note(h, "generic_rotate");
     return rq::generic_rotate(h, a, transpose, o, static_cast<hipStream_t>(stream));
 }
 
@@ -321,9 +324,32 @@ int rq_dequantize_rotate(const rq_hadamard_t* h, const void* codes, const float*
     if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
     const rq::RowArgs a = row_args(h, nullptr, RQ_F32, rows, h->f.n, h->f.n, bits);
     const rq::OutArgs o{Y, out_dtype, d_out, ld_out};
-    const_cast<rq_hadamard*>(h)->last_kernel = "generic_dequant_rotate";
+    note(h, "generic_dequant_rotate");
     return rq::generic_dequant_rotate(h, a, static_cast<const uint32_t*>(codes), scales, mins, transpose,
                                       o, static_cast<hipStream_t>(stream));
+}
+
+static int dequantize_impl(const rq_hadamard_t* h, const void* codes, const float* scales, const float* mins,
+                           bool asym, int64_t rows, int bits, float* Y, void* stream) {
+    if (!h || rows < 0 || (bits != 3 && bits != 4)) return RQ_ERR_ARG;
+    if (asym && h->f.n % RQ_GROUP != 0) return RQ_ERR_ARG;
+    if (rows == 0) return RQ_OK;
+    if (!codes || !scales || !Y || (asym && !mins)) return RQ_ERR_ARG;
+    if (!aligned(codes, 4) || !aligned(scales, 4) || !aligned(mins, 4) || !aligned(Y, 4)) return RQ_ERR_ARG;
+    if (h->device < 0) return RQ_ERR_HIP;
+    note(h, "dequantize");
+    return rq::dequantize_rows(static_cast<const uint32_t*>(codes), scales, asym ? mins : nullptr, rows, h->f.n,
+                               bits, Y, static_cast<hipStream_t>(stream));
+}
+
+int rq_dequantize(const rq_hadamard_t* h, const void* codes, const float* scales, int64_t rows, int bits,
+                  float* Y, void* stream) {
+    return dequantize_impl(h, codes, scales, nullptr, false, rows, bits, Y, stream);
+}
+
+int rq_dequantize_asym(const rq_hadamard_t* h, const void* codes, const float* scales, const float* mins,
+                       int64_t rows, int bits, float* Y, void* stream) {
+    return dequantize_impl(h, codes, scales, mins, true, rows, bits, Y, stream);
 }
 
 int rq_expand_limit(int n, int bits, int bits_reduced, int64_t* d_max) {
@@ -338,9 +364,11 @@ size_t rq_quant_error_workspace(int64_t rows, int n_clips) {
     return r * (size_t)n_clips * sizeof(double);
 }
 
-static int quant_error_impl(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
-                            int64_t ld, int bits, const float* clips, int n_clips, float* mse,
-                            void* workspace, size_t workspace_bytes, void* stream, bool asym) {
+}  // extern "C"
+
+int rq::quant_error_impl(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
+                         int64_t ld, int bits, const float* clips, int n_clips, float* mse,
+                         void* workspace, size_t workspace_bytes, void* stream, bool asym) {
     int rc = check_rows(h, X, dtype, rows, d, ld, bits);
     if (rc != RQ_OK) return rc;
     if (asym && h->f.n % RQ_GROUP != 0) return RQ_ERR_ARG;
@@ -357,53 +385,65 @@ static int quant_error_impl(const rq_hadamard_t* h, const void* X, int dtype, in
         cl.clip_over_lvl[k] = (double)clips[k] / lvl;
     }
     if (h->device < 0) return RQ_ERR_HIP;
-    rq_hadamard* hm = const_cast<rq_hadamard*>(h);
     const rq::RowArgs a = row_args(h, X, dtype, rows, d, ld, bits);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (asym) {
         if (h->variant == 0 && rows > 0 && rq::wave_asym_supports(h, a)) {
-            hm->last_kernel = "wave_quant_error_asym";
+            note(h, "wave_quant_error_asym");
             rc = rq::wave_quant_error_asym(h, a, cl, n_clips, static_cast<double*>(workspace), s);
             if (rc != RQ_OK) return rc;
             return rq::reduce_partials(static_cast<double*>(workspace), rows, n_clips, mse, s);
         }
         if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
-        hm->last_kernel = "generic_lds_asym";
+        note(h, "generic_lds_asym");
         return rq::generic_quant_error_asym(h, a, cl, n_clips, mse, static_cast<double*>(workspace), s);
     }
     if (h->variant == 0 && rows > 0 && rq::wave_quant_error_supports(h, a)) {
-        hm->last_kernel = "wave_quant_error";
+        note(h, "wave_quant_error");
         rc = rq::wave_quant_error(h, a, cl, n_clips, static_cast<double*>(workspace), s);
         if (rc != RQ_OK) return rc;
         return rq::reduce_partials(static_cast<double*>(workspace), rows, n_clips, mse, s);
     }
     if (h->variant == 0 && rows > 0 && rq::wg_block_supports(h, a, true)) {
-        hm->last_kernel = "wg_block_quant_error";
+        note(h, "wg_block_quant_error");
         rc = rq::wg_block_quant_error(h, a, cl, n_clips, static_cast<double*>(workspace), s);
         if (rc != RQ_OK) return rc;
         return rq::reduce_partials(static_cast<double*>(workspace), rows, n_clips, mse, s);
     }
     if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
-    hm->last_kernel = "generic_lds";
+    note(h, "generic_lds");
     return rq::generic_quant_error(h, a, cl, n_clips, mse, static_cast<double*>(workspace), s);
 }
+
+extern "C" {
 
 int rq_quant_error(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
                    int64_t ld, int bits, const float* clips, int n_clips, float* mse,
                    void* workspace, size_t workspace_bytes, void* stream) {
-    return quant_error_impl(h, X, dtype, rows, d, ld, bits, clips, n_clips, mse, workspace, workspace_bytes,
+    return rq::quant_error_impl(h, X, dtype, rows, d, ld, bits, clips, n_clips, mse, workspace, workspace_bytes,
                             stream, false);
 }
 
 int rq_quant_error_asym(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, int d,
                         int64_t ld, int bits, const float* clips, int n_clips, float* mse,
                         void* workspace, size_t workspace_bytes, void* stream) {
-    return quant_error_impl(h, X, dtype, rows, d, ld, bits, clips, n_clips, mse, workspace, workspace_bytes,
-                            stream, true);
+    return rq::quant_error_impl(h, X, dtype, rows, d, ld, bits, clips, n_clips, mse, workspace, workspace_bytes,
+                                stream, true);
 }
 
+namespace {
+// Probes evaluated per batch of the search: 5 steps ahead (the 31 nodes of the outcome tree, plus the
+// starting point in the first batch) on small tensors, 3 steps (7 nodes + 1) on large ones, where the
+// extra candidates would cost more than the launches they save.
+constexpr int64_t kGbsSmall = (int64_t)1 << 22;              // rows * n up to which 5 steps are taken
+int gbs_depth(int64_t rows, int n) { return (double)rows * (double)n <= (double)kGbsSmall ? 5 : 3; }
+}  // namespace
+
 size_t rq_gbs_workspace(int64_t rows) {
-    const size_t q = rq_quant_error_workspace(rows, RQ_MAX_CLIPS);
+    if (rows < 0) return 0;
+    // the order is not known here: with the smallest one (32) more than 2^22 / 32 rows always take 3 steps
+    const int cands = rows * 32 <= kGbsSmall ? 32 : 8;
+    const size_t q = rq_quant_error_workspace(rows, cands);
     return q ? q + 256 : 0;
 }
 
@@ -464,14 +504,15 @@ static int gbs_impl(const rq_hadamard_t* h, const void* X, int dtype, int64_t ro
     // launches and stream synchronisations (each costs more than a candidate on a small tensor).
     // Small tensors look 5 steps ahead (31 candidates), large ones 3 (7 candidates: about the work
     // of the 3 rotations it saves).
-    const int depth = (double)rows * (double)h->f.n <= (double)(1 << 22) ? 5 : 3;
+    const int depth = gbs_depth(rows, h->f.n);
     float vals[RQ_MAX_CLIPS];
     float clips[RQ_MAX_CLIPS];
     auto evaluate = [&](int count) -> int {
-        int r = quant_error_impl(h, X, dtype, rows, d, ld, bits, clips, count, d_mse, qws, qws_bytes, stream, asym);
+        int r = rq::quant_error_impl(h, X, dtype, rows, d, ld, bits, clips, count, d_mse, qws, qws_bytes, stream, asym);
         if (r != RQ_OK) return r;
-        if (hipStreamSynchronize(s) != hipSuccess ||
-            hipMemcpy(vals, d_mse, sizeof(float) * count, hipMemcpyDeviceToHost) != hipSuccess)
+        // read back on the caller's stream: no other stream is made to wait
+        if (hipMemcpyAsync(vals, d_mse, sizeof(float) * count, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess)
             return RQ_ERR_HIP;
         return RQ_OK;
     };

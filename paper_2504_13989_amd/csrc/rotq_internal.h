@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <vector>
 
@@ -23,9 +24,13 @@ struct rq_hadamard {
     bool dense_ok = false;           // d_tiles holds the whole matrix for the dense-block kernel
     bool generic_ok = false;         // the general LDS kernel can hold a row of this order
     bool generic_f64_ok = false;     // ... and an fp64 copy of it (how fp32 rows are quantized)
-    int variant = 0;                 // 0 auto, 1 general LDS kernel
-    int split = 0;                   // long Sylvester rows: 0 auto, 2 / 4 waves per row, -1 never split
-    const char* last_kernel = "";
+    // test / measurement hook (rq_hadamard_set_variant); atomic so that a hot-path call on another
+    // thread reads a whole value
+    std::atomic<int> variant{0};     // 0 auto, 1 general LDS kernel
+    std::atomic<int> split{0};       // long Sylvester rows: 0 auto, 2 / 4 waves per row, -1 never split
+    // diagnostic only: name of the kernel family the most recent hot-path call chose.  The hot-path
+    // calls take the handle as const and may run on several host threads at once, hence atomic.
+    mutable std::atomic<const char*> last_kernel{""};
 };
 
 namespace rq {
@@ -141,6 +146,15 @@ int wg_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip,
                              float* scales, hipStream_t s);
 int wg_block_quant_error(const rq_hadamard* h, const RowArgs& a, const ClipList& clips, int n_clips,
                          double* partial, hipStream_t s);
+
+// The shared body of rq_quant_error / rq_quant_error_asym (argument checks, dispatch, reduction).
+int quant_error_impl(const rq_hadamard* h, const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits,
+                     const float* clips, int n_clips, float* mse, void* workspace, size_t workspace_bytes,
+                     void* stream, bool asym);
+
+// Codes (+ scales, + mins) to values in the rotated domain, no rotation.
+int dequantize_rows(const uint32_t* codes, const float* scales, const float* mins, int64_t rows, int n, int bits,
+                    float* Y, hipStream_t s);
 
 // Traffic-only reference kernel (measurement aid): rows of n = 512 T 16-bit values.
 int stream_reference(const void* X, int64_t rows, int n, int64_t ld, int bits, uint32_t* codes, float* scales,

@@ -296,3 +296,35 @@ def test_quantize_asym_argument_errors(L):
     assert call(d=64) == E and call(d=200) == E and call(ld=128) == E
     assert call(bits=2) == E and call(clip=0.0) == E and call(clip=1.5) == E
     assert call(X=0) == E and call(X=4097) == E and call(codes=0) == E and call(scales=4098) == E and call(mins=0) == E
+
+
+def test_dequantize_argument_errors(L):
+    E = binding.RQ_ERR_ARG
+    vp = C.c_void_p
+    h = binding.hadamard_build(128)
+    h96 = binding.hadamard_build(96)
+
+    def deq(hh, codes=0x1000, scales=0x2000, rows=4, bits=3, Y=0x3000):
+        return L.rq_dequantize(hh, vp(codes), vp(scales), rows, bits, vp(Y), None)
+
+    def deqa(hh, codes=0x1000, scales=0x2000, mins=0x4000, rows=4, bits=3, Y=0x3000):
+        return L.rq_dequantize_asym(hh, vp(codes), vp(scales), vp(mins), rows, bits, vp(Y), None)
+
+    assert deq(None) == E and deq(h._h, codes=0) == E and deq(h._h, scales=0) == E and deq(h._h, Y=0) == E
+    assert deq(h._h, bits=2) == E and deq(h._h, bits=5) == E and deq(h._h, rows=-1) == E
+    assert deq(h._h, codes=0x1002) == E and deq(h._h, scales=0x2001) == E and deq(h._h, Y=0x3002) == E
+    assert deq(h._h, rows=0, codes=0, scales=0, Y=0) == binding.RQ_OK
+    assert deq(h._h) == binding.RQ_ERR_HIP                     # host-only handle: refused after validation
+    assert deqa(None) == E and deqa(h._h, mins=0) == E and deqa(h._h, mins=0x4002) == E and deqa(h._h, bits=7) == E
+    assert deqa(h96._h) == E                                    # groups of 128 need n % 128 == 0
+    assert deqa(h._h, rows=0, codes=0, scales=0, mins=0, Y=0) == binding.RQ_OK
+    h.close()
+    h96.close()
+
+
+def test_gbs_workspace_follows_the_batch_size(L):
+    # 32 candidates per batch on small tensors, 8 once rows * n must exceed 2^22 for every order
+    assert L.rq_gbs_workspace(512) == 512 * 32 * 8 + 256
+    assert L.rq_gbs_workspace(131072) == 131072 * 32 * 8 + 256
+    assert L.rq_gbs_workspace(131073) == 131073 * 8 * 8 + 256
+    assert L.rq_gbs_workspace(4194304) == 4194304 * 8 * 8 + 256

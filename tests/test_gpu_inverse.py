@@ -168,3 +168,48 @@ def test_rotate_on_the_wave_path(torch, n, d, rows, in_dtype):
     yt = binding.rotate(h, xt, transpose=True)
     torch.cuda.synchronize()
     parity.check_float_rows(yt.cpu().numpy(), want, what=f"n={n} transposed")
+
+
+@pytest.mark.parametrize("name,rows,b", [("tiny", 64, 3), ("llama_hidden", 50, 4), ("qwen_hidden", 41, 3),
+                                         ("ffn_expand", 30, 4), ("ffn_down", 9, 3), ("kv_k", 1029, 3)])
+def test_dequantize_in_the_rotated_domain(torch, name, rows, b):
+    """rq_dequantize (section 2.1, X^ = round(X / Delta) * Delta): one fp32 product per element, so the
+    result equals the oracle's fp64 product of the same code and the same fp32 scale, rounded once."""
+    w = wl.WORKLOADS[name].with_rows(rows)
+    x = wl.generate(w)
+    h = handle(w.n)
+    say(f"dequantize {name} rows={rows} n={w.n} b={b}")
+    q, delta, _, _ = oracle.rotate_quantize(x, w.n, b, w.clip)
+    packed = oracle.pack_codes(q, b)
+    scales32 = delta.astype(np.float32)
+    out = binding.dequantize(h, torch.from_numpy(packed).cuda(), torch.from_numpy(scales32).cuda(), b)
+    torch.cuda.synchronize()
+    assert h.last_kernel == "dequantize"
+    want = oracle.dequantize(q, scales32.astype(np.float64)).astype(np.float32)
+    assert np.array_equal(out.cpu().numpy(), want), f"{name}: dequantized values differ"
+    # the GPU's own codes and scales: the values the kernel chose, back in the rotated domain
+    codes, scales = binding.rotate_quantize(h, parity.to_device(x), b, w.clip)
+    yh = binding.dequantize(h, codes, scales, b)
+    torch.cuda.synchronize()
+    qg = oracle.unpack_codes(codes.cpu().numpy(), b, w.n)
+    want = oracle.dequantize(qg, scales.cpu().numpy().astype(np.float64)).astype(np.float32)
+    assert np.array_equal(yh.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("name,rows,b", [("kv_k", 300, 3), ("kv_v", 1027, 4), ("llama_hidden", 20, 3)])
+def test_dequantize_asym_in_the_rotated_domain(torch, name, rows, b):
+    w = wl.WORKLOADS[name].with_rows(rows)
+    x = wl.generate(w)
+    h = handle(w.n)
+    say(f"dequantize asym {name} rows={rows} n={w.n} b={b}")
+    y = oracle.rotate(x, w.n)
+    q, delta, lo, _ = oracle.quantize_asym(y, b, w.clip)
+    packed = oracle.pack_codes(q, b)
+    d32, l32 = delta.astype(np.float32), lo.astype(np.float32)
+    out = binding.dequantize(h, torch.from_numpy(packed).cuda(), torch.from_numpy(d32).cuda(), b,
+                             mins=torch.from_numpy(l32).cuda())
+    torch.cuda.synchronize()
+    want = oracle.dequantize_asym(q, d32.astype(np.float64), l32.astype(np.float64))
+    got = out.cpu().numpy().astype(np.float64)
+    # one fused multiply-add in fp32: half an ulp of the result
+    assert np.all(np.abs(got - want) <= 2.0 ** -24 * np.abs(want) + 1e-45), f"{name}: dequantized values differ"
