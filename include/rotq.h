@@ -52,6 +52,7 @@ extern "C" {
 #define RQ_ERR_NO_ORDER  -2   /* n has no supported factorisation p * 2^k, n % 8 != 0, or no kernel can hold a row of n */
 #define RQ_ERR_HIP       -3   /* HIP allocation / launch failure, or the handle has no device table */
 #define RQ_ERR_NOMEM     -4   /* host allocation failure */
+#define RQ_ERR_TOO_LARGE -5   /* rq_quant_error_noalloc: rows * n_clips exceeds the static scratch buffer */
 
 #define RQ_BF16 0             /* X elements are bfloat16 (2 bytes) */
 #define RQ_F32  1             /* X elements are float (4 bytes) */
@@ -299,6 +300,25 @@ int rq_quant_error_asym(const rq_hadamard_t* h,
                         const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits,
                         const float* clips, int n_clips,
                         float* mse, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * For callers that cannot allocate device memory - code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: rq_quant_error without a workspace argument.  The per-row
+ * partial sums go to a static device array of RQ_NOALLOC_SCRATCH_BYTES that every GPU the library runs
+ * on holds until the process ends (its address on the handle's device is taken when the handle is
+ * built).  The call allocates nothing and frees nothing; same kernels and same results as
+ * rq_quant_error.
+ *   limit: rq_quant_error_workspace(rows, n_clips) <= RQ_NOALLOC_SCRATCH_BYTES, i.e.
+ *          rows * n_clips <= 524288 (e.g. 8192 rows x 64 clip ratios); beyond it RQ_ERR_TOO_LARGE.
+ * All calls on one GPU share the array: calls that may overlap in time on that GPU (different
+ * streams, or different host threads) race on it and must be ordered by the caller.  The handle's
+ * device must be the current device.
+ * Other arguments and errors as rq_quant_error.
+ */
+#define RQ_NOALLOC_SCRATCH_BYTES (4u << 20)
+int rq_quant_error_noalloc(const rq_hadamard_t* h,
+                           const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits,
+                           const float* clips, int n_clips, float* mse, void* stream);
 
 /* Bytes of device workspace rq_gbs_search needs for `rows` rows; 0 on bad arguments. */
 size_t rq_gbs_workspace(int64_t rows);

@@ -13,7 +13,8 @@ from typing import Optional, Sequence
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librotq.so")
 
-RQ_OK, RQ_ERR_ARG, RQ_ERR_NO_ORDER, RQ_ERR_HIP, RQ_ERR_NOMEM = 0, -1, -2, -3, -4
+RQ_OK, RQ_ERR_ARG, RQ_ERR_NO_ORDER, RQ_ERR_HIP, RQ_ERR_NOMEM, RQ_ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5
+RQ_NOALLOC_SCRATCH_BYTES = 4 << 20
 RQ_BF16, RQ_F32, RQ_F16 = 0, 1, 2
 RQ_MAX_CLIPS = 64
 
@@ -56,6 +57,7 @@ def lib() -> C.CDLL:
     L.rq_quant_error_workspace.restype = C.c_size_t
     L.rq_quant_error.argtypes = [vp, vp, i32, i64, i32, i64, i32, f32p, i32, vp, vp, C.c_size_t, vp]
     L.rq_quant_error_asym.argtypes = L.rq_quant_error.argtypes
+    L.rq_quant_error_noalloc.argtypes = [vp, vp, i32, i64, i32, i64, i32, f32p, i32, vp, vp]
     L.rq_dequantize.argtypes = [vp, vp, vp, i64, i32, vp, vp]
     L.rq_dequantize_asym.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp]
     L.rq_gbs_workspace.argtypes = [i64]
@@ -357,6 +359,19 @@ def quant_error(h: Hadamard, x, bits: int, clips: Sequence[float], mse=None, wor
     rc = fn(h._h, C.c_void_p(x2.data_ptr()), _dtype_code(x2), rows, d, ld, int(bits), arr, k,
             C.c_void_p(mse.data_ptr()), C.c_void_p(workspace.data_ptr()), ws_bytes, _stream_ptr(stream))
     _check(rc, "rq_quant_error_asym" if asym else "rq_quant_error")
+    return mse
+
+
+def quant_error_noalloc(h: Hadamard, x, bits: int, clips: Sequence[float], mse, stream=None):
+    """rq_quant_error_noalloc on a CUDA tensor x [..., d]: rq_quant_error with the library's static
+    scratch array in place of a workspace.  `mse` (float32 [len(clips)], device) is the caller's: the
+    call itself allocates nothing."""
+    x2, rows, d, ld = _rows_view(x)
+    k = len(clips)
+    arr = (C.c_float * k)(*[float(c) for c in clips])
+    rc = lib().rq_quant_error_noalloc(h._h, C.c_void_p(x2.data_ptr()), _dtype_code(x2), rows, d, ld, int(bits),
+                                      arr, k, C.c_void_p(mse.data_ptr()), _stream_ptr(stream))
+    _check(rc, "rq_quant_error_noalloc")
     return mse
 
 

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "librotq.so")
 
-SOURCES = ["hadamard.cpp", "rotq_api.cpp", "kernels_generic.hip", "kernels_wave.hip", "kernels_wgblock.hip", "kernels_dense.hip", "kernels_ref.hip", "kernels_waveblock2.hip", "kernels_rotate.hip", "kernels_plainasym.hip", "kernels_dequant.hip"]
+SOURCES = ["hadamard.cpp", "rotq_api.cpp", "kernels_generic.hip", "kernels_wave.hip", "kernels_wgblock.hip", "kernels_dense.hip", "kernels_ref.hip", "kernels_waveblock2.hip", "kernels_rotate.hip", "kernels_plainasym.hip", "kernels_dequant.hip", "noalloc.hip"]
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",

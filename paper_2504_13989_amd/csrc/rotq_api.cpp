@@ -132,6 +132,9 @@ int rq_hadamard_build(int n, rq_hadamard_t** out) {
     }
     h->device = dev;
     h->generic_ok = rq::generic_prepare(h);
+    // set-up time is when the static scratch array's address on this device is asked for; a failure
+    // only makes rq_quant_error_noalloc return RQ_ERR_HIP
+    (void)rq::static_scratch(dev);
     *out = h;
     return RQ_OK;
 }
@@ -585,6 +588,7 @@ const char* rq_strerror(int code) {
         case RQ_ERR_NO_ORDER: return "no supported Hadamard order";
         case RQ_ERR_HIP: return "HIP failure or handle without device tables";
         case RQ_ERR_NOMEM: return "out of host memory";
+        case RQ_ERR_TOO_LARGE: return "input larger than the static scratch buffer of the no-allocation call";
         default: return "unknown error";
     }
 }

@@ -152,6 +152,10 @@ int quant_error_impl(const rq_hadamard* h, const void* X, int dtype, int64_t row
                      const float* clips, int n_clips, float* mse, void* workspace, size_t workspace_bytes,
                      void* stream, bool asym);
 
+// Device address of the library's static scratch array on device `dev`; the first call for a device must
+// be made with that device current (rq_hadamard_build does so).  nullptr when it cannot be resolved.
+void* static_scratch(int dev);
+
 // Codes (+ scales, + mins) to values in the rotated domain, no rotation.
 int dequantize_rows(const uint32_t* codes, const float* scales, const float* mins, int64_t rows, int n, int bits,
                     float* Y, hipStream_t s);

@@ -322,6 +322,25 @@ def test_dequantize_argument_errors(L):
     h96.close()
 
 
+def test_quant_error_noalloc_argument_errors(L):
+    E = binding.RQ_ERR_ARG
+    h = binding.hadamard_build(128)
+    clips = (C.c_float * 3)(0.5, 0.75, 1.0)
+
+    def call(hh=h._h, X=0x1000, rows=4, d=128, ld=128, bits=3, cl=clips, k=3, mse=0x4000):
+        return L.rq_quant_error_noalloc(hh, C.c_void_p(X), 0, rows, d, ld, bits, cl, k, C.c_void_p(mse), None)
+
+    assert call(hh=None) == E
+    assert call(rows=-1) == E and call(k=0) == E and call(k=65) == E
+    # beyond the static scratch array: refused with an error of its own, whatever else is wrong
+    limit = binding.RQ_NOALLOC_SCRATCH_BYTES // 8
+    assert call(rows=limit // 3 + 1) == binding.RQ_ERR_TOO_LARGE
+    assert call(rows=limit // 64 + 1, k=64, cl=(C.c_float * 64)(*([0.9] * 64))) == binding.RQ_ERR_TOO_LARGE
+    assert b"static scratch" in L.rq_strerror(binding.RQ_ERR_TOO_LARGE)
+    assert call() == binding.RQ_ERR_HIP                         # host-only handle (no GPU here)
+    h.close()
+
+
 def test_gbs_workspace_follows_the_batch_size(L):
     # 32 candidates per batch on small tensors, 8 once rows * n must exceed 2^22 for every order
     assert L.rq_gbs_workspace(512) == 512 * 32 * 8 + 256
