@@ -30,26 +30,39 @@
 // 4 <= p <= 256.
 #include "wave_common.h"
 
+#ifdef RQ_WG_PROF
+// experiment only: per-phase cycle stamps of the first rows of the first blocks
+__device__ unsigned long long g_prof[64 * 16 * 64 * 8];   // [block][wave][iter][stamp]
+#define RQ_STAMP(k)                                                                                   \
+    do {                                                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                            \
+        if (!QE && blockIdx.x < 64 && prof_it < 64 && lane == 0)                                      \
+            g_prof[((blockIdx.x * 16 + wave) * 64 + prof_it) * 8 + (k)] = __builtin_readcyclecounter(); \
+        __builtin_amdgcn_sched_barrier(0);                                                            \
+    } while (0)
+extern "C" int rq_debug_prof_read(void* host) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_prof), sizeof(g_prof));
+}
+#else
+#define RQ_STAMP(k)
+#endif
+
 namespace rq {
 namespace {
 
-// 16-byte units per LDS column, at least 4 KK (32 block rows per contraction step).  The 16 lanes
-// of a DPP row read one unit each from 16 neighbouring columns, and all 16 must fall into different
-// 16-byte slots of the 256-byte bank window:
-//   KK odd   exactly 4 KK units: a column is an odd multiple of 64 bytes, so four neighbouring
-//            columns start in the four quarters of the window; the unit index is xor-ed with c >> 2
-//            (two bits), which separates the four columns that share a quarter;
-//   KK even  a multiple of 8 that is = 8 (mod 16): columns start in alternating halves and the
-//            unit index is xor-ed with c >> 1 (three bits).
+// LDS operand buffer: for every (column tile nt, contraction step kk) one 1 KB block holding the data
+// operand of that matrix-core instruction in lane order - lane (g, c) finds the 8 block rows
+// 32 kk + 8 g .. + 7 of column (c, nt) at byte lane * 16 of the block.  A read instruction thus takes
+// 1 KB of consecutive bytes and a phase-1 write instruction (8 bytes per lane: 4 block rows) 512
+// consecutive bytes: neither meets a bank conflict, with no swizzle and no padding.  (Measured with a
+// read-only probe on this chip: 16-byte reads in lane order move 488 bytes per ns and CU, a layout that
+// gives the 16 lanes of a DPP row 16 different 16-byte slots of a 256-byte window in scattered order only
+// 375.)
 template <int KK>
-constexpr int wg_chunks() {
-    if (KK % 2 == 1) return 4 * KK;
-    int n = ((4 * KK + 7) / 8) * 8;
-    return (n % 16 == 8) ? n : n + 8;
-}
+constexpr size_t wg_ops_bytes() { return (size_t)8 * KK * 1024; }
 
 template <int KK>
-constexpr size_t wg_lds_bytes() { return (size_t)128 * wg_chunks<KK>() * 16 + (size_t)KK * 32 * 48; }
+constexpr size_t wg_lds_bytes() { return wg_ops_bytes<KK>() + (size_t)KK * 32 * 48; }
 
 // Register budget, as waves per SIMD (512 VGPRs per SIMD lane).  The hardware deals the waves of
 // successive workgroups round robin over the four SIMDs, so a CU holds 4 x this many waves:
@@ -80,21 +93,15 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
     constexpr int SEG = 8 << CB;                         // columns of one block row (2^k)
     constexpr bool PF = wg_waves_per_simd<KK>() == 4;    // loads run one pass ahead
     __shared__ float esum[QE ? 16 : 1][QE ? RPW : 1][QE ? RQ_MAX_CLIPS : 1];   // [wave][row of the pass][clip]
-    constexpr int NCH = wg_chunks<KK>();
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    uint8_t* const ops = lds_raw;                        // [128 columns][NCH] x 16 bytes
-    uint8_t* const stage = lds_raw + 128 * NCH * 16;     // packed codes of the row (b = 3)
+    uint8_t* const ops = lds_raw;                        // [column tile][contraction step] x 1 KB, see wg_ops_bytes
+    uint8_t* const stage = lds_raw + wg_ops_bytes<KK>(); // packed codes of the row (b = 3)
     __shared__ float wmax[16 * RPW];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nw = blockDim.x >> 6;                      // ceil(pb / 16)
     const int g = lane >> 4, cphys = lane & 15;
     const int c = (cphys & 4) ? (cphys ^ 3) : cphys;    // logical column group (8 columns)
-    // LDS column of (column group c, position ic inside the group) is ic * 16 + c: the 16 lanes of a
-    // DPP row then touch 16 neighbouring columns, whose 16-byte units are 16 different ones of a
-    // 256-byte bank window (see wg_chunks).
-    constexpr bool Q4 = NCH % 8 == 4;                    // quarter-window layout (KK odd)
-    const int swz = Q4 ? (c >> 2) & 3 : (c >> 1) & 7;
     const int rsub = CB == 4 ? 0 : c >> CB;              // row of the pass
     const int cl = CB == 4 ? c : c & ((1 << CB) - 1);    // 8-column chunk inside that row
 
@@ -111,16 +118,14 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
     // of B: any in-bounds data will do, and it reads the last four real rows.
     const int r0 = 16 * wave + 4 * g;
     const int eoff0 = (r0 < pb ? r0 : pb - 4) * SEG + cl * 8;
-    // 8-byte half of the 16-byte unit that holds block rows 8 q .. 8 q + 7, q = 2 wave + g / 2
-    const int wr_unit = ((2 * wave + (g >> 1)) ^ swz) * 16 + (g & 1) * 8;
-
-    const uint8_t* const rd0 = ops + c * (NCH * 16) + ((g ^ swz) * 16);
-    const uint8_t* const rd1 = ops + c * (NCH * 16) + (((4 + g) ^ swz) * 16);
-    uint8_t* const wr0 = ops + c * (NCH * 16) + wr_unit;
+    // phase-1 writes: the lane's block rows 16 wave + 4 g .. + 3 are one 8-byte half of the unit that
+    // reader lane (2 (wave & 1) + g / 2, c) takes in contraction step wave / 2
+    uint8_t* const wr0 = ops + ((((wave >> 1) * 4 + 2 * (wave & 1) + (g >> 1)) * 16 + cphys) * 16 + (g & 1) * 8);
+    const uint8_t* const rd0 = ops + lane * 16;
 
     // Units for block rows at or beyond 16 nw are never written by phase 1 but are read by the last
     // contraction step (against zero columns of B): clear the buffer once so they hold zeros.
-    for (int i = threadIdx.x; i < 128 * NCH; i += blockDim.x)
+    for (int i = threadIdx.x; i < 8 * KK * 64; i += blockDim.x)
         reinterpret_cast<u32x4*>(ops)[i] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
 
@@ -147,10 +152,17 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
         load_row(CB == 4 || r < a.rows ? r : a.rows - 1);
     };
     if (PF && (int64_t)blockIdx.x < n_pass) load_pass(blockIdx.x);
+    [[maybe_unused]] int prof_it = -1;
     for (int64_t pass = blockIdx.x; pass < n_pass; pass += gridDim.x) {
         const int64_t row = pass * RPW + rsub;
         const bool live = CB == 4 || row < a.rows;
+        ++prof_it;
+        RQ_STAMP(0);
         if (!PF) load_pass(pass);
+#ifdef RQ_WG_PROF
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+        RQ_STAMP(1);
         // ---- phase 1
 #pragma unroll
         for (int ic = 0; ic < 8; ++ic) {
@@ -158,44 +170,28 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
             uint2 v;
             v.x = __builtin_amdgcn_perm(R[1][ic >> 1], R[0][ic >> 1], sel);
             v.y = __builtin_amdgcn_perm(R[3][ic >> 1], R[2][ic >> 1], sel);
-            *reinterpret_cast<uint2*>(wr0 + ic * 16 * (NCH * 16)) = v;
+            *reinterpret_cast<uint2*>(wr0 + ic * (KK * 1024)) = v;
         }
+        RQ_STAMP(2);
         __syncthreads();
+        RQ_STAMP(3);
         if (PF && pass + gridDim.x < n_pass) load_pass(pass + gridDim.x);
         // ---- phase 2
-        // Long contractions (KK >= 6, one workgroup of 12 - 16 waves per CU): the 8 KK operand reads are kept
-        // DEPTH ahead of the matrix-core instructions that use them, in a ring of DEPTH register quads
-        // (left to itself the compiler issues each read right before its use and waits for it: one LDS
-        // round trip per instruction; 28672- and 32768-wide rows gain 4 %).  Items run over pairs of column
-        // tiles, so that consecutive instructions alternate between two accumulators.
         f32x4 acc[8];
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if constexpr (KK < 6) {
-            // each read right before its use: with 80 registers a ring of reads in flight spills (11008-wide
-            // rows 0.585 -> 0.50 of peak), and for KK = 4 it measured no gain (13824 + 1.5 %, 16384 - 3 %):
-            // the other resident waves cover the LDS latency
-#pragma unroll
-            for (int nt = 0; nt < 8; ++nt)
-#pragma unroll
-                for (int kk = 0; kk < KK; ++kk) {
-                    const u32x4 raw = *reinterpret_cast<const u32x4*>(
-                        Q4 ? rd0 + nt * 16 * (NCH * 16) + kk * 64
-                           : ((kk & 1) ? rd1 : rd0) + nt * 16 * (NCH * 16) + (kk >> 1) * 128);
-                    acc[nt] = mfma_pm1<F16>(A[kk], raw, acc[nt]);
-                }
-        } else {
-            constexpr int DEPTH = 4, ITEMS = 8 * KK;
-            // item i -> (column tile, contraction step)
-            auto item_nt = [](int i) { return 2 * (i / (2 * KK)) + (i & 1); };
-            auto item_kk = [](int i) { return (i % (2 * KK)) >> 1; };
-            // unit (4 kk + g) ^ swz: a two-bit xor leaves one per-lane base plus a compile-time offset,
-            // a three-bit xor two bases (kk even / odd)
-            auto read_item = [&](int i) {
-                const int nt = item_nt(i), kk = item_kk(i);
-                return *reinterpret_cast<const u32x4*>(
-                    Q4 ? rd0 + nt * 16 * (NCH * 16) + kk * 64
-                       : ((kk & 1) ? rd1 : rd0) + nt * 16 * (NCH * 16) + (kk >> 1) * 128);
+        {
+            // The 8 KK operand reads run DEPTH ahead of the matrix-core instructions that use them, in a ring
+            // of DEPTH register quads; the contraction step is the outer loop, so that consecutive
+            // instructions go to different accumulators and none waits for its predecessor's result.
+            // (3 where the 80-register kernels have room for it, 2 in their padded-row and quant_error forms)
+#ifdef RQ_WG_DEPTH
+            constexpr int DEPTH = RQ_WG_DEPTH, ITEMS = 8 * KK;
+#else
+            constexpr int DEPTH = KK >= 6 ? 4 : (FULL && !QE) ? 3 : 2, ITEMS = 8 * KK;
+#endif
+            auto read_item = [&](int i) {                // item i = (contraction step i / 8, column tile i % 8)
+                return *reinterpret_cast<const u32x4*>(rd0 + ((i % 8) * KK + i / 8) * 1024);
             };
             u32x4 ring[DEPTH];
 #pragma unroll
@@ -203,11 +199,12 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
 #pragma unroll
             for (int i = 0; i < ITEMS; ++i) {
                 __builtin_amdgcn_sched_barrier(0);
-                acc[item_nt(i)] = mfma_pm1<F16>(A[item_kk(i)], ring[i % DEPTH], acc[item_nt(i)]);
+                acc[i % 8] = mfma_pm1<F16>(A[i / 8], ring[i % DEPTH], acc[i % 8]);
                 if (i + DEPTH < ITEMS) ring[i % DEPTH] = read_item(i + DEPTH);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        RQ_STAMP(4);
         // ---- phase 3
 #pragma unroll
         for (int s = 1; s < 8; s <<= 1)
@@ -240,7 +237,9 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
         }
         m = wave_absmax<CB>(m);                          // over the lanes that share the row
         if (g == 0 && cl == 0) wmax[wave * RPW + rsub] = m;
+        RQ_STAMP(5);
         __syncthreads();    // also: every wave is done reading this row's operands from LDS
+        RQ_STAMP(6);
         m = wmax[rsub];
         for (int w = 1; w < nw; ++w) m = fmaxf(m, wmax[w * RPW + rsub]);
         // ---- phase 4
@@ -317,6 +316,7 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
                                             reinterpret_cast<u32x4*>(out) + unit);
         }
         if (wave == 0 && g == 0 && cl == 0 && live) a.scales[row] = (float)(a.c2 * (double)m);
+        RQ_STAMP(7);
     }
 }
 
@@ -394,6 +394,9 @@ int launch_kk(const rq_hadamard* h, const WaveArgs& a, int bits, int pb, int cb,
     const int by_waves = 4 * wg_waves_per_simd<KK>() / nw;   // see the register budget note at the kernel
     if (per_cu > by_waves) per_cu = by_waves;
     if (per_cu < 1) per_cu = 1;
+#ifdef RQ_WG_PERCU
+    per_cu = RQ_WG_PERCU;
+#endif
     const int64_t cap = (int64_t)h->num_cu * per_cu;
     const int rpw = 16 >> cb;
     const int64_t passes = (a.rows + rpw - 1) / rpw;
