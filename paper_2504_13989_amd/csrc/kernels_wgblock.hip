@@ -8,12 +8,12 @@
 // the 16 block rows 16 w .. 16 w + 15 on input and on output:
 //   phase 1  the wave loads its block rows (16-byte chunks, 4 per lane), transposes 16-bit
 //            values inside each lane (v_perm_b32) so that consecutive block rows of one column are
-//            adjacent, and writes them to LDS laid out [column][block row]; 16-byte units are
-//            xor-swizzled by the lane's column group so that writes and reads avoid bank
-//            conflicts;
+//            adjacent, and writes them to LDS as the data operands of phase 2, one 1 KB block per
+//            matrix-core instruction in lane order (no bank conflicts on either side);
 //   phase 2  the wave computes its 16 output block rows for all 128 columns: 8 column tiles x
 //            KK = ceil(pb / 32) contraction steps of v_mfma_f32_16x16x32_bf16, its KK operand tiles of
-//            B resident in registers, the data operands read from LDS (16 bytes per lane);
+//            B resident in registers, the data operands read from LDS (16 bytes per lane) a few
+//            instructions ahead of their use;
 //   phase 3  128-point transform along the columns: three register stages, four fused DPP
 //            stages, absmax; workgroup absmax through LDS;
 //   phase 4  scale, round/clamp, pack; b = 4 stores dwords, b = 3 assembles the row's bytes in LDS
@@ -29,23 +29,6 @@
 // and the output rows are per row of the pass.  Here the block is H_p itself, of any order
 // 4 <= p <= 256.
 #include "wave_common.h"
-
-#ifdef RQ_WG_PROF
-// experiment only: per-phase cycle stamps of the first rows of the first blocks
-__device__ unsigned long long g_prof[64 * 16 * 64 * 8];   // [block][wave][iter][stamp]
-#define RQ_STAMP(k)                                                                                   \
-    do {                                                                                              \
-        __builtin_amdgcn_sched_barrier(0);                                                            \
-        if (!QE && blockIdx.x < 64 && prof_it < 64 && lane == 0)                                      \
-            g_prof[((blockIdx.x * 16 + wave) * 64 + prof_it) * 8 + (k)] = __builtin_readcyclecounter(); \
-        __builtin_amdgcn_sched_barrier(0);                                                            \
-    } while (0)
-extern "C" int rq_debug_prof_read(void* host) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_prof), sizeof(g_prof));
-}
-#else
-#define RQ_STAMP(k)
-#endif
 
 namespace rq {
 namespace {
@@ -152,17 +135,10 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
         load_row(CB == 4 || r < a.rows ? r : a.rows - 1);
     };
     if (PF && (int64_t)blockIdx.x < n_pass) load_pass(blockIdx.x);
-    [[maybe_unused]] int prof_it = -1;
     for (int64_t pass = blockIdx.x; pass < n_pass; pass += gridDim.x) {
         const int64_t row = pass * RPW + rsub;
         const bool live = CB == 4 || row < a.rows;
-        ++prof_it;
-        RQ_STAMP(0);
         if (!PF) load_pass(pass);
-#ifdef RQ_WG_PROF
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
-        RQ_STAMP(1);
         // ---- phase 1
 #pragma unroll
         for (int ic = 0; ic < 8; ++ic) {
@@ -172,9 +148,7 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
             v.y = __builtin_amdgcn_perm(R[3][ic >> 1], R[2][ic >> 1], sel);
             *reinterpret_cast<uint2*>(wr0 + ic * (KK * 1024)) = v;
         }
-        RQ_STAMP(2);
         __syncthreads();
-        RQ_STAMP(3);
         if (PF && pass + gridDim.x < n_pass) load_pass(pass + gridDim.x);
         // ---- phase 2
         f32x4 acc[8];
@@ -185,11 +159,7 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
             // of DEPTH register quads; the contraction step is the outer loop, so that consecutive
             // instructions go to different accumulators and none waits for its predecessor's result.
             // (3 where the 80-register kernels have room for it, 2 in their padded-row and quant_error forms)
-#ifdef RQ_WG_DEPTH
-            constexpr int DEPTH = RQ_WG_DEPTH, ITEMS = 8 * KK;
-#else
             constexpr int DEPTH = KK >= 6 ? 4 : (FULL && !QE) ? 3 : 2, ITEMS = 8 * KK;
-#endif
             auto read_item = [&](int i) {                // item i = (contraction step i / 8, column tile i % 8)
                 return *reinterpret_cast<const u32x4*>(rd0 + ((i % 8) * KK + i / 8) * 1024);
             };
@@ -204,7 +174,6 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        RQ_STAMP(4);
         // ---- phase 3
 #pragma unroll
         for (int s = 1; s < 8; s <<= 1)
@@ -237,9 +206,7 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
         }
         m = wave_absmax<CB>(m);                          // over the lanes that share the row
         if (g == 0 && cl == 0) wmax[wave * RPW + rsub] = m;
-        RQ_STAMP(5);
         __syncthreads();    // also: every wave is done reading this row's operands from LDS
-        RQ_STAMP(6);
         m = wmax[rsub];
         for (int w = 1; w < nw; ++w) m = fmaxf(m, wmax[w * RPW + rsub]);
         // ---- phase 4
@@ -316,7 +283,6 @@ void k_wg_block(WaveArgs a, int pb, QeArgs qe) {
                                             reinterpret_cast<u32x4*>(out) + unit);
         }
         if (wave == 0 && g == 0 && cl == 0 && live) a.scales[row] = (float)(a.c2 * (double)m);
-        RQ_STAMP(7);
     }
 }
 
@@ -394,9 +360,6 @@ int launch_kk(const rq_hadamard* h, const WaveArgs& a, int bits, int pb, int cb,
     const int by_waves = 4 * wg_waves_per_simd<KK>() / nw;   // see the register budget note at the kernel
     if (per_cu > by_waves) per_cu = by_waves;
     if (per_cu < 1) per_cu = 1;
-#ifdef RQ_WG_PERCU
-    per_cu = RQ_WG_PERCU;
-#endif
     const int64_t cap = (int64_t)h->num_cu * per_cu;
     const int rpw = 16 >> cb;
     const int64_t passes = (a.rows + rpw - 1) / rpw;
