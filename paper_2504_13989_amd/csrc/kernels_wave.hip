@@ -231,14 +231,76 @@ __global__ __launch_bounds__(64 * S) void k_wave_sylvester_split(WaveArgs a) {
 // Lane (g, r, c): DPP row g holds contraction slots, r selects the row of the pass, c the
 // column chunk; the matrix cores transform the (g, i) bits, CB DPP stages the c bits.
 // GUARD: the super-group may be ragged (rows missing at the end) or d < n.
+// The vector ALU is what these kernels are bound by (about ten instructions per value), so the work that
+// is per row rather than per value is done once for four passes at a time: the lane maxima of four
+// passes cross the four DPP rows together (the row-swap instructions work on two registers at once) and
+// leave pass k's maximum in DPP row k; that row alone forms the row's scale and multiplier (one
+// division sequence for four passes) and stores the scale (one store of 16 floats for four passes);
+// three more swaps hand the four multipliers back to every lane.  The codes go out through the
+// iteration's base address in scalar registers plus one per-lane byte offset computed once.
+//
+// v_permlane16_swap(a, b) leaves a = [a0 b0 a2 b2], b = [a1 b1 a3 b3] (DPP rows of the old a, b);
+// v_permlane32_swap(a, b) leaves a = [a0 a1 b0 b1], b = [a2 a3 b2 b3].
+__device__ __forceinline__ void swap16(uint32_t& x, uint32_t& y) {
+    const auto r = __builtin_amdgcn_permlane16_swap(x, y, false, false);
+    x = r[0]; y = r[1];
+}
+__device__ __forceinline__ void swap32(uint32_t& x, uint32_t& y) {
+    const auto r = __builtin_amdgcn_permlane32_swap(x, y, false, false);
+    x = r[0]; y = r[1];
+}
+// Maxima of four passes over the four DPP rows: DPP row k of the result holds pass k's maximum.
+// Non-negative floats are compared as unsigned patterns; SIGNED takes a float maximum (written as
+// an instruction: the compiler would canonicalize operands that come out of assembly blocks first).
+template <bool SIGNED = false>
+__device__ __forceinline__ uint32_t max_raw(uint32_t a, uint32_t b) {
+    if constexpr (SIGNED) {
+        uint32_t r;
+        asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+        return r;
+    } else {
+        return max(a, b);
+    }
+}
+template <bool SIGNED = false>
+__device__ __forceinline__ uint32_t rows_reduce4(uint32_t A, uint32_t B, uint32_t C, uint32_t D) {
+    swap16(A, B);
+    uint32_t x = max_raw<SIGNED>(A, B);           // [A01 B01 A23 B23]
+    swap16(C, D);
+    uint32_t y = max_raw<SIGNED>(C, D);           // [C01 D01 C23 D23]
+    swap32(x, y);                                 // x = [A01 B01 C01 D01], y = [A23 B23 C23 D23]
+    return max_raw<SIGNED>(x, y);
+}
+// Float maximum of two values at once over the four lanes of a quad (DPP-fused).
+__device__ __forceinline__ void quad_max_pair(float& a, float& b) {
+    asm("s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 3"
+        : "+v"(a), "+v"(b));
+}
+// The reverse: out[k] = the value DPP row k holds, in every lane (same position inside the row).
+__device__ __forceinline__ void rows_bcast4(uint32_t z, uint32_t (&out)[4]) {
+    uint32_t z2 = z;
+    swap16(z, z2);                                // z = [z0 z0 z2 z2], z2 = [z1 z1 z3 z3]
+    uint32_t zc = z, z2c = z2;
+    swap32(z, zc);                                // z = [z0 z0 z0 z0], zc = [z2 z2 z2 z2]
+    swap32(z2, z2c);
+    out[0] = z; out[1] = z2; out[2] = zc; out[3] = z2c;
+}
+
 template <int CB, int BITS, int U, bool GUARD, bool ASYM, bool F16>
 __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_t* base, uint32_t* obase,
-                                                float* sbase, int64_t row0, int rem, const u32x4& A0, const u32x4& A1,
+                                                float* sbase, float* mbase, int rem, const u32x4& A0, const u32x4& A1,
                                                 const float (&sf)[4], float flip, int g, int c, int rsub,
                                                 int chunk,
                                                 float c1h, float c1l, float c2h, float c2l) {
     constexpr int RPW = 16 >> CB;
     constexpr int ROW_DWORDS = (32 << CB) * BITS / 32;
+    static_assert(U % 4 == 0, "passes are taken four at a time");
     u32x4 raw[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -252,54 +314,97 @@ __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_
             raw[u] = load16(p);
         }
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int rr = u * RPW + rsub;
-        const bool live = !GUARD || rr < rem;
-        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        f32x4 v0 = mfma_pm1<F16>(A0, raw[u], z);
-        f32x4 v1 = mfma_pm1<F16>(A1, raw[u], z);
-        lane_stages_mfma<CB>(v0, sf);
-        lane_stages_mfma<CB>(v1, sf);
-        uint32_t w;
-        float m = 0.0f;
-        if constexpr (ASYM) {
-            // one group of 128 = the whole row (section 5.1, KV cache): min / max instead of absmax
-            static_assert(!ASYM || CB == 2, "asymmetric groups: rows of 128 only");
-            // the lane holds flip * y (see lane_stages_fused): its own extremes swap with the sign
-            const float yv[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-            const float lo = min8(yv), hi = max8(yv);
-            float mx = flip > 0.0f ? hi : -lo;
-            float nm = flip > 0.0f ? -lo : hi;                    // -min
-            quad_rows_max_pair(mx, nm);
-            const float mn = -nm;
-            const double r64 = (double)mx - (double)mn;           // exact
-            const float rh = (float)r64, rl = (float)(r64 - (double)rh);
-            const bool flat = !(rh > 0.0f);
-            const float s = flat ? 0.0f : flip * div_pair2(c1h, c1l, rh, rl);
-            constexpr double kMid = (double)(1 << (BITS - 1)) / (double)((1 << BITS) - 1);
-            const float cen = flip * (float)(a.clip * fma(r64, kMid, (double)mn));
-            const float bias = flat ? Quant<BITS>::kMagic : Quant<BITS>::kBias;
-            w = Quant<BITS>::pack8u(yv, cen, s, bias);
-            if (live && g == 0 && c == 0) {
-                sbase[rr] = rh * (float)a.c2;
-                a.mins[row0 + rr] = mn * (float)a.c3;
-            }
-        } else {
-            m = absmax4(absmax4(0.0f, v0), v1);
-            m = wave_absmax<CB>(m);                          // over the lanes that share the row
-            const float s = m > 0.0f ? flip * div_pair(c1h, c1l, m) : 0.0f;
-            w = Quant<BITS>::pack8(v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3], s);
-        }
-        uint32_t* out = obase + rr * ROW_DWORDS;
+    const uint32_t code_off = (uint32_t)(rsub * ROW_DWORDS + (BITS == 4 ? chunk : (chunk >> 2) * 3 + (c & 3))) * 4u;
+    uint32_t* const out0 = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(obase) + code_off);
+    auto store_pass = [&](int u, uint32_t w) {
+        const bool live = !GUARD || u * RPW + rsub < rem;
+        uint32_t* out = out0 + u * RPW * ROW_DWORDS;
         if (BITS == 4) {
-            if (live) store_codes(out + chunk, w);
+            if (live) store_codes(out, w);
         } else {
             const int qpos = c & 3;
             const uint32_t dw = merge24<(CB >= 3)>(w, qpos);
-            if (live && qpos < 3) store_codes(out + (chunk >> 2) * 3 + qpos, dw);
+            if (live && qpos < 3) store_codes(out, dw);
         }
-        if (!ASYM && live && g == 0 && c == 0) sbase[rr] = fmaf(m, c2l, m * c2h);
+    };
+#pragma unroll
+    for (int u0 = 0; u0 < U; u0 += 4) {
+        f32x4 v0[4], v1[4];
+        // row of the four passes that this lane's DPP row answers for, and whether this lane stores for it
+        const int srow = (u0 + g) * RPW + rsub;
+        const bool store_lane = c == 0 && (!GUARD || srow < rem);
+        if constexpr (ASYM) {
+            // one group of 128 = the whole row (section 5.1, KV cache): min / max instead of absmax
+            static_assert(!ASYM || CB == 2, "asymmetric groups: rows of 128 only");
+            uint32_t mxu[4], nmu[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+                v0[k] = mfma_pm1<F16>(A0, raw[u0 + k], z);
+                v1[k] = mfma_pm1<F16>(A1, raw[u0 + k], z);
+                lane_stages_mfma<CB>(v0[k], sf);
+                lane_stages_mfma<CB>(v1[k], sf);
+                // the lane holds flip * y (see lane_stages_fused): its own extremes swap with the sign
+                const float yv[8] = {v0[k][0], v0[k][1], v0[k][2], v0[k][3], v1[k][0], v1[k][1], v1[k][2], v1[k][3]};
+                const float lo = min8(yv), hi = max8(yv);
+                float mx = flip > 0.0f ? hi : -lo;
+                float nm = flip > 0.0f ? -lo : hi;                    // -min
+                quad_max_pair(mx, nm);                                // over the quad: the row's lanes in this DPP row
+                mxu[k] = __float_as_uint(mx);
+                nmu[k] = __float_as_uint(nm);
+            }
+            const float mx = __uint_as_float(rows_reduce4<true>(mxu[0], mxu[1], mxu[2], mxu[3]));
+            const float mn = -__uint_as_float(rows_reduce4<true>(nmu[0], nmu[1], nmu[2], nmu[3]));
+            // DPP row k: the group parameters of pass u0 + k
+            const double r64 = (double)mx - (double)mn;           // exact
+            const float rh = (float)r64, rl = (float)(r64 - (double)rh);
+            const bool flat = !(rh > 0.0f);
+            const float q = flat ? 0.0f : div_pair2(c1h, c1l, rh, rl);
+            constexpr double kMid = (double)(1 << (BITS - 1)) / (double)((1 << BITS) - 1);
+            const float cen = (float)(a.clip * fma(r64, kMid, (double)mn));
+            if (store_lane) {
+                sbase[srow] = rh * (float)a.c2;
+                mbase[srow] = mn * (float)a.c3;
+            }
+            uint32_t q4[4], c4[4];
+            rows_bcast4(__float_as_uint(q), q4);
+            rows_bcast4(__float_as_uint(cen), c4);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float yv[8] = {v0[k][0], v0[k][1], v0[k][2], v0[k][3], v1[k][0], v1[k][1], v1[k][2], v1[k][3]};
+                const float qk = __uint_as_float(q4[k]);
+                const float bias = qk > 0.0f ? Quant<BITS>::kBias : Quant<BITS>::kMagic;   // a flat group: code 0
+                store_pass(u0 + k, Quant<BITS>::pack8u(yv, flip * __uint_as_float(c4[k]), flip * qk, bias));
+            }
+        } else {
+            uint32_t mu[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+                v0[k] = mfma_pm1<F16>(A0, raw[u0 + k], z);
+                v1[k] = mfma_pm1<F16>(A1, raw[u0 + k], z);
+                lane_stages_mfma<CB>(v0[k], sf);
+                lane_stages_mfma<CB>(v1[k], sf);
+                uint32_t m = __float_as_uint(absmax4(absmax4(0.0f, v0[k]), v1[k]));
+                // inside the DPP row: the lanes that share the row (CB lane bits)
+                m = max(m, dpp_u<kDppXor1>(m));
+                m = max(m, dpp_u<kDppXor2>(m));
+                if (CB >= 3) m = max(m, dpp_u<kDppHalfMirror>(m));
+                if (CB >= 4) m = max(m, dpp_u<kDppRor8>(m));
+                mu[k] = m;
+            }
+            // DPP row k: absmax, scale and multiplier of pass u0 + k
+            const float m = __uint_as_float(rows_reduce4(mu[0], mu[1], mu[2], mu[3]));
+            const float qd = div_pair(c1h, c1l, m);
+            const float q = m > 0.0f ? qd : 0.0f;
+            if (store_lane) sbase[srow] = fmaf(m, c2l, m * c2h);
+            uint32_t q4[4];
+            rows_bcast4(__float_as_uint(q), q4);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                store_pass(u0 + k, Quant<BITS>::pack8(v0[k][0], v0[k][1], v0[k][2], v0[k][3], v1[k][0], v1[k][1], v1[k][2],
+                                                      v1[k][3], flip * __uint_as_float(q4[k])));
+        }
     }
 }
 
@@ -333,11 +438,12 @@ __global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
         const uint16_t* base = a.X + row0 * a.ld;
         uint32_t* obase = a.codes + row0 * ROW_DWORDS;
         float* sbase = a.scales + row0;
+        float* mbase = ASYM ? a.mins + row0 : nullptr;
         if (rem == SUPER && full_d)
-            short_rows_pass<CB, BITS, U, false, ASYM, F16>(a, base, obase, sbase, row0, rem, A0, A1, sf, flip, g, c, rsub, chunk,
+            short_rows_pass<CB, BITS, U, false, ASYM, F16>(a, base, obase, sbase, mbase, rem, A0, A1, sf, flip, g, c, rsub, chunk,
                                                 c1h, c1l, c2h, c2l);
         else
-            short_rows_pass<CB, BITS, U, true, ASYM, F16>(a, base, obase, sbase, row0, rem, A0, A1, sf, flip, g, c, rsub, chunk,
+            short_rows_pass<CB, BITS, U, true, ASYM, F16>(a, base, obase, sbase, mbase, rem, A0, A1, sf, flip, g, c, rsub, chunk,
                                                c1h, c1l, c2h, c2l);
     }
 }
