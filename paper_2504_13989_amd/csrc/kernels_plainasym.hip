@@ -106,6 +106,12 @@ __global__ __launch_bounds__(64) void k_plain_asym(const void* X, int64_t n_grou
         else if (n_groups <= 0xffffffffll) row0 = (uint32_t)g0 / (uint32_t)gpr;
         else row0 = g0 / gpr;
         const uint32_t rem0 = (uint32_t)(g0 - row0 * gpr);
+        // outputs of the iteration: a base in scalar registers plus per-lane offsets; lane c of a group
+        // keeps the parameters of pass c, so that the iteration's U * 4 scales and minima leave in one store each
+        uint32_t* const cbase = codes + g0 * (4 * BITS);
+        const uint32_t code_off = (uint32_t)(g * (4 * BITS) + (BITS == 4 ? c : (c >> 2) * 3 + (c & 3))) * 4u;
+        uint32_t* const out0 = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(cbase) + code_off);
+        float keep_d = 0.0f, keep_m = 0.0f;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t gi = g0 + u * 4 + g;
@@ -165,22 +171,25 @@ __global__ __launch_bounds__(64) void k_plain_asym(const void* X, int64_t n_grou
                 w = (w << BITS) + __float_as_uint(__builtin_amdgcn_fmed3f(v[k], Quant<BITS>::kLo, Quant<BITS>::kHi));
             w -= Quant<BITS>::csum();
             if (BITS == 4) {
-                if (live) store_codes(codes + gi * 16 + c, w);
+                if (live) store_codes(out0 + u * (16 * BITS), w);
             } else {
                 const int qpos = c & 3;
                 const uint32_t dw = merge24<false>(w, qpos);
-                if (live && qpos < 3) store_codes(codes + gi * 12 + (c >> 2) * 3 + qpos, dw);
+                if (live && qpos < 3) store_codes(out0 + u * (16 * BITS), dw);
             }
-            if (live && c == 0) {
-                float delta = clipf * r * (float)(1.0 / kL);        // each factor good to 6e-8
-                if (!(r < 3e38f)) {                                 // max - min beyond fp32
-                    float mx_here = mx;
-                    asm volatile("" : "+v"(mx_here));
-                    delta = (float)((clip * (double)mx_here - clip * (double)mn) * (1.0 / kL));
-                }
-                scales[gi] = delta;
-                mins[gi] = clipf * mn;
+            float delta = clipf * r * (float)(1.0 / kL);            // each factor good to 6e-8
+            if (!(r < 3e38f)) {                                     // max - min beyond fp32
+                float mx_here = mx;
+                asm volatile("" : "+v"(mx_here));
+                delta = (float)((clip * (double)mx_here - clip * (double)mn) * (1.0 / kL));
             }
+            keep_d = c == u ? delta : keep_d;
+            keep_m = c == u ? clipf * mn : keep_m;
+        }
+        const int64_t gs = g0 + c * 4 + g;                          // lane c < U: group of pass c
+        if (c < U && gs < n_groups) {
+            scales[gs] = keep_d;
+            mins[gs] = keep_m;
         }
     }
 }
