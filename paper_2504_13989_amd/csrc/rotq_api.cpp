@@ -324,9 +324,14 @@ int rq_dequantize_rotate(const rq_hadamard_t* h, const void* codes, const float*
         !aligned(Y, out_dtype == RQ_F32 ? 4 : 2))
         return RQ_ERR_ARG;
     if (h->device < 0) return RQ_ERR_HIP;
-    if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
     const rq::RowArgs a = row_args(h, nullptr, RQ_F32, rows, h->f.n, h->f.n, bits);
     const rq::OutArgs o{Y, out_dtype, d_out, ld_out};
+    if (h->variant == 0 && rq::wave_dequant_rotate_supports(h, a, mins, o)) {   // Sylvester orders: H is symmetric
+        note(h, "wave_dequant_rotate");
+        return rq::wave_dequant_rotate(h, a, static_cast<const uint32_t*>(codes), scales, mins, o,
+                                       static_cast<hipStream_t>(stream));
+    }
+    if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
     note(h, "generic_dequant_rotate");
     return rq::generic_dequant_rotate(h, a, static_cast<const uint32_t*>(codes), scales, mins, transpose,
                                       o, static_cast<hipStream_t>(stream));

@@ -129,6 +129,11 @@ int plain_quantize_asym(const void* X, int dtype, int64_t rows, int d, int64_t l
 // Rotation alone on the wave path: 16-bit rows of Sylvester order 128 .. 8192, 16-byte aligned rows in and out.
 bool wave_rotate_supports(const rq_hadamard* h, const RowArgs& a, const OutArgs& o);
 int wave_rotate(const rq_hadamard* h, const RowArgs& a, const OutArgs& o, hipStream_t s);
+// Packed codes (+ scales, + mins when a row is one group of 128) to rows in the original basis on the
+// wave path: Sylvester orders 128 .. 8192.
+bool wave_dequant_rotate_supports(const rq_hadamard* h, const RowArgs& a, const float* mins, const OutArgs& o);
+int wave_dequant_rotate(const rq_hadamard* h, const RowArgs& a, const uint32_t* codes, const float* scales,
+                        const float* mins, const OutArgs& o, hipStream_t s);
 
 // Dense-block kernel: bf16 rows, any order n <= 4096 that the wave kernels do not serve (the whole
 // matrix on the matrix cores), e.g. 1544 as one Paley block.

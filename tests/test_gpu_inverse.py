@@ -213,3 +213,70 @@ def test_dequantize_asym_in_the_rotated_domain(torch, name, rows, b):
     got = out.cpu().numpy().astype(np.float64)
     # one fused multiply-add in fp32: half an ulp of the result
     assert np.all(np.abs(got - want) <= 2.0 ** -24 * np.abs(want) + 1e-45), f"{name}: dequantized values differ"
+
+
+@pytest.mark.parametrize("n,rows", [(128, 1029), (256, 333), (512, 65), (1024, 40), (2048, 9), (4096, 77), (8192, 5)])
+@pytest.mark.parametrize("b", [3, 4])
+def test_dequantize_rotate_on_the_wave_path(torch, n, rows, b):
+    """Packed codes back to the original basis for Sylvester orders (sections 2.1, 2.3): every code value
+    occurs, every output type, a narrower output, a padded output row, row counts that leave a ragged
+    last pass."""
+    rng = np.random.default_rng(7 * n + rows + b)
+    _, qmin, qmax = oracle.quant_params(b)
+    q = rng.integers(qmin, qmax + 1, size=(rows, n)).astype(np.int8)
+    q[0] = qmin
+    q[1 % rows] = qmax
+    q[2 % rows] = 0
+    scales32 = np.exp(rng.normal(0.0, 3.0, size=rows)).astype(np.float32)
+    scales32[3 % rows] = 0.0
+    packed = torch.from_numpy(oracle.pack_codes(q, b)).cuda()
+    sc = torch.from_numpy(scales32).cuda()
+    h = handle(n)
+    want = oracle.rotate_back(oracle.dequantize(q, scales32.astype(np.float64)), n, n)
+    for out_dtype, tol_bits in ((torch.float32, None), (torch.bfloat16, 8), (torch.float16, 11)):
+        say(f"wave dequantize_rotate n={n} rows={rows} b={b} -> {out_dtype}")
+        y = binding.dequantize_rotate(h, packed, sc, b, out_dtype=out_dtype)
+        torch.cuda.synchronize()
+        assert h.last_kernel == "wave_dequant_rotate"
+        got = y.double().cpu().numpy()
+        amax = np.abs(want).max(axis=1, keepdims=True)
+        if tol_bits is None:
+            parity.check_float_rows(y.cpu().numpy(), want, what=f"n={n} b={b} f32")
+        else:
+            ok = np.isfinite(got) | (tol_bits == 11)            # large scales overflow fp16: not compared there
+            err = np.abs(got - want)
+            lim = np.abs(want) * 2.0 ** -tol_bits + 1e-5 * amax + (6.2e-5 if tol_bits == 11 else 0.0)
+            fin = np.isfinite(got)
+            assert np.all(err[fin] <= lim[fin]), f"n={n} b={b} {out_dtype}: {err[fin].max()}"
+            assert ok.all()
+    d_out = max(8, (n // 2 + 8) // 8 * 8)
+    buf = torch.full((rows, d_out + 16), 7.0, dtype=torch.float32, device="cuda")
+    binding.dequantize_rotate(h, packed, sc, b, d_out=d_out, out=buf[:, :d_out])
+    torch.cuda.synchronize()
+    assert h.last_kernel == "wave_dequant_rotate"
+    parity.check_float_rows(buf[:, :d_out].cpu().numpy(), want[:, :d_out], what=f"n={n} b={b} d_out={d_out}")
+    assert bool((buf[:, d_out:] == 7.0).all())
+    # H is symmetric for these orders: H and H^T give the same rows
+    y0 = binding.dequantize_rotate(h, packed, sc, b, transpose=False)
+    torch.cuda.synchronize()
+    parity.check_float_rows(y0.cpu().numpy(), want, what=f"n={n} b={b} untransposed")
+
+
+@pytest.mark.parametrize("rows", [1029, 3, 64])
+@pytest.mark.parametrize("b", [3, 4])
+def test_dequantize_rotate_group_codes_on_the_wave_path(torch, rows, b):
+    """The asymmetric group codes of the KV-cache setting (section 5.1) with one group per head row."""
+    n = 128
+    rng = np.random.default_rng(rows + b)
+    q = rng.integers(0, 1 << b, size=(rows, n)).astype(np.int8)
+    q[0] = 0
+    q[1 % rows] = (1 << b) - 1
+    d32 = np.exp(rng.normal(0.0, 2.0, size=(rows, 1))).astype(np.float32)
+    l32 = (rng.normal(0.0, 5.0, size=(rows, 1)) * d32).astype(np.float32)
+    h = handle(n)
+    want = oracle.rotate_back(oracle.dequantize_asym(q, d32.astype(np.float64), l32.astype(np.float64)), n, n)
+    y = binding.dequantize_rotate(h, torch.from_numpy(oracle.pack_codes(q, b)).cuda(), torch.from_numpy(d32).cuda(), b,
+                                  mins=torch.from_numpy(l32).cuda())
+    torch.cuda.synchronize()
+    assert h.last_kernel == "wave_dequant_rotate"
+    parity.check_float_rows(y.cpu().numpy(), want, what=f"group codes rows={rows} b={b}")
