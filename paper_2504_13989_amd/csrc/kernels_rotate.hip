@@ -78,42 +78,6 @@ __device__ __forceinline__ u32x4 code_operand(const uint32_t* base, const CodeLa
     return r;
 }
 
-// Eight consecutive results of a lane (carrying the lane's sign in `k`) to columns col .. col + 7.
-// OUT: 0 bf16, 1 fp32, 2 fp16 (round to nearest even).
-template <int OUT>
-__device__ __forceinline__ void store8(void* Y, int64_t idx, const float (&v)[8], float k, float add0 = 0.0f) {
-    float o[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) o[i] = v[i] * k;
-    o[0] += add0;
-    if constexpr (OUT == 1) {
-        u32x4* p = reinterpret_cast<u32x4*>(static_cast<float*>(Y) + idx);
-#ifdef RQ_ROT_NT32
-        __builtin_nontemporal_store(u32x4{__float_as_uint(o[0]), __float_as_uint(o[1]), __float_as_uint(o[2]), __float_as_uint(o[3])}, p);
-        __builtin_nontemporal_store(u32x4{__float_as_uint(o[4]), __float_as_uint(o[5]), __float_as_uint(o[6]), __float_as_uint(o[7])}, p + 1);
-#else
-        p[0] = u32x4{__float_as_uint(o[0]), __float_as_uint(o[1]), __float_as_uint(o[2]), __float_as_uint(o[3])};
-        p[1] = u32x4{__float_as_uint(o[4]), __float_as_uint(o[5]), __float_as_uint(o[6]), __float_as_uint(o[7])};
-#endif
-    } else {
-        uint32_t w[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            uint32_t lo, hi;
-            if constexpr (OUT == 0) {
-                const uint32_t a = __float_as_uint(o[2 * i]), b = __float_as_uint(o[2 * i + 1]);
-                lo = (a + 0x7fffu + ((a >> 16) & 1u)) >> 16;
-                hi = (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
-            } else {
-                lo = __builtin_bit_cast(uint16_t, (_Float16)o[2 * i]);
-                hi = __builtin_bit_cast(uint16_t, (_Float16)o[2 * i + 1]);
-            }
-            w[i] = lo | (hi << 16);
-        }
-        __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(Y) + idx));
-    }
-}
-
 // n = 512 T: one wave per row.
 template <int T, bool F16, int OUT, int SRC = 0>
 __global__ __launch_bounds__(64) void k_wave_rotate(RotArgs a) {

@@ -19,6 +19,8 @@
 // DPP stages use xor-1, xor-2 (quad_perm), half-row mirror (xor-7) and a rotation by 8 (xor-8),
 // each a single DPP-modified add.  With the mirror, a lane's logical column index is its lane
 // number with the two low bits complemented when bit 2 is set.
+#include <type_traits>
+
 #include "wave_common.h"
 
 namespace rq {
@@ -557,6 +559,44 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
     }
 }
 
+// Rotation alone for the same block orders (rq_rotate: the online rotation of a tensor that is not
+// quantized, offline weight fusion, the inverse rotation with the transposed block's operand tiles):
+// the row's rotation as above, then one multiply and a 16-byte (bf16 / fp16) or 32-byte (fp32) store
+// per lane and block row.
+struct BlockRotArgs {
+    void* Y;
+    int d_out;
+    int64_t ld_out;
+    float inv;            // 1 / sqrt(n)
+};
+
+template <bool FULL, int NV, bool F16, int OUT>
+__global__ __launch_bounds__(64) void k_wave_block_rotate(WaveArgs a, int pb, BlockRotArgs o) {
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, cphys = lane & 15;
+    const int c = (cphys & 4) ? (cphys ^ 3) : cphys;
+    const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
+    float sf[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
+    const float k = ((__builtin_popcount(c) & 1) ? -1.0f : 1.0f) * o.inv;
+    const int base_g = 8 * g < pb - 8 ? 8 * g : pb - 8;
+    const int e_base = base_g * 128 + c * 8;
+    for (int64_t row = blockIdx.x; row < a.rows; row += gridDim.x) {
+        float y[8][NV];
+        (void)block_rotate_row<FULL, NV, F16>(a, row, e_base, A0, A1, sf, y);
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int ao = 4 * j + g;                      // output block row of this register
+            const int col = ao * 128 + c * 8;
+            if (ao < pb && col < o.d_out) {
+                const float v8[8] = {y[0][j], y[1][j], y[2][j], y[3][j], y[4][j], y[5][j], y[6][j], y[7][j]};
+                store8<OUT>(o.Y, row * o.ld_out + col, v8, k);
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // quant_error for bf16 rows of Sylvester order n = 512 T (1024 .. 8192): the rotation of
 // k_wave_sylvester, then for each clip ratio of this wave's share [k0, k1) the row's squared
@@ -1084,6 +1124,55 @@ int wave_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float cli
         case 6: launch_block_nv<6>(a.bits, full, grid, s, w, pb); break;
         case 7: launch_block_nv<7>(a.bits, full, grid, s, w, pb); break;
         case 8: launch_block_nv<8>(a.bits, full, grid, s, w, pb); break;
+        default: return RQ_ERR_NO_ORDER;
+    }
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+template <int NV>
+static void launch_block_rotate_nv(bool full, bool f16, int out, unsigned grid, hipStream_t s, const WaveArgs& w, int pb,
+                                   const BlockRotArgs& o) {
+    auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, dim3(grid), dim3(64), 0, s, w, pb, o); };
+    auto pick_out = [&](auto full_c, auto f16_c) {
+        constexpr bool FL = decltype(full_c)::value, FH = decltype(f16_c)::value;
+        if (out == 0) go(k_wave_block_rotate<FL, NV, FH, 0>);
+        else if (out == 1) go(k_wave_block_rotate<FL, NV, FH, 1>);
+        else go(k_wave_block_rotate<FL, NV, FH, 2>);
+    };
+    if (full) {
+        if (f16) pick_out(std::true_type{}, std::true_type{}); else pick_out(std::true_type{}, std::false_type{});
+    } else {
+        if (f16) pick_out(std::false_type{}, std::true_type{}); else pick_out(std::false_type{}, std::false_type{});
+    }
+}
+
+bool wave_block_rotate_supports(const rq_hadamard* h, const RowArgs& a, int transpose, const OutArgs& o) {
+    if (!wave_block_supports(h, a)) return false;
+    if (transpose && (!h->d_tiles_t || (a.dtype == RQ_F16 && !h->d_tiles_t_f16))) return false;
+    if ((reinterpret_cast<uintptr_t>(o.Y) & 15) != 0 || (o.d_out & 7) != 0) return false;
+    return o.dtype == RQ_F32 ? (o.ld_out & 3) == 0 : (o.ld_out & 7) == 0;
+}
+
+int wave_block_rotate(const rq_hadamard* h, const RowArgs& a, int transpose, const OutArgs& o, hipStream_t s) {
+    const bool f16 = a.dtype == RQ_F16;
+    const void* tiles = transpose ? (f16 ? h->d_tiles_t_f16 : h->d_tiles_t) : (f16 ? h->d_tiles_f16 : h->d_tiles);
+    WaveArgs w{static_cast<const uint16_t*>(a.X), a.rows, a.d, a.ld, static_cast<const u32x4*>(tiles), nullptr, nullptr,
+               0.0, 0.0};
+    w.f16 = f16;
+    const BlockRotArgs bo{o.Y, o.d_out, o.ld_out, (float)(1.0 / std::sqrt((double)a.n))};
+    const int out = o.dtype == RQ_BF16 ? 0 : o.dtype == RQ_F32 ? 1 : 2;
+    const int pb = a.p << (a.log2m - 7);
+    const int64_t cap = 1 << 24;
+    const unsigned grid = (unsigned)(a.rows < cap ? a.rows : cap);
+    const bool full = a.d == a.n;
+    switch ((pb + 3) / 4) {
+        case 2: launch_block_rotate_nv<2>(full, f16, out, grid, s, w, pb, bo); break;
+        case 3: launch_block_rotate_nv<3>(full, f16, out, grid, s, w, pb, bo); break;
+        case 4: launch_block_rotate_nv<4>(full, f16, out, grid, s, w, pb, bo); break;
+        case 5: launch_block_rotate_nv<5>(full, f16, out, grid, s, w, pb, bo); break;
+        case 6: launch_block_rotate_nv<6>(full, f16, out, grid, s, w, pb, bo); break;
+        case 7: launch_block_rotate_nv<7>(full, f16, out, grid, s, w, pb, bo); break;
+        case 8: launch_block_rotate_nv<8>(full, f16, out, grid, s, w, pb, bo); break;
         default: return RQ_ERR_NO_ORDER;
     }
     return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;

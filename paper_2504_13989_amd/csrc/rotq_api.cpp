@@ -103,6 +103,20 @@ int rq_hadamard_build(int n, rq_hadamard_t** out) {
             tiles = pb <= 32 ? rq::wave_block_tiles(bm, pb) : rq::wg_block_tiles(bm, pb);
             if (pb > 32) h->wg_ok = rq::wg_block_prepare(pb);
             f16_table = true;
+            if (pb <= 32) {
+                // the transposed block's tiles: rq_rotate with transpose = 1 (Paley I blocks are not symmetric)
+                std::vector<int8_t> bt((size_t)pb * pb);
+                for (int i = 0; i < pb; ++i)
+                    for (int j = 0; j < pb; ++j) bt[(size_t)i * pb + j] = bm[(size_t)j * pb + i];
+                const std::vector<uint32_t> tt = rq::wave_block_tiles(bt, pb), tth = rq::tiles_to_f16(tt);
+                const size_t bb = tt.size() * sizeof(uint32_t);
+                if (hipMalloc(&h->d_tiles_t, bb) != hipSuccess || hipMalloc(&h->d_tiles_t_f16, bb) != hipSuccess ||
+                    hipMemcpy(h->d_tiles_t, tt.data(), bb, hipMemcpyHostToDevice) != hipSuccess ||
+                    hipMemcpy(h->d_tiles_t_f16, tth.data(), bb, hipMemcpyHostToDevice) != hipSuccess) {
+                    rq_hadamard_free(h);
+                    return RQ_ERR_HIP;
+                }
+            }
             if (pb > 32 && pb <= 64) {
                 // these blocks also have a one-wave kernel (rotate_quantize), with operand tiles of its own
                 const std::vector<uint32_t> t2 = rq::wave_block2_tiles(bm, pb), t2h = rq::tiles_to_f16(t2);
@@ -144,6 +158,8 @@ void rq_hadamard_free(rq_hadamard_t* h) {
     if (h->d_block) (void)hipFree(h->d_block);
     if (h->d_tiles) (void)hipFree(h->d_tiles);
     if (h->d_tiles_f16) (void)hipFree(h->d_tiles_f16);
+    if (h->d_tiles_t) (void)hipFree(h->d_tiles_t);
+    if (h->d_tiles_t_f16) (void)hipFree(h->d_tiles_t_f16);
     if (h->d_tiles2) (void)hipFree(h->d_tiles2);
     if (h->d_tiles2_f16) (void)hipFree(h->d_tiles2_f16);
     delete h;
@@ -305,6 +321,10 @@ int rq_rotate(const rq_hadamard_t* h, const void* X, int dtype, int64_t rows, in
     if (h->variant == 0 && rq::wave_rotate_supports(h, a, o)) {      // Sylvester orders: H is symmetric
         note(h, "wave_rotate");
         return rq::wave_rotate(h, a, o, static_cast<hipStream_t>(stream));
+    }
+    if (h->variant == 0 && rq::wave_block_rotate_supports(h, a, transpose, o)) {
+        note(h, "wave_block_rotate");
+        return rq::wave_block_rotate(h, a, transpose, o, static_cast<hipStream_t>(stream));
     }
     if (!rq::generic_supports(h)) return RQ_ERR_NO_ORDER;
     note(h, "generic_rotate");

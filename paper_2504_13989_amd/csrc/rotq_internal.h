@@ -16,6 +16,8 @@ struct rq_hadamard {
     int8_t* d_block = nullptr;       // device copy of `block`
     void* d_tiles = nullptr;         // device MFMA operand tiles of the block stage (bf16)
     void* d_tiles_f16 = nullptr;     // the same tiles encoded in fp16 (wave kernels only)
+    void* d_tiles_t = nullptr;       // blocks up to 32: operand tiles of the transposed block (rq_rotate with
+    void* d_tiles_t_f16 = nullptr;   // transpose = 1), bf16 and fp16
     void* d_tiles2 = nullptr;        // blocks of 33 .. 64: operand tiles of the one-wave kernel (d_tiles holds the
     void* d_tiles2_f16 = nullptr;    // workgroup kernel's), bf16 and fp16
     int max_lds = 0;                 // bytes of LDS one workgroup may use on `device`
@@ -112,6 +114,10 @@ std::vector<uint32_t> wave_block_tiles(const std::vector<int8_t>& bm, int pb);
 bool wave_block_supports(const rq_hadamard* h, const RowArgs& a);
 int wave_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uint32_t* codes,
                                float* scales, hipStream_t s);
+
+// Rotation alone for those orders (H_n, or H_n^T with the transposed block's tiles).
+bool wave_block_rotate_supports(const rq_hadamard* h, const RowArgs& a, int transpose, const OutArgs& o);
+int wave_block_rotate(const rq_hadamard* h, const RowArgs& a, int transpose, const OutArgs& o, hipStream_t s);
 
 // One-wave block kernel for blocks of 33 .. 64 (n <= 8192): bf16 / fp16 rows, 16-byte aligned.
 std::vector<uint32_t> wave_block2_tiles(const std::vector<int8_t>& bm, int pb);

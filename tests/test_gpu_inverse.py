@@ -280,3 +280,38 @@ def test_dequantize_rotate_group_codes_on_the_wave_path(torch, rows, b):
     torch.cuda.synchronize()
     assert h.last_kernel == "wave_dequant_rotate"
     parity.check_float_rows(y.cpu().numpy(), want, what=f"group codes rows={rows} b={b}")
+
+
+@pytest.mark.parametrize("n,d,rows", [(3584, 3584, 41), (3072, 3000, 30), (1536, 1536, 77), (2560, 2400, 9), (1024 + 512, 1536, 3)])
+@pytest.mark.parametrize("in_dtype", ["bf16", "f16"])
+def test_rotate_block_orders_on_the_wave_path(torch, n, d, rows, in_dtype):
+    """rq_rotate for Paley-block orders up to 32 x 128 (sections 2.3.3, 4.2): H_n and H_n^T (Paley I blocks are
+    not symmetric), every output type, a narrower output."""
+    rng = np.random.default_rng(n + d + rows)
+    xf = rng.standard_t(4.0, size=(rows, d)).astype(np.float32)
+    xf[:, 5] *= 25
+    x = wl.f32_to_bf16_bits(xf) if in_dtype == "bf16" else xf.astype(np.float16)
+    h = handle(n)
+    xt = parity.to_device(x)
+    xp = np.zeros((rows, n))
+    xp[:, :d] = oracle.as_f64(x)
+    for transpose, want in ((False, oracle.rotate(x, n)), (True, oracle.rotate_back(xp, n, n))):
+        for out_dtype, tol_bits in ((torch.float32, None), (torch.bfloat16, 8), (torch.float16, 11)):
+            say(f"wave block rotate n={n} d={d} rows={rows} {in_dtype} -> {out_dtype} transpose={transpose}")
+            y = binding.rotate(h, xt, transpose=transpose, out_dtype=out_dtype)
+            torch.cuda.synchronize()
+            assert h.last_kernel == "wave_block_rotate"
+            if tol_bits is None:
+                parity.check_float_rows(y.cpu().numpy(), want, what=f"n={n} f32 transpose={transpose}")
+            else:
+                got = y.double().cpu().numpy()
+                amax = np.abs(want).max(axis=1, keepdims=True)
+                err = np.abs(got - want)
+                assert np.all(err <= np.abs(want) * 2.0 ** -tol_bits + 1e-5 * amax + (6.2e-5 if tol_bits == 11 else 0.0))
+        d_out = (n // 3) // 8 * 8
+        buf = torch.full((rows, d_out + 8), 7.0, dtype=torch.float32, device="cuda")
+        binding.rotate(h, xt, transpose=transpose, d_out=d_out, out=buf[:, :d_out])
+        torch.cuda.synchronize()
+        assert h.last_kernel == "wave_block_rotate"
+        parity.check_float_rows(buf[:, :d_out].cpu().numpy(), want[:, :d_out], what=f"n={n} d_out={d_out}")
+        assert bool((buf[:, d_out:] == 7.0).all())
