@@ -83,6 +83,32 @@ def _min_ms(torch, fn, n=6, rounds=8):
     return best
 
 
+def _graph_ms(torch, fn, n=20, rounds=8):
+    """Short calls: n of them captured in one HIP graph and replayed, so that what is timed is the GPU's
+    launch-to-launch rate and not how fast Python can issue calls.  Best of `rounds` replays, HIP events."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(n):
+            fn()
+    g.replay()
+    torch.cuda.synchronize()
+    best = float("inf")
+    for _ in range(rounds):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1) / n)
+    return best
+
+
 def time_all_configs(torch, binding, wl):
     """Every configuration's rotate_quantize at its own row count and at a steady-state row count
     (input >= 1 GiB, rows tiled from a 2048-row seeded sample), plus quant_error on the
@@ -103,7 +129,9 @@ def time_all_configs(torch, binding, wl):
                 x = x0.repeat(max(1, rows // base_rows), 1)
                 codes = torch.empty((x.shape[0], w.n * b // 8), dtype=torch.uint8, device="cuda")
                 scales = torch.empty((x.shape[0],), dtype=torch.float32, device="cuda")
-                ms = _min_ms(torch, lambda: binding.rotate_quantize(h, x, b, w.clip, codes=codes, scales=scales))
+                call = lambda: binding.rotate_quantize(h, x, b, w.clip, codes=codes, scales=scales)
+                # the config-exact launches are a few microseconds long: graph replay, inputs warm
+                ms = _graph_ms(torch, call) if label == "config_rows" and not name.startswith("kv") else _min_ms(torch, call)
                 gbps = x.shape[0] * row_bytes / ms / 1e6
                 entry[label] = {"rows": int(x.shape[0]), "us": ms * 1e3, "GBps": gbps,
                                 "frac_hbm_peak": gbps / HBM_PEAK_GBPS}
@@ -155,6 +183,37 @@ def time_all_configs(torch, binding, wl):
     gbps = x.shape[0] * 4 * w.d / ms / 1e6
     res["rotate_heads_bf16"] = {"n": w.n, "rows": int(x.shape[0]), "us": ms * 1e3, "GBps": gbps,
                                 "frac_hbm_peak": gbps / HBM_PEAK_GBPS, "kernel": h.last_kernel}
+    # the way back for the key cache as the paper quantizes it (section 5.1: asymmetric groups of 128, 3 bits):
+    # packed codes + Delta + lo -> bf16 head rows in the original basis
+    codes, scales, mins = binding.rotate_quantize_asym(h, x, 3, w.clip)
+    ms = _min_ms(torch, lambda: binding.dequantize_rotate(h, codes, scales, 3, mins=mins, out=y))
+    gbps = x.shape[0] * (w.n * 3 // 8 + 8 + 2 * w.d) / ms / 1e6
+    res["dequantize_rotate_kv_asym_b3"] = {"n": w.n, "rows": int(x.shape[0]), "out": "bf16", "us": ms * 1e3, "GBps": gbps,
+                                           "frac_hbm_peak": gbps / HBM_PEAK_GBPS, "kernel": h.last_kernel}
+    del x, y, codes, scales, mins
+    # the way back for hidden-state rows (codes + scale -> rows in the original basis), bf16 and fp32 out
+    w = wl.WORKLOADS["llama_hidden"]
+    x = torch.from_numpy(wl.generate(w).view(np.int16)).cuda().view(torch.bfloat16).repeat(32, 1)
+    h = binding.hadamard_build(w.n)
+    codes, scales = binding.rotate_quantize(h, x, 4, w.clip)
+    for dt, key, esz in ((torch.bfloat16, "bf16", 2), (torch.float32, "f32", 4)):
+        y = torch.empty((x.shape[0], w.n), dtype=dt, device="cuda")
+        ms = _min_ms(torch, lambda: binding.dequantize_rotate(h, codes, scales, 4, out=y))
+        gbps = x.shape[0] * (w.n * 4 // 8 + 4 + esz * w.n) / ms / 1e6
+        res[f"dequantize_rotate_llama_b4_{key}"] = {"n": w.n, "rows": int(x.shape[0]), "out": key, "us": ms * 1e3, "GBps": gbps,
+                                                    "frac_hbm_peak": gbps / HBM_PEAK_GBPS, "kernel": h.last_kernel}
+        del y
+    del x, codes, scales
+    # rotation alone on a Paley-block order (H_28 (x) H_128): bf16 in, bf16 out, H and H^T
+    w = wl.WORKLOADS["qwen_hidden"]
+    x = torch.from_numpy(wl.generate(w.with_rows(2048)).view(np.int16)).cuda().view(torch.bfloat16).repeat(36, 1)
+    h = binding.hadamard_build(w.n)
+    y = torch.empty_like(x)
+    for tr, key in ((False, "rotate_qwen_bf16"), (True, "rotate_qwen_bf16_transposed")):
+        ms = _min_ms(torch, lambda: binding.rotate(h, x, transpose=tr, out=y))
+        gbps = x.shape[0] * 4 * w.d / ms / 1e6
+        res[key] = {"n": w.n, "rows": int(x.shape[0]), "us": ms * 1e3, "GBps": gbps,
+                    "frac_hbm_peak": gbps / HBM_PEAK_GBPS, "kernel": h.last_kernel}
     del x, y
     w = wl.WORKLOADS["llama_hidden"]
     x = torch.from_numpy(wl.generate(w).view(np.int16)).cuda().view(torch.bfloat16).repeat(64, 1)
@@ -175,7 +234,7 @@ def time_all_configs(torch, binding, wl):
         h = binding.hadamard_build(1544)
         codes = torch.empty((rows, 1544 * 4 // 8), dtype=torch.uint8, device="cuda")
         scales = torch.empty((rows,), dtype=torch.float32, device="cuda")
-        ms = _min_ms(torch, lambda: binding.rotate_quantize(h, x, 4, w.clip, codes=codes, scales=scales), n=5, rounds=3)
+        ms = _graph_ms(torch, lambda: binding.rotate_quantize(h, x, 4, w.clip, codes=codes, scales=scales), n=5, rounds=4)
         flops = 2.0 * 1544 * 1544 * rows
         res[f"dense_1544_b4_rows{rows}"] = {
             "n": 1544, "bits": 4, "rows": rows, "us": ms * 1e3, "kernel": h.last_kernel,
@@ -193,7 +252,7 @@ def time_all_configs(torch, binding, wl):
         h = binding.hadamard_build(w.n)
         mse = torch.empty(len(clips), dtype=torch.float32, device="cuda")
         ws = torch.empty(binding.quant_error_workspace(rows, len(clips)) // 8, dtype=torch.float64, device="cuda")
-        ms = _min_ms(torch, lambda: binding.quant_error(h, x, 3, clips, mse=mse, workspace=ws), n=5, rounds=3)
+        ms = _graph_ms(torch, lambda: binding.quant_error(h, x, 3, clips, mse=mse, workspace=ws), n=10, rounds=4)
         ec = rows * w.n * len(clips)
         res[f"quant_error_{name}_b3"] = {"rows": rows, "n": w.n, "clips": len(clips), "us": ms * 1e3,
                                          "kernel": h.last_kernel, "element_candidates_per_s": ec / ms * 1e3,
@@ -204,14 +263,20 @@ def time_all_configs(torch, binding, wl):
     h = binding.hadamard_build(w.n)
     mse = torch.empty(len(clips), dtype=torch.float32, device="cuda")
     ws = torch.empty(binding.quant_error_workspace(w.rows, len(clips)) // 8, dtype=torch.float64, device="cuda")
-    ms = _min_ms(torch, lambda: binding.quant_error(h, x, 3, clips, mse=mse, workspace=ws))
+    ms = _graph_ms(torch, lambda: binding.quant_error(h, x, 3, clips, mse=mse, workspace=ws))
     ec = w.rows * w.n * len(clips)
     res["quant_error_calib_b3"] = {
         "rows": w.rows, "n": w.n, "clips": len(clips), "us": ms * 1e3, "kernel": h.last_kernel,
         "element_candidates_per_s": ec / ms * 1e3,
         "roofline": {"bound": "alu", "unit": "T lane-ops/s", "achieved": 5 * ec / ms / 1e9,
                      "peak": VALU_PEAK_TLANEOPS, "frac": 5 * ec / ms / 1e9 / VALU_PEAK_TLANEOPS,
-                     "note": "5 VALU lane-ops per element-candidate; two launches (row sums, reduction)"}}
+                     "frac_of_published_fp32_vector_peak": 5 * ec / ms / 1e9 / 78.6,
+                     "note": "5 VALU lane-ops per element-candidate; two launches (row sums, reduction); peak = "
+                             "256 CUs x 64 lanes x 2.4 GHz without packed fp32 (compiled out), the published "
+                             "78.6 T lane-ops/s counts packed issue"}}
+    ms = _graph_ms(torch, lambda: binding.quant_error_noalloc(h, x, 3, clips, mse))
+    res["quant_error_noalloc_calib_b3"] = {"rows": w.rows, "n": w.n, "clips": len(clips), "us": ms * 1e3,
+                                           "kernel": h.last_kernel, "note": "static device scratch instead of a workspace"}
     # Algorithm 1 on the calibration tensor with quant_error as the objective (host loop, batched probes)
     t0 = time.perf_counter()
     n_search = 20
@@ -275,11 +340,46 @@ def cpu_baseline(x_bits, n, bits, clip):
                       f"quantize + pack, {dt:.2f} s", "tokens_per_s": reps * rows / dt}
 
 
+def parity_stats(torch, binding, wl):
+    """Part of the cpu_baseline leg (the only place bench.py touches the oracle): one checked launch per
+    configuration on a bounded sample of its rows, outside every timed region.  Per configuration: code
+    mismatches against the oracle, how many of them lie inside the 1e-6 band around a rounding boundary
+    (the others would be errors), the size of that band's population, the largest relative scale error."""
+    sys.path.insert(0, os.path.join(ROOT, "oracle"))
+    import rotq_oracle as oracle
+    out = {}
+    for name, rows in (("tiny", 64), ("llama_hidden", 256), ("qwen_hidden", 256), ("ffn_expand", 256),
+                       ("ffn_down", 16), ("kv_k", 4096), ("kv_v", 4096)):
+        w = wl.WORKLOADS[name].with_rows(rows)
+        x = wl.generate(w)
+        xt = (torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16) if x.dtype == np.uint16
+              else torch.from_numpy(x).cuda())
+        h = binding.hadamard_build(w.n)
+        for b in w.bits:
+            codes, scales = binding.rotate_quantize(h, xt, b, w.clip)
+            torch.cuda.synchronize()
+            q, delta, t, _ = oracle.rotate_quantize(x, w.n, b, w.clip)
+            qg = oracle.unpack_codes(codes.cpu().numpy(), b, w.n)
+            mism = qg != q
+            exempt = oracle.boundary_exempt(t, b, 1e-6)
+            sg = scales.cpu().numpy().astype(np.float64)
+            nz = delta > 0
+            rel = np.abs(sg[nz] - delta[nz]) / delta[nz]
+            out[f"{name}_b{b}"] = {"rows": rows, "elements": int(q.size), "kernel": h.last_kernel,
+                                   "mismatches": int(mism.sum()),
+                                   "mismatches_off_boundary": int((mism & ~exempt).sum()),
+                                   "exempt_fraction": float(exempt.mean()),
+                                   "max_rel_scale_err": float(rel.max()) if rel.size else 0.0}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--repeats", type=int, default=7,
+                    help="the timed region (one replay of K steps) is run this many times; the median is reported")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-steady-state", action="store_true")
     ap.add_argument("--no-stream-reference", action="store_true",
@@ -347,14 +447,22 @@ def main():
     for _ in range(max(1, args.warmup // max(1, args.steps)) + 1):
         graph.replay()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    graph.replay()
-    e1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    kernel_ms = e0.elapsed_time(e1) / args.steps          # average launch duration, HIP events
+    # the timed region is one replay = exactly K steps, bracketed by synchronisation on both sides; it is
+    # repeated and the median taken, so that a short run (K = 20: 0.15 ms) is not at the mercy of one
+    # scheduling hiccup of the host
+    walls, kerns = [], []
+    for _ in range(args.repeats):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        walls.append((time.perf_counter() - t0) * 1e3)
+        kerns.append(e0.elapsed_time(e1))
+    wall_ms = float(np.median(walls))
+    kernel_ms = float(np.median(kerns)) / args.steps       # average launch duration, HIP events
     ms_per_step = wall_ms / args.steps
     kernel_name = h.last_kernel
 
@@ -368,6 +476,9 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "ms_per_step_min": min(walls) / args.steps,
+        "ms_per_step_events": kernel_ms,
+        "timed_region_repeats": args.repeats,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -383,7 +494,9 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(kernel_name), "kernel": kernel_name,
-                     "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": batch_bytes},
+                     "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": batch_bytes,
+                     "traffic_source": "rocprofv3 FETCH_SIZE / WRITE_SIZE of this launch shape, profiles/"
+                                       "hbm_traffic_wave_sylvester_llama_hidden_b4.txt (independent of timing)"},
     }
     if not args.no_stream_reference:
         # the same ring and graph with the traffic-only kernel: the practical floor of this launch shape
@@ -424,13 +537,20 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_steady_state:
-        out["steady_state"] = time_steady_state(torch, binding, h, base, bits, clip, 131072)
+        st = time_steady_state(torch, binding, h, base, bits, clip, 131072)
+        out["steady_state"] = st
+        # the same kernel on a launch long enough to leave launch latency behind (1 GiB of input)
+        out["roofline_steady"] = {"bound": "hbm", "achieved": st["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                  "frac": st["frac_hbm_peak"], "kernel": kernel_name, "rows": st["rows"],
+                                  "kernel_ms": st["ms_per_launch"],
+                                  "algorithmic_bytes_per_launch": st["rows"] * row_bytes}
     if not args.no_configs:
         del xs, codes, scales
         torch.cuda.empty_cache()
         out["configs"] = time_all_configs(torch, binding, wl)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(x_bits, w.n, bits, clip)
+        out["cpu_baseline"]["parity"] = parity_stats(torch, binding, wl)
     print(json.dumps(out))
 
 
