@@ -294,7 +294,40 @@ __device__ __forceinline__ void rows_bcast4(uint32_t z, uint32_t (&out)[4]) {
     out[0] = z; out[1] = z2; out[2] = zc; out[3] = z2c;
 }
 
-template <int CB, int BITS, int U, bool GUARD, bool ASYM, bool F16>
+// Codes of eight values on the rows as they are (PLAIN kernels): the single-rounding fma as everywhere, plus
+// the residual e = t - round(t).  Un-rotated 16-bit inputs sit on a coarse grid and land on or next to a
+// rounding tie far more often than rotated values, so a value whose residual is within the window `thr` of a
+// tie is retaken from the definition in fp64 (`exact`), for that value only; one test guards the eight.
+template <int BITS, typename Exact>
+__device__ __forceinline__ uint32_t pack8_plain(const float (&x)[8], float cen, float s, float bias, float thr,
+                                                bool any_exact, uint32_t tail_xor, Exact exact) {
+    float v[8], e[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const float dx = x[k] - cen;
+        v[k] = fmaf(dx, s, bias);
+        e[k] = fmaf(dx, s, bias - v[k]);                           // t - round(t)
+    }
+    float emax;
+    asm("v_max3_f32 %0, |%1|, |%2|, |%3|\n\t"
+        "v_max3_f32 %0, %0, |%4|, |%5|\n\t"
+        "v_max3_f32 %0, %0, |%6|, |%7|\n\t"
+        "v_max_f32 %0, %0, |%8|"
+        : "=&v"(emax)
+        : "v"(e[0]), "v"(e[1]), "v"(e[2]), "v"(e[3]), "v"(e[4]), "v"(e[5]), "v"(e[6]), "v"(e[7]));
+    if (!(emax <= thr) && any_exact) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (!(__builtin_fabsf(e[k]) <= thr)) v[k] = exact(x[k]);
+    }
+    uint32_t w = 0;
+#pragma unroll
+    for (int k = 7; k >= 0; --k)
+        w = (w << BITS) + __float_as_uint(__builtin_amdgcn_fmed3f(v[k], Quant<BITS>::kLo, Quant<BITS>::kHi));
+    return (w - Quant<BITS>::csum()) ^ tail_xor;
+}
+
+template <int CB, int BITS, int U, bool GUARD, bool ASYM, bool F16, bool PLAIN = false>
 __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_t* base, uint32_t* obase,
                                                 float* sbase, float* mbase, int rem, const u32x4& A0, const u32x4& A1,
                                                 const float (&sf)[4], float flip, int g, int c, int rsub,
@@ -385,8 +418,10 @@ __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_
                 const f32x4 z = {0.f, 0.f, 0.f, 0.f};
                 v0[k] = mfma_pm1<F16>(A0, raw[u0 + k], z);
                 v1[k] = mfma_pm1<F16>(A1, raw[u0 + k], z);
-                lane_stages_mfma<CB>(v0[k], sf);
-                lane_stages_mfma<CB>(v1[k], sf);
+                if constexpr (!PLAIN) {
+                    lane_stages_mfma<CB>(v0[k], sf);
+                    lane_stages_mfma<CB>(v1[k], sf);
+                }
                 uint32_t m = __float_as_uint(absmax4(absmax4(0.0f, v0[k]), v1[k]));
                 // inside the DPP row: the lanes that share the row (CB lane bits)
                 m = max(m, dpp_u<kDppXor1>(m));
@@ -402,16 +437,42 @@ __device__ __forceinline__ void short_rows_pass(const WaveArgs& a, const uint16_
             if (store_lane) sbase[srow] = fmaf(m, c2l, m * c2h);
             uint32_t q4[4];
             rows_bcast4(__float_as_uint(q), q4);
+            if constexpr (PLAIN) {
+                uint32_t m4[4];
+                rows_bcast4(__float_as_uint(m), m4);
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
-                store_pass(u0 + k, Quant<BITS>::pack8(v0[k][0], v0[k][1], v0[k][2], v0[k][3], v1[k][0], v1[k][1], v1[k][2],
-                                                      v1[k][3], flip * __uint_as_float(q4[k])));
+                for (int k = 0; k < 4; ++k) {
+                    const float yv[8] = {v0[k][0], v0[k][1], v0[k][2], v0[k][3], v1[k][0], v1[k][1], v1[k][2], v1[k][3]};
+                    const float qk = __uint_as_float(q4[k]), mk = __uint_as_float(m4[k]);
+                    // (no window where the multiplier overflows: fp64 throughout)
+                    const float thr = (mk < 4e37f && qk < 1e30f) ? 0.49998f : -1.0f;
+                    constexpr double kL = (double)((1 << BITS) - 1);
+                    constexpr float kQmin = -(float)(1 << (BITS - 1)), kQmax = (float)((1 << (BITS - 1)) - 1);
+                    const uint32_t w = pack8_plain<BITS>(yv, 0.0f, qk, Quant<BITS>::kBias, thr, mk > 0.0f, Quant<BITS>::msb(), [&](float x) {
+                        float m_here = mk;
+                        asm volatile("" : "+v"(m_here));              // keeps the fp64 work inside the branch
+                        const double delta64 = a.clip * (double)m_here / kL;
+                        return Quant<BITS>::kBias + fminf(fmaxf((float)rint((double)x / delta64), kQmin), kQmax);
+                    });
+                    store_pass(u0 + k, w);
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    store_pass(u0 + k, Quant<BITS>::pack8(v0[k][0], v0[k][1], v0[k][2], v0[k][3], v1[k][0], v1[k][1], v1[k][2],
+                                                          v1[k][3], flip * __uint_as_float(q4[k])));
+            }
         }
     }
 }
 
-template <int CB, int BITS, int U, bool ASYM = false, bool F16 = false>
-__global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
+// PLAIN: the same passes on the rows as they are (rq_quantize on head rows that arrive
+// rotated, sections 2.1, 5.1): the matrix cores multiply by the identity - which turns the eight 16-bit
+// values of a lane into fp32 without a vector-ALU instruction - and the butterfly stages are left out.
+template <int CB, int BITS, int U, bool ASYM = false, bool F16 = false, bool PLAIN = false>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(U == 8 && !PLAIN ? 4 : 1)))   // 128 registers
+void k_wave_short(WaveArgs a) {
+    static_assert(!(PLAIN && ASYM), "the rotation-free group quantizer has a kernel of its own");
     static_assert(CB >= 2 && CB <= 4, "unsupported shape");
     constexpr int RPW = 16 >> CB;
     constexpr int N = 32 << CB;
@@ -423,11 +484,27 @@ __global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
     const int rsub = nnl >> CB;
     const int c = (CB >= 3 && (cphys & 4)) ? (cphys ^ 3) : cphys;
     const int chunk = (g << CB) + c;
-    const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
+    u32x4 A0, A1;
+    if constexpr (PLAIN) {
+        // identity as two operand tiles: output row mm = 4 go + io of half hh is contraction slot (go, 4 hh + io),
+        // so a lane gets its own eight values back in order; operand lane (gA, mm) holds slots (gA, 0 .. 7)
+        const int gA = lane >> 4, mm = lane & 15;
+        const uint32_t one = F16 ? 0x3C00u : 0x3F80u;
+        A0 = u32x4{0u, 0u, 0u, 0u};
+        A1 = u32x4{0u, 0u, 0u, 0u};
+        if (gA == (mm >> 2)) {
+            const int io = mm & 3;                                  // slot io (tile 0) / 4 + io (tile 1)
+            A0[io >> 1] = one << ((io & 1) * 16);
+            A1[2 + (io >> 1)] = one << ((io & 1) * 16);
+        }
+    } else {
+        A0 = a.tiles[lane];
+        A1 = a.tiles[64 + lane];
+    }
     float sf[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) sf[b] = ((c >> b) & 1) ? -1.0f : 1.0f;
-    const float flip = (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;        // all stages are the fused ones
+    const float flip = PLAIN ? 1.0f : (__builtin_popcount(c) & 1) ? -1.0f : 1.0f;     // all stages are the fused ones
     const float c1h = (float)a.c1, c1l = (float)(a.c1 - (double)c1h);
     const float c2h = (float)a.c2, c2l = (float)(a.c2 - (double)c2h);
     const bool full_d = a.d == N;
@@ -442,11 +519,11 @@ __global__ __launch_bounds__(64) void k_wave_short(WaveArgs a) {
         float* sbase = a.scales + row0;
         float* mbase = ASYM ? a.mins + row0 : nullptr;
         if (rem == SUPER && full_d)
-            short_rows_pass<CB, BITS, U, false, ASYM, F16>(a, base, obase, sbase, mbase, rem, A0, A1, sf, flip, g, c, rsub, chunk,
-                                                c1h, c1l, c2h, c2l);
+            short_rows_pass<CB, BITS, U, false, ASYM, F16, PLAIN>(a, base, obase, sbase, mbase, rem, A0, A1, sf, flip, g, c, rsub, chunk,
+                                                       c1h, c1l, c2h, c2l);
         else
-            short_rows_pass<CB, BITS, U, true, ASYM, F16>(a, base, obase, sbase, mbase, rem, A0, A1, sf, flip, g, c, rsub, chunk,
-                                               c1h, c1l, c2h, c2l);
+            short_rows_pass<CB, BITS, U, true, ASYM, F16, PLAIN>(a, base, obase, sbase, mbase, rem, A0, A1, sf, flip, g, c, rsub, chunk,
+                                                      c1h, c1l, c2h, c2l);
     }
 }
 
@@ -1320,6 +1397,44 @@ int wave_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float clip, uin
         case 13: return launch_long<16>(h, w, a.bits, s);
         default: return RQ_ERR_NO_ORDER;
     }
+}
+
+// Rotation-free quantizers on head rows of 128, 256 or 512 16-bit values: the short-row passes with the
+// identity on the matrix cores.
+template <int CB, int U>
+static int launch_plain_short_u(const WaveArgs& a, int bits, hipStream_t s) {
+    constexpr int SUPER = (16 >> CB) * U;
+    const int64_t items = (a.rows + SUPER - 1) / SUPER;
+    const int64_t cap = 1 << 24;
+    const dim3 grid((unsigned)(items < cap ? items : cap)), block(64);
+    auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, 0, s, a); };
+    if (a.f16) {
+        if (bits == 4) go(k_wave_short<CB, 4, U, false, true, true>); else go(k_wave_short<CB, 3, U, false, true, true>);
+    } else {
+        if (bits == 4) go(k_wave_short<CB, 4, U, false, false, true>); else go(k_wave_short<CB, 3, U, false, false, true>);
+    }
+    return hipGetLastError() == hipSuccess ? RQ_OK : RQ_ERR_HIP;
+}
+
+template <int CB>
+static int launch_plain_short(const WaveArgs& a, int bits, hipStream_t s) {
+    return short_deep(a, 32 << CB) ? launch_plain_short_u<CB, 8>(a, bits, s) : launch_plain_short_u<CB, 4>(a, bits, s);
+}
+
+bool plain_wave_short_supports(const void* X, int dtype, int d, int64_t ld) {
+    return (dtype == RQ_BF16 || dtype == RQ_F16) && (d == 128 || d == 256 || d == 512) && ld % 8 == 0 &&
+           (reinterpret_cast<uintptr_t>(X) % 16) == 0;
+}
+
+int plain_wave_short_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
+                              uint32_t* codes, float* scales, hipStream_t s) {
+    const double lvl = (double)((1 << bits) - 1);
+    WaveArgs w{static_cast<const uint16_t*>(X), rows, d, ld, nullptr, codes, scales, lvl / (double)clip, (double)clip / lvl};
+    w.clip = (double)clip;
+    w.f16 = dtype == RQ_F16;
+    if (d == 128) return launch_plain_short<2>(w, bits, s);
+    if (d == 256) return launch_plain_short<3>(w, bits, s);
+    return launch_plain_short<4>(w, bits, s);
 }
 
 bool plain_wave_supports(const void* X, int dtype, int d, int64_t ld) {

@@ -283,7 +283,10 @@ int rq_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int b
     if (rows == 0) return RQ_OK;
     if (!X || !aligned(X, dtype == RQ_F32 ? 4 : 2)) return RQ_ERR_ARG;
     if (!codes || !scales || !aligned(codes, 4) || !aligned(scales, 4)) return RQ_ERR_ARG;
-    if (rq::plain_short_supports(X, dtype, d, ld))          // head rows: several rows per wave
+    if (rq::plain_wave_short_supports(X, dtype, d, ld))     // head rows of 128 / 256 / 512: the short-row passes
+        return rq::plain_wave_short_quantize(X, dtype, rows, d, ld, bits, clip, static_cast<uint32_t*>(codes), scales,
+                                             static_cast<hipStream_t>(stream));
+    if (rq::plain_short_supports(X, dtype, d, ld))          // other short rows: several rows per wave
         return rq::plain_short_quantize(X, dtype, rows, d, ld, bits, clip, static_cast<uint32_t*>(codes), scales,
                                         static_cast<hipStream_t>(stream));
     if (rq::plain_wave_supports(X, dtype, d, ld))

@@ -84,6 +84,11 @@ int plain_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, in
 bool plain_wave_supports(const void* X, int dtype, int d, int64_t ld);
 int plain_wave_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
                         uint32_t* codes, float* scales, hipStream_t s);
+// The same on head rows of 128 / 256 / 512 16-bit values: the short-row passes of the rotating kernels with the
+// identity on the matrix cores.
+bool plain_wave_short_supports(const void* X, int dtype, int d, int64_t ld);
+int plain_wave_short_quantize(const void* X, int dtype, int64_t rows, int d, int64_t ld, int bits, float clip,
+                              uint32_t* codes, float* scales, hipStream_t s);
 bool generic_supports(const rq_hadamard* h);
 bool generic_prepare(rq_hadamard* h);
 

@@ -163,6 +163,11 @@ def test_short_rows_large_inputs_ragged_end(torch, n, rows):
         assert h.last_kernel == "wave_sylvester"
         parity.check_rotate_quantize(x[pick], n, b, 0.9, codes[idx].cpu().numpy(), scales[idx].cpu().numpy(),
                                      f"large short n={n} b={b}")
+        cp, sp = binding.quantize(xt, b, 0.9)              # the rotation-free quantizer's eight-pass launch
+        torch.cuda.synchronize()
+        parity.check_quantize_plain(x[pick], b, 0.9, cp[idx].cpu().numpy(), sp[idx].cpu().numpy(),
+                                    f"large short plain n={n} b={b}")
+        del cp, sp
         if n == 128:
             ca, sa, ma = binding.rotate_quantize_asym(h, xt, b, 0.9)
             torch.cuda.synchronize()
