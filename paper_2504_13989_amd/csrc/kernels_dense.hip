@@ -6,16 +6,20 @@
 // X[row][a], v_mfma_f32_16x16x32_bf16 with
 //   B operand  16 rows x 32 inputs straight from memory: lane (g, r) loads the 16 bytes
 //              X[row0 + r][32 kk + 8 g ..] (exact bf16, no conversion, no transposition);
-//   A operand  a 16 x 32 tile of +-1 (bf16) from a table built with the handle, [kk][mt][lane]: the tiles
-//              of one contraction step are contiguous, and all workgroups walk the table in step;
+//   A operand  a 16 x 32 tile of +-1 (bf16), made in registers from one sign bit per entry: the handle
+//              holds the matrix as n^2 / 8 bytes of signs, a lane's 8 signs of a tile sit in a 32-bit word
+//              (four tiles per word) at the positions where one rotation of the word brings two of them
+//              to bits 15 and 31, so an operand register costs a rotate and an and-or:
+//              8 vector instructions per tile against 16 NT matrix-core cycles;
 //   D          lane (g, r) register j = output 16 mt + 4 g + j of row r, fp32.
-// A workgroup of 8 waves owns 16 rows (32 when there are rows enough: every tile of the table then
-// serves two groups of rows); wave w owns the output tiles mt = w, w + 8, ... and keeps
-// their accumulators in registers over the whole contraction.  Then: row absmax (registers, the
-// four lane rows, the eight waves through LDS), scale, round/clamp (section 2.1 with the clip
-// ratio of section 3.1), pack into an LDS image of the 16 packed rows, copy out coalesced.
-// The table is read once per workgroup (n^2 / 8 bytes per row): the kernel is bound by that L2
-// traffic and the matrix cores, not by HBM.
+// A workgroup of 8 waves owns 16 NT rows (NT = 1, 2 or 4 by the number of rows: every tile then serves NT
+// groups of rows); wave w owns the output tiles mt = w, w + 8, ... and keeps their accumulators in
+// registers over the whole contraction.  Then: row absmax (registers, the four lane rows, the
+// eight waves through LDS), scale, round/clamp (section 2.1 with the clip ratio of section 3.1),
+// pack into an LDS image of the packed rows, copy out coalesced.
+// A wave reads 16 bytes of signs per lane and contraction step (n^2 / 8 bytes per workgroup in all,
+// against 2 n^2 when the table held bf16 tiles and the kernel was bound by reading them from the L2
+// cache): what is left is the matrix cores and the vector instructions that feed them.
 #include "wave_common.h"
 
 namespace rq {
@@ -23,25 +27,74 @@ namespace {
 
 constexpr int kDenseWaves = 8;
 
+// 32-bit sign words per lane and (contraction step, wave): four tiles per word, whole 16-byte loads
+constexpr int dense_words(int mtw) { return mtw <= 16 ? 4 : 8; }
+
+// Operand register d (entries 2 d, 2 d + 1 of the lane's eight) of the tile in slot jj of a sign word:
+// the rotation by 4 jj + d brings their signs to bits 15 and 31.  `mask` (0x80008000) and `one`
+// (0x3F803F80) are passed in registers so that the and-or is one instruction.
+template <int RHO>
+__device__ __forceinline__ uint32_t sign_pair(uint32_t word, uint32_t mask, uint32_t one) {
+    const uint32_t x = RHO ? __builtin_amdgcn_alignbit(word, word, RHO) : word;
+    return (x & mask) | one;
+}
+
+template <int JJ>
+__device__ __forceinline__ u32x4 sign_tile(uint32_t word, uint32_t mask, uint32_t one) {
+    return u32x4{sign_pair<4 * JJ>(word, mask, one), sign_pair<4 * JJ + 1>(word, mask, one),
+                 sign_pair<4 * JJ + 2>(word, mask, one), sign_pair<4 * JJ + 3>(word, mask, one)};
+}
+
+// Steps of the contraction per group: the rows' chunks of a group (64 kDenseGroup bytes per row) are staged
+// in LDS at once, and the sign table is padded to whole groups plus one.
+constexpr int kDenseGroup = 4;
+constexpr int dense_steps_padded(int n) { return (((n + 31) / 32 + kDenseGroup - 1) / kDenseGroup + 1) * kDenseGroup; }
+
 template <int MTW, int NT, int BITS>
 __global__ __launch_bounds__(64 * kDenseWaves) void k_dense_block(WaveArgs a, int n) {
     constexpr int RB = 16 * NT;                          // rows per workgroup
-    extern __shared__ __attribute__((aligned(16))) uint8_t stage[];      // RB packed rows
+    constexpr int QV = dense_words(MTW) / 4;             // 16-byte sign loads per lane and step
+    constexpr int G = kDenseGroup;
+    constexpr int CPR = 4 * G;                           // 16-byte chunks per row and group
+    constexpr int PITCH = 64 * G + 16;                   // LDS bytes per staged row: 16 rows apart = 16 different banks
+    // LDS: two staging buffers of RB rows x PITCH while the contraction runs, then the RB packed rows
+    extern __shared__ __attribute__((aligned(16))) uint8_t stage[];
     __shared__ float wmax[kDenseWaves][RB];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, r = lane & 15;
     const int MT = (n + 15) >> 4, KK = (n + 31) >> 5;
+    const int NG = (KK + G - 1) / G;
     const int row_bytes = n * BITS / 8;
     const int64_t row0 = (int64_t)blockIdx.x * RB;
     bool row_ok[NT];
-    const uint16_t* xr[NT];
 #pragma unroll
-    for (int q = 0; q < NT; ++q) {
-        const int64_t row = row0 + 16 * q + r;
-        row_ok[q] = row < a.rows;
-        xr[q] = a.X + (row_ok[q] ? row : 0) * a.ld;
-    }
+    for (int q = 0; q < NT; ++q) row_ok[q] = row0 + 16 * q + r < a.rows;
+    uint32_t kmask = 0x80008000u, kone = 0x3F803F80u;
+    asm volatile("" : "+v"(kmask), "+v"(kone));          // kept in registers, see sign_pair
+    const u32x4* const signs = a.tiles + ((size_t)wave * 64 + lane) * QV;     // + kk * 8 * 64 * QV
+
+    // Loader role: thread t brings chunk t % CPR of row t / CPR of every group from memory - 16 consecutive
+    // lanes read 256 consecutive bytes - and puts it into LDS, where lane (g, r) of every wave finds the
+    // operand chunks of its rows.  (Loading the operands directly, lane (g, r) from row r, makes every lane
+    // of a load instruction a different cache line: measured, the address path then takes longer than the
+    // matrix cores.)  A chunk beyond the row's d inputs, or of a row beyond the last, is zero
+    // (section 4.2): its load goes to an address inside X and the zero is put in on the way to LDS.
+    const int lrow = threadIdx.x / CPR, lchunk = threadIdx.x % CPR;
+    const bool loader = lrow < RB;
+    const bool lrow_ok = loader && row0 + lrow < a.rows;
+    const uint16_t* const lptr = a.X + (lrow_ok ? row0 + lrow : 0) * a.ld;
+    uint8_t* const lds_w = stage + (loader ? lrow : 0) * PITCH + lchunk * 16;
+    const uint8_t* const lds_r = stage + r * PITCH + g * 16;
+    auto gload = [&](int grp) {
+        const int e = (grp * CPR + lchunk) * 8;
+        return *reinterpret_cast<const u32x4*>(lptr + (e < a.d ? e : 0));
+    };
+    auto lds_store = [&](int grp, u32x4 v) {
+        const int e = (grp * CPR + lchunk) * 8;
+        if (!(lrow_ok && e < a.d)) v = u32x4{0u, 0u, 0u, 0u};
+        if (loader) *reinterpret_cast<u32x4*>(lds_w + (grp & 1) * (RB * PITCH)) = v;
+    };
 
     f32x4 acc[MTW][NT];
 #pragma unroll
@@ -49,43 +102,81 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_dense_block(WaveArgs a, in
 #pragma unroll
         for (int q = 0; q < NT; ++q) acc[j][q] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // The contraction is software-pipelined two steps deep: the operands of step kk + 1 are requested
-    // before the matrix-core instructions of step kk are issued (two register stages, loop unrolled
-    // by two), because a wave otherwise sits out a full memory latency per step with only two waves
-    // per SIMD to cover it.  With NT = 2 every operand tile of the table serves two groups of 16 rows.
-    u32x4 tA[MTW], tB[MTW], xA[NT], xB[NT];
-    auto fetch = [&](int kk, u32x4 (&t)[MTW], u32x4 (&x)[NT]) {
-        const int e0 = 32 * kk + 8 * g;
-#pragma unroll
-        for (int q = 0; q < NT; ++q) {
-            const bool in = row_ok[q] && e0 < a.d;       // zero padding beyond d (section 4.2)
-            x[q] = load16(xr[q] + (in ? e0 : 0));
-            if (!in) x[q] = u32x4{0u, 0u, 0u, 0u};
-        }
+    // tile slots of a wave beyond the matrix (mt >= MT) are computed like the others - their signs read as
+    // +1 - so that a step is one straight run of instructions; their outputs are never used.  Entries of a
+    // tile beyond column n meet the zero chunks of X.
+    auto contract = [&](const u32x4 (&sg)[QV], const u32x4 (&x)[NT]) {
 #pragma unroll
         for (int j = 0; j < MTW; ++j) {
-            const int mt = wave + kDenseWaves * j;
-            if (mt < MT) t[j] = a.tiles[((size_t)kk * MT + mt) * 64 + lane];
+            const uint32_t word = sg[j / 16][(j / 4) % 4];
+            const u32x4 t = (j % 4) == 0   ? sign_tile<0>(word, kmask, kone)
+                            : (j % 4) == 1 ? sign_tile<1>(word, kmask, kone)
+                            : (j % 4) == 2 ? sign_tile<2>(word, kmask, kone)
+                                           : sign_tile<3>(word, kmask, kone);
+#pragma unroll
+            for (int q = 0; q < NT; ++q)
+                acc[j][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t),
+                                                                    __builtin_bit_cast(bf16x8, x[q]), acc[j][q], 0, 0, 0);
         }
+        // issue order: the 8 vector instructions that make tile j + 1 go between the matrix-core instructions
+        // of tile j (into other registers than tile j's, which those are still reading)
+        __builtin_amdgcn_sched_group_barrier(0x2, 8, 0);
+#pragma unroll
+        for (int j = 0; j < MTW; ++j)
+#pragma unroll
+            for (int q = 0; q < NT; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x8, 1, 0);
+                if (j + 1 < MTW) __builtin_amdgcn_sched_group_barrier(0x2, 8 / NT, 0);
+            }
     };
-    auto contract = [&](const u32x4 (&t)[MTW], const u32x4 (&x)[NT]) {
+
+    // Group n of the contraction: its sign words were requested a group earlier (registers), its chunks
+    // of X are in LDS buffer n & 1; while it runs, the signs of group n + 1 are requested, the chunks of
+    // group n + 1 (requested a group earlier) go to the other LDS buffer and those of group n + 2 are
+    // requested.  Everything beyond the last group is padding: sign words of zeros, chunks masked to zero.
+    u32x4 sC[G][QV], sN[G][QV];
+    u32x4 R = gload(0);
 #pragma unroll
-        for (int j = 0; j < MTW; ++j) {
-            const int mt = wave + kDenseWaves * j;
-            if (mt < MT) {
+    for (int i = 0; i < G; ++i)
+#pragma unroll
+        for (int v = 0; v < QV; ++v) sC[i][v] = signs[(size_t)i * (kDenseWaves * 64 * QV) + v];
+    lds_store(0, R);
+    R = gload(1);
+    __syncthreads();
+    for (int grp = 0; grp < NG; ++grp) {
+#pragma unroll
+        for (int i = 0; i < G; ++i)
+#pragma unroll
+            for (int v = 0; v < QV; ++v)
+                sN[i][v] = signs[(size_t)((grp + 1) * G + i) * (kDenseWaves * 64 * QV) + v];
+        const uint8_t* const rd = lds_r + (grp & 1) * (RB * PITCH);
+        u32x4 xa[NT], xb[NT];                            // operands of the even / odd steps of the group
+#pragma unroll
+        for (int q = 0; q < NT; ++q) xa[q] = *reinterpret_cast<const u32x4*>(rd + 16 * q * PITCH);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < G; i += 2) {
+#pragma unroll
+            for (int q = 0; q < NT; ++q) xb[q] = *reinterpret_cast<const u32x4*>(rd + 16 * q * PITCH + (i + 1) * 64);
+            __builtin_amdgcn_sched_barrier(0);
+            contract(sC[i], xa);
+            __builtin_amdgcn_sched_barrier(0);
+            if (i + 2 < G) {
 #pragma unroll
                 for (int q = 0; q < NT; ++q)
-                    acc[j][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t[j]),
-                                                                        __builtin_bit_cast(bf16x8, x[q]), acc[j][q], 0, 0, 0);
+                    xa[q] = *reinterpret_cast<const u32x4*>(rd + 16 * q * PITCH + (i + 2) * 64);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            contract(sC[i + 1], xb);
+            __builtin_amdgcn_sched_barrier(0);
         }
-    };
-    fetch(0, tA, xA);
-    for (int kk = 0; kk < KK; kk += 2) {
-        if (kk + 1 < KK) fetch(kk + 1, tB, xB);
-        contract(tA, xA);
-        if (kk + 2 < KK) fetch(kk + 2, tA, xA);
-        if (kk + 1 < KK) contract(tB, xB);
+        lds_store(grp + 1, R);
+        R = gload(grp + 2);
+#pragma unroll
+        for (int i = 0; i < G; ++i)
+#pragma unroll
+            for (int v = 0; v < QV; ++v) sC[i][v] = sN[i][v];
+        __syncthreads();
     }
 
     // absmax of the lane's rows: this lane's registers, the four lane rows, the eight waves
@@ -94,7 +185,8 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_dense_block(WaveArgs a, in
     for (int q = 0; q < NT; ++q) {
         float v = 0.0f;
 #pragma unroll
-        for (int j = 0; j < MTW; ++j) v = absmax4(v, acc[j][q]);
+        for (int j = 0; j < MTW; ++j)
+            if (16 * (wave + kDenseWaves * j) + 4 * g < n) v = absmax4(v, acc[j][q]);   // outputs of the matrix only
         v = __uint_as_float(rows_max_u32(__float_as_uint(v)));
         if (g == 0) wmax[wave][16 * q + r] = v;
     }
@@ -161,7 +253,8 @@ template <int MTW, int NT>
 int launch_dense(const WaveArgs& a, int n, int bits, hipStream_t s) {
     const int64_t groups = (a.rows + 16 * NT - 1) / (16 * NT);
     if (groups > 0x7fffffffLL) return RQ_ERR_ARG;
-    const size_t lds = (size_t)16 * NT * n * bits / 8;
+    const size_t rows_lds = (size_t)16 * NT * n * bits / 8, stage_lds = (size_t)2 * 16 * NT * (64 * kDenseGroup + 16);
+    const size_t lds = rows_lds > stage_lds ? rows_lds : stage_lds;
     if (bits == 4)
         hipLaunchKernelGGL((k_dense_block<MTW, NT, 4>), dim3((unsigned)groups), dim3(64 * kDenseWaves), lds, s, a, n);
     else
@@ -171,22 +264,28 @@ int launch_dense(const WaveArgs& a, int n, int bits, hipStream_t s) {
 
 }  // namespace
 
-// Matrix-core operand table of the whole n x n matrix `hm` (row-major +-1): [kk][mt][lane] x 16
-// bytes; operand lane (gA, mm) of tile (mt, kk) holds H[16 mt + mm][32 kk + 8 gA + i], i = 0..7, as
-// bf16, zero outside the matrix.
+// Sign table of the whole n x n matrix `hm` (row-major +-1) for k_dense_block: [kk][wave][lane][word],
+// dense_words(tiles per wave) 32-bit words.  Lane (gA, mm) of wave w finds in word j / 4 the signs of its
+// tile j (outputs 16 (w + 8 j) + mm, inputs 32 kk + 8 gA + i, i = 0..7; set = -1): with rho = 4 (j % 4) +
+// i / 2, entry i sits at bit (15 + rho) % 32 when i is even and (31 + rho) % 32 when it is odd - the
+// places that a rotation of the word by rho brings to bits 15 and 31.  Entries outside the matrix are 0.
 std::vector<uint32_t> dense_block_tiles(const std::vector<int8_t>& hm, int n) {
     const int MT = (n + 15) / 16, KK = (n + 31) / 32;
-    std::vector<uint32_t> t((size_t)MT * KK * 64 * 4, 0u);
-    for (int mt = 0; mt < MT; ++mt)
-        for (int kk = 0; kk < KK; ++kk)
+    const int mtw = (MT + kDenseWaves - 1) / kDenseWaves, words = dense_words(mtw);
+    std::vector<uint32_t> t((size_t)dense_steps_padded(n) * kDenseWaves * 64 * words, 0u);   // zeros beyond step KK
+    for (int kk = 0; kk < KK; ++kk)
+        for (int w = 0; w < kDenseWaves; ++w)
             for (int lane = 0; lane < 64; ++lane) {
                 const int gA = lane >> 4, mm = lane & 15;
-                const int ao = 16 * mt + mm;
-                for (int i = 0; i < 8; ++i) {
-                    const int ai = 32 * kk + 8 * gA + i;
-                    uint32_t v = 0;
-                    if (ao < n && ai < n) v = hm[(size_t)ao * n + ai] > 0 ? 0x3F80u : 0xBF80u;
-                    t[(((size_t)kk * MT + mt) * 64 + lane) * 4 + (i >> 1)] |= v << ((i & 1) * 16);
+                uint32_t* out = &t[(((size_t)kk * kDenseWaves + w) * 64 + lane) * words];
+                for (int j = 0; j < mtw; ++j) {
+                    const int ao = 16 * (w + kDenseWaves * j) + mm;
+                    for (int i = 0; i < 8; ++i) {
+                        const int ai = 32 * kk + 8 * gA + i;
+                        if (ao >= n || ai >= n || hm[(size_t)ao * n + ai] > 0) continue;
+                        const int rho = 4 * (j % 4) + i / 2;
+                        out[j / 4] |= 1u << (((i & 1) ? 31 + rho : 15 + rho) % 32);
+                    }
                 }
             }
     return t;
@@ -205,13 +304,22 @@ int dense_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float cl
                static_cast<const u32x4*>(h->d_tiles), codes, scales,
                lvl / (double)clip, (double)clip / (std::sqrt((double)a.n) * lvl)};
     const int mtw = ((a.n + 15) / 16 + kDenseWaves - 1) / kDenseWaves;
-    // 32 rows per workgroup halve the traffic of the operand table; used when that still leaves a
-    // workgroup for every CU and the accumulators fit the register budget (two waves per SIMD)
-    const bool two = a.rows >= (int64_t)32 * h->num_cu && mtw <= 13;
-    if (mtw <= 4) return two ? launch_dense<4, 2>(w, a.n, a.bits, s) : launch_dense<4, 1>(w, a.n, a.bits, s);
-    if (mtw <= 8) return two ? launch_dense<8, 2>(w, a.n, a.bits, s) : launch_dense<8, 1>(w, a.n, a.bits, s);
-    if (mtw <= 13) return two ? launch_dense<13, 2>(w, a.n, a.bits, s) : launch_dense<13, 1>(w, a.n, a.bits, s);
+    // 32 or 64 rows per workgroup: every operand tile made in registers then serves two or four groups of
+    // rows; used when that still leaves a workgroup for every CU and the accumulators fit the register
+    // budget (two waves per SIMD)
+    const bool two = a.rows >= (int64_t)32 * h->num_cu;
+#define RQ_DENSE_CASE(M) \
+    if (mtw <= M) return two ? launch_dense<M, 2>(w, a.n, a.bits, s) : launch_dense<M, 1>(w, a.n, a.bits, s)
+    RQ_DENSE_CASE(4);
+    RQ_DENSE_CASE(6);
+    RQ_DENSE_CASE(8);
+    RQ_DENSE_CASE(10);
+    RQ_DENSE_CASE(13);
+#undef RQ_DENSE_CASE
     if (mtw <= 16) return launch_dense<16, 1>(w, a.n, a.bits, s);
+    if (mtw <= 20) return launch_dense<20, 1>(w, a.n, a.bits, s);
+    if (mtw <= 24) return launch_dense<24, 1>(w, a.n, a.bits, s);
+    if (mtw <= 28) return launch_dense<28, 1>(w, a.n, a.bits, s);
     if (mtw <= 32) return launch_dense<32, 1>(w, a.n, a.bits, s);
     return RQ_ERR_NO_ORDER;
 }

@@ -233,7 +233,9 @@ def test_large_blocks_and_byte_granular_rows(torch, n, d, dtype):
 
 @pytest.mark.parametrize("n,rows", [(32, 100), (64, 33), (96, 16), (104, 17), (1544, 333), (4080, 40), (4088, 5),
                                     # 32 rows per workgroup from 32 rows per CU on (ragged last group)
-                                    (1544, 8192 + 21), (104, 9001)])
+                                    (1544, 8192 + 21), (104, 9001),
+                                    # the other register-tile sizes of the kernel (tiles per wave 5, 9, 14, 17)
+                                    (568, 50), (1040, 37), (1784, 20), (2144, 18), (568, 8192 + 5)])
 def test_dense_block_kernel_shapes(torch, n, rows):
     # orders below 128 and whole-dimension blocks on the matrix cores; ragged last group of 16 rows
     if oracle.factor_order(n) is None:
