@@ -136,9 +136,11 @@ __global__ __launch_bounds__(64) void k_wave_rotate(RotArgs a) {
             }
             if (SRC && t == 0) acc[0][0][0] += corr;
             const int col = (t * 64 + chunk) * 8;
-            if (col < a.d_out) {
-                const float v8[8] = {acc[t][0][0], acc[t][0][1], acc[t][0][2], acc[t][0][3],
-                                     acc[t][1][0], acc[t][1][1], acc[t][1][2], acc[t][1][3]};
+            const float v8[8] = {acc[t][0][0], acc[t][0][1], acc[t][0][2], acc[t][0][3],
+                                 acc[t][1][0], acc[t][1][1], acc[t][1][2], acc[t][1][3]};
+            if constexpr (OUT == 1) {
+                store8_f32_quad(static_cast<float*>(a.Y), row * a.ld_out, col, a.d_out, true, lane, v8, k);
+            } else if (col < a.d_out) {
                 store8<OUT>(a.Y, row * a.ld_out + col, v8, k);
             }
         }
@@ -199,8 +201,11 @@ __global__ __launch_bounds__(64) void k_wave_rotate_short(RotArgs a) {
             lane_stage<kDppXor1>(v1, sg0);
             lane_stages_tail<CB>(v0, sf);
             lane_stages_tail<CB>(v1, sf);
-            if (row < a.rows && chunk * 8 < a.d_out) {
-                const float v8[8] = {v0[0] + corr, v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+            const float v8[8] = {v0[0] + corr, v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+            if constexpr (OUT == 1) {
+                store8_f32_quad(static_cast<float*>(a.Y), row * a.ld_out, chunk * 8, a.d_out, row < a.rows, lane, v8,
+                                ks[u], add0[u]);
+            } else if (row < a.rows && chunk * 8 < a.d_out) {
                 store8<OUT>(a.Y, row * a.ld_out + chunk * 8, v8, ks[u], add0[u]);
             }
         }

@@ -666,8 +666,10 @@ __global__ __launch_bounds__(64) void k_wave_block_rotate(WaveArgs a, int pb, Bl
         for (int j = 0; j < NV; ++j) {
             const int ao = 4 * j + g;                      // output block row of this register
             const int col = ao * 128 + c * 8;
-            if (ao < pb && col < o.d_out) {
-                const float v8[8] = {y[0][j], y[1][j], y[2][j], y[3][j], y[4][j], y[5][j], y[6][j], y[7][j]};
+            const float v8[8] = {y[0][j], y[1][j], y[2][j], y[3][j], y[4][j], y[5][j], y[6][j], y[7][j]};
+            if constexpr (OUT == 1) {
+                store8_f32_quad(static_cast<float*>(o.Y), row * o.ld_out, col, o.d_out, ao < pb, lane, v8, k);
+            } else if (ao < pb && col < o.d_out) {
                 store8<OUT>(o.Y, row * o.ld_out + col, v8, k);
             }
         }

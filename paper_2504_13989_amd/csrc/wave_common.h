@@ -482,13 +482,8 @@ __device__ __forceinline__ void store8(void* Y, int64_t idx, const float (&v)[8]
     o[0] += add0;
     if constexpr (OUT == 1) {
         u32x4* p = reinterpret_cast<u32x4*>(static_cast<float*>(Y) + idx);
-#ifdef RQ_ROT_NT32
-        __builtin_nontemporal_store(u32x4{__float_as_uint(o[0]), __float_as_uint(o[1]), __float_as_uint(o[2]), __float_as_uint(o[3])}, p);
-        __builtin_nontemporal_store(u32x4{__float_as_uint(o[4]), __float_as_uint(o[5]), __float_as_uint(o[6]), __float_as_uint(o[7])}, p + 1);
-#else
         p[0] = u32x4{__float_as_uint(o[0]), __float_as_uint(o[1]), __float_as_uint(o[2]), __float_as_uint(o[3])};
         p[1] = u32x4{__float_as_uint(o[4]), __float_as_uint(o[5]), __float_as_uint(o[6]), __float_as_uint(o[7])};
-#endif
     } else {
         uint32_t w[4];
 #pragma unroll
@@ -506,6 +501,37 @@ __device__ __forceinline__ void store8(void* Y, int64_t idx, const float (&v)[8]
         }
         __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(Y) + idx));
     }
+}
+
+// fp32 results of a quad of lanes.  The four lanes of a quad hold four neighbouring 8-column chunks of one
+// row (32 bytes each; lanes p and p ^ 2 hold chunks two apart), so a lane storing its own two 16-byte
+// halves makes two instructions that each write every other 16 bytes of the row.  Here lanes 2, 3 of the
+// quad take the upper halves of lanes 0, 1 for the first store and lanes 0, 1 the lower halves of lanes
+// 2, 3 for the second: each instruction writes whole 64-byte pieces.  Every lane of the wave must be
+// active (the exchange reads neighbouring lanes); `row_ok` and the bound d_out decide what is stored.
+// col: first column of the lane's own chunk, idx: index of the row's column 0 in Y.
+__device__ __forceinline__ void store8_f32_quad(float* Y, int64_t idx, int col, int d_out, bool row_ok, int lane,
+                                                const float (&v)[8], float k, float add0 = 0.0f) {
+    float o[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = v[i] * k;
+    o[0] += add0;
+    const bool upper = (lane & 2) != 0;
+    uint32_t d1[4], d2[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int lo = (int)__float_as_uint(o[j]), hi = (int)__float_as_uint(o[4 + j]);
+        // quad_perm [0,1,0,1]: lanes 2, 3 read lanes 0, 1; quad_perm [2,3,2,3]: lanes 0, 1 read lanes 2, 3
+        const int from_lower = __builtin_amdgcn_update_dpp(0, hi, 0x44, 0xF, 0xF, true);
+        const int from_upper = __builtin_amdgcn_update_dpp(0, lo, 0xEE, 0xF, 0xF, true);
+        d1[j] = (uint32_t)(upper ? from_lower : lo);
+        d2[j] = (uint32_t)(upper ? hi : from_upper);
+    }
+    const int base1 = upper ? (col ^ 16) : col, base2 = upper ? col : (col ^ 16);
+    if (row_ok && base1 < d_out)
+        *reinterpret_cast<u32x4*>(Y + idx + base1 + (upper ? 4 : 0)) = u32x4{d1[0], d1[1], d1[2], d1[3]};
+    if (row_ok && base2 < d_out)
+        *reinterpret_cast<u32x4*>(Y + idx + base2 + (upper ? 4 : 0)) = u32x4{d2[0], d2[1], d2[2], d2[3]};
 }
 
 // Squared quantization error of one rotated row for the clip ratios [k0, k1) (sections 2.1, 3.1):
