@@ -179,42 +179,51 @@ def quadratic_character(i: int, j: int, q: int) -> int:
     return 1 if d in _field_squares(q) else -1
 
 
-def paley1(p: int) -> np.ndarray:
-    """Order p+1 Hadamard matrix, p prime with p = 3 (mod 4); Algorithm 2 (Appendix B).
+def jacobsthal(q: int) -> np.ndarray:
+    """Q[i, j] = chi(a_i - a_j) over GF(q) (section 2.3.3): zero diagonal, +1 where the difference of
+    the two field elements is a non-zero square, -1 elsewhere.  For a prime q the elements are the
+    residues and Q is the circulant of the Legendre symbols; for a prime power the differences are
+    taken digit by digit (elements numbered by their base-p coefficient vectors)."""
+    p, k = prime_power(q)
+    idx = np.arange(q)
+    if k == 1:
+        chi = np.array([legendre_symbol(r, q) for r in range(q)], dtype=np.int64)
+        return chi[(idx[:, None] - idx[None, :]) % q]
+    digits = np.stack([(idx // p ** t) % p for t in range(k)], axis=1)           # [q, k]
+    diff = (digits[:, None, :] - digits[None, :, :]) % p                        # [q, q, k]
+    diff_idx = (diff * (p ** np.arange(k))).sum(axis=2)
+    squares = _field_squares(q)
+    chi = np.array([0 if i == 0 else (1 if x in squares else -1) for i, x in enumerate(field_elements(q))],
+                   dtype=np.int64)
+    return chi[diff_idx]
 
-    All ones; first row and first column (except the corner) are -1; the diagonal below the
-    corner is -1; every other entry [i, j] is the Legendre symbol of (i-1) - (j-1)."""
+
+def paley1(p: int) -> np.ndarray:
+    """Order p+1 Hadamard matrix, p a prime (power) with p = 3 (mod 4); Appendix B, Algorithm 2.
+
+    The matrix is the Jacobsthal matrix with -1 on its diagonal, Q - I, bordered by a first row and a
+    first column of -1 around a +1 corner - the same entries as the listing's element-wise rule
+    (the pins hold the order-4 matrix written out)."""
     if prime_power(p) is None or p % 4 != 3:
         raise ValueError("Paley construction needs a prime (power) p = 3 (mod 4)")
     n = p + 1
-    h = np.ones((n, n), dtype=np.int64)
-    prime = is_prime(p)
-    for i in range(1, n):
-        h[i, 0] = -1
-        h[0, i] = -1
-        for j in range(1, n):
-            if i == j:
-                h[i, j] = -1
-            else:
-                h[i, j] = legendre_symbol((i - 1) - (j - 1), p) if prime else quadratic_character(i - 1, j - 1, p)
+    h = np.full((n, n), -1, dtype=np.int64)
+    h[0, 0] = 1
+    h[1:, 1:] = jacobsthal(p) - np.eye(p, dtype=np.int64)
     return h
 
 
 def paley2(q: int) -> np.ndarray:
-    """Order 2(q+1) Hadamard matrix, q prime with q = 1 (mod 4) (textbook Paley II).
+    """Order 2(q+1) Hadamard matrix, q a prime (power) with q = 1 (mod 4) (textbook Paley II).
 
-    C is (q+1) x (q+1): C[0,0] = 0, C[0,j] = C[j,0] = 1, C[i,j] = legendre(i-j, q) otherwise.
-    H[2i+u, 2j+v] = C[i,j] * A[u,v] + (i == j) * B[u,v], A = [[1,1],[1,-1]], B = [[1,-1],[-1,-1]]."""
+    C = the symmetric conference matrix of order q+1: the Jacobsthal matrix bordered by a row and a
+    column of +1 around a 0 corner.  H = C (x) [[1,1],[1,-1]] + I (x) [[1,-1],[-1,-1]]."""
     if prime_power(q) is None or q % 4 != 1:
         raise ValueError("Paley II construction needs a prime (power) q = 1 (mod 4)")
     m = q + 1
-    c = np.zeros((m, m), dtype=np.int64)
-    c[0, 1:] = 1
-    c[1:, 0] = 1
-    prime = is_prime(q)
-    for i in range(1, m):
-        for j in range(1, m):
-            c[i, j] = legendre_symbol(i - j, q) if prime else quadratic_character(i - 1, j - 1, q)
+    c = np.ones((m, m), dtype=np.int64)
+    c[0, 0] = 0
+    c[1:, 1:] = jacobsthal(q)
     a = np.array([[1, 1], [1, -1]], dtype=np.int64)
     b = np.array([[1, -1], [-1, -1]], dtype=np.int64)
     return np.kron(c, a) + np.kron(np.eye(m, dtype=np.int64), b)
@@ -512,34 +521,29 @@ def boundary_exempt(t: np.ndarray, b: int, tol: float = 1e-6) -> np.ndarray:
 def gbs_search(f, eps: float, max_evals: int = 64):
     """Clip-ratio search for ONE projection: the inner loop of Algorithm 1 (section 4.1).
 
-    a = 0, b = 1, m = 1/2 with f_m = f(m); iterations alternate a left probe x = (a + m)/2 (even
-    iteration) and a right probe x = (b + m)/2 (odd).  If f(x) < f_m the probe becomes the new
-    middle and the bracket end on the far side of the old middle moves to the old middle; else
-    the bracket end on the probe's side moves to the probe.  Stops when b - a <= eps.
-    Returns (m, f_m, trace) with trace = [(x, f(x)), ...] in evaluation order (first entry is
+    State: the best point so far and, on either side of it, the nearest point already evaluated (0 and
+    1 to begin with, the best point 1/2).  Each step probes the midpoint between the best point and
+    one of those two neighbours - left, right, left, ... - and either the probe becomes the best point
+    (the old best point is then its neighbour on that side) or it becomes the nearer neighbour on its
+    own side.  Stops when the two neighbours are within eps of each other.
+    Returns (best, f(best), trace) with trace = [(x, f(x)), ...] in evaluation order (first entry is
     the initial middle).  The paper leaves eps open; max_evals only guards against eps <= 0."""
-    a, b = 0.0, 1.0
-    m = (a + b) / 2
-    fm = f(m)
-    trace = [(m, fm)]
-    it = 0
-    while b - a > eps and len(trace) < max_evals:
-        x = (a + m) / 2 if it % 2 == 0 else (b + m) / 2
+    near = [0.0, 1.0]                                   # nearest evaluated points: [left of best, right of best]
+    best = 0.5
+    f_best = f(best)
+    trace = [(best, f_best)]
+    side = 0                                            # 0: probe towards the left neighbour, 1: the right one
+    while near[1] - near[0] > eps and len(trace) < max_evals:
+        x = (near[side] + best) / 2
         fx = f(x)
         trace.append((x, fx))
-        if fx < fm:
-            if x < m:
-                b = m
-            else:
-                a = m
-            m, fm = x, fx
+        if fx < f_best:
+            near[1 - side] = best                       # the old best point now bounds the far side
+            best, f_best = x, fx
         else:
-            if x < m:
-                a = x
-            else:
-                b = x
-        it += 1
-    return m, fm, trace
+            near[side] = x
+        side = 1 - side
+    return best, f_best, trace
 
 
 def gbs(objectives, eps: float):

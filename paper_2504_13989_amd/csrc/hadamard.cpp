@@ -4,6 +4,8 @@
 // (section 2.3.3).
 #include "hadamard.h"
 
+#include <algorithm>
+
 namespace rq {
 
 bool is_prime(int v) {
@@ -172,43 +174,52 @@ bool factor_order(int n, Factorisation* f) {
     return false;
 }
 
+// Jacobsthal matrix of GF(q), row-major q x q: entry (i, j) = chi(a_i - a_j) - 0 on the diagonal, +1 for
+// a non-zero square, -1 otherwise (section 2.3.3).  For a prime q the rows are the cyclic shifts of the
+// Legendre symbols; for a prime power the difference of two elements is taken through element_diff.
+static std::vector<int8_t> jacobsthal(int q) {
+    std::vector<int8_t> m((size_t)q * q);
+    if (is_prime(q)) {
+        std::vector<int8_t> by_diff((size_t)q);
+        for (int r = 0; r < q; ++r) by_diff[r] = (int8_t)legendre(r, q);
+        for (int i = 0; i < q; ++i)
+            for (int j = 0; j < q; ++j) m[(size_t)i * q + j] = by_diff[(i - j + q) % q];
+        return m;
+    }
+    int fp = 0, fk = 0;
+    prime_power(q, &fp, &fk);
+    const std::vector<int8_t> chi = character_table(q);
+    for (int i = 0; i < q; ++i)
+        for (int j = 0; j < q; ++j) m[(size_t)i * q + j] = chi[element_diff(i, j, fp, fk)];
+    return m;
+}
+
 std::vector<int8_t> build_block(const Factorisation& f) {
     const int p = f.p;
     std::vector<int8_t> h((size_t)p * p, 1);
-    // chi(a_i - a_j): the Legendre symbol of i - j for a prime q, the quadratic character of
-    // GF(q) for a prime power
-    int fp = 0, fk = 0;
-    std::vector<int8_t> chi;
-    if (f.kind != 0 && !is_prime(f.q)) {
-        prime_power(f.q, &fp, &fk);
-        chi = character_table(f.q);
-    }
-    auto character = [&](int i, int j) -> int {
-        if (chi.empty()) return legendre((int64_t)i - j, f.q);
-        return chi[element_diff(i, j, fp, fk)];
-    };
+    if (f.kind == 0) return h;
+    const int q = f.q;
+    const std::vector<int8_t> core = jacobsthal(q);
     if (f.kind == 1) {
-        // order q+1: corner +1, rest of first row and column -1, diagonal -1, entry [i][j] the
-        // Legendre symbol of i - j elsewhere
-        for (int i = 1; i < p; ++i) {
-            h[(size_t)i * p] = -1;
-            h[i] = -1;
-            for (int j = 1; j < p; ++j)
-                h[(size_t)i * p + j] = (i == j) ? -1 : (int8_t)character(i - 1, j - 1);
-        }
-    } else if (f.kind == 2) {
-        // order 2(q+1): 2x2 blocks; off-diagonal block (i,j) is c_ij * [[1,1],[1,-1]] with c the
-        // bordered symmetric conference matrix, diagonal blocks are [[1,-1],[-1,-1]]
-        const int m = f.q + 1;
+        // order q + 1 (Appendix B, Algorithm 2): Q - I inside a border of -1 with a +1 corner
+        std::fill(h.begin(), h.end(), (int8_t)-1);
+        h[0] = 1;
+        for (int i = 0; i < q; ++i)
+            for (int j = 0; j < q; ++j)
+                if (i != j) h[(size_t)(i + 1) * p + (j + 1)] = core[(size_t)i * q + j];
+    } else {
+        // order 2 (q + 1): the conference matrix C (Q inside a border of +1 with a 0 corner) spread over
+        // 2 x 2 cells - C_ij [[1, 1], [1, -1]] off the diagonal, [[1, -1], [-1, -1]] on it
+        const int m = q + 1;
         for (int i = 0; i < m; ++i)
             for (int j = 0; j < m; ++j) {
-                int8_t* b = &h[(size_t)(2 * i) * p + 2 * j];
-                if (i == j) {
-                    b[0] = 1; b[1] = -1; b[p] = -1; b[p + 1] = -1;
-                } else {
-                    int c = (i == 0 || j == 0) ? 1 : character(i - 1, j - 1);
-                    b[0] = (int8_t)c; b[1] = (int8_t)c; b[p] = (int8_t)c; b[p + 1] = (int8_t)-c;
-                }
+                const int c = (i == 0 || j == 0) ? 1 : core[(size_t)(i - 1) * q + (j - 1)];
+                int8_t* cell = &h[(size_t)(2 * i) * p + 2 * j];
+                const bool diag = i == j;
+                cell[0] = (int8_t)(diag ? 1 : c);
+                cell[1] = (int8_t)(diag ? -1 : c);
+                cell[p] = (int8_t)(diag ? -1 : c);
+                cell[p + 1] = (int8_t)(diag ? -1 : -c);
             }
     }
     return h;

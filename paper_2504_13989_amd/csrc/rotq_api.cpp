@@ -481,20 +481,24 @@ size_t rq_gbs_workspace(int64_t rows) {
 namespace {
 
 // State of Algorithm 1's inner loop (section 4.1): bracket [a, b], best point m, iteration parity.
+// State of the search of Algorithm 1 (section 4.1): the best point so far and the nearest evaluated
+// point on either side of it; probes go to the midpoint towards the left and the right neighbour in turn.
 struct GbsState {
-    double a, b, m;
-    int it;
-    double probe() const { return (it % 2 == 0) ? (a + m) / 2 : (b + m) / 2; }
-    // the update of the listing after probing x: `better` = the probe beat the best point
+    double near[2];       // nearest evaluated points: [0] left of best, [1] right of best
+    double best;
+    int side;             // neighbour the next probe goes towards
+    double width() const { return near[1] - near[0]; }
+    double probe() const { return 0.5 * (near[side] + best); }
+    // after probing x = probe(): `better` = the probe beat the best point, which then bounds the far side
     GbsState next(double x, bool better) const {
         GbsState n = *this;
         if (better) {
-            if (x < m) n.b = m; else n.a = m;
-            n.m = x;
+            n.near[1 - side] = best;
+            n.best = x;
         } else {
-            if (x < m) n.a = x; else n.b = x;
+            n.near[side] = x;
         }
-        n.it = it + 1;
+        n.side = 1 - side;
         return n;
     }
 };
@@ -503,7 +507,7 @@ struct GbsState {
 // (node i: children 2 i for "better", 2 i + 1 for "not better"); the positions do not depend on the
 // objective values, only on the outcomes.  x[i] < 0 marks a node the search cannot reach.
 void gbs_tree(const GbsState& st, double eps, int depth, int idx, double* x) {
-    if (depth == 0 || st.b - st.a <= eps) return;
+    if (depth == 0 || st.width() <= eps) return;
     const double p = st.probe();
     x[idx] = p;
     gbs_tree(st.next(p, true), eps, depth - 1, 2 * idx, x);
@@ -553,16 +557,16 @@ static int gbs_impl(const rq_hadamard_t* h, const void* X, int dtype, int64_t ro
         if (trace_mse) trace_mse[evals] = v;
         ++evals;
     };
-    GbsState st{0.0, 1.0, 0.5, 0};
+    GbsState st{{0.0, 1.0}, 0.5, 0};
     float fm = 0.0f;
     bool first = true;
-    while (first || (st.b - st.a > (double)eps && evals < max_evals)) {
+    while (first || (st.width() > (double)eps && evals < max_evals)) {
         double x[64];
         int slot[64];
         for (int i = 0; i < 64; ++i) x[i] = -1.0;
         gbs_tree(st, (double)eps, depth, 1, x);
         int count = 0;
-        if (first) clips[count++] = (float)st.m;          // the starting point rides along with the first batch
+        if (first) clips[count++] = (float)st.best;          // the starting point rides along with the first batch
         for (int i = 1; i < (1 << depth); ++i)
             if (x[i] >= 0.0) {
                 slot[i] = count;
@@ -577,7 +581,7 @@ static int gbs_impl(const rq_hadamard_t* h, const void* X, int dtype, int64_t ro
             first = false;
         }
         int idx = 1;
-        for (int lvl = 0; lvl < depth && st.b - st.a > (double)eps && evals < max_evals; ++lvl) {
+        for (int lvl = 0; lvl < depth && st.width() > (double)eps && evals < max_evals; ++lvl) {
             const double p = x[idx];
             const float fx = vals[slot[idx]];
             record((float)p, fx);
@@ -587,7 +591,7 @@ static int gbs_impl(const rq_hadamard_t* h, const void* X, int dtype, int64_t ro
             idx = 2 * idx + (better ? 0 : 1);
         }
     }
-    *clip_out = (float)st.m;
+    *clip_out = (float)st.best;
     *mse_out = fm;
     if (n_evals) *n_evals = evals;
     return RQ_OK;

@@ -39,12 +39,12 @@ def test_pin(oracle, check):
 MUTATIONS = {
     "sylvester_sign": ("np.block([[h, h], [h, -h]])", "np.block([[h, h], [-h, h]])"),
     "legendre_flipped": ("return 1 if a in _nonzero_squares(p) else -1", "return -1 if a in _nonzero_squares(p) else 1"),
-    "paley1_diag_plus": ("            if i == j:\n                h[i, j] = -1", "            if i == j:\n                h[i, j] = 1"),
-    "paley1_transposed": ("legendre_symbol((i - 1) - (j - 1), p)", "legendre_symbol((j - 1) - (i - 1), p)"),
-    "paley1_border": ("h[0, i] = -1", "h[0, i] = 1"),
+    "paley1_diag_plus": ("jacobsthal(p) - np.eye(p, dtype=np.int64)", "jacobsthal(p) + np.eye(p, dtype=np.int64)"),
+    "paley1_transposed": ("return chi[(idx[:, None] - idx[None, :]) % q]", "return chi[(idx[None, :] - idx[:, None]) % q]"),
+    "paley1_border": ("    h[0, 0] = 1\n    h[1:, 1:] = jacobsthal(p)", "    h[0, :] = 1\n    h[1:, 1:] = jacobsthal(p)"),
     "paley1_no_guard": ("if prime_power(p) is None or p % 4 != 3:", "if prime_power(p) is None:"),
     "paley2_b_sign": ("b = np.array([[1, -1], [-1, -1]]", "b = np.array([[1, -1], [-1, 1]]"),
-    "paley2_border": ("c[1:, 0] = 1", "c[1:, 0] = -1"),
+    "paley2_border": ("    c[0, 0] = 0\n    c[1:, 1:] = jacobsthal(q)", "    c[1:, 0] = -1\n    c[0, 0] = 0\n    c[1:, 1:] = jacobsthal(q)"),
     "paley2_kron_order": ("return np.kron(c, a) + np.kron(np.eye(m, dtype=np.int64), b)",
                           "return np.kron(a, c) + np.kron(b, np.eye(m, dtype=np.int64))"),
     "paley_kind_priority": ("if p >= 4 and is_prime(p - 1) and (p - 1) % 4 == 3:\n        return 1, p - 1",
@@ -87,10 +87,10 @@ MUTATIONS = {
     "asym_offset_dropped": ("return (cg * delta[:, :, None] + lo[:, :, None]).reshape(rows, n)", "return (cg * delta[:, :, None]).reshape(rows, n)"),
     "asym_signed_range": ("codes = np.clip(np.rint(t), 0, lvl).astype(np.uint8)", "codes = np.clip(np.rint(t), 0, lvl - 1).astype(np.uint8)"),
     "asym_group_axis": ("yg = y.reshape(rows, n // group, group)\n    lo = clip64", "yg = y.reshape(rows, group, n // group).transpose(0, 2, 1)\n    lo = clip64"),
-    "gbs_probe_parity": ("x = (a + m) / 2 if it % 2 == 0 else (b + m) / 2", "x = (a + m) / 2 if it % 2 == 1 else (b + m) / 2"),
-    "gbs_keep_worse": ("        if fx < fm:\n            if x < m:\n                b = m", "        if fx > fm:\n            if x < m:\n                b = m"),
-    "gbs_bracket_swap": ("            if x < m:\n                a = x\n            else:\n                b = x", "            if x < m:\n                b = x\n            else:\n                a = x"),
-    "gbs_stop": ("while b - a > eps and", "while b - a > 4 * eps and"),
+    "gbs_probe_parity": ("    side = 0 ", "    side = 1 "),
+    "gbs_keep_worse": ("        if fx < f_best:", "        if fx > f_best:"),
+    "gbs_bracket_swap": ("            near[side] = x", "            near[1 - side] = x"),
+    "gbs_stop": ("while near[1] - near[0] > eps and", "while near[1] - near[0] > 4 * eps and"),
 }
 
 
