@@ -203,7 +203,13 @@ def time_all_configs(torch, binding, wl):
         res[f"dequantize_rotate_llama_b4_{key}"] = {"n": w.n, "rows": int(x.shape[0]), "out": key, "us": ms * 1e3, "GBps": gbps,
                                                     "frac_hbm_peak": gbps / HBM_PEAK_GBPS, "kernel": h.last_kernel}
         del y
-    del x, codes, scales
+    # codes + scale -> values in the rotated domain (section 2.1's X^ = round(X / Delta) * Delta), fp32 out
+    y = torch.empty((x.shape[0], w.n), dtype=torch.float32, device="cuda")
+    ms = _min_ms(torch, lambda: binding.dequantize(h, codes, scales, 4, out=y))
+    gbps = x.shape[0] * (w.n * 4 // 8 + 4 + 4 * w.n) / ms / 1e6
+    res["dequantize_llama_b4_f32"] = {"n": w.n, "rows": int(x.shape[0]), "out": "f32", "us": ms * 1e3, "GBps": gbps,
+                                      "frac_hbm_peak": gbps / HBM_PEAK_GBPS, "kernel": h.last_kernel}
+    del x, y, codes, scales
     # rotation alone on a Paley-block order (H_28 (x) H_128): bf16 in, bf16 out, H and H^T
     w = wl.WORKLOADS["qwen_hidden"]
     x = torch.from_numpy(wl.generate(w.with_rows(2048)).view(np.int16)).cuda().view(torch.bfloat16).repeat(36, 1)

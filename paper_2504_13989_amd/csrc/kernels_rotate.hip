@@ -85,6 +85,7 @@ __global__ __launch_bounds__(64) void k_wave_rotate(RotArgs a) {
     const int g = lane >> 4, cphys = lane & 15;
     const int c = (cphys & 4) ? (cphys ^ 3) : cphys;
     const int chunk = (g << 4) + c;
+    __shared__ __attribute__((aligned(16))) float lds_out[OUT == 1 ? 512 : 4];   // fp32 results pass through LDS, see store_block_f32
     const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
     float sf[4];
 #pragma unroll
@@ -139,7 +140,10 @@ __global__ __launch_bounds__(64) void k_wave_rotate(RotArgs a) {
             const float v8[8] = {acc[t][0][0], acc[t][0][1], acc[t][0][2], acc[t][0][3],
                                  acc[t][1][0], acc[t][1][1], acc[t][1][2], acc[t][1][3]};
             if constexpr (OUT == 1) {
-                store8_f32_quad(static_cast<float*>(a.Y), row * a.ld_out, col, a.d_out, true, lane, v8, k);
+                float* const yr = static_cast<float*>(a.Y) + row * a.ld_out + t * 512;
+                store_block_f32(lds_out, chunk, lane, v8, k, 0.0f, [&](int e, const u32x4& unit) {
+                    if (t * 512 + e < a.d_out) __builtin_nontemporal_store(unit, reinterpret_cast<u32x4*>(yr + e));
+                });
             } else if (col < a.d_out) {
                 store8<OUT>(a.Y, row * a.ld_out + col, v8, k);
             }
@@ -160,6 +164,7 @@ __global__ __launch_bounds__(64) void k_wave_rotate_short(RotArgs a) {
     const int rsub = nnl >> CB;
     const int c = (CB >= 3 && (cphys & 4)) ? (cphys ^ 3) : cphys;
     const int chunk = (g << CB) + c;
+    __shared__ __attribute__((aligned(16))) float lds_out[OUT == 1 ? 512 : 4];   // fp32 results pass through LDS, see store_block_f32
     const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
     float sf[4];
 #pragma unroll
@@ -203,8 +208,14 @@ __global__ __launch_bounds__(64) void k_wave_rotate_short(RotArgs a) {
             lane_stages_tail<CB>(v1, sf);
             const float v8[8] = {v0[0] + corr, v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
             if constexpr (OUT == 1) {
-                store8_f32_quad(static_cast<float*>(a.Y), row * a.ld_out, chunk * 8, a.d_out, row < a.rows, lane, v8,
-                                ks[u], add0[u]);
+                // the pass's RPW rows are one block of 64 chunks: row rsub, chunk `chunk`
+                const int64_t prow0 = row0 + u * RPW;
+                store_block_f32(lds_out, rsub * (4 << CB) + chunk, lane, v8, ks[u], add0[u], [&](int e, const u32x4& unit) {
+                    const int64_t orow = prow0 + (e >> (5 + CB));
+                    const int ocol = e & ((32 << CB) - 1);
+                    if (orow < a.rows && ocol < a.d_out)
+                        __builtin_nontemporal_store(unit, reinterpret_cast<u32x4*>(static_cast<float*>(a.Y) + orow * a.ld_out + ocol));
+                });
             } else if (row < a.rows && chunk * 8 < a.d_out) {
                 store8<OUT>(a.Y, row * a.ld_out + chunk * 8, v8, ks[u], add0[u]);
             }

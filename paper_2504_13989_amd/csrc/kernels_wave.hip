@@ -652,6 +652,7 @@ __global__ __launch_bounds__(64) void k_wave_block_rotate(WaveArgs a, int pb, Bl
     const int lane = threadIdx.x;
     const int g = lane >> 4, cphys = lane & 15;
     const int c = (cphys & 4) ? (cphys ^ 3) : cphys;
+    __shared__ __attribute__((aligned(16))) float lds_out[OUT == 1 ? 512 : 4];   // fp32 results pass through LDS, see store_block_f32
     const u32x4 A0 = a.tiles[lane], A1 = a.tiles[64 + lane];
     float sf[4];
 #pragma unroll
@@ -668,7 +669,12 @@ __global__ __launch_bounds__(64) void k_wave_block_rotate(WaveArgs a, int pb, Bl
             const int col = ao * 128 + c * 8;
             const float v8[8] = {y[0][j], y[1][j], y[2][j], y[3][j], y[4][j], y[5][j], y[6][j], y[7][j]};
             if constexpr (OUT == 1) {
-                store8_f32_quad(static_cast<float*>(o.Y), row * o.ld_out, col, o.d_out, ao < pb, lane, v8, k);
+                // block rows 4 j .. 4 j + 3 are one block of 64 chunks: block row g, chunk c
+                float* const yr = static_cast<float*>(o.Y) + row * o.ld_out + 4 * j * 128;
+                store_block_f32(lds_out, g * 16 + c, lane, v8, k, 0.0f, [&](int e, const u32x4& unit) {
+                    if (4 * j + (e >> 7) < pb && 4 * j * 128 + e < o.d_out)
+                        __builtin_nontemporal_store(unit, reinterpret_cast<u32x4*>(yr + e));
+                });
             } else if (ao < pb && col < o.d_out) {
                 store8<OUT>(o.Y, row * o.ld_out + col, v8, k);
             }
