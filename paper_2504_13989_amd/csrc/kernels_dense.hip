@@ -143,7 +143,7 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_dense_block(WaveArgs a, in
     lds_store(0, R);
     R = gload(1);
     __syncthreads();
-    for (int grp = 0; grp < NG; ++grp) {
+    for (int grp = 0; grp + 1 < NG; ++grp) {
 #pragma unroll
         for (int i = 0; i < G; ++i)
 #pragma unroll
@@ -177,6 +177,21 @@ __global__ __launch_bounds__(64 * kDenseWaves) void k_dense_block(WaveArgs a, in
 #pragma unroll
             for (int v = 0; v < QV; ++v) sC[i][v] = sN[i][v];
         __syncthreads();
+    }
+    {
+        // last group: only the steps that exist (KK need not be a multiple of G), nothing left to request
+        const int rem = KK - (NG - 1) * G;
+        const uint8_t* const rd = lds_r + ((NG - 1) & 1) * (RB * PITCH);
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            if (i < rem) {
+                u32x4 x[NT];
+#pragma unroll
+                for (int q = 0; q < NT; ++q) x[q] = *reinterpret_cast<const u32x4*>(rd + 16 * q * PITCH + i * 64);
+                contract(sC[i], x);
+            }
+        }
+        __syncthreads();                                 // the staging buffers become the packed rows' image
     }
 
     // absmax of the lane's rows: this lane's registers, the four lane rows, the eight waves
