@@ -2,6 +2,7 @@
 #include <cmath>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "rotq_internal.h"
 
@@ -481,6 +482,37 @@ size_t rq_gbs_workspace(int64_t rows) {
 namespace {
 
 // State of Algorithm 1's inner loop (section 4.1): bracket [a, b], best point m, iteration parity.
+// RQ_MAX_CLIPS floats of pinned host memory and their device address, one buffer per host thread and device,
+// allocated at the first search of that thread on that device and kept until the process ends (a search is a
+// host loop that synchronises its stream, so the buffer is never in use by two searches at once).
+struct MappedVals {
+    float* host = nullptr;
+    float* dev = nullptr;
+};
+
+MappedVals mapped_vals(int device) {
+    struct Entry { int device; MappedVals mv; };
+    thread_local std::vector<Entry> cache;
+    for (const Entry& e : cache)
+        if (e.device == device) return e.mv;
+    MappedVals mv;
+    int cur = -1;
+    void* hp = nullptr;
+    void* dp = nullptr;
+    if (hipGetDevice(&cur) == hipSuccess && cur == device &&
+        hipHostMalloc(&hp, sizeof(float) * RQ_MAX_CLIPS, hipHostMallocMapped) == hipSuccess) {
+        if (hipHostGetDevicePointer(&dp, hp, 0) == hipSuccess && dp) {
+            mv.host = static_cast<float*>(hp);
+            mv.dev = static_cast<float*>(dp);
+        } else {
+            (void)hipHostFree(hp);
+        }
+    }
+    (void)hipGetLastError();
+    cache.push_back(Entry{device, mv});
+    return mv;
+}
+
 // State of the search of Algorithm 1 (section 4.1): the best point so far and the nearest evaluated
 // point on either side of it; probes go to the midpoint towards the left and the right neighbour in turn.
 struct GbsState {
@@ -542,9 +574,19 @@ static int gbs_impl(const rq_hadamard_t* h, const void* X, int dtype, int64_t ro
     const int depth = gbs_depth(rows, h->f.n);
     float vals[RQ_MAX_CLIPS];
     float clips[RQ_MAX_CLIPS];
+    // The objective values of a batch come back through pinned host memory that the reduction kernel writes
+    // itself (mapped into the device's address space): a batch then costs one synchronisation of the caller's
+    // stream and no copy.  Where that memory cannot be had, they are copied back on the same stream.
+    const MappedVals mv = mapped_vals(h->device);
     auto evaluate = [&](int count) -> int {
-        int r = rq::quant_error_impl(h, X, dtype, rows, d, ld, bits, clips, count, d_mse, qws, qws_bytes, stream, asym);
+        float* out = mv.dev ? mv.dev : d_mse;
+        int r = rq::quant_error_impl(h, X, dtype, rows, d, ld, bits, clips, count, out, qws, qws_bytes, stream, asym);
         if (r != RQ_OK) return r;
+        if (mv.dev) {
+            if (hipStreamSynchronize(s) != hipSuccess) return RQ_ERR_HIP;
+            std::memcpy(vals, mv.host, sizeof(float) * count);
+            return RQ_OK;
+        }
         // read back on the caller's stream: no other stream is made to wait
         if (hipMemcpyAsync(vals, d_mse, sizeof(float) * count, hipMemcpyDeviceToHost, s) != hipSuccess ||
             hipStreamSynchronize(s) != hipSuccess)
