@@ -333,7 +333,10 @@ size_t rq_gbs_workspace(int64_t rows);
  * max_evals evaluations of f.  The probes and their values are those of that loop taken one at a
  * time; they are evaluated ahead in batches (one rq_quant_error launch covers every probe the next
  * few steps can ask for, whatever the comparisons give), each batch followed by a synchronisation of
- * `stream` and a read-back: a calibration call, not a hot-path call.
+ * `stream`: a calibration call, not a hot-path call.  The values of a batch come back through 256
+ * bytes of pinned host memory that the library allocates at the first search of a host thread on a
+ * device and keeps until the process ends (copied back on `stream` instead where that allocation
+ * fails); nothing else is allocated.
  *   eps          [in]  bracket width to stop at, > 0
  *   max_evals    [in]  1 .. 256
  *   workspace    [in]  DEVICE, >= rq_gbs_workspace(rows) bytes, 8-byte aligned, scratch
