@@ -196,6 +196,33 @@ def test_dequantize_in_the_rotated_domain(torch, name, rows, b):
     assert np.array_equal(yh.cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("n,rows", [(96, 1000), (160, 333), (896, 77), (1544, 13), (128, 600001), (1024, 70001)])
+@pytest.mark.parametrize("b", [3, 4])
+def test_dequantize_launch_shapes(torch, n, rows, b):
+    """rq_dequantize on random codes: rows shorter than a workgroup that share one (row lengths that are not a
+    power of two included), rows cut into segments, more row groups than the grid holds (the row loop), and an
+    output that is not 16-byte aligned."""
+    rng = np.random.default_rng(1000 * n + b)
+    q = rng.integers(-(1 << (b - 1)), 1 << (b - 1), size=(rows, n), dtype=np.int64).astype(np.int8)
+    packed = oracle.pack_codes(q, b)
+    scales32 = rng.uniform(0.01, 3.0, size=rows).astype(np.float32)
+    scales32[rows // 2] = 0.0
+    h = handle(n)
+    say(f"dequantize shapes n={n} rows={rows} b={b}")
+    ct, st = torch.from_numpy(packed).cuda(), torch.from_numpy(scales32).cuda()
+    out = binding.dequantize(h, ct, st, b)
+    torch.cuda.synchronize()
+    want = (q.astype(np.float32) * scales32[:, None]).astype(np.float32)       # one exact-input fp32 product each
+    assert np.array_equal(out.cpu().numpy(), want)
+    if rows <= 1000:
+        buf = torch.full((rows * n + 8,), 7.0, dtype=torch.float32, device="cuda")
+        view = buf[1:1 + rows * n].view(rows, n)                                # 4-byte aligned only
+        binding.dequantize(h, ct, st, b, out=view)
+        torch.cuda.synchronize()
+        assert np.array_equal(view.cpu().numpy(), want)
+        assert buf[0].item() == 7.0 and bool((buf[1 + rows * n:] == 7.0).all().item())
+
+
 @pytest.mark.parametrize("name,rows,b", [("kv_k", 300, 3), ("kv_v", 1027, 4), ("llama_hidden", 20, 3)])
 def test_dequantize_asym_in_the_rotated_domain(torch, name, rows, b):
     w = wl.WORKLOADS[name].with_rows(rows)
