@@ -4,16 +4,17 @@
 // Here the rotation really is a dense contraction, y = H_n x with n multiply-adds per output
 // (sections 2.3.3, 4.2), so it runs on the matrix cores as a GEMM: D[a'][row] = sum_a H[a'][a]
 // X[row][a], v_mfma_f32_16x16x32_bf16 with
-//   B operand  16 rows x 32 inputs straight from memory: lane (g, r) loads the 16 bytes
-//              X[row0 + r][32 kk + 8 g ..] (exact bf16, no conversion, no transposition);
+//   B operand  16 rows x 32 inputs as they are in memory: lane (g, r) takes the 16 bytes
+//              X[row0 + r][32 kk + 8 g ..] (exact bf16, no conversion), staged through LDS so that the
+//              loads from memory are coalesced (see the loader role in the kernel);
 //   A operand  a 16 x 32 tile of +-1 (bf16), made in registers from one sign bit per entry: the handle
 //              holds the matrix as n^2 / 8 bytes of signs, a lane's 8 signs of a tile sit in a 32-bit word
 //              (four tiles per word) at the positions where one rotation of the word brings two of them
 //              to bits 15 and 31, so an operand register costs a rotate and an and-or:
 //              8 vector instructions per tile against 16 NT matrix-core cycles;
 //   D          lane (g, r) register j = output 16 mt + 4 g + j of row r, fp32.
-// A workgroup of 8 waves owns 16 NT rows (NT = 1, 2 or 4 by the number of rows: every tile then serves NT
-// groups of rows); wave w owns the output tiles mt = w, w + 8, ... and keeps their accumulators in
+// A workgroup of 8 waves owns 16 NT rows (NT = 1, or 2 when there are rows enough: every tile then serves
+// two groups of rows); wave w owns the output tiles mt = w, w + 8, ... and keeps their accumulators in
 // registers over the whole contraction.  Then: row absmax (registers, the four lane rows, the
 // eight waves through LDS), scale, round/clamp (section 2.1 with the clip ratio of section 3.1),
 // pack into an LDS image of the packed rows, copy out coalesced.
@@ -319,9 +320,9 @@ int dense_block_rotate_quantize(const rq_hadamard* h, const RowArgs& a, float cl
                static_cast<const u32x4*>(h->d_tiles), codes, scales,
                lvl / (double)clip, (double)clip / (std::sqrt((double)a.n) * lvl)};
     const int mtw = ((a.n + 15) / 16 + kDenseWaves - 1) / kDenseWaves;
-    // 32 or 64 rows per workgroup: every operand tile made in registers then serves two or four groups of
-    // rows; used when that still leaves a workgroup for every CU and the accumulators fit the register
-    // budget (two waves per SIMD)
+    // 32 rows per workgroup: every operand tile made in registers then serves two groups of rows; used when
+    // that still leaves a workgroup for every CU and the accumulators fit the register budget (two waves
+    // per SIMD; 64 rows need 208 accumulator registers per wave and spill)
     const bool two = a.rows >= (int64_t)32 * h->num_cu;
 #define RQ_DENSE_CASE(M) \
     if (mtw <= M) return two ? launch_dense<M, 2>(w, a.n, a.bits, s) : launch_dense<M, 1>(w, a.n, a.bits, s)
