@@ -4,7 +4,8 @@
 // per-head H_128 as the keys whose rotated form goes into the quantized cache - so it gets the same
 // treatment as rotate_quantize: one wave per row (n >= 1024) or 16 >> CB rows per wave pass
 // (n = 32 << CB), five stages on the matrix cores, the rest in registers and DPP, 16-byte loads and
-// stores.  H_{2^k} is symmetric, so the transposed product is the same kernel.
+// stores (fp32 results pass through LDS first, so that every store instruction covers 1 KB of consecutive
+// bytes: store_block_f32).  H_{2^k} is symmetric, so the transposed product is the same kernel.
 //
 // The same kernels take packed codes instead of rows (rq_dequantize_rotate: x = H^T (code Delta) / sqrt(n),
 // sections 2.1, 2.3): a b-bit code u (offset binary) becomes the bf16 pattern 0x4300 | u = 128 + u by bit

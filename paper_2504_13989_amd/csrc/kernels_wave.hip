@@ -638,8 +638,9 @@ __global__ __launch_bounds__(64) void k_wave_block(WaveArgs a, int pb) {
 
 // Rotation alone for the same block orders (rq_rotate: the online rotation of a tensor that is not
 // quantized, offline weight fusion, the inverse rotation with the transposed block's operand tiles):
-// the row's rotation as above, then one multiply and a 16-byte (bf16 / fp16) or 32-byte (fp32) store
-// per lane and block row.
+// the row's rotation as above, then one multiply and a 16-byte store per lane and block row (bf16 / fp16);
+// fp32 results pass through LDS so that a store instruction covers 1 KB of consecutive bytes
+// (store_block_f32).
 struct BlockRotArgs {
     void* Y;
     int d_out;
