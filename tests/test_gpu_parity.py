@@ -262,6 +262,19 @@ def test_leading_dimension_and_row_views(torch):
     x = wl.generate(w)
     codes, scales, kern = run_rq(torch, x, w.n, 3, 0.9, ld=w.d + 8)
     parity.check_rotate_quantize(x, w.n, 3, 0.9, codes, scales, f"ld [{kern}]")
+    # dense-block kernel: rows narrower than the order inside a wider allocation (zero padding beyond d, the
+    # loader's row pitch), a ragged last group of rows, degenerate rows
+    rng = np.random.default_rng(15)
+    xf = rng.standard_t(3.0, size=(70, 1536)).astype(np.float32)
+    xf[5] = 0.0
+    xf[6, :] = 0.0
+    xf[6, 1535] = 4.0
+    xd = wl.f32_to_bf16_bits(xf)
+    for b in (3, 4):
+        codes, scales, kern = run_rq(torch, xd, 1544, b, 0.9, ld=1600)
+        assert kern == "dense_block"
+        parity.check_rotate_quantize(xd, 1544, b, 0.9, codes, scales, f"dense ld [{kern}]")
+        assert scales[5] == 0 and not codes[5].any()
     # 4-D KV view [B, H, S, 128]
     w = wl.WORKLOADS["kv_k"].with_rows(2 * 3 * 40)
     x = wl.generate(w)
